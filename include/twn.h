@@ -1,0 +1,183 @@
+/* twn.h — C ABI of the MI355X (gfx950) Ternary Weight Networks hot path.
+ *
+ * The library implements, as HIP kernels, the two halves of the method of
+ * "Ternary Weight Networks" (arXiv 1605.04711):
+ *   1. threshold ternarization of float32 weights (Sec. 2.3: Eq. 3, Eq. 5 and
+ *      the rule of thumb Delta = f * mean|W|; Alg. 1 steps 3-7), emitted as
+ *      2-bit codes (Sec. 2.1 "Model compression") plus Delta, alpha, |I_Delta|;
+ *   2. the forward block Z = X * (alpha W~) (Eq. 2; Alg. 1 step 8) for
+ *      convolutions and inner products, and its straight-through backward
+ *      (Alg. 1 steps 9-10: gradients computed with T = alpha W~ and handed to
+ *      the float32 master weights).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *     Descriptors (`twn_*_desc`, `twn_epilogue`) are HOST structs, read before
+ *     the call returns.
+ *   - The caller owns every buffer.  The library never allocates, frees or
+ *     keeps device memory; scratch space is passed in as `workspace`
+ *     (size from the matching `*_workspace_bytes` host function; contents on
+ *     entry are irrelevant and on exit unspecified; may be NULL when 0 bytes).
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *     only enqueue work; none synchronises.  Scalar results (Delta, alpha, nnz)
+ *     are written to device memory and are consumed from there by later calls.
+ *   - Return value: TWN_OK or a negative twn_status.  Arguments are validated
+ *     on the host before anything is launched, so every error except
+ *     TWN_ERR_HIP is raised without touching the GPU and leaves all buffers
+ *     untouched.  Nothing throws or aborts.
+ *   - Finite inputs are a precondition (NaN/Inf give unspecified results).
+ *
+ * Packed ternary weight format ("twn2")
+ *   A filter bank [rows][C][R][S] is stored as a matrix [rows][K], K = R*S*C,
+ *   with k = (r*S + s)*C + c (input channel fastest, matching NHWC activations).
+ *   Each row is padded with zero codes to a multiple of 128 weights and takes
+ *   twn_packed_words_per_row(K) = 8*ceil(K/128) little-endian uint32 words.
+ *   Word j of a row holds the codes k = 16j..16j+15: the code of k = 16j+2i is
+ *   in bits [2i, 2i+1], the code of k = 16j+2i+1 in bits [16+2i, 17+2i]
+ *   (i = 0..7).  A 2-bit field is (bit0: weight non-zero, bit1: weight
+ *   negative): 00 = 0, 01 = +1, 11 = -1; 10 is never produced.  The transposed
+ *   copy used by the backward-data pass has one row per input channel c and
+ *   K_T = R*S*rows with k_T = (r*S + s)*rows + o.  Packed buffers must be
+ *   16-byte aligned.
+ */
+#ifndef TWN_H
+#define TWN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TWN_OK = 0,
+    TWN_ERR_NULL = -1,        /* a required pointer is NULL */
+    TWN_ERR_SHAPE = -2,       /* non-positive / inconsistent / too large sizes */
+    TWN_ERR_ALIGN = -3,       /* a pointer or leading dimension is misaligned */
+    TWN_ERR_UNSUPPORTED = -4, /* dtype / variant / option not implemented */
+    TWN_ERR_WORKSPACE = -5,   /* workspace NULL or too small */
+    TWN_ERR_HIP = -6          /* the HIP runtime refused a launch */
+} twn_status;
+
+typedef enum { TWN_F32 = 0, TWN_BF16 = 1 } twn_dtype;
+
+/* How the contraction consumes the ternary weights (Eq. 2 allows alpha to sit
+ * on the weights, on the inputs or on the outputs). */
+typedef enum {
+    TWN_VAR_BF16_POSTSCALE = 0,     /* 2-bit codes -> exact bf16 in registers, bf16 MFMA, alpha in the fp32 epilogue */
+    TWN_VAR_BF16_ALPHA_LDS = 1,     /* 2-bit codes -> bf16 {-alpha,0,+alpha} staged in LDS, bf16 MFMA (comparison) */
+    TWN_VAR_I8_STORED_POSTSCALE = 2,/* weights stored as int8 {-1,0,1} (8 bits/weight), bf16 MFMA, alpha afterwards (comparison) */
+    TWN_VAR_FP32 = 3                /* float32 activations, float32 FMA accumulation */
+} twn_variant;
+
+/* Filter bank [rows][C][R][S], float32, contiguous (fully-connected: R=S=1). */
+typedef struct {
+    int32_t rows, C, R, S;
+} twn_weight_desc;
+
+/* Y[M][N] = alpha * X[M][K] . W~[N][K]^T  (+ bias[N]) */
+typedef struct {
+    int64_t M;
+    int32_t N, K;
+    int32_t x_dtype, y_dtype;   /* twn_dtype */
+    int32_t variant;            /* twn_variant */
+    int64_t ldx, ldy;           /* row strides in elements; 0 = dense (K, N) */
+    int32_t alpha_groups;       /* 1 = one alpha for the layer; N = one per output row group (must divide N) */
+} twn_gemm_desc;
+
+/* NHWC activations [N][H][W][C], filters [O][C][R][S], output [N][P][Q][O]
+ * with P = (H + 2*pad_h - dil_h*(R-1) - 1)/stride_h + 1 (same for Q). */
+typedef struct {
+    int32_t N, H, W, C;
+    int32_t O, R, S;
+    int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int32_t x_dtype, y_dtype;   /* twn_dtype; for the backward, x_dtype covers X and dY, y_dtype covers dX */
+    int32_t variant;            /* twn_variant */
+    int32_t alpha_groups;       /* 1 or a divisor of O */
+} twn_conv_desc;
+
+/* Optional fused tail of the forward block (X_next = g(Z) of Eq. 2, with the
+ * batch-norm affine of the ternary block of Sec. 2.4 folded to scale/shift):
+ *   y = relu?( (alpha*acc) * scale[o] + shift[o] + residual )
+ * scale / shift: float32 [O] or NULL; residual: same shape and dtype as Y or
+ * NULL; relu: 0/1.  `shift` alone is a bias. */
+typedef struct {
+    const float* scale;
+    const float* shift;
+    const void* residual;
+    int32_t relu;
+} twn_epilogue;
+
+const char* twn_status_str(int32_t status);   /* host; static string */
+int32_t twn_abi_version(void);                 /* host */
+
+/* ---- packed format helpers (host, pure) --------------------------------- */
+int64_t twn_packed_words_per_row(int64_t K);           /* 8*ceil(K/128); 0 if K <= 0 */
+size_t  twn_packed_bytes(int32_t rows, int64_t K);     /* rows * words_per_row * 4 */
+
+/* ---- 1. ternarization (Sec. 2.3; Alg. 1 steps 3-7) ------------------------
+ * W: float32 [rows][C][R][S], 16-byte aligned.  The tensor is split into
+ * `groups` equal groups of consecutive filters (groups must divide rows):
+ * groups = 1 is one (Delta, alpha) per layer, groups = rows is one per filter
+ * as Alg. 1 prints it.  Per group g, with n the number of weights in it:
+ *     Delta_g = (float)((double)delta_factor * sum|W_i| / n)      (rule of thumb)
+ *     code_i  = +1 if W_i > Delta_g, -1 if W_i < -Delta_g, else 0  (Eq. 3)
+ *     nnz_g   = |{i : |W_i| > Delta_g}|
+ *     alpha_g = (float)(sum_{|W_i|>Delta_g} |W_i| / nnz_g), 0 when nnz_g = 0  (Eq. 5)
+ * Sums are accumulated in float64 in a fixed order (results are bit-identical
+ * run to run); comparisons are float32.
+ * Outputs: packed [rows][words_per_row(R*S*C)] (twn2 format above);
+ * packed_T [C][words_per_row(R*S*rows)] or NULL; delta, alpha: float32[groups];
+ * nnz: uint64[groups].  delta_factor must be in (0, 1]. */
+size_t  twn_ternarize_workspace_bytes(const twn_weight_desc* wd, int32_t groups);
+int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int32_t groups,
+                      float delta_factor,
+                      uint32_t* packed, uint32_t* packed_T,
+                      float* delta, float* alpha, uint64_t* nnz,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Expand a packed matrix [rows][words_per_row(K)] to int8 codes [rows][K]
+ * (the input of TWN_VAR_I8_STORED_POSTSCALE; also lets a caller inspect codes). */
+int32_t twn_unpack_i8(const uint32_t* packed, int32_t rows, int64_t K, int8_t* codes, void* stream);
+
+/* ---- 2a. inner product forward (Eq. 2; Alg. 1 step 8) ---------------------
+ * X: [M][ldx] of x_dtype; `weights`: packed twn2 [N][words_per_row(K)]
+ * (for TWN_VAR_I8_STORED_POSTSCALE: int8 [N][K]); alpha: float32[alpha_groups];
+ * ep may be NULL; Y: [M][ldy] of y_dtype.  bf16 variants need x_dtype = BF16,
+ * X 16-byte aligned and ldx % 8 == 0; TWN_VAR_FP32 needs x_dtype = F32. */
+size_t  twn_gemm_fwd_workspace_bytes(const twn_gemm_desc* d);
+int32_t twn_gemm_fwd(const twn_gemm_desc* d, const void* X, const void* weights,
+                     const float* alpha, const twn_epilogue* ep, void* Y,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- 2b. convolution forward (Eq. 2; Alg. 1 step 8) -----------------------
+ * Cross-correlation (no kernel flip), zero padding.  X NHWC of x_dtype,
+ * `weights` as for the GEMM with rows = O and K = R*S*C, Y NHWC of y_dtype. */
+size_t  twn_conv2d_fwd_workspace_bytes(const twn_conv_desc* d);
+int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weights,
+                       const float* alpha, const twn_epilogue* ep, void* Y,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- 2c. straight-through backward (Alg. 1 steps 9-10) --------------------
+ * Ordinary back-propagation with T = alpha W~ in place of W:
+ *   dX[n,h,w,c]   = sum_{o,r,s} alpha_o * dY[n,p,q,o] * W~[o,c,r,s]   over the (p,q) that read (h,w)
+ *   dW[o,c,r,s]   = dW_beta * dW[o,c,r,s] + sum_{n,p,q} X[n,ih,iw,c] * dY[n,p,q,o]
+ *   dbias[o]      = sum_{n,p,q} dY[n,p,q,o]
+ * dW is dL/dT, delivered unchanged as the gradient of the float32 master
+ * weights (identity straight-through estimator: no clipping, no alpha, no
+ * codes), float32 in [O][C][R][S] order.  X, dY of x_dtype (bf16), dX of
+ * y_dtype.  packed_T is the transposed copy from twn_ternarize.  Any of dX
+ * (with packed_T/alpha), dW (with X), dbias may be NULL to skip that part.
+ * dW_beta is 0 (overwrite) or 1 (accumulate).  A fully-connected layer is the
+ * case H=W=R=S=1. */
+size_t  twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d);
+int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY,
+                           const uint32_t* packed_T, const float* alpha,
+                           void* dX, float* dW, float* dbias, float dW_beta,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWN_H */

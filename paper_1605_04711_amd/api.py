@@ -1,0 +1,273 @@
+"""ctypes binding of libtwn.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/twn.h).
+PyTorch supplies device memory (`torch.empty(..., device='cuda')`), pointers
+(`.data_ptr()`) and the current HIP stream; all arithmetic runs in the library's
+kernels.  There is no fallback: a missing library raises.
+"""
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+TWN_F32, TWN_BF16 = 0, 1
+TWN_VAR_BF16_POSTSCALE, TWN_VAR_BF16_ALPHA_LDS, TWN_VAR_I8_STORED_POSTSCALE, TWN_VAR_FP32 = 0, 1, 2, 3
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtwn.so")
+_lib = None
+
+EXPORTS = [
+    "twn_status_str", "twn_abi_version", "twn_packed_words_per_row", "twn_packed_bytes",
+    "twn_ternarize_workspace_bytes", "twn_ternarize", "twn_unpack_i8",
+    "twn_gemm_fwd_workspace_bytes", "twn_gemm_fwd",
+    "twn_conv2d_fwd_workspace_bytes", "twn_conv2d_fwd",
+    "twn_conv2d_bwd_ste_workspace_bytes", "twn_conv2d_bwd_ste",
+]
+
+
+class TwnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, status_str(status), status))
+
+
+class WeightDesc(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int32), ("C", ctypes.c_int32), ("R", ctypes.c_int32), ("S", ctypes.c_int32)]
+
+
+class GemmDesc(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("x_dtype", ctypes.c_int32), ("y_dtype", ctypes.c_int32), ("variant", ctypes.c_int32),
+                ("ldx", ctypes.c_int64), ("ldy", ctypes.c_int64), ("alpha_groups", ctypes.c_int32)]
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "H", "W", "C", "O", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w",
+                 "x_dtype", "y_dtype", "variant", "alpha_groups")]
+
+
+class Epilogue(ctypes.Structure):
+    _fields_ = [("scale", ctypes.c_void_p), ("shift", ctypes.c_void_p), ("residual", ctypes.c_void_p),
+                ("relu", ctypes.c_int32)]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Load libtwn.so (built by `python -m paper_1605_04711_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_1605_04711_amd.build`" % _LIB_PATH)
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, sz, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
+        L.twn_status_str.restype = ctypes.c_char_p
+        L.twn_status_str.argtypes = [i32]
+        L.twn_abi_version.restype = i32
+        L.twn_packed_words_per_row.restype = i64
+        L.twn_packed_words_per_row.argtypes = [i64]
+        L.twn_packed_bytes.restype = sz
+        L.twn_packed_bytes.argtypes = [i32, i64]
+        L.twn_ternarize_workspace_bytes.restype = sz
+        L.twn_ternarize_workspace_bytes.argtypes = [ctypes.POINTER(WeightDesc), i32]
+        L.twn_ternarize.restype = i32
+        L.twn_ternarize.argtypes = [vp, ctypes.POINTER(WeightDesc), i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.twn_unpack_i8.restype = i32
+        L.twn_unpack_i8.argtypes = [vp, i32, i64, vp, vp]
+        L.twn_gemm_fwd_workspace_bytes.restype = sz
+        L.twn_gemm_fwd_workspace_bytes.argtypes = [ctypes.POINTER(GemmDesc)]
+        L.twn_gemm_fwd.restype = i32
+        L.twn_gemm_fwd.argtypes = [ctypes.POINTER(GemmDesc), vp, vp, vp, ctypes.POINTER(Epilogue), vp, vp, sz, vp]
+        L.twn_conv2d_fwd_workspace_bytes.restype = sz
+        L.twn_conv2d_fwd_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+        L.twn_conv2d_fwd.restype = i32
+        L.twn_conv2d_fwd.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, ctypes.POINTER(Epilogue), vp, vp, sz, vp]
+        L.twn_conv2d_bwd_ste_workspace_bytes.restype = sz
+        L.twn_conv2d_bwd_ste_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+        L.twn_conv2d_bwd_ste.restype = i32
+        L.twn_conv2d_bwd_ste.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, vp, f32, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def status_str(status):
+    return lib().twn_status_str(int(status)).decode()
+
+
+def _check(status, where):
+    if status != 0:
+        raise TwnError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return TWN_F32
+    if t.dtype == torch.bfloat16:
+        return TWN_BF16
+    raise TypeError("only float32 and bfloat16 tensors are accepted")
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def twn_packed_words_per_row(k):
+    return int(lib().twn_packed_words_per_row(int(k)))
+
+
+def twn_packed_bytes(rows, k):
+    return int(lib().twn_packed_bytes(int(rows), int(k)))
+
+
+@dataclass
+class TernaryWeights:
+    """Device-resident result of twn_ternarize for one filter bank [rows][C][R][S]."""
+    rows: int
+    C: int
+    R: int
+    S: int
+    groups: int
+    packed: torch.Tensor                 # uint32 viewed as int32 [rows][words_per_row(R*S*C)]
+    packed_T: Optional[torch.Tensor]     # [C][words_per_row(R*S*rows)] or None
+    delta: torch.Tensor                  # float32 [groups]
+    alpha: torch.Tensor                  # float32 [groups]
+    nnz: torch.Tensor                    # int64 [groups]
+
+    @property
+    def K(self):
+        return self.R * self.S * self.C
+
+
+def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, workspace=None, stream=None):
+    """W: float32 CUDA tensor [rows][C][R][S] (or [rows][K] for a fully-connected layer)."""
+    if W.dim() == 2:
+        rows, c = W.shape
+        r = s = 1
+    else:
+        rows, c, r, s = W.shape
+    if not W.is_contiguous() or W.dtype != torch.float32 or not W.is_cuda:
+        raise TypeError("W must be a contiguous float32 CUDA tensor")
+    L = lib()
+    wd = WeightDesc(rows, c, r, s)
+    dev = W.device
+    if out is None:
+        k, kt = r * s * c, r * s * rows
+        packed = torch.empty((rows, twn_packed_words_per_row(k)), dtype=torch.int32, device=dev)
+        packed_t = torch.empty((c, twn_packed_words_per_row(kt)), dtype=torch.int32, device=dev) if transposed else None
+        out = TernaryWeights(rows, c, r, s, groups, packed, packed_t,
+                             torch.empty(groups, dtype=torch.float32, device=dev),
+                             torch.empty(groups, dtype=torch.float32, device=dev),
+                             torch.empty(groups, dtype=torch.int64, device=dev))
+    if workspace is None:
+        workspace = _workspace(L.twn_ternarize_workspace_bytes(ctypes.byref(wd), groups), dev)
+    rc = L.twn_ternarize(_ptr(W), ctypes.byref(wd), groups, ctypes.c_float(delta_factor),
+                         _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha), _ptr(out.nnz),
+                         _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "twn_ternarize")
+    return out
+
+
+def twn_unpack_i8(packed, rows, k, stream=None):
+    codes = torch.empty((rows, k), dtype=torch.int8, device=packed.device)
+    _check(lib().twn_unpack_i8(_ptr(packed), rows, k, _ptr(codes), _stream(stream)), "twn_unpack_i8")
+    return codes
+
+
+def _epilogue(scale, shift, residual, relu):
+    if scale is None and shift is None and residual is None and not relu:
+        return None
+    return Epilogue(None if scale is None else scale.data_ptr(), None if shift is None else shift.data_ptr(),
+                    None if residual is None else residual.data_ptr(), 1 if relu else 0)
+
+
+def twn_gemm_fwd(X, tw, y_dtype=torch.bfloat16, variant=None, scale=None, shift=None, residual=None,
+                 relu=False, out=None, stream=None):
+    """Y[M][N] = alpha * X[M][K] . W~[N][K]^T; X bf16 (MFMA) or float32 (fp32 variant)."""
+    m, k = X.shape
+    if k != tw.K:
+        raise ValueError("K mismatch")
+    if variant is None:
+        variant = TWN_VAR_FP32 if X.dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
+    Y = out if out is not None else torch.empty((m, tw.rows), dtype=y_dtype, device=X.device)
+    d = GemmDesc(m, tw.rows, k, _dtype_code(X), _dtype_code(Y), variant, X.stride(0), Y.stride(0), tw.groups)
+    ep = _epilogue(scale, shift, residual, relu)
+    rc = lib().twn_gemm_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
+                            None if ep is None else ctypes.byref(ep), _ptr(Y), None, 0, _stream(stream))
+    _check(rc, "twn_gemm_fwd")
+    return Y
+
+
+def _conv_desc(x_shape, tw, stride, pad, dil, x_code, y_code, variant):
+    n, h, w, c = x_shape
+    if c != tw.C:
+        raise ValueError("channel mismatch")
+    return ConvDesc(n, h, w, c, tw.rows, tw.R, tw.S, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1],
+                    x_code, y_code, variant, tw.groups)
+
+
+def conv_out_shape(x_shape, tw, stride, pad, dil):
+    n, h, w, _ = x_shape
+    p = (h + 2 * pad[0] - dil[0] * (tw.R - 1) - 1) // stride[0] + 1
+    q = (w + 2 * pad[1] - dil[1] * (tw.S - 1) - 1) // stride[1] + 1
+    return (n, p, q, tw.rows)
+
+
+def twn_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), y_dtype=torch.bfloat16, variant=None,
+                   scale=None, shift=None, residual=None, relu=False, out=None, stream=None):
+    """X NHWC; returns Y NHWC [N][P][Q][O]."""
+    if variant is None:
+        variant = TWN_VAR_FP32 if X.dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
+    Y = out if out is not None else torch.empty(conv_out_shape(X.shape, tw, stride, pad, dil), dtype=y_dtype,
+                                                device=X.device)
+    d = _conv_desc(X.shape, tw, stride, pad, dil, _dtype_code(X), _dtype_code(Y), variant)
+    ep = _epilogue(scale, shift, residual, relu)
+    rc = lib().twn_conv2d_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
+                              None if ep is None else ctypes.byref(ep), _ptr(Y), None, 0, _stream(stream))
+    _check(rc, "twn_conv2d_fwd")
+    return Y
+
+
+def twn_conv2d_bwd_ste_workspace_bytes(x_shape, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1)):
+    d = _conv_desc(x_shape, tw, stride, pad, dil, TWN_BF16, TWN_BF16, TWN_VAR_BF16_POSTSCALE)
+    return int(lib().twn_conv2d_bwd_ste_workspace_bytes(ctypes.byref(d)))
+
+
+def twn_conv2d_bwd_ste(X, dY, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), need_dx=True, need_dw=True,
+                       need_dbias=False, dx_dtype=torch.bfloat16, dW=None, accumulate=False, dX=None,
+                       workspace=None, x_shape=None, stream=None):
+    """Returns (dX or None, dW float32 [O][C][R][S] or None, dbias or None)."""
+    xs = tuple(X.shape) if X is not None else tuple(x_shape)
+    dev = dY.device
+    if need_dx and dX is None:
+        dX = torch.empty(xs, dtype=dx_dtype, device=dev)
+    if need_dw and dW is None:
+        dW = torch.empty((tw.rows, tw.C, tw.R, tw.S), dtype=torch.float32, device=dev)
+    dbias = torch.empty(tw.rows, dtype=torch.float32, device=dev) if need_dbias else None
+    d = _conv_desc(xs, tw, stride, pad, dil, TWN_BF16, _dtype_code(dX) if need_dx else TWN_BF16,
+                   TWN_VAR_BF16_POSTSCALE)
+    L = lib()
+    if workspace is None:
+        workspace = _workspace(L.twn_conv2d_bwd_ste_workspace_bytes(ctypes.byref(d)), dev)
+    rc = L.twn_conv2d_bwd_ste(ctypes.byref(d), _ptr(X), _ptr(dY), _ptr(tw.packed_T), _ptr(tw.alpha),
+                              _ptr(dX) if need_dx else None, _ptr(dW) if need_dw else None, _ptr(dbias),
+                              ctypes.c_float(1.0 if accumulate else 0.0), _ptr(workspace), workspace.numel(),
+                              _stream(stream))
+    _check(rc, "twn_conv2d_bwd_ste")
+    return (dX if need_dx else None), (dW if need_dw else None), dbias

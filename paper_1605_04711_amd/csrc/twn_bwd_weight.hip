@@ -1,0 +1,318 @@
+// Weight gradient of the straight-through backward (Alg. 1 steps 9-10):
+//   dW[o][c][r][s] = sum_{n,p,q} X[n, p*sh-ph+r*dh, q*sw-pw+s*dw, c] * dY[n,p,q,o]
+// This is dL/dT; it involves neither alpha nor the codes and is handed to the
+// float32 master weights unchanged (identity straight-through estimator).
+//
+// Dense bf16 x bf16 -> fp32 MFMA GEMM  D[o][j] = sum_pix dY[pix][o] * Xg[pix][j],
+// j = (r*S+s)*C + c.  The reduction index (pixels) is the slow index of both
+// NHWC operands, so tiles are transposed on their way into LDS: a thread loads
+// the same 8 channels of two neighbouring pixels (2 x 16 bytes, coalesced
+// across lanes along the channel axis), interleaves them into eight 32-bit
+// words {pixel, pixel+1} and writes those to rows [channel][pixel].  MFMA
+// fragments are then plain ds_read_b128 along the pixel axis.  The 16-byte
+// chunk index of a row is XOR-swizzled with (row & 7) ^ ((row >> 3) & 7), which
+// keeps both the transposing writes and the fragment reads at the minimum
+// number of LDS bank passes.  The pixel range is split over blockIdx.y; partial
+// tiles go to a workspace and are summed in a fixed order (deterministic).
+#include "twn_kernels.h"
+
+namespace twn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Exact unsigned division of numerators below 2^31 by a runtime constant.
+struct FastDiv {
+    uint32_t mul, shift, d;
+};
+
+static FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f{0, 0, d};
+    if (d <= 1) return f;
+    uint32_t l = 0;
+    while ((1u << l) < d) ++l;
+    const uint32_t s = 31 + l;
+    f.mul = static_cast<uint32_t>(((1ULL << s) + d - 1) / d);
+    f.shift = s - 32;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
+    return f.mul ? (__umulhi(n, f.mul) >> f.shift) : n;
+}
+
+struct WGArgs {
+    WeightGrad w;
+    FastDiv divPQ, divQ, divC, divS;
+    int64_t pixels;
+    int32_t J;
+    int32_t slabs_per_split;
+};
+
+constexpr int kWgTile = 128;
+
+__device__ __forceinline__ int wg_swz(int row, int chunk) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void weight_grad_kernel(const WGArgs a) {
+    __shared__ __attribute__((aligned(16))) uint16_t At[2][kWgTile * 64];   // [o][pix]
+    __shared__ __attribute__((aligned(16))) uint16_t Bt[2][kWgTile * 64];   // [j][pix]
+
+    const WeightGrad& w = a.w;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lh = lane >> 5;
+
+    const int tiles_j = (a.J + kWgTile - 1) / kWgTile;
+    const int o0 = static_cast<int>(blockIdx.x / tiles_j) * kWgTile;
+    const int j0 = static_cast<int>(blockIdx.x % tiles_j) * kWgTile;
+    const int split = blockIdx.y;
+    const int64_t slab_begin = static_cast<int64_t>(split) * a.slabs_per_split;
+    const int64_t total_slabs = (a.pixels + 63) / 64;
+    int64_t slab_end = slab_begin + a.slabs_per_split;
+    if (slab_end > total_slabs) slab_end = total_slabs;
+
+    // staging tasks: chunk column cc (8 channels) and pixel pairs pp0, pp0+16
+    const int cc = tid & 15;
+    const int pp0 = tid >> 4;
+    // fixed per thread: the tap and channel of this thread's 8 columns of Xg
+    const int jj = j0 + cc * 8;
+    int tr = 0, ts = 0, tc = 0;
+    if (VEC) {
+        const uint32_t rs = fdiv(jj, a.divC);
+        tc = jj - rs * w.C;
+        tr = fdiv(rs, a.divS);
+        ts = rs - tr * w.S;
+    }
+    const int oo = o0 + cc * 8;
+
+    u32x4 ra[2][2], rb[2][2];   // [task][pixel of the pair]
+
+    auto load_x_elem = [&](int64_t pix, int j) -> uint32_t {
+        if (pix >= a.pixels || j >= a.J) return 0;
+        const uint32_t n = fdiv(static_cast<uint32_t>(pix), a.divPQ);
+        const uint32_t rem = static_cast<uint32_t>(pix) - n * a.divPQ.d;
+        const uint32_t p = fdiv(rem, a.divQ);
+        const uint32_t q = rem - p * w.Q;
+        const uint32_t rs = fdiv(j, a.divC);
+        const int c = j - rs * w.C;
+        const int r = fdiv(rs, a.divS);
+        const int s = rs - r * w.S;
+        const int ih = static_cast<int>(p) * w.sh - w.ph + r * w.dh;
+        const int iw = static_cast<int>(q) * w.sw - w.pw + s * w.dw;
+        if (static_cast<unsigned>(ih) >= static_cast<unsigned>(w.H) ||
+            static_cast<unsigned>(iw) >= static_cast<unsigned>(w.W)) return 0;
+        return w.X[((static_cast<int64_t>(n) * w.H + ih) * w.W + iw) * w.C + c];
+    };
+
+    auto load_slab = [&](int64_t slab) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int64_t pix = slab * 64 + (pp0 + 16 * t) * 2 + e;
+                if (VEC) {
+                    const bool pok = pix < a.pixels;
+                    ra[t][e] = (pok && oo < w.O)
+                                   ? *reinterpret_cast<const u32x4*>(w.dY + pix * w.O + oo)
+                                   : u32x4{0, 0, 0, 0};
+                    bool ok = pok && jj < a.J;
+                    int64_t off = 0;
+                    if (ok) {
+                        const uint32_t n = fdiv(static_cast<uint32_t>(pix), a.divPQ);
+                        const uint32_t rem = static_cast<uint32_t>(pix) - n * a.divPQ.d;
+                        const uint32_t p = fdiv(rem, a.divQ);
+                        const uint32_t q = rem - p * w.Q;
+                        const int ih = static_cast<int>(p) * w.sh - w.ph + tr * w.dh;
+                        const int iw = static_cast<int>(q) * w.sw - w.pw + ts * w.dw;
+                        ok = static_cast<unsigned>(ih) < static_cast<unsigned>(w.H) &&
+                             static_cast<unsigned>(iw) < static_cast<unsigned>(w.W);
+                        off = ((static_cast<int64_t>(n) * w.H + ih) * w.W + iw) * w.C + tc;
+                    }
+                    rb[t][e] = ok ? *reinterpret_cast<const u32x4*>(w.X + off) : u32x4{0, 0, 0, 0};
+                } else {
+                    uint32_t va[4] = {0, 0, 0, 0}, vb[4] = {0, 0, 0, 0};
+                    for (int i = 0; i < 8; ++i) {
+                        uint32_t x = 0;
+                        if (pix < a.pixels && oo + i < w.O) x = w.dY[pix * w.O + oo + i];
+                        va[i >> 1] |= x << ((i & 1) * 16);
+                        vb[i >> 1] |= load_x_elem(pix, jj + i) << ((i & 1) * 16);
+                    }
+                    ra[t][e] = u32x4{va[0], va[1], va[2], va[3]};
+                    rb[t][e] = u32x4{vb[0], vb[1], vb[2], vb[3]};
+                }
+            }
+        }
+    };
+
+    // interleave two pixels of 8 channels into 8 words {pix, pix+1} and write rows [channel][pixel]
+    auto store_t = [&](uint16_t* dst, const u32x4& p0, const u32x4& p1, int pp) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t even = (p0[i] & 0xFFFFu) | (p1[i] << 16);
+            const uint32_t odd = (p0[i] >> 16) | (p1[i] & 0xFFFF0000u);
+            const int row0 = cc * 8 + 2 * i;
+            const int chunk = pp >> 2;
+            *reinterpret_cast<uint32_t*>(&dst[row0 * 64 + wg_swz(row0, chunk) * 8 + (pp & 3) * 2]) = even;
+            *reinterpret_cast<uint32_t*>(&dst[(row0 + 1) * 64 + wg_swz(row0 + 1, chunk) * 8 + (pp & 3) * 2]) = odd;
+        }
+    };
+
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            store_t(At[buf], ra[t][0], ra[t][1], pp0 + 16 * t);
+            store_t(Bt[buf], rb[t][0], rb[t][1], pp0 + 16 * t);
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
+
+    if (slab_begin < slab_end) {
+        load_slab(slab_begin);
+        store_slab(0);
+    }
+    __syncthreads();
+    for (int64_t slab = slab_begin; slab < slab_end; ++slab) {
+        const int cur = static_cast<int>((slab - slab_begin) & 1);
+        const bool more = slab + 1 < slab_end;
+        if (more) load_slab(slab + 1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 af[2], bf[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const int row = wm * 64 + mi * 32 + lrow;
+                af[mi] = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4*>(&At[cur][row * 64 + wg_swz(row, lh * 4 + kk) * 8]));
+            }
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const int row = wn * 64 + ni * 32 + lrow;
+                bf[ni] = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4*>(&Bt[cur][row * 64 + wg_swz(row, lh * 4 + kk) * 8]));
+            }
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bf[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (more) store_slab(cur ^ 1);
+        __syncthreads();
+    }
+
+    float* out = w.partial + static_cast<int64_t>(split) * w.O * a.J;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int j = j0 + wn * 64 + ni * 32 + lrow;
+            if (j >= a.J) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int o = o0 + wm * 64 + mi * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+                if (o < w.O) out[static_cast<int64_t>(o) * a.J + j] = acc[mi][ni][e];
+            }
+        }
+}
+
+// dW[o][c][r][s] = beta*dW + sum over splits (fixed order) of partial[split][o][(r*S+s)*C + c]
+__global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __restrict__ partial, int splits,
+                                                                 int O, int C, int RS, float beta,
+                                                                 float* __restrict__ dW) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t J = static_cast<int64_t>(RS) * C;
+    const int64_t total = J * O;
+    if (id >= total) return;
+    const int64_t o = id / J;
+    const int64_t rem = id - o * J;      // = c*RS + rs in the [O][C][R][S] layout
+    const int64_t c = rem / RS;
+    const int64_t rs = rem - c * RS;
+    const int64_t src = o * J + rs * C + c;
+    float s = 0.0f;
+    for (int sp = 0; sp < splits; ++sp) s += partial[static_cast<int64_t>(sp) * total + src];
+    dW[id] = (beta != 0.0f) ? beta * dW[id] + s : s;
+}
+
+// dbias partials: block (x = 64-channel group, y = pixel split) sums its pixel range.
+constexpr int kBiasSplits = 64;
+__global__ __launch_bounds__(256) void bias_grad_partial_kernel(const uint16_t* __restrict__ dY, int64_t pixels,
+                                                                int O, float* __restrict__ partial) {
+    __shared__ float red[4][64];
+    const int ch = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int py = threadIdx.x >> 6;
+    const int64_t per = (pixels + kBiasSplits - 1) / kBiasSplits;
+    const int64_t begin = blockIdx.y * per;
+    int64_t end = begin + per;
+    if (end > pixels) end = pixels;
+    float s = 0.0f;
+    if (ch < O)
+        for (int64_t p = begin + py; p < end; p += 4) s += bf16_to_f32(dY[p * O + ch]);
+    red[py][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (py == 0 && ch < O) partial[static_cast<int64_t>(blockIdx.y) * O + ch] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+}
+
+__global__ __launch_bounds__(256) void bias_grad_final_kernel(const float* __restrict__ partial, int O,
+                                                              float* __restrict__ dbias) {
+    const int ch = blockIdx.x * blockDim.x + threadIdx.x;
+    if (ch >= O) return;
+    float s = 0.0f;
+    for (int i = 0; i < kBiasSplits; ++i) s += partial[static_cast<int64_t>(i) * O + ch];
+    dbias[ch] = s;
+}
+
+int32_t weight_grad_splits(int64_t pixels, int32_t O, int64_t J) {
+    const int64_t tiles = ((O + kWgTile - 1) / kWgTile) * ((J + kWgTile - 1) / kWgTile);
+    const int64_t slabs = (pixels + 63) / 64;
+    int64_t want = env_int("TWN_WG_BLOCKS", 1024);
+    int64_t splits = (want + tiles - 1) / tiles;
+    if (splits > slabs) splits = slabs;
+    if (splits > 1024) splits = 1024;
+    if (splits < 1) splits = 1;
+    // every split must own at least one slab
+    const int64_t per = (slabs + splits - 1) / splits;
+    splits = (slabs + per - 1) / per;
+    return static_cast<int32_t>(splits);
+}
+
+int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
+    WGArgs a;
+    a.w = w;
+    a.pixels = static_cast<int64_t>(w.N) * w.P * w.Q;
+    a.J = w.R * w.S * w.C;
+    a.divPQ = make_fastdiv(static_cast<uint32_t>(w.P) * w.Q);
+    a.divQ = make_fastdiv(w.Q);
+    a.divC = make_fastdiv(w.C);
+    a.divS = make_fastdiv(w.S);
+    if (a.pixels >= (1LL << 31)) return TWN_ERR_SHAPE;
+    const int64_t slabs = (a.pixels + 63) / 64;
+    a.slabs_per_split = static_cast<int32_t>((slabs + w.splits - 1) / w.splits);
+    if (w.dW) {
+        const int tiles = ((w.O + kWgTile - 1) / kWgTile) * ((a.J + kWgTile - 1) / kWgTile);
+        const dim3 grid(tiles, w.splits);
+        const bool vec = (w.C % 8 == 0) && (w.O % 8 == 0);
+        if (vec) weight_grad_kernel<true><<<grid, 256, 0, st>>>(a);
+        else weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
+        const int64_t total = static_cast<int64_t>(w.O) * a.J;
+        weight_grad_reduce_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(
+            w.partial, w.splits, w.O, w.C, w.R * w.S, w.beta, w.dW);
+    }
+    if (w.dbias) {
+        float* bp = w.partial + static_cast<int64_t>(w.splits) * w.O * a.J;
+        bias_grad_partial_kernel<<<dim3((w.O + 63) / 64, kBiasSplits), 256, 0, st>>>(w.dY, a.pixels, w.O, bp);
+        bias_grad_final_kernel<<<(w.O + 255) / 256, 256, 0, st>>>(bp, w.O, w.dbias);
+    }
+    return launch_status();
+}
+
+}  // namespace twn

@@ -1,0 +1,252 @@
+// C-ABI entry points of the forward block (Eq. 2; Alg. 1 step 8) and of the
+// straight-through backward (Alg. 1 steps 9-10): host-side validation and the
+// translation of descriptors into kernel launches.
+#include "twn_kernels.h"
+
+using namespace twn;
+
+namespace {
+
+int out_dim(int h, int r, int stride, int pad, int dil) {
+    const int64_t eff = static_cast<int64_t>(h) + 2LL * pad - static_cast<int64_t>(dil) * (r - 1) - 1;
+    if (eff < 0) return 0;
+    return static_cast<int>(eff / stride + 1);
+}
+
+int32_t check_conv_desc(const twn_conv_desc* d, int* P, int* Q) {
+    if (!d) return TWN_ERR_NULL;
+    if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->O <= 0 || d->R <= 0 || d->S <= 0)
+        return TWN_ERR_SHAPE;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->dil_h <= 0 || d->dil_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return TWN_ERR_SHAPE;
+    if (d->alpha_groups < 1 || d->O % d->alpha_groups != 0) return TWN_ERR_SHAPE;
+    *P = out_dim(d->H, d->R, d->stride_h, d->pad_h, d->dil_h);
+    *Q = out_dim(d->W, d->S, d->stride_w, d->pad_w, d->dil_w);
+    if (*P <= 0 || *Q <= 0) return TWN_ERR_SHAPE;
+    const int64_t K = static_cast<int64_t>(d->R) * d->S * d->C;
+    const int64_t KT = static_cast<int64_t>(d->R) * d->S * d->O;
+    if (K >= (1LL << 30) || KT >= (1LL << 30)) return TWN_ERR_SHAPE;
+    if (static_cast<int64_t>(d->N) * d->H * d->W >= (1LL << 31)) return TWN_ERR_SHAPE;
+    if (static_cast<int64_t>(d->N) * (*P) * (*Q) >= (1LL << 31)) return TWN_ERR_SHAPE;
+    if (d->H >= (1 << 24) || d->W >= (1 << 24)) return TWN_ERR_SHAPE;
+    return TWN_OK;
+}
+
+int32_t check_dtype(int32_t t) { return (t == TWN_F32 || t == TWN_BF16) ? TWN_OK : TWN_ERR_UNSUPPORTED; }
+
+int32_t check_variant(int32_t variant, int32_t x_dtype) {
+    switch (variant) {
+        case TWN_VAR_BF16_POSTSCALE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
+        case TWN_VAR_FP32: return x_dtype == TWN_F32 ? TWN_OK : TWN_ERR_UNSUPPORTED;
+        case TWN_VAR_BF16_ALPHA_LDS:
+        case TWN_VAR_I8_STORED_POSTSCALE: return TWN_ERR_UNSUPPORTED;
+        default: return TWN_ERR_UNSUPPORTED;
+    }
+}
+
+void set_epilogue(GatherGemm& g, const twn_epilogue* ep) {
+    g.scale = ep ? ep->scale : nullptr;
+    g.shift = ep ? ep->shift : nullptr;
+    g.residual = ep ? ep->residual : nullptr;
+    g.relu = ep ? (ep->relu != 0) : 0;
+}
+
+int32_t dispatch(const GatherGemm& g, int variant, hipStream_t st) {
+    if (variant == TWN_VAR_FP32) return launch_gather_gemm_fp32(g, st);
+    return launch_gather_gemm_mfma(g, variant, st);
+}
+
+}  // namespace
+
+extern "C" size_t twn_gemm_fwd_workspace_bytes(const twn_gemm_desc* d) {
+    (void)d;
+    return 0;
+}
+
+extern "C" int32_t twn_gemm_fwd(const twn_gemm_desc* d, const void* X, const void* weights,
+                                const float* alpha, const twn_epilogue* ep, void* Y,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!d || !X || !weights || !alpha || !Y) return TWN_ERR_NULL;
+    if (d->M <= 0 || d->N <= 0 || d->K <= 0 || d->M >= (1LL << 31) || d->K >= (1 << 30)) return TWN_ERR_SHAPE;
+    if (d->alpha_groups < 1 || d->N % d->alpha_groups != 0) return TWN_ERR_SHAPE;
+    int32_t rc = check_dtype(d->x_dtype);
+    if (rc == TWN_OK) rc = check_dtype(d->y_dtype);
+    if (rc == TWN_OK) rc = check_variant(d->variant, d->x_dtype);
+    if (rc != TWN_OK) return rc;
+    const int64_t ldx = d->ldx ? d->ldx : d->K;
+    const int64_t ldy = d->ldy ? d->ldy : d->N;
+    if (ldx < d->K || ldy < d->N) return TWN_ERR_SHAPE;
+    if (!aligned(weights, 16)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_BF16 && !aligned(X, 2)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_BF16 && d->K % 8 == 0 && ldx % 8 == 0 && !aligned(X, 16)) return TWN_ERR_ALIGN;
+
+    GatherGemm g{};
+    g.X = X;
+    g.Wq = weights;
+    g.alpha = alpha;
+    set_epilogue(g, ep);
+    g.Y = Y;
+    g.M = d->M;
+    g.xs = ldx;
+    g.ldy = ldy;
+    g.IH = g.IW = g.OH = g.OW = 1;
+    g.IC = d->K;
+    g.NC = d->N;
+    g.R = g.S = 1;
+    g.sh = g.sw = g.dh = g.dw = g.divh = g.divw = 1;
+    g.ph = g.pw = 0;
+    g.K = d->K;
+    g.wpr = static_cast<int32_t>(twn_packed_words_per_row(d->K));
+    g.rows_per_group = d->N / d->alpha_groups;
+    g.y_f32 = (d->y_dtype == TWN_F32);
+    g.plain_gemm = 1;
+    return dispatch(g, d->variant, as_stream(stream));
+}
+
+extern "C" size_t twn_conv2d_fwd_workspace_bytes(const twn_conv_desc* d) {
+    (void)d;
+    return 0;
+}
+
+extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weights,
+                                  const float* alpha, const twn_epilogue* ep, void* Y,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    int P, Q;
+    int32_t rc = check_conv_desc(d, &P, &Q);
+    if (rc != TWN_OK) return rc;
+    if (!X || !weights || !alpha || !Y) return TWN_ERR_NULL;
+    rc = check_dtype(d->x_dtype);
+    if (rc == TWN_OK) rc = check_dtype(d->y_dtype);
+    if (rc == TWN_OK) rc = check_variant(d->variant, d->x_dtype);
+    if (rc != TWN_OK) return rc;
+    if (!aligned(weights, 16)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_BF16 && !aligned(X, (d->C % 8 == 0) ? 16 : 2)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
+
+    GatherGemm g{};
+    g.X = X;
+    g.Wq = weights;
+    g.alpha = alpha;
+    set_epilogue(g, ep);
+    g.Y = Y;
+    g.M = static_cast<int64_t>(d->N) * P * Q;
+    g.xs = d->C;
+    g.ldy = d->O;
+    g.IH = d->H;
+    g.IW = d->W;
+    g.IC = d->C;
+    g.OH = P;
+    g.OW = Q;
+    g.NC = d->O;
+    g.R = d->R;
+    g.S = d->S;
+    g.sh = d->stride_h;
+    g.sw = d->stride_w;
+    g.ph = d->pad_h;
+    g.pw = d->pad_w;
+    g.dh = d->dil_h;
+    g.dw = d->dil_w;
+    g.divh = g.divw = 1;
+    g.K = d->R * d->S * d->C;
+    g.wpr = static_cast<int32_t>(twn_packed_words_per_row(g.K));
+    g.rows_per_group = d->O / d->alpha_groups;
+    g.y_f32 = (d->y_dtype == TWN_F32);
+    g.plain_gemm = (d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 &&
+                    d->pad_w == 0);
+    return dispatch(g, d->variant, as_stream(stream));
+}
+
+extern "C" size_t twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d) {
+    int P, Q;
+    if (check_conv_desc(d, &P, &Q) != TWN_OK) return 0;
+    const int64_t pixels = static_cast<int64_t>(d->N) * P * Q;
+    const int64_t J = static_cast<int64_t>(d->R) * d->S * d->C;
+    const int64_t splits = weight_grad_splits(pixels, d->O, J);
+    return static_cast<size_t>((splits * d->O * J + 64LL * d->O) * sizeof(float));
+}
+
+extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY,
+                                      const uint32_t* packed_T, const float* alpha,
+                                      void* dX, float* dW, float* dbias, float dW_beta,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    int P, Q;
+    int32_t rc = check_conv_desc(d, &P, &Q);
+    if (rc != TWN_OK) return rc;
+    if (!dY) return TWN_ERR_NULL;
+    if (dX && (!packed_T || !alpha)) return TWN_ERR_NULL;
+    if (dW && !X) return TWN_ERR_NULL;
+    if (d->x_dtype != TWN_BF16 || d->variant != TWN_VAR_BF16_POSTSCALE) return TWN_ERR_UNSUPPORTED;
+    rc = check_dtype(d->y_dtype);
+    if (rc != TWN_OK) return rc;
+    if (dW_beta != 0.0f && dW_beta != 1.0f) return TWN_ERR_UNSUPPORTED;
+    if (!aligned(dY, (d->O % 8 == 0) ? 16 : 2)) return TWN_ERR_ALIGN;
+    if (X && !aligned(X, (d->C % 8 == 0) ? 16 : 2)) return TWN_ERR_ALIGN;
+    if (packed_T && !aligned(packed_T, 16)) return TWN_ERR_ALIGN;
+    if (dW && !aligned(dW, 4)) return TWN_ERR_ALIGN;
+    if (dW || dbias) {
+        const size_t need = twn_conv2d_bwd_ste_workspace_bytes(d);
+        if (!workspace || workspace_bytes < need || !aligned(workspace, 16)) return TWN_ERR_WORKSPACE;
+    }
+    hipStream_t st = as_stream(stream);
+
+    if (dX) {
+        // dX = gather over dY: row (n,h,w), k = (r,s,o):
+        //   p = (h + ph - r*dh)/sh when divisible, q likewise; weights = transposed packed copy.
+        GatherGemm g{};
+        g.X = dY;
+        g.Wq = packed_T;
+        g.alpha = alpha;
+        g.Y = dX;
+        g.M = static_cast<int64_t>(d->N) * d->H * d->W;
+        g.xs = d->O;
+        g.ldy = d->C;
+        g.IH = P;
+        g.IW = Q;
+        g.IC = d->O;
+        g.OH = d->H;
+        g.OW = d->W;
+        g.NC = d->C;
+        g.R = d->R;
+        g.S = d->S;
+        g.sh = g.sw = 1;
+        g.ph = -d->pad_h;
+        g.pw = -d->pad_w;
+        g.dh = -d->dil_h;
+        g.dw = -d->dil_w;
+        g.divh = d->stride_h;
+        g.divw = d->stride_w;
+        g.K = d->R * d->S * d->O;
+        g.wpr = static_cast<int32_t>(twn_packed_words_per_row(g.K));
+        // alpha multiplies per forward output channel o, which is a K index here: only a
+        // single alpha can be applied after the sum.
+        if (d->alpha_groups != 1) return TWN_ERR_UNSUPPORTED;
+        g.rows_per_group = d->C;
+        g.y_f32 = (d->y_dtype == TWN_F32);
+        g.plain_gemm = (d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 &&
+                        d->pad_w == 0);
+        rc = launch_gather_gemm_mfma(g, TWN_VAR_BF16_POSTSCALE, st);
+        if (rc != TWN_OK) return rc;
+    }
+    if (dW || dbias) {
+        WeightGrad w{};
+        w.X = static_cast<const uint16_t*>(X);
+        w.dY = static_cast<const uint16_t*>(dY);
+        w.dW = dW;
+        w.dbias = dbias;
+        w.partial = static_cast<float*>(workspace);
+        w.beta = dW_beta;
+        w.N = d->N; w.H = d->H; w.W = d->W; w.C = d->C; w.O = d->O; w.R = d->R; w.S = d->S;
+        w.P = P; w.Q = Q;
+        w.sh = d->stride_h; w.sw = d->stride_w; w.ph = d->pad_h; w.pw = d->pad_w;
+        w.dh = d->dil_h; w.dw = d->dil_w;
+        w.splits = weight_grad_splits(static_cast<int64_t>(d->N) * P * Q, d->O,
+                                      static_cast<int64_t>(d->R) * d->S * d->C);
+        rc = launch_weight_grad(w, st);
+    }
+    return rc;
+}

@@ -1,0 +1,291 @@
+// Implicit-GEMM ternary convolution / inner product on gfx950 bf16 MFMA
+// (Eq. 2, Alg. 1 step 8; the same kernel serves the backward-data pass of
+// Alg. 1 step 9 through a re-expressed gather).
+//
+// Design, per workgroup tile BM (pixels) x BN (output channels), K slabs of 64:
+//   * activations: 16-byte global loads (8 bf16 of one tap) -> LDS, rows of
+//     128 bytes with the 16-byte chunk index XOR-swizzled by (row & 7), read
+//     back with ds_read_b128 as the A operand of v_mfma_f32_32x32x16_bf16;
+//   * weights never touch LDS: each lane loads the 32 packed codes (8 bytes)
+//     of its own output channel and its own half of the K slab straight from
+//     global memory (the packed bank is small and L2-resident) and expands
+//     them in registers.  The twn2 format keeps even-k codes in the low
+//     half-word and odd-k codes in the high half-word of each 32-bit word, and
+//     a 2-bit field (non-zero, negative) shifted to bits [14,15] of a bf16 is
+//     exactly {0, +2.0, -2.0}; so one shift and one AND produce two B-operand
+//     elements.  The factor 2 is folded into alpha in the fp32 epilogue.
+//   * MFMA k-slot mapping: in MFMA step kk (0..3) of a slab, lane-half h
+//     (lane/32) carries k = 32h + 8kk .. +7 for both operands.
+#include "twn_kernels.h"
+
+namespace twn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+enum { kModeGemm = 0, kModeVec8 = 1, kModeScalar = 2 };
+
+template <int BM, int BN, int WM, int WN, int MODE>
+__global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const GatherGemm g) {
+    constexpr int T = 64 * WM * WN;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int NLOAD = BM * 8 / T;
+    constexpr int ROWSTEP = T / 8;
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "tile/wave mismatch");
+    static_assert((BM * 8) % T == 0, "A tile must split evenly over threads");
+
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][BM * 64];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = lane & 31, lh = lane >> 5;
+
+    const int tiles_n = (g.NC + BN - 1) / BN;
+    const int64_t tile_m = blockIdx.x / tiles_n;
+    const int tile_n = static_cast<int>(blockIdx.x % tiles_n);
+    const int64_t m0 = tile_m * BM;
+    const int n0 = tile_n * BN;
+
+    const uint16_t* __restrict__ X = static_cast<const uint16_t*>(g.X);
+    const uint32_t* __restrict__ Wq = static_cast<const uint32_t*>(g.Wq);
+
+    // ---- per-thread A-load slots: NLOAD rows, one 16-byte chunk (8 k) each ----
+    const int kc = tid & 7;
+    int64_t pixbase[NLOAD];
+    int ih0[NLOAD], iw0[NLOAD];
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int row = (tid >> 3) + i * ROWSTEP;
+        const int64_t m = m0 + row;
+        if (m < g.M) {
+            if (MODE == kModeGemm) {
+                pixbase[i] = m;
+                ih0[i] = 0;
+                iw0[i] = 0;
+            } else {
+                const int ow = static_cast<int>(m % g.OW);
+                const int64_t t = m / g.OW;
+                const int oh = static_cast<int>(t % g.OH);
+                const int64_t n = t / g.OH;
+                pixbase[i] = n * g.IH * g.IW;
+                ih0[i] = oh * g.sh - g.ph;
+                iw0[i] = ow * g.sw - g.pw;
+            }
+        } else {
+            pixbase[i] = 0;
+            ih0[i] = -(1 << 28);   // fails every bounds test below
+            iw0[i] = -(1 << 28);
+        }
+    }
+
+    u32x4 areg[NLOAD];
+    u32x2 breg[NI], breg_next[NI];
+
+    auto tap_coord = [&](int base, int tap, int step, int div, int limit, int& out) -> bool {
+        int t = base + tap * step;
+        if (div > 1) {
+            if (t < 0 || (t % div) != 0) return false;
+            t /= div;
+        }
+        out = t;
+        return static_cast<unsigned>(t) < static_cast<unsigned>(limit);
+    };
+
+    auto load_a = [&](int kt) {
+        const int k = kt * 64 + kc * 8;
+        if (MODE == kModeGemm) {
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                const bool ok = (ih0[i] == 0) && (k < g.K);
+                areg[i] = ok ? *reinterpret_cast<const u32x4*>(X + pixbase[i] * g.xs + k) : u32x4{0, 0, 0, 0};
+            }
+        } else if (MODE == kModeVec8) {
+            const int rs = k / g.IC;
+            const int c = k - rs * g.IC;
+            const int r = rs / g.S;
+            const int s = rs - r * g.S;
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                int th, tw;
+                bool ok = tap_coord(ih0[i], r, g.dh, g.divh, g.IH, th);
+                ok = tap_coord(iw0[i], s, g.dw, g.divw, g.IW, tw) && ok;
+                ok = ok && (k < g.K);
+                areg[i] = ok ? *reinterpret_cast<const u32x4*>(
+                                   X + (pixbase[i] + static_cast<int64_t>(th) * g.IW + tw) * g.xs + c)
+                             : u32x4{0, 0, 0, 0};
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                uint32_t w4[4] = {0, 0, 0, 0};
+                for (int e = 0; e < 8; ++e) {
+                    const int ke = k + e;
+                    uint32_t v = 0;
+                    if (ke < g.K) {
+                        const int rs = ke / g.IC;
+                        const int c = ke - rs * g.IC;
+                        const int r = rs / g.S;
+                        const int s = rs - r * g.S;
+                        int th, tw;
+                        bool ok = tap_coord(ih0[i], r, g.dh, g.divh, g.IH, th);
+                        ok = tap_coord(iw0[i], s, g.dw, g.divw, g.IW, tw) && ok;
+                        if (ok) v = X[(pixbase[i] + static_cast<int64_t>(th) * g.IW + tw) * g.xs + c];
+                    }
+                    w4[e >> 1] |= v << ((e & 1) * 16);
+                }
+                areg[i] = u32x4{w4[0], w4[1], w4[2], w4[3]};
+            }
+        }
+    };
+
+    auto store_a = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const int row = (tid >> 3) + i * ROWSTEP;
+            const int chunk = kc ^ (row & 7);
+            *reinterpret_cast<u32x4*>(&lds[buf][row * 64 + chunk * 8]) = areg[i];
+        }
+    };
+
+    auto load_b = [&](int kt, u32x2* dst) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int ncol = n0 + wn * TN + ni * 32 + lrow;
+            dst[ni] = (ncol < g.NC)
+                          ? *reinterpret_cast<const u32x2*>(Wq + static_cast<int64_t>(ncol) * g.wpr + kt * 4 + 2 * lh)
+                          : u32x2{0, 0};
+        }
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
+
+    const int KT = (g.K + 63) / 64;
+    load_a(0);
+    load_b(0, breg_next);
+    store_a(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) breg[ni] = breg_next[ni];
+        const bool more = (kt + 1 < KT);
+        if (more) {
+            load_a(kt + 1);
+            load_b(kt + 1, breg_next);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 bfrag[NI];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const uint32_t word = breg[ni][kk >> 1];
+                u32x4 b;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = (kk & 1) * 4 + r;
+                    b[r] = (word << (14 - 2 * i)) & 0xC000C000u;
+                }
+                bfrag[ni] = __builtin_bit_cast(bf16x8, b);
+            }
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int row = wm * TM + mi * 32 + lrow;
+                const int chunk = (lh * 4 + kk) ^ (row & 7);
+                const u32x4 a = *reinterpret_cast<const u32x4*>(&lds[cur][row * 64 + chunk * 8]);
+                const bf16x8 afrag = __builtin_bit_cast(bf16x8, a);
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[ni], acc[mi][ni], 0, 0, 0);
+            }
+        }
+        if (more) store_a(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: y = relu?((alpha*acc)*scale + shift + residual) ----
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int ncol = n0 + wn * TN + ni * 32 + lrow;
+        if (ncol >= g.NC) continue;
+        const float al = 0.5f * g.alpha[ncol / g.rows_per_group];   // codes were expanded to +-2
+        const float sc = g.scale ? g.scale[ncol] : 1.0f;
+        const float sf = g.shift ? g.shift[ncol] : 0.0f;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int64_t m = m0 + wm * TM + mi * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+                if (m >= g.M) continue;
+                float v = (acc[mi][ni][e] * al) * sc + sf;
+                const int64_t off = m * g.ldy + ncol;
+                if (g.y_f32) {
+                    if (g.residual) v += static_cast<const float*>(g.residual)[off];
+                    if (g.relu) v = fmaxf(v, 0.0f);
+                    static_cast<float*>(g.Y)[off] = v;
+                } else {
+                    if (g.residual) v += bf16_to_f32(static_cast<const uint16_t*>(g.residual)[off]);
+                    if (g.relu) v = fmaxf(v, 0.0f);
+                    static_cast<uint16_t*>(g.Y)[off] = f32_to_bf16(v);
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+static int32_t launch_tile(const GatherGemm& g, int mode, hipStream_t st) {
+    const int64_t tiles_m = (g.M + BM - 1) / BM;
+    const int64_t tiles_n = (g.NC + BN - 1) / BN;
+    const int64_t blocks = tiles_m * tiles_n;
+    if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
+    const dim3 grid(static_cast<unsigned>(blocks));
+    const dim3 block(64 * WM * WN);
+    switch (mode) {
+        case kModeGemm: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeGemm><<<grid, block, 0, st>>>(g); break;
+        case kModeVec8: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeVec8><<<grid, block, 0, st>>>(g); break;
+        default: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeScalar><<<grid, block, 0, st>>>(g); break;
+    }
+    return launch_status();
+}
+
+int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st) {
+    if (variant != TWN_VAR_BF16_POSTSCALE) return TWN_ERR_UNSUPPORTED;
+    int mode;
+    if (g.IC % 8 != 0 || g.xs % 8 != 0) mode = kModeScalar;
+    else mode = g.plain_gemm ? kModeGemm : kModeVec8;
+
+    // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.
+    int tile = env_int("TWN_TILE", 0);
+    if (tile == 0) {
+        auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
+        const int64_t want = 256;
+        if (g.NC <= 64) tile = (blocks(256, 64) >= want) ? 3 : 5;
+        else if (g.NC <= 128) tile = (blocks(256, 128) >= want) ? 2 : 4;
+        else if (blocks(256, 256) >= want) tile = 1;
+        else if (blocks(256, 128) >= want) tile = 2;
+        else tile = 4;
+    }
+    switch (tile) {
+        case 1: return launch_tile<256, 256, 2, 2>(g, mode, st);
+        case 2: return launch_tile<256, 128, 2, 2>(g, mode, st);
+        case 3: return launch_tile<256, 64, 4, 1>(g, mode, st);
+        case 4: return launch_tile<128, 128, 2, 2>(g, mode, st);
+        case 5: return launch_tile<128, 64, 4, 1>(g, mode, st);
+        case 6: return launch_tile<256, 256, 2, 4>(g, mode, st);
+        default: return TWN_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace twn

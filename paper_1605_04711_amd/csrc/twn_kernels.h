@@ -1,0 +1,59 @@
+// Internal launch interface between the C-ABI entry points and the kernels.
+#pragma once
+
+#include "twn_common.h"
+
+namespace twn {
+
+// One implicit-GEMM problem:  Y[m][n] = epilogue( sum_k A[m][k] * code[n][k] ).
+// Rows m enumerate (batch, oh, ow) of the *output* of the gather; k enumerates
+// (r, s, c) with c fastest.  A[m][k] is read from the NHWC tensor `X` at
+//   th = oh*sh - ph + r*dh,  tw = ow*sw - pw + s*dw
+// (after an exact division by divh/divw when those are > 1), zero outside
+// [0,IH) x [0,IW).  The forward convolution uses this directly; the
+// backward-data pass is the same gather over dY with sh = sw = 1, negated
+// padding and tap step, and div = the forward stride.
+struct GatherGemm {
+    const void* X;          // bf16 (MFMA path) or float32 (fp32 path), NHWC, pixel stride `xs` elements
+    const void* Wq;         // packed twn2 codes [NC][wpr]  (or int8 [NC][K] for the int8-stored variant)
+    const float* alpha;     // [NC / rows_per_group]
+    const float* scale;     // [NC] or null
+    const float* shift;     // [NC] or null
+    const void* residual;   // like Y or null
+    void* Y;                // [M][ldy]
+    int64_t M;
+    int64_t xs;             // elements between consecutive pixels of X
+    int64_t ldy;
+    int32_t IH, IW, IC;
+    int32_t OH, OW;
+    int32_t NC;             // GEMM N (output channels)
+    int32_t R, S;
+    int32_t sh, sw, ph, pw, dh, dw, divh, divw;
+    int32_t K;              // R*S*IC
+    int32_t wpr;            // packed words per row
+    int32_t rows_per_group;
+    int32_t relu;
+    int32_t y_f32;          // 1: Y (and residual) float32, 0: bf16
+    int32_t plain_gemm;     // 1: R=S=1, stride 1, no padding, OH*OW pixels == rows of X
+};
+
+int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st);
+int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
+
+// dW[o][c][r][s] = beta*dW + sum_{n,p,q} X[n,ih,iw,c] * dY[n,p,q,o]; dbias[o] = sum dY.
+struct WeightGrad {
+    const uint16_t* X;      // bf16 NHWC [N][H][W][C]
+    const uint16_t* dY;     // bf16 NHWC [N][P][Q][O]
+    float* dW;              // [O][C][R][S]
+    float* dbias;           // [O] or null
+    float* partial;         // workspace: [splits][O][R*S*C] float32
+    float beta;
+    int32_t N, H, W, C, O, R, S, P, Q;
+    int32_t sh, sw, ph, pw, dh, dw;
+    int32_t splits;
+};
+
+int32_t weight_grad_splits(int64_t pixels, int32_t O, int64_t J);
+int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st);
+
+}  // namespace twn

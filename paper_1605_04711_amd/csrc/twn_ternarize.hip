@@ -1,0 +1,345 @@
+// Threshold ternarization on gfx950 (Sec. 2.3: rule of thumb for Delta, Eq. 3
+// codes, Eq. 5 alpha; Alg. 1 steps 3-7).  HBM-streaming kernels:
+//
+//   abs_sum          pass 1: per-block float64 partial sums of |W|
+//   mask_pack_flat   pass 2: Delta from the partials, then one more stream of W:
+//                    masked float64 sum, count, and the 2-bit codes written in
+//                    the same pass (flat layouts: R*S == 1 and K % 128 == 0)
+//   mask_stats       pass 2 without the pack (any layout)
+//   pack_gather      codes for any [rows][C][R][S] layout, normal or transposed
+//   group_stats      one block per group when there are several groups (per filter)
+//   finalize         fixed-order sum of the pass-2 partials -> Delta, alpha, nnz
+//
+// All cross-thread sums run in a fixed order, so results are bit-identical
+// from run to run; no floating-point atomics are used.
+#include "twn_common.h"
+
+namespace twn {
+
+constexpr int kTernThreads = 256;
+constexpr int kChunk = kTernThreads * 16;   // weights per block iteration
+constexpr int kMaxBlocks = 4096;
+
+struct TernWorkspace {
+    double p1[kMaxBlocks];     // pass-1 partial sums of |W|
+    double p2[kMaxBlocks];     // pass-2 partial masked sums
+    uint64_t cnt[kMaxBlocks];  // pass-2 partial counts
+};
+
+__global__ __launch_bounds__(kTernThreads) void abs_sum_kernel(const float* __restrict__ W, int64_t n,
+                                                               double* __restrict__ partial) {
+    __shared__ double scratch[16];
+    const int tid = threadIdx.x;
+    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    double acc = 0.0;
+    for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const int64_t base = c * kChunk;
+        if (base + kChunk <= n) {
+            const float4* src = reinterpret_cast<const float4*>(W + base);
+            float4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = src[j * kTernThreads + tid];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc += static_cast<double>(fabsf(v[j].x));
+                acc += static_cast<double>(fabsf(v[j].y));
+                acc += static_cast<double>(fabsf(v[j].z));
+                acc += static_cast<double>(fabsf(v[j].w));
+            }
+        } else {
+            for (int j = 0; j < 4; ++j)
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t idx = base + (int64_t)(j * kTernThreads + tid) * 4 + e;
+                    if (idx < n) acc += static_cast<double>(fabsf(W[idx]));
+                }
+        }
+    }
+    const double total = block_sum(acc, scratch);
+    if (tid == 0) partial[blockIdx.x] = total;
+}
+
+// Delta = (float)((double)f * S1 / n), S1 = fixed-order sum of the pass-1 partials.
+__device__ __forceinline__ float delta_from_partials(const double* __restrict__ p1, int nb1, float f,
+                                                     int64_t n, double* scratch) {
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < nb1; i += blockDim.x) acc += p1[i];
+    const double s1 = block_sum(acc, scratch);
+    return static_cast<float>((static_cast<double>(f) * s1) / static_cast<double>(n));
+}
+
+__device__ __forceinline__ uint32_t quad_or(uint32_t v) {
+    // OR across the 4 lanes of a quad (DPP quad_perm [1,0,3,2] then [2,3,0,1]).
+    v |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0xB1, 0xF, 0xF, false));
+    v |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x4E, 0xF, 0xF, false));
+    return v;
+}
+
+// Pass 2 for flat layouts: the packed word index is (flat weight index)/16.
+// A wave covers 1024 consecutive weights per step with four fully coalesced
+// float4 loads; the four lanes of a quad hold the 16 weights of one output
+// word, which is assembled with two DPP ORs and written by the lane whose
+// position in the quad equals the load index, so each wave stores 256
+// contiguous bytes.
+__global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
+    const float* __restrict__ W, int64_t n, const double* __restrict__ p1, int nb1, float f,
+    uint32_t* __restrict__ packed, double* __restrict__ p2, uint64_t* __restrict__ cnt, int reverse) {
+    __shared__ double scratch[16];
+    __shared__ unsigned long long scratch_u[16];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int ql = lane & 3;
+    const float delta = delta_from_partials(p1, nb1, f, n, scratch);
+
+    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    const int64_t n4 = n >> 2;       // n % 16 == 0 here
+    const int64_t nwords = n >> 4;
+    double acc = 0.0;
+    uint32_t count = 0;
+    for (int64_t it = blockIdx.x; it < nchunks; it += gridDim.x) {
+        const int64_t c = reverse ? (nchunks - 1 - it) : it;
+        const int64_t wbase = c * kChunk + wave * 1024;   // first weight of this wave's span
+        const float4* src = reinterpret_cast<const float4*>(W + wbase);
+        const int64_t f4base = wbase >> 2;
+        float4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t i4 = f4base + j * 64 + lane;
+            v[j] = (i4 < n4) ? src[j * 64 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        uint32_t mine = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t f0 = code_field(v[j].x, delta), f1 = code_field(v[j].y, delta);
+            const uint32_t f2 = code_field(v[j].z, delta), f3 = code_field(v[j].w, delta);
+            if (f0) acc += static_cast<double>(fabsf(v[j].x));
+            if (f1) acc += static_cast<double>(fabsf(v[j].y));
+            if (f2) acc += static_cast<double>(fabsf(v[j].z));
+            if (f3) acc += static_cast<double>(fabsf(v[j].w));
+            count += (f0 & 1u) + (f1 & 1u) + (f2 & 1u) + (f3 & 1u);
+            uint32_t word = ((f0 | (f2 << 2)) << (4 * ql)) | ((f1 | (f3 << 2)) << (16 + 4 * ql));
+            word = quad_or(word);
+            if (ql == j) mine = word;
+        }
+        const int64_t widx = (wbase >> 4) + (lane >> 2) + 16 * ql;
+        if (widx < nwords) packed[widx] = mine;
+    }
+    const double total = block_sum(acc, scratch);
+    const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
+    if (tid == 0) {
+        p2[blockIdx.x] = total;
+        cnt[blockIdx.x] = ctotal;
+    }
+}
+
+__global__ __launch_bounds__(kTernThreads) void mask_stats_kernel(
+    const float* __restrict__ W, int64_t n, const double* __restrict__ p1, int nb1, float f,
+    double* __restrict__ p2, uint64_t* __restrict__ cnt) {
+    __shared__ double scratch[16];
+    __shared__ unsigned long long scratch_u[16];
+    const int tid = threadIdx.x;
+    const float delta = delta_from_partials(p1, nb1, f, n, scratch);
+    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    double acc = 0.0;
+    uint32_t count = 0;
+    for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const int64_t base = c * kChunk;
+        for (int j = 0; j < 16; ++j) {
+            const int64_t idx = base + j * kTernThreads + tid;
+            if (idx < n) {
+                const float a = fabsf(W[idx]);
+                if (a > delta) {
+                    acc += static_cast<double>(a);
+                    ++count;
+                }
+            }
+        }
+    }
+    const double total = block_sum(acc, scratch);
+    const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
+    if (tid == 0) {
+        p2[blockIdx.x] = total;
+        cnt[blockIdx.x] = ctotal;
+    }
+}
+
+__global__ __launch_bounds__(kTernThreads) void finalize_kernel(
+    const double* __restrict__ p1, int nb1, const double* __restrict__ p2,
+    const uint64_t* __restrict__ cnt, int nb2, float f, int64_t n,
+    float* __restrict__ delta, float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
+    __shared__ double scratch[16];
+    __shared__ unsigned long long scratch_u[16];
+    const float d = delta_from_partials(p1, nb1, f, n, scratch);
+    double acc = 0.0;
+    unsigned long long c = 0;
+    for (int i = threadIdx.x; i < nb2; i += blockDim.x) {
+        acc += p2[i];
+        c += cnt[i];
+    }
+    const double s = block_sum(acc, scratch);
+    const unsigned long long total = block_sum(c, scratch_u);
+    if (threadIdx.x == 0) {
+        delta[0] = d;
+        nnz[0] = total;
+        alpha[0] = total ? static_cast<float>(s / static_cast<double>(total)) : 0.0f;
+    }
+}
+
+// One block per group: both passes over the group's contiguous weights.
+__global__ __launch_bounds__(kTernThreads) void group_stats_kernel(
+    const float* __restrict__ W, int64_t n_per_group, float f,
+    float* __restrict__ delta, float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
+    __shared__ double scratch[16];
+    __shared__ unsigned long long scratch_u[16];
+    const float* seg = W + static_cast<int64_t>(blockIdx.x) * n_per_group;
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < n_per_group; i += blockDim.x) acc += static_cast<double>(fabsf(seg[i]));
+    const double s1 = block_sum(acc, scratch);
+    const float d = static_cast<float>((static_cast<double>(f) * s1) / static_cast<double>(n_per_group));
+    acc = 0.0;
+    uint32_t count = 0;
+    for (int64_t i = threadIdx.x; i < n_per_group; i += blockDim.x) {
+        const float a = fabsf(seg[i]);
+        if (a > d) {
+            acc += static_cast<double>(a);
+            ++count;
+        }
+    }
+    const double s = block_sum(acc, scratch);
+    const unsigned long long total = block_sum(static_cast<unsigned long long>(count), scratch_u);
+    if (threadIdx.x == 0) {
+        delta[blockIdx.x] = d;
+        nnz[blockIdx.x] = total;
+        alpha[blockIdx.x] = total ? static_cast<float>(s / static_cast<double>(total)) : 0.0f;
+    }
+}
+
+// Codes for any layout.  One thread per output word.
+//   normal:     out row = filter o,        k   = (r*S+s)*C + c
+//   transposed: out row = input channel c, k_T = (r*S+s)*rows + o
+// Threads are ordered so that neighbouring threads read neighbouring source
+// weights where the layout allows it.
+__global__ __launch_bounds__(256) void pack_gather_kernel(
+    const float* __restrict__ W, int rows, int C, int RS, const float* __restrict__ delta,
+    int rows_per_group, uint32_t* __restrict__ out, int wpr, int transposed) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    int64_t out_rows = transposed ? C : rows;
+    if (id >= out_rows * wpr) return;
+    int row, j;
+    if (transposed) {
+        row = static_cast<int>(id % C);   // input channel, fastest across threads
+        j = static_cast<int>(id / C);
+    } else {
+        row = static_cast<int>(id / wpr);
+        j = static_cast<int>(id % wpr);
+    }
+    const int64_t K = transposed ? static_cast<int64_t>(RS) * rows : static_cast<int64_t>(RS) * C;
+    uint32_t word = 0;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int64_t k = static_cast<int64_t>(j) * 16 + t;
+        if (k < K) {
+            int o, c, rs;
+            if (transposed) {
+                rs = static_cast<int>(k / rows);
+                o = static_cast<int>(k - static_cast<int64_t>(rs) * rows);
+                c = row;
+            } else {
+                rs = static_cast<int>(k / C);
+                c = static_cast<int>(k - static_cast<int64_t>(rs) * C);
+                o = row;
+            }
+            const float w = W[(static_cast<int64_t>(o) * C + c) * RS + rs];
+            const uint32_t fld = code_field(w, delta[o / rows_per_group]);
+            word |= fld << ((t & 1) * 16 + (t >> 1) * 2);
+        }
+    }
+    out[static_cast<int64_t>(row) * wpr + j] = word;
+}
+
+__global__ __launch_bounds__(256) void unpack_i8_kernel(const uint32_t* __restrict__ packed, int rows,
+                                                        int64_t K, int wpr, int8_t* __restrict__ codes) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (id >= static_cast<int64_t>(rows) * K) return;
+    const int64_t row = id / K, k = id % K;
+    const uint32_t word = packed[row * wpr + (k >> 4)];
+    const int t = static_cast<int>(k & 15);
+    const uint32_t fld = (word >> ((t & 1) * 16 + (t >> 1) * 2)) & 3u;
+    codes[id] = (fld & 1u) ? ((fld & 2u) ? -1 : 1) : 0;
+}
+
+}  // namespace twn
+
+using namespace twn;
+
+extern "C" size_t twn_ternarize_workspace_bytes(const twn_weight_desc* wd, int32_t groups) {
+    if (!wd || groups < 1) return 0;
+    return sizeof(TernWorkspace);
+}
+
+extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int32_t groups,
+                                 float delta_factor, uint32_t* packed, uint32_t* packed_T,
+                                 float* delta, float* alpha, uint64_t* nnz,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (!W || !wd || !packed || !delta || !alpha || !nnz) return TWN_ERR_NULL;
+    if (wd->rows <= 0 || wd->C <= 0 || wd->R <= 0 || wd->S <= 0) return TWN_ERR_SHAPE;
+    if (groups < 1 || wd->rows % groups != 0) return TWN_ERR_SHAPE;
+    if (!(delta_factor > 0.0f) || delta_factor > 1.0f) return TWN_ERR_SHAPE;
+    const int64_t RS = static_cast<int64_t>(wd->R) * wd->S;
+    const int64_t K = RS * wd->C;
+    const int64_t KT = RS * wd->rows;
+    const int64_t n = K * wd->rows;
+    if (RS > (1 << 15) || K >= (1LL << 31) || KT >= (1LL << 31) || n >= (1LL << 40)) return TWN_ERR_SHAPE;
+    if (!aligned(W, 16) || !aligned(packed, 16) || (packed_T && !aligned(packed_T, 16))) return TWN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sizeof(TernWorkspace) || !aligned(workspace, 8)) return TWN_ERR_WORKSPACE;
+
+    hipStream_t st = as_stream(stream);
+    const int wpr = static_cast<int>(twn_packed_words_per_row(K));
+    const int wprT = static_cast<int>(twn_packed_words_per_row(KT));
+    const int rows_per_group = wd->rows / groups;
+    bool packed_done = false;
+
+    if (groups == 1) {
+        TernWorkspace* ws = static_cast<TernWorkspace*>(workspace);
+        const int64_t nchunks = (n + kChunk - 1) / kChunk;
+        int want = env_int("TWN_TERN_BLOCKS", 2048);
+        if (want < 1) want = 1;
+        if (want > kMaxBlocks) want = kMaxBlocks;
+        const int nb = static_cast<int>(nchunks < want ? nchunks : want);
+        abs_sum_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1);
+        const bool flat = (RS == 1) && (K % 128 == 0);
+        if (flat) {
+            const int reverse = env_int("TWN_TERN_REVERSE", 1);
+            mask_pack_flat_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1, nb, delta_factor, packed,
+                                                               ws->p2, ws->cnt, reverse);
+            packed_done = true;
+        } else {
+            mask_stats_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1, nb, delta_factor, ws->p2, ws->cnt);
+        }
+        finalize_kernel<<<1, kTernThreads, 0, st>>>(ws->p1, nb, ws->p2, ws->cnt, nb, delta_factor, n,
+                                                    delta, alpha, nnz);
+    } else {
+        group_stats_kernel<<<groups, kTernThreads, 0, st>>>(W, n / groups, delta_factor, delta, alpha, nnz);
+    }
+    if (!packed_done) {
+        const int64_t words = static_cast<int64_t>(wd->rows) * wpr;
+        pack_gather_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(
+            W, wd->rows, wd->C, static_cast<int>(RS), delta, rows_per_group, packed, wpr, 0);
+    }
+    if (packed_T) {
+        const int64_t words = static_cast<int64_t>(wd->C) * wprT;
+        pack_gather_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(
+            W, wd->rows, wd->C, static_cast<int>(RS), delta, rows_per_group, packed_T, wprT, 1);
+    }
+    return launch_status();
+}
+
+extern "C" int32_t twn_unpack_i8(const uint32_t* packed, int32_t rows, int64_t K, int8_t* codes, void* stream) {
+    if (!packed || !codes) return TWN_ERR_NULL;
+    if (rows <= 0 || K <= 0 || K >= (1LL << 31)) return TWN_ERR_SHAPE;
+    if (!aligned(packed, 16)) return TWN_ERR_ALIGN;
+    const int64_t total = static_cast<int64_t>(rows) * K;
+    unpack_i8_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, as_stream(stream)>>>(
+        packed, rows, K, static_cast<int>(twn_packed_words_per_row(K)), codes);
+    return launch_status();
+}

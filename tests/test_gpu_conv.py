@@ -1,0 +1,229 @@
+"""GPU parity of the forward block (Eq. 2; Alg. 1 step 8) and of the
+straight-through backward (Alg. 1 steps 9-10) against the direct-loop oracle.
+Bar: max relative error <= 2e-2 on bf16-MFMA paths, <= 1e-5 on float32 paths,
+with err = max |y - ref| / max(|ref|, 1e-2 rms(ref)).  Weights go through the
+whole pipeline: twn_ternarize on the GPU, oracle ternarizer on the CPU."""
+
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv as oc
+from oracle import ternarize as ot
+from paper_1605_04711_amd import api
+from paper_1605_04711_amd import workloads as wl
+from parity import BF16_TOL, FP32_TOL, rel_err, to_dev_bf16, to_dev_f32, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+F = 0.7
+
+
+def make_layer(seed, x_shape, w_shape, bf16=True, groups=1, transposed=False):
+    g = np.random.default_rng(seed)
+    x = g.standard_normal(x_shape).astype(np.float32)
+    if bf16:
+        x = wl.bf16_round(x)
+    fan_in = int(np.prod(w_shape[1:]))
+    w = (g.standard_normal(w_shape) * np.sqrt(2.0 / fan_in)).astype(np.float32)
+    tw = api.twn_ternarize(to_dev_f32(w), F, groups=groups, transposed=transposed)
+    w4 = w if w.ndim == 4 else w.reshape(w.shape[0], w.shape[1], 1, 1)
+    codes, delta, alpha, nnz = ot.ternarize(w4, F, groups=groups)
+    return x, w, tw, codes, alpha
+
+
+GEMM_CASES = [(300, 200, 320), (257, 130, 64), (1, 10, 1024), (128, 1000, 512), (64, 40, 100), (513, 257, 136)]
+
+
+@pytest.mark.parametrize("m,n,k", GEMM_CASES)
+def test_gemm_fwd_bf16(m, n, k):
+    x, w, tw, codes, alpha = make_layer(m + n + k, (m, k), (n, k))
+    y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
+    yb = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.bfloat16)
+    ref = oc.gemm_fwd(x, codes.reshape(n, k), alpha)
+    assert rel_err(to_host_f64(y), ref) <= 1e-4          # fp32 accumulation of exact bf16 products
+    assert rel_err(to_host_f64(yb), ref) <= BF16_TOL
+
+
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
+def test_gemm_fwd_every_tile_shape(tile, monkeypatch):
+    monkeypatch.setenv("TWN_TILE", str(tile))
+    m, n, k = 520, 300, 448
+    x, w, tw, codes, alpha = make_layer(tile, (m, k), (n, k))
+    y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
+    ref = oc.gemm_fwd(x, codes.reshape(n, k), alpha)
+    assert rel_err(to_host_f64(y), ref) <= 1e-4
+
+
+def test_gemm_epilogue_groups_and_strides():
+    m, n, k = 200, 96, 256
+    x, w, tw, codes, alpha = make_layer(11, (m, k), (n, k), groups=n)
+    g = np.random.default_rng(2)
+    scale = g.uniform(0.5, 1.5, n).astype(np.float32)
+    shift = g.standard_normal(n).astype(np.float32)
+    res = wl.bf16_round(g.standard_normal((m, n)).astype(np.float32))
+    xpad = torch.zeros((m, k + 8), dtype=torch.bfloat16, device="cuda")
+    xpad[:, :k] = to_dev_bf16(x)
+    y = api.twn_gemm_fwd(xpad[:, :k], tw, scale=to_dev_f32(scale), shift=to_dev_f32(shift),
+                         residual=to_dev_bf16(res), relu=True)
+    ref = oc.epilogue(oc.gemm_fwd(x, codes.reshape(n, k), alpha), scale, shift, res, relu=True)
+    assert rel_err(to_host_f64(y), ref) <= BF16_TOL
+    assert float(to_host_f64(y).min()) >= 0.0
+
+
+CONV_CASES = [
+    # N  H   W   C   O   R  S  stride  pad     dil
+    (2, 13, 11, 16, 40, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (3, 17, 17, 64, 128, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (2, 14, 14, 128, 256, 3, 3, (2, 2), (1, 1), (1, 1)),
+    (1, 19, 19, 32, 48, 3, 3, (1, 1), (6, 6), (6, 6)),
+    (2, 12, 12, 32, 64, 5, 5, (1, 1), (0, 0), (1, 1)),
+    (2, 31, 29, 3, 64, 7, 7, (2, 2), (3, 3), (1, 1)),
+    (2, 16, 16, 3, 128, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (2, 14, 14, 64, 128, 1, 1, (2, 2), (0, 0), (1, 1)),
+    (5, 9, 9, 24, 10, 1, 1, (1, 1), (0, 0), (1, 1)),
+    (1, 10, 12, 8, 8, 3, 2, (2, 1), (1, 0), (1, 2)),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(CONV_CASES)))
+def test_conv2d_fwd_bf16(ci):
+    n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
+    x, w, tw, codes, alpha = make_layer(100 + ci, (n, h, w_, c), (o, c, r, s))
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, y_dtype=torch.float32)
+    ref = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    assert tuple(y.shape) == ref.shape
+    assert rel_err(to_host_f64(y), ref) <= 1e-4
+    yb = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl)
+    assert rel_err(to_host_f64(yb), ref) <= BF16_TOL
+
+
+def test_conv2d_fwd_fused_block_tail():
+    n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[1]
+    x, w, tw, codes, alpha = make_layer(7, (n, h, w_, c), (o, c, r, s), groups=o)
+    g = np.random.default_rng(3)
+    scale = g.uniform(0.5, 1.5, o).astype(np.float32)
+    shift = g.standard_normal(o).astype(np.float32)
+    ref0 = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    res = wl.bf16_round(g.standard_normal(ref0.shape).astype(np.float32))
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, scale=to_dev_f32(scale), shift=to_dev_f32(shift),
+                           residual=to_dev_bf16(res), relu=True)
+    assert rel_err(to_host_f64(y), oc.epilogue(ref0, scale, shift, res, relu=True)) <= BF16_TOL
+
+
+def test_lenet_layers_fp32():
+    for li, layer in enumerate(wl.lenet5(8)):
+        x = wl.uniform01(0, wl.IDX_INPUT + li, layer.x_shape)
+        w = wl.kaiming_weights(0, li, layer)
+        tw = api.twn_ternarize(to_dev_f32(w), F)
+        codes, delta, alpha, nnz = ot.ternarize(w, F)
+        y = api.twn_conv2d_fwd(to_dev_f32(x), tw, (layer.stride,) * 2, (layer.pad,) * 2, (layer.dil,) * 2,
+                               y_dtype=torch.float32, relu=True)
+        ref = oc.epilogue(oc.conv2d_fwd(x, codes, alpha, (layer.stride,) * 2, (layer.pad,) * 2, (layer.dil,) * 2),
+                          relu=True)
+        assert rel_err(to_host_f64(y), ref) <= FP32_TOL, layer.name
+    # the fully-connected layers through the GEMM entry point
+    layer = wl.lenet5(8)[2]
+    x = wl.uniform01(0, 77, (8, layer.C))
+    w = wl.kaiming_weights(0, 2, layer)
+    tw = api.twn_ternarize(to_dev_f32(w.reshape(layer.O, layer.C)), F)
+    codes, delta, alpha, nnz = ot.ternarize(w, F)
+    y = api.twn_gemm_fwd(to_dev_f32(x), tw, y_dtype=torch.float32)
+    assert rel_err(to_host_f64(y), oc.gemm_fwd(x, codes.reshape(layer.O, layer.C), alpha)) <= FP32_TOL
+
+
+BWD_CASES = [0, 1, 2, 3, 4, 6, 7, 8, 9]
+
+
+@pytest.mark.parametrize("ci", BWD_CASES)
+def test_conv2d_bwd_ste(ci):
+    n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
+    x, w, tw, codes, alpha = make_layer(200 + ci, (n, h, w_, c), (o, c, r, s), transposed=True)
+    p, q = oc.out_size(h, r, st[0], pd[0], dl[0]), oc.out_size(w_, s, st[1], pd[1], dl[1])
+    dy = wl.bf16_round(np.random.default_rng(300 + ci).standard_normal((n, p, q, o)).astype(np.float32))
+    dx, dw, db = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, need_dbias=True,
+                                        dx_dtype=torch.float32)
+    ref_dx = oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)
+    ref_dw = oc.conv2d_bwd_weight(x, dy, codes.shape, st, pd, dl)
+    assert rel_err(to_host_f64(dx), ref_dx) <= 1e-4
+    assert rel_err(to_host_f64(dw), ref_dw) <= 1e-4
+    assert rel_err(to_host_f64(db), oc.bias_grad(dy)) <= 1e-4
+    dxb, _, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, need_dw=False)
+    assert rel_err(to_host_f64(dxb), ref_dx) <= BF16_TOL
+    # accumulate into an existing gradient; dW does not depend on the codes or alpha (identity STE)
+    _, dw2, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, need_dx=False,
+                                       dW=dw.clone(), accumulate=True)
+    assert rel_err(to_host_f64(dw2), 2 * ref_dw) <= 1e-4
+
+
+def test_fc_backward_is_the_1x1_case():
+    m, k, n = 128, 512, 1000
+    x, w, tw, codes, alpha = make_layer(9, (m, 1, 1, k), (n, k, 1, 1), transposed=True)
+    dy = wl.bf16_round(np.random.default_rng(10).standard_normal((m, 1, 1, n)).astype(np.float32))
+    dx, dw, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, dx_dtype=torch.float32)
+    assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, x.shape)) <= 1e-4
+    assert rel_err(to_host_f64(dw), oc.conv2d_bwd_weight(x, dy, codes.shape)) <= 1e-4
+
+
+def _sample(total, count, seed):
+    return np.unique(np.random.default_rng(seed).integers(0, total, size=count))
+
+
+def test_full_size_gemm_sampled():
+    """Config: X [8192 x 4096] bf16 N(0,1), W [4096 x 4096] N(0, 0.02^2), f = 0.7; sampled outputs."""
+    m, n, k = 8192, 4096, 4096
+    x = wl.bf16_round(wl.normal(3, wl.IDX_INPUT, (m, k)))
+    w = wl.normal(3, 1, (n, k), std=0.02)
+    tw = api.twn_ternarize(to_dev_f32(w), F)
+    y = api.twn_gemm_fwd(to_dev_bf16(x), tw)
+    torch.cuda.synchronize()
+    delta = ot.threshold(w, F)
+    codes = ot.codes_from_threshold(w, delta)
+    nnz = int(np.count_nonzero(codes))
+    alpha = np.float32(float(np.sum(np.abs(w)[codes != 0], dtype=np.float64)) / nnz)
+    assert int(tw.nnz.cpu()[0]) == nnz
+    idx = np.concatenate([_sample(m * n, 20000, 5), np.array([0, n - 1, (m - 1) * n, m * n - 1])])
+    ref = oc.gemm_fwd_at(x, codes, alpha, idx)
+    got = to_host_f64(y).ravel()[idx]
+    assert rel_err(got, ref) <= BF16_TOL
+
+
+@pytest.mark.parametrize("name", ["stem", "l1.0.conv1", "l2.0.conv1", "l2.0.down", "l3.1.conv2", "l4.1.conv2", "fc"])
+def test_full_size_resnet18_layers_sampled(name):
+    layers = {l.name: (i, l) for i, l in enumerate(wl.resnet18(64))}
+    li, layer = layers[name]
+    x = wl.bf16_round(wl.normal(2, wl.IDX_INPUT + li, layer.x_shape))
+    w = wl.kaiming_weights(2, li, layer)
+    tw = api.twn_ternarize(to_dev_f32(w), F)
+    codes, delta, alpha, nnz = ot.ternarize(w, F)
+    st, pd, dl = (layer.stride,) * 2, (layer.pad,) * 2, (layer.dil,) * 2
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl)
+    total = int(np.prod(layer.y_shape))
+    # random outputs plus the four image corners of the first and last image (border taps)
+    n_, p_, q_, o_ = layer.y_shape
+    corners = [((b * p_ + pp) * q_ + qq) * o_ for b in (0, n_ - 1) for pp in (0, p_ - 1) for qq in (0, q_ - 1)]
+    idx = np.concatenate([_sample(total, 20000, li), np.array(corners)])
+    ref = oc.conv2d_fwd_at(x, codes, alpha, idx, st, pd, dl)
+    assert rel_err(to_host_f64(y).ravel()[idx], ref) <= BF16_TOL
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c4", "c6", "fc1"])
+def test_full_size_vgg7_backward_sampled(name):
+    layers = {l.name: (i, l) for i, l in enumerate(wl.vgg7(128))}
+    li, layer = layers[name]
+    x = wl.bf16_round(wl.normal(1, wl.IDX_INPUT + li, layer.x_shape))
+    dy = wl.bf16_round(wl.normal(1, wl.IDX_DY + 10 * li, layer.y_shape))
+    w = wl.kaiming_weights(1, li, layer)
+    tw = api.twn_ternarize(to_dev_f32(w), F, transposed=True)
+    codes, delta, alpha, nnz = ot.ternarize(w, F)
+    st, pd, dl = (layer.stride,) * 2, (layer.pad,) * 2, (layer.dil,) * 2
+    dx, dw, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, need_dx=(name != "c1"))
+    i2 = _sample(layer.n_weights, 300, li + 7)
+    ref_dw = oc.conv2d_bwd_weight_at(x, dy, layer.w_shape, i2, st, pd, dl)
+    assert rel_err(to_host_f64(dw).ravel()[i2], ref_dw) <= 1e-3
+    if dx is not None:
+        i1 = _sample(int(np.prod(layer.x_shape)), 20000, li)
+        ref_dx = oc.conv2d_bwd_data_at(dy, codes, alpha, layer.x_shape, i1, st, pd, dl)
+        assert rel_err(to_host_f64(dx).ravel()[i1], ref_dx) <= BF16_TOL
