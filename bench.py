@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the TWN hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of the VGG-7 / CIFAR
+workload (batch 128, bf16 activations): ternarize all 8 weight tensors
+(Delta, alpha, 2-bit codes and the transposed copy), forward every conv / FC
+layer with the fused scale-shift-ReLU tail, then the straight-through backward
+(dX and dW) of every layer.  Inputs are seeded synthetic tensors already
+resident in HBM.  Prints ONE JSON line on stdout; per-layer detail goes to stderr.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # dense bf16 MFMA, MI355X
+PEAK_HBM_GBPS = 8000.0
+F = 0.7
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-extras", action="store_true", help="skip the GEMM / ternarize-2^28 / ResNet-18 side measurements")
+    ap.add_argument("--cpu-batch", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_1605_04711_amd import api
+    from paper_1605_04711_amd import workloads as wl
+
+    if not os.path.exists(api.library_path()):
+        from paper_1605_04711_amd import build as b
+        b.build()
+    api.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    def dev_bf16(a):
+        return torch.from_numpy(wl.f32_to_bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16).reshape(a.shape)
+
+    # ---------------- workload: VGG-7, batch 128 ----------------
+    CFG = 1
+    layers = wl.vgg7(128)
+    W, X, dY, Y, dX, dW, tws, wsb, scale, shift = [], [], [], [], [], [], [], [], [], []
+    tern_ws = None
+    for li, L in enumerate(layers):
+        w = wl.kaiming_weights(CFG, li, L)
+        W.append(torch.from_numpy(w).to(dev))
+        X.append(dev_bf16(wl.normal(CFG, wl.IDX_INPUT + li, L.x_shape)))
+        dY.append(dev_bf16(wl.normal(CFG, wl.IDX_DY + 10 * li, L.y_shape)))
+        Y.append(torch.empty(L.y_shape, dtype=torch.bfloat16, device=dev))
+        dX.append(torch.empty(L.x_shape, dtype=torch.bfloat16, device=dev) if li > 0 else None)
+        dW.append(torch.empty(L.w_shape, dtype=torch.float32, device=dev))
+        scale.append(torch.ones(L.O, dtype=torch.float32, device=dev))
+        shift.append(torch.zeros(L.O, dtype=torch.float32, device=dev))
+        tws.append(api.twn_ternarize(W[li], F, transposed=True))
+        wsb.append(torch.empty(max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, tws[li], (L.stride,) * 2,
+                                                                              (L.pad,) * 2, (L.dil,) * 2)),
+                               dtype=torch.uint8, device=dev))
+    tern_ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
+    geo = [((L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2) for L in layers]
+
+    flops_fwd = sum(L.flops for L in layers)
+    flops_dx = sum(L.flops for L in layers[1:])
+    flops_dw = flops_fwd
+    flops_step = flops_fwd + flops_dx + flops_dw
+    tern_bytes = sum(L.n_weights for L in layers) * 8.5      # two reads + two 2-bit copies
+
+    def do_ternarize():
+        for li in range(len(layers)):
+            api.twn_ternarize(W[li], F, transposed=True, out=tws[li], workspace=tern_ws)
+
+    def do_fwd():
+        for li in range(len(layers)):
+            st, pd, dl = geo[li]
+            api.twn_conv2d_fwd(X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li], relu=True, out=Y[li])
+
+    def do_dx():
+        for li in range(len(layers) - 1, 0, -1):
+            st, pd, dl = geo[li]
+            api.twn_conv2d_bwd_ste(None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False, dX=dX[li],
+                                   x_shape=layers[li].x_shape, workspace=wsb[li])
+
+    def do_dw():
+        for li in range(len(layers) - 1, -1, -1):
+            st, pd, dl = geo[li]
+            api.twn_conv2d_bwd_ste(X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True, dW=dW[li],
+                                   workspace=wsb[li])
+
+    phases = [("ternarize", do_ternarize), ("fwd", do_fwd), ("bwd_data", do_dx), ("bwd_weight", do_dw)]
+
+    for _ in range(args.warmup):
+        for _, fn in phases:
+            fn()
+    torch.cuda.synchronize()
+
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in phases]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        for pi, (_, fn) in enumerate(phases):
+            ev[s][pi][0].record()
+            fn()
+            ev[s][pi][1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    phase_ms = [sum(ev[s][pi][0].elapsed_time(ev[s][pi][1]) for s in range(args.steps)) / args.steps
+                for pi in range(len(phases))]
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+    log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phases[i][0], phase_ms[i]) for i in range(len(phases))))
+
+    # the forward/backward-data kernel (one launch per layer) against the bf16 MFMA peak
+    mfma_flops = flops_fwd + flops_dx
+    mfma_ms = phase_ms[1] + phase_ms[2]
+    launches = len(layers) + len(layers) - 1
+    dw_tflops = flops_dw / (phase_ms[3] * 1e-3) / 1e12
+    gg_tflops = mfma_flops / (mfma_ms * 1e-3) / 1e12
+    if phase_ms[3] > mfma_ms:
+        roof = {"kernel": "weight_grad_kernel", "bound": "mfma", "achieved": round(dw_tflops, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(dw_tflops / PEAK_BF16_TFLOPS, 4),
+                "traffic": None, "launches_per_step": len(layers), "avg_launch_us": round(phase_ms[3] * 1e3 / len(layers), 2)}
+    else:
+        roof = {"kernel": "gather_gemm_mfma_kernel", "bound": "mfma", "achieved": round(gg_tflops, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gg_tflops / PEAK_BF16_TFLOPS, 4),
+                "traffic": None, "launches_per_step": launches, "avg_launch_us": round(mfma_ms * 1e3 / launches, 2)}
+
+    def time_call(fn, reps=10, warm=2):
+        for _ in range(warm):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # per-layer detail (stderr)
+    log("%-6s %22s %10s %10s %10s %10s" % ("layer", "(M,N,K)", "fwd us", "fwd TF/s", "dX TF/s", "dW TF/s"))
+    for li, L in enumerate(layers):
+        st, pd, dl = geo[li]
+        tf = time_call(lambda: api.twn_conv2d_fwd(X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li],
+                                                  relu=True, out=Y[li]))
+        tdx = time_call(lambda: api.twn_conv2d_bwd_ste(None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False,
+                                                       dX=dX[li], x_shape=L.x_shape, workspace=wsb[li])) if li else float("nan")
+        tdw = time_call(lambda: api.twn_conv2d_bwd_ste(X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True,
+                                                       dW=dW[li], workspace=wsb[li]))
+        log("%-6s %22s %10.1f %10.1f %10.1f %10.1f" % (L.name, str(L.gemm_mnk), tf * 1e3, L.flops / tf / 1e9,
+                                                       L.flops / tdx / 1e9, L.flops / tdw / 1e9))
+
+    extras = {"phase_ms": {phases[i][0]: round(phase_ms[i], 4) for i in range(len(phases))},
+              "fwd_tflops": round(flops_fwd / (phase_ms[1] * 1e-3) / 1e12, 2),
+              "bwd_data_tflops": round(flops_dx / (phase_ms[2] * 1e-3) / 1e12, 2),
+              "bwd_weight_tflops": round(dw_tflops, 2),
+              "ternarize_layers_GBps": round(tern_bytes / (phase_ms[0] * 1e-3) / 1e9, 1)}
+
+    if not args.no_extras:
+        del X, dY, Y, dX, dW
+        torch.cuda.empty_cache()
+        # stand-alone GEMM: X [8192 x 4096] bf16, W [4096 x 4096] N(0, 0.02^2)
+        g = wl.gemm_config()
+        gx = dev_bf16(wl.normal(3, wl.IDX_INPUT, (g.N, g.C)))
+        gw = torch.from_numpy(wl.normal(3, 1, (g.O, g.C), std=0.02)).to(dev)
+        gtw = api.twn_ternarize(gw, F)
+        gy = torch.empty((g.N, g.O), dtype=torch.bfloat16, device=dev)
+        t = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=20, warm=3)
+        extras["gemm_8192x4096x4096"] = {"us": round(t * 1e3, 1), "tflops": round(g.flops / t / 1e9, 1),
+                                         "frac_mfma_peak": round(g.flops / t / 1e9 / PEAK_BF16_TFLOPS, 4)}
+        log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq" % (t * 1e3, g.flops / t / 1e9))
+        del gx, gw, gy
+        # ternarize-only: 2^28 float32 N(0,1)
+        rows = 1 << 14
+        big = torch.from_numpy(wl.normal(3, 0, (rows, rows))).to(dev)
+        btw = api.twn_ternarize(big, F)
+        t = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=tern_ws), reps=20, warm=3)
+        nbytes = (1 << 28) * 8.25
+        extras["ternarize_2p28"] = {"us": round(t * 1e3, 1), "GBps": round(nbytes / t / 1e6, 1),
+                                    "frac_hbm_peak": round(nbytes / t / 1e6 / PEAK_HBM_GBPS, 4)}
+        log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight)" % (t * 1e3, nbytes / t / 1e6))
+        del big, btw
+        torch.cuda.empty_cache()
+        # ResNet-18 forward, batch 64 (per-layer synthetic inputs, fused scale/shift/ReLU tail)
+        rl = wl.resnet18(64)
+        tot = 0.0
+        for li, L in enumerate(rl):
+            x = dev_bf16(wl.normal(2, wl.IDX_INPUT + li, L.x_shape))
+            tw = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev), F)
+            y = torch.empty(L.y_shape, dtype=torch.bfloat16, device=dev)
+            sc = torch.ones(L.O, dtype=torch.float32, device=dev)
+            sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
+            st, pd, dl = (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2
+            t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y), reps=10)
+            tot += t
+            log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq" % (L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
+            del x, y
+        rflops = sum(L.flops for L in rl)
+        extras["resnet18_b64_fwd"] = {"ms": round(tot, 4), "img_per_s": round(64 / (tot * 1e-3), 1),
+                                      "tflops": round(rflops / tot / 1e9, 1),
+                                      "frac_mfma_peak": round(rflops / tot / 1e9 / PEAK_BF16_TFLOPS, 4)}
+        log("resnet18 b64 conv/fc layers: %.3f ms, %.0f img/s" % (tot, 64 / (tot * 1e-3)))
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle import conv as oc
+        from oracle import ternarize as ot
+        oc.build()
+        cores = oc.max_threads()
+        nb = args.cpu_batch
+        t_tern = 0.0
+        t_conv = 0.0
+        for li, L in enumerate(layers):
+            w = wl.kaiming_weights(CFG, li, L)
+            a = time.perf_counter()
+            codes, delta, alpha, nnz = ot.ternarize(w, F)
+            t_tern += time.perf_counter() - a
+            Ls = L.with_batch(nb)
+            x = wl.bf16_round(wl.normal(CFG, wl.IDX_INPUT + li, Ls.x_shape))
+            dy = wl.bf16_round(wl.normal(CFG, wl.IDX_DY + 10 * li, Ls.y_shape))
+            st, pd, dl = geo[li]
+            a = time.perf_counter()
+            oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+            if li:
+                oc.conv2d_bwd_data(dy, codes, alpha, Ls.x_shape, st, pd, dl)
+            oc.conv2d_bwd_weight(x, dy, Ls.w_shape, st, pd, dl)
+            t_conv += time.perf_counter() - a
+        t_full = t_tern + t_conv * (128.0 / nb)
+        cpu = {"value": round(flops_step / t_full / 1e12, 6), "unit": "TFLOP/s-eq", "cores": cores, "kind": "oracle",
+               "sample": "ternarize of all 8 VGG-7 tensors in full (%.2f s, numpy sort, 1 thread) + fwd/dX/dW of every layer "
+                         "at batch %d of 128 (%.2f s, C direct loops, %d OpenMP threads), conv time scaled linearly to batch 128"
+                         % (t_tern, nb, t_conv, cores)}
+        log("cpu oracle: ternarize %.2f s, conv(b%d) %.2f s -> %.5f TFLOP/s-eq" % (t_tern, nb, t_conv, cpu["value"]))
+
+    out = {
+        "metric": "ternary conv/GEMM throughput, dense-equivalent (2MNK per contraction; ternarize + fwd + STE bwd per step)",
+        "value": round(value, 3), "unit": "TFLOP/s-eq", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "vgg7_cifar_b128_twn_step", "layers": len(layers), "batch": 128, "delta_factor": F,
+                   "gflop_per_step": round(flops_step / 1e9, 1), "img_per_s": round(128 / (ms_per_step * 1e-3), 1)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "extras": extras,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -68,7 +68,7 @@ typedef enum {
     TWN_VAR_BF16_POSTSCALE = 0,     /* 2-bit codes -> exact bf16 in registers, bf16 MFMA, alpha in the fp32 epilogue */
     TWN_VAR_BF16_ALPHA_LDS = 1,     /* 2-bit codes -> bf16 {-alpha,0,+alpha} staged in LDS, bf16 MFMA (comparison) */
     TWN_VAR_I8_STORED_POSTSCALE = 2,/* weights stored as int8 {-1,0,1} (8 bits/weight), bf16 MFMA, alpha afterwards (comparison) */
-    TWN_VAR_FP32 = 3                /* float32 activations, float32 FMA accumulation */
+    TWN_VAR_FP32 = 3                /* float32 activations and outputs, vector-ALU FMAs with float64 running sums */
 } twn_variant;
 
 /* Filter bank [rows][C][R][S], float32, contiguous (fully-connected: R=S=1). */

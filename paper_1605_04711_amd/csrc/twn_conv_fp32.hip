@@ -1,7 +1,10 @@
 // float32 path of the ternary convolution / inner product (Eq. 2, Alg. 1 step 8)
-// for float32 activations: LDS-tiled implicit GEMM on the vector ALUs with
-// float32 FMA accumulation.  Weights are the same packed twn2 codes, expanded
-// to {-1, 0, +1} floats while staging the tile; alpha is applied afterwards.
+// for float32 activations: LDS-tiled implicit GEMM on the vector ALUs.  Inputs
+// and outputs are float32; the running sums are kept in float64 (products with
+// a code are exact, so only the additions round) because float32 accumulation
+// of cancelling sums cannot hold a 1e-5 relative bound on small outputs.
+// Weights are the same packed twn2 codes, expanded to {-1, 0, +1} floats while
+// staging the tile; alpha is applied afterwards.
 // The layers that use it (LeNet-sized) are launch-bound, so the kernel is kept
 // simple: 64x64 output tile, K slabs of 16, 4x4 outputs per thread.
 #include "twn_kernels.h"
@@ -41,7 +44,7 @@ __global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm 
     const int bn = n0 + bcol;
 
     const int ty = tid >> 4, tx = tid & 15;
-    float acc[4][4] = {};
+    double acc[4][4] = {};
 
     for (int k0 = 0; k0 < g.K; k0 += kF32K) {
 #pragma unroll
@@ -77,15 +80,15 @@ __global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm 
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < kF32K; ++k) {
-            float a[4], b[4];
+            double a[4], b[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+            for (int i = 0; i < 4; ++i) a[i] = static_cast<double>(As[k][ty * 4 + i]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
+            for (int j = 0; j < 4; ++j) b[j] = static_cast<double>(Bs[k][tx * 4 + j]);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
         }
         __syncthreads();
     }
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm 
         for (int i = 0; i < 4; ++i) {
             const int64_t m = m0 + ty * 4 + i;
             if (m >= g.M) continue;
-            float v = (acc[i][j] * al) * sc + sf;
+            float v = (static_cast<float>(acc[i][j]) * al) * sc + sf;
             const int64_t off = m * g.ldy + ncol;
             if (g.y_f32) {
                 if (g.residual) v += static_cast<const float*>(g.residual)[off];
