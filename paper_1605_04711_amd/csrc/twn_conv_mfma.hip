@@ -185,8 +185,21 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
             load_a(kt + 1);
             load_b(kt + 1, breg_next);
         }
+        // A fragments are fetched one MFMA step ahead of their use
+        bf16x8 afrag[2][MI];
+        auto read_a = [&](int kk, bf16x8* dst) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int row = wm * TM + mi * 32 + lrow;
+                const int chunk = (lh * 4 + kk) ^ (row & 7);
+                dst[mi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&lds[cur][row * 64 + chunk * 8]));
+            }
+        };
+        read_a(0, afrag[0]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
+            if (kk + 1 < 4) read_a(kk + 1, afrag[(kk + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this step's MFMAs
             bf16x8 bfrag[NI];
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
@@ -200,15 +213,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
                 bfrag[ni] = __builtin_bit_cast(bf16x8, b);
             }
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                const int row = wm * TM + mi * 32 + lrow;
-                const int chunk = (lh * 4 + kk) ^ (row & 7);
-                const u32x4 a = *reinterpret_cast<const u32x4*>(&lds[cur][row * 64 + chunk * 8]);
-                const bf16x8 afrag = __builtin_bit_cast(bf16x8, a);
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[ni], acc[mi][ni], 0, 0, 0);
-            }
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[kk & 1][mi], bfrag[ni], acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (more) store_a(cur ^ 1);
         __syncthreads();
@@ -268,6 +277,11 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
 
     // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.
     int tile = env_int("TWN_TILE", 0);
+    if (mode != kModeScalar && (tile == 0 || tile > 10)) {
+        // multi-stage direct-to-LDS kernel
+        if (tile == 0) tile = (g.NC <= 64) ? 13 : (g.NC <= 128) ? 12 : 11;
+        return launch_gather_gemm_dma(g, tile, st);
+    }
     if (tile == 0) {
         auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
         const int64_t want = 256;

@@ -1,0 +1,397 @@
+// Multi-stage implicit-GEMM ternary convolution / inner product on gfx950
+// (Eq. 2, Alg. 1 step 8; also the backward-data pass of Alg. 1 step 9).
+//
+// Same arithmetic as the register-staged kernel (bf16 activations as the MFMA A
+// operand, 2-bit codes expanded in registers to +-2.0 / 0 as the B operand,
+// alpha/2 applied in the fp32 epilogue), but every tile travels global -> LDS
+// by direct 16-byte LDS loads (global_load_lds_dwordx4), STAGES slabs deep:
+//   * per K slab of 64 a workgroup stages BM rows x 128 bytes of activations
+//     (16-byte chunks XOR-swizzled by row & 7: the swizzle is applied by
+//     choosing which global chunk each lane fetches, because a direct LDS load
+//     always writes lane j of a wave at byte 16*j of its 1 KB destination) and
+//     BN x 16 bytes of packed codes (64 codes of each output channel);
+//   * loads for slab kt+STAGES-1 are issued while slab kt is multiplied; one
+//     s_waitcnt vmcnt(N) + s_barrier per slab hands a landed slab to all waves;
+//   * lanes outside the image / beyond M, N or K fetch from a 16-byte zero
+//     block instead, so padding costs no branches and slabs past the end of K
+//     are harmless zero loads that keep the outstanding-load count constant.
+#include "twn_kernels.h"
+
+namespace twn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __attribute__((aligned(16))) const uint32_t kZeroBlock[4] = {0u, 0u, 0u, 0u};
+
+// Exact unsigned division of numerators below 2^31 by a runtime constant.
+struct FastDivU {
+    uint32_t mul, shift;
+};
+
+static FastDivU make_fastdiv_u(uint32_t d) {
+    FastDivU f{0, 0};
+    if (d <= 1) return f;
+    uint32_t l = 0;
+    while ((1u << l) < d) ++l;
+    const uint32_t s = 31 + l;
+    f.mul = static_cast<uint32_t>(((1ULL << s) + d - 1) / d);
+    f.shift = s - 32;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fdiv_u(uint32_t n, const FastDivU& f) {
+    return f.mul ? (__umulhi(n, f.mul) >> f.shift) : n;
+}
+
+struct DmaArgs {
+    GatherGemm g;
+    FastDivU divIC, divS;
+};
+
+// s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding).
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+__device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM>
+__global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_gemm_dma_kernel(const DmaArgs a) {
+    static_assert(WM * WN == 4, "four waves per workgroup");
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int NLOAD = BM / 32;                 // 1 KB (8 rows) per wave-level load, 4 waves
+    constexpr int A_BYTES = BM * 128;
+    constexpr int B_BYTES = BN * 16;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int PD = STAGES - 1;                 // slabs in flight ahead of the one being multiplied
+    constexpr int PER_STAGE = NLOAD + 1;           // vector-memory loads per wave per slab
+    constexpr int EPI_ROW = 144;                   // bytes per pixel row of the epilogue staging (64 bf16 + pad)
+    constexpr int EPI_STAGE_BYTES = 4 * TM * EPI_ROW;
+    static_assert(BM % 32 == 0 && BN % 64 == 0 && TN % 64 == 0, "tile shape");
+    static_assert(EPI_STAGE_BYTES + 2 * BN * 4 <= STAGES * STAGE_BYTES, "epilogue staging must fit in the pipeline LDS");
+
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+    const GatherGemm& g = a.g;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = lane & 31, lh = lane >> 5;
+
+    // workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles
+    const uint32_t nb = gridDim.x, b = blockIdx.x;
+    const uint32_t q = nb >> 3, r = nb & 7, xcd = b & 7, idx = b >> 3;
+    const uint32_t t = (xcd < r) ? xcd * (q + 1) + idx : r * (q + 1) + (xcd - r) * q + idx;
+    const uint32_t tiles_n = (g.NC + BN - 1) / BN;
+    const int64_t m0 = static_cast<int64_t>(t / tiles_n) * BM;
+    const int n0 = static_cast<int>(t % tiles_n) * BN;
+
+    const uint16_t* __restrict__ X = static_cast<const uint16_t*>(g.X);
+    const uint32_t* __restrict__ Wq = static_cast<const uint32_t*>(g.Wq);
+    const void* zero = kZeroBlock;
+
+    // ---- A loads: wave-level load i of this wave covers rows (i*4 + wave)*8 .. +7 ----
+    const int kc = (lane & 7) ^ ((lane >> 3) & 7);     // logical 16-byte chunk this lane fetches
+    int64_t abase[NLOAD];                              // GEMM: element offset of the row; conv: pixel base
+    int ih0[NLOAD], iw0[NLOAD];
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int row = (i * 4 + wave) * 8 + (lane >> 3);
+        const int64_t m = m0 + row;
+        if (m < g.M) {
+            if (GEMM) {
+                abase[i] = m * g.xs;
+                ih0[i] = 0;
+                iw0[i] = 0;
+            } else {
+                const int ow = static_cast<int>(m % g.OW);
+                const int64_t tt = m / g.OW;
+                const int oh = static_cast<int>(tt % g.OH);
+                abase[i] = (tt / g.OH) * g.IH * g.IW;
+                ih0[i] = oh * g.sh - g.ph;
+                iw0[i] = ow * g.sw - g.pw;
+            }
+        } else {
+            abase[i] = 0;
+            ih0[i] = -(1 << 28);
+            iw0[i] = -(1 << 28);
+        }
+    }
+    // ---- B load: this wave stages the packed codes of 64 output channels (one lane per channel) ----
+    const int brow = (wave * 64) % BN + lane;
+    const int bcol = n0 + brow;
+    const uint32_t* bsrc = (bcol < g.NC) ? Wq + static_cast<int64_t>(bcol) * g.wpr : nullptr;
+
+    const int KT = (g.K + 63) / 64;
+
+    auto tap_coord = [&](int base, int tap, int step, int div, int limit, int& out) -> bool {
+        int v = base + tap * step;
+        if (div > 1) {
+            if (v < 0 || (v % div) != 0) return false;
+            v /= div;
+        }
+        out = v;
+        return static_cast<unsigned>(v) < static_cast<unsigned>(limit);
+    };
+
+    auto issue = [&](int kt, int stage) {
+        unsigned char* sbase = smem + stage * STAGE_BYTES;
+        const int k = kt * 64 + kc * 8;
+        const bool kok = (kt < KT) && (k < g.K);
+        if (GEMM) {
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                const void* src = (kok && ih0[i] == 0) ? static_cast<const void*>(X + abase[i] + k) : zero;
+                dma16(src, sbase + (i * 4 + wave) * 1024);
+            }
+        } else {
+            const uint32_t rs = fdiv_u(static_cast<uint32_t>(k), a.divIC);
+            const int c = k - static_cast<int>(rs) * g.IC;
+            const int rr = static_cast<int>(fdiv_u(rs, a.divS));
+            const int ss = static_cast<int>(rs) - rr * g.S;
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                int th, tw;
+                bool ok = tap_coord(ih0[i], rr, g.dh, g.divh, g.IH, th);
+                ok = tap_coord(iw0[i], ss, g.dw, g.divw, g.IW, tw) && ok && kok;
+                const void* src = ok ? static_cast<const void*>(
+                                           X + (abase[i] + static_cast<int64_t>(th) * g.IW + tw) * g.xs + c)
+                                     : zero;
+                dma16(src, sbase + (i * 4 + wave) * 1024);
+            }
+        }
+        const void* bs = (bsrc && kt < KT) ? static_cast<const void*>(bsrc + kt * 4) : zero;
+        dma16(bs, sbase + A_BYTES + ((wave * 64) % BN) * 16);
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
+
+    // prologue: PD slabs in flight, the first one landed and visible to every wave
+#pragma unroll
+    for (int s = 0; s < PD; ++s) issue(s, s);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * PER_STAGE));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    int stage = 0;          // slab kt lives in stage kt % STAGES
+    int fill = PD;          // stage that slab kt + PD goes to
+    for (int kt = 0; kt < KT; ++kt) {
+        const unsigned char* sa = smem + stage * STAGE_BYTES;
+        const unsigned char* sb = sa + A_BYTES;
+
+        // LDS reads of this slab go out first; the address arithmetic and issue of the
+        // next global loads run while they are in flight
+        u32x2 breg[NI];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            breg[ni] = *reinterpret_cast<const u32x2*>(sb + (wn * TN + ni * 32 + lrow) * 16 + lh * 8);
+
+        bf16x8 afrag[2][MI];
+        auto read_a = [&](int kk, bf16x8* dst) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int row = wm * TM + mi * 32 + lrow;
+                const int chunk = (lh * 4 + kk) ^ (row & 7);
+                dst[mi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sa + row * 128 + chunk * 16));
+            }
+        };
+        read_a(0, afrag[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        issue(kt + PD, fill);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk + 1 < 4) read_a(kk + 1, afrag[(kk + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this step's MFMAs
+            bf16x8 bfrag[NI];
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+                const uint32_t word = breg[ni][kk >> 1];
+                u32x4 bb;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = (kk & 1) * 4 + e;
+                    bb[e] = (word << (14 - 2 * i)) & 0xC000C000u;
+                }
+                bfrag[ni] = __builtin_bit_cast(bf16x8, bb);
+            }
+            // weights are the row operand, activations the column operand: a lane then owns
+            // 4 consecutive output channels of one pixel per accumulator quad
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ni], afrag[kk & 1][mi], acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // slab kt+1 (issued PD-1 iterations ago) must have landed; the PD-1 younger slabs may stay in flight
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * PER_STAGE));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+        fill = (fill + 1 == STAGES) ? 0 : fill + 1;
+    }
+    // the trailing zero loads still target LDS: drain them in every wave before LDS is reused
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    // ---- epilogue: y = relu?((alpha*acc)*scale + shift + residual) ----
+    // accumulator element e of tile (mi, ni) in this lane:
+    //   pixel   m = wm*TM + mi*32 + lrow
+    //   channel n = wn*TN + ni*32 + (e>>2)*8 + lh*4 + (e&3)
+    float* colmul = reinterpret_cast<float*>(smem + EPI_STAGE_BYTES);   // [BN] 0.5*alpha*scale
+    float* coladd = colmul + BN;                                        // [BN] shift
+    for (int i = tid; i < BN; i += 256) {
+        const int ncol = n0 + i;
+        float mul = 0.0f, add = 0.0f;
+        if (ncol < g.NC) {
+            mul = 0.5f * g.alpha[ncol / g.rows_per_group] * (g.scale ? g.scale[ncol] : 1.0f);   // codes were +-2
+            add = g.shift ? g.shift[ncol] : 0.0f;
+        }
+        colmul[i] = mul;
+        coladd[i] = add;
+    }
+    __syncthreads();
+
+    const bool vec_store = !g.y_f32 && (g.NC % 8 == 0) && (g.ldy % 8 == 0);
+    if (vec_store) {
+        // bf16 output: finish each value in fp32, round once, transpose 64-channel chunks through
+        // LDS (this wave's own region) and write 16 bytes per lane, 128 contiguous bytes per pixel
+        unsigned char* stg = smem + wave * (TM * EPI_ROW);
+        const uint16_t* res = static_cast<const uint16_t*>(g.residual);
+        uint16_t* Yb = static_cast<uint16_t*>(g.Y);
+#pragma unroll
+        for (int nc = 0; nc < NI / 2; ++nc) {
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const int64_t m = m0 + wm * TM + mi * 32 + lrow;
+#pragma unroll
+                for (int nh = 0; nh < 2; ++nh) {
+                    const int ni = nc * 2 + nh;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const int nl = wn * TN + ni * 32 + q4 * 8 + lh * 4;     // column within the block tile
+                        const f32x4 mul = *reinterpret_cast<const f32x4*>(colmul + nl);
+                        const f32x4 add = *reinterpret_cast<const f32x4*>(coladd + nl);
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][q4 * 4 + e] * mul[e] + add[e];
+                        if (res && m < g.M && n0 + nl < g.NC) {
+                            const u32x2 rr = *reinterpret_cast<const u32x2*>(res + m * g.ldy + n0 + nl);
+                            v[0] += __uint_as_float(rr[0] << 16);
+                            v[1] += __uint_as_float(rr[0] & 0xFFFF0000u);
+                            v[2] += __uint_as_float(rr[1] << 16);
+                            v[3] += __uint_as_float(rr[1] & 0xFFFF0000u);
+                        }
+                        if (g.relu) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+                        }
+                        u32x2 pk;
+                        pk[0] = static_cast<uint32_t>(f32_to_bf16(v[0])) | (static_cast<uint32_t>(f32_to_bf16(v[1])) << 16);
+                        pk[1] = static_cast<uint32_t>(f32_to_bf16(v[2])) | (static_cast<uint32_t>(f32_to_bf16(v[3])) << 16);
+                        *reinterpret_cast<u32x2*>(stg + (mi * 32 + lrow) * EPI_ROW + (nh * 32 + q4 * 8 + lh * 4) * 2) = pk;
+                    }
+                }
+            }
+            // same wave wrote and reads: LDS executes a wave's operations in order
+#pragma unroll
+            for (int it = 0; it < TM / 8; ++it) {
+                const int row = it * 8 + (lane >> 3);
+                const int c16 = lane & 7;
+                const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
+                const int64_t m = m0 + wm * TM + row;
+                const int ncol = n0 + wn * TN + nc * 64 + c16 * 8;
+                if (m < g.M && ncol < g.NC) *reinterpret_cast<u32x4*>(Yb + m * g.ldy + ncol) = val;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int64_t m = m0 + wm * TM + mi * 32 + lrow;
+            if (m >= g.M) continue;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int nl = wn * TN + ni * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+                    const int ncol = n0 + nl;
+                    if (ncol >= g.NC) continue;
+                    float v = acc[mi][ni][e] * colmul[nl] + coladd[nl];
+                    const int64_t off = m * g.ldy + ncol;
+                    if (g.y_f32) {
+                        if (g.residual) v += static_cast<const float*>(g.residual)[off];
+                        if (g.relu) v = fmaxf(v, 0.0f);
+                        static_cast<float*>(g.Y)[off] = v;
+                    } else {
+                        if (g.residual) v += bf16_to_f32(static_cast<const uint16_t*>(g.residual)[off]);
+                        if (g.relu) v = fmaxf(v, 0.0f);
+                        static_cast<uint16_t*>(g.Y)[off] = f32_to_bf16(v);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES>
+static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
+    constexpr int SMEM = STAGES * (BM * 128 + BN * 16);
+    static_assert(SMEM <= 160 * 1024, "LDS budget");
+    const int64_t blocks = ((g.M + BM - 1) / BM) * ((g.NC + BN - 1) / BN);
+    if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
+    DmaArgs a;
+    a.g = g;
+    a.divIC = make_fastdiv_u(static_cast<uint32_t>(g.IC));
+    a.divS = make_fastdiv_u(static_cast<uint32_t>(g.S));
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    static bool allowed[2] = {false, false};
+    if (g.plain_gemm) {
+        auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, true>;
+        if (!allowed[0]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    SMEM) != hipSuccess) return TWN_ERR_HIP;
+            allowed[0] = true;
+        }
+        k<<<dim3(static_cast<unsigned>(blocks)), dim3(256), SMEM, st>>>(a);
+    } else {
+        auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, false>;
+        if (!allowed[1]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    SMEM) != hipSuccess) return TWN_ERR_HIP;
+            allowed[1] = true;
+        }
+        k<<<dim3(static_cast<unsigned>(blocks)), dim3(256), SMEM, st>>>(a);
+    }
+    return launch_status();
+}
+
+// Tile ids: 11 = 128x256 (3 stages), 12 = 128x128, 13 = 128x64, 14 = 256x256 (4 stages), 15 = 128x256 (4 stages)
+int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
+    switch (tile) {
+        case 11: return launch_dma_tile<128, 256, 2, 2, 3>(g, st);
+        case 12: return launch_dma_tile<128, 128, 2, 2, 3>(g, st);
+        case 13: return launch_dma_tile<128, 64, 4, 1, 3>(g, st);
+        case 14: return launch_dma_tile<256, 256, 2, 2, 4>(g, st);
+        case 15: return launch_dma_tile<128, 256, 2, 2, 4>(g, st);
+        case 16: return launch_dma_tile<256, 128, 2, 2, 3>(g, st);
+        default: return TWN_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace twn

@@ -38,6 +38,7 @@ struct GatherGemm {
 };
 
 int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st);
+int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 
 // dW[o][c][r][s] = beta*dW + sum_{n,p,q} X[n,ih,iw,c] * dY[n,p,q,o]; dbias[o] = sum dY.
