@@ -4,7 +4,7 @@
 //
 // Design, per workgroup tile BM (pixels) x BN (output channels), K slabs of 64:
 //   * activations: 16-byte global loads (8 bf16 of one tap) -> LDS, rows of
-//     128 bytes with the 16-byte chunk index XOR-swizzled by (row & 7), read
+//     128 bytes with the 16-byte chunk index XOR-swizzled by ((row >> 1) & 7), read
 //     back with ds_read_b128 as the A operand of v_mfma_f32_32x32x16_bf16;
 //   * weights never touch LDS: each lane loads the 32 packed codes (8 bytes)
 //     of its own output channel and its own half of the K slab straight from
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
             const int row = (tid >> 3) + i * ROWSTEP;
-            const int chunk = kc ^ (row & 7);
+            const int chunk = kc ^ ((row >> 1) & 7);
             *reinterpret_cast<u32x4*>(&lds[buf][row * 64 + chunk * 8]) = areg[i];
         }
     };
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 const int row = wm * TM + mi * 32 + lrow;
-                const int chunk = (lh * 4 + kk) ^ (row & 7);
+                const int chunk = (lh * 4 + kk) ^ ((row >> 1) & 7);
                 dst[mi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&lds[cur][row * 64 + chunk * 8]));
             }
         };
@@ -279,9 +279,15 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
     int tile = env_int("TWN_TILE", 0);
     if (mode != kModeScalar && (tile == 0 || tile > 10)) {
         // multi-stage direct-to-LDS kernel
-        if (tile == 0) tile = (g.NC <= 64) ? 13 : (g.NC <= 128) ? 12 : 11;
+        if (tile == 0) {
+            auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
+            if (g.NC <= 64) tile = 13;
+            else if (g.NC <= 128) tile = (blocks(256, 128) >= 512) ? 20 : 12;
+            else tile = (blocks(128, 256) >= 512) ? 17 : 12;
+        }
         return launch_gather_gemm_dma(g, tile, st);
     }
+    if (tile > 10) tile = 0;   // ids above 10 name tiles of the direct-to-LDS kernel
     if (tile == 0) {
         auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
         const int64_t want = 256;

@@ -6,7 +6,7 @@
 // alpha/2 applied in the fp32 epilogue), but every tile travels global -> LDS
 // by direct 16-byte LDS loads (global_load_lds_dwordx4), STAGES slabs deep:
 //   * per K slab of 64 a workgroup stages BM rows x 128 bytes of activations
-//     (16-byte chunks XOR-swizzled by row & 7: the swizzle is applied by
+//     (16-byte chunks XOR-swizzled by (row >> 1) & 7: the swizzle is applied by
 //     choosing which global chunk each lane fetches, because a direct LDS load
 //     always writes lane j of a wave at byte 16*j of its 1 KB destination) and
 //     BN x 16 bytes of packed codes (64 codes of each output channel);
@@ -60,20 +60,32 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
                                      (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 }
 
+// workgroups per CU the register allocation should allow: two waves per SIMD where LDS permits
+constexpr int dma_min_blocks(int nw, int smem) {
+    int by_waves = 8 / nw, by_lds = (160 * 1024) / smem;
+    int b = by_waves < by_lds ? by_waves : by_lds;
+    return b < 1 ? 1 : b;
+}
+
 template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM>
-__global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_gemm_dma_kernel(const DmaArgs a) {
-    static_assert(WM * WN == 4, "four waves per workgroup");
+__global__ __launch_bounds__(64 * WM * WN, dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
+void gather_gemm_dma_kernel(const DmaArgs a) {
+    constexpr int NW = WM * WN;                    // waves per workgroup
+    constexpr int NT = 64 * NW;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
-    constexpr int NLOAD = BM / 32;                 // 1 KB (8 rows) per wave-level load, 4 waves
+    constexpr int NLOAD = BM / (8 * NW);           // 1 KB (8 rows) per wave-level load
     constexpr int A_BYTES = BM * 128;
     constexpr int B_BYTES = BN * 16;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int PD = STAGES - 1;                 // slabs in flight ahead of the one being multiplied
     constexpr int PER_STAGE = NLOAD + 1;           // vector-memory loads per wave per slab
-    constexpr int EPI_ROW = 144;                   // bytes per pixel row of the epilogue staging (64 bf16 + pad)
-    constexpr int EPI_STAGE_BYTES = 4 * TM * EPI_ROW;
-    static_assert(BM % 32 == 0 && BN % 64 == 0 && TN % 64 == 0, "tile shape");
+    // epilogue staging: EPI_CH channels of every pixel row of a wave's tile at a time (64 when LDS allows)
+    constexpr int EPI_CH = (NW * TM * 144 + 2 * BN * 4 <= STAGES * STAGE_BYTES) ? 64 : 32;
+    constexpr int EPI_ROW = EPI_CH * 2 + 16;       // bytes per staged pixel row (pad keeps 16-byte reads conflict-free)
+    constexpr int EPI_NI = EPI_CH / 32;            // 32-channel MFMA tiles per staged chunk
+    constexpr int EPI_STAGE_BYTES = NW * TM * EPI_ROW;
+    static_assert(BM % (8 * NW) == 0 && BN % 64 == 0 && TN % 64 == 0 && TM % 32 == 0, "tile shape");
     static_assert(EPI_STAGE_BYTES + 2 * BN * 4 <= STAGES * STAGE_BYTES, "epilogue staging must fit in the pipeline LDS");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -97,13 +109,15 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_ge
     const uint32_t* __restrict__ Wq = static_cast<const uint32_t*>(g.Wq);
     const void* zero = kZeroBlock;
 
-    // ---- A loads: wave-level load i of this wave covers rows (i*4 + wave)*8 .. +7 ----
-    const int kc = (lane & 7) ^ ((lane >> 3) & 7);     // logical 16-byte chunk this lane fetches
+    // ---- A loads: wave-level load i of this wave covers rows (i*NW + wave)*8 .. +7 ----
+    // LDS row r keeps logical chunk c at position c ^ ((r >> 1) & 7): with 64 banks, 16 consecutive rows of
+    // one logical chunk then fall in 16 different 16-byte bank groups (conflict-free ds_read_b128)
+    const int kc = (lane & 7) ^ ((wave & 1) * 4 + ((lane >> 4) & 3));   // logical chunk this lane fetches
     int64_t abase[NLOAD];                              // GEMM: element offset of the row; conv: pixel base
     int ih0[NLOAD], iw0[NLOAD];
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
-        const int row = (i * 4 + wave) * 8 + (lane >> 3);
+        const int row = (i * NW + wave) * 8 + (lane >> 3);
         const int64_t m = m0 + row;
         if (m < g.M) {
             if (GEMM) {
@@ -149,7 +163,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_ge
 #pragma unroll
             for (int i = 0; i < NLOAD; ++i) {
                 const void* src = (kok && ih0[i] == 0) ? static_cast<const void*>(X + abase[i] + k) : zero;
-                dma16(src, sbase + (i * 4 + wave) * 1024);
+                dma16(src, sbase + (i * NW + wave) * 1024);
             }
         } else {
             const uint32_t rs = fdiv_u(static_cast<uint32_t>(k), a.divIC);
@@ -164,7 +178,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_ge
                 const void* src = ok ? static_cast<const void*>(
                                            X + (abase[i] + static_cast<int64_t>(th) * g.IW + tw) * g.xs + c)
                                      : zero;
-                dma16(src, sbase + (i * 4 + wave) * 1024);
+                dma16(src, sbase + (i * NW + wave) * 1024);
             }
         }
         const void* bs = (bsrc && kt < KT) ? static_cast<const void*>(bsrc + kt * 4) : zero;
@@ -204,7 +218,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_ge
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 const int row = wm * TM + mi * 32 + lrow;
-                const int chunk = (lh * 4 + kk) ^ (row & 7);
+                const int chunk = (lh * 4 + kk) ^ ((row >> 1) & 7);
                 dst[mi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sa + row * 128 + chunk * 16));
             }
         };
@@ -256,7 +270,7 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_ge
     //   channel n = wn*TN + ni*32 + (e>>2)*8 + lh*4 + (e&3)
     float* colmul = reinterpret_cast<float*>(smem + EPI_STAGE_BYTES);   // [BN] 0.5*alpha*scale
     float* coladd = colmul + BN;                                        // [BN] shift
-    for (int i = tid; i < BN; i += 256) {
+    for (int i = tid; i < BN; i += NT) {
         const int ncol = n0 + i;
         float mul = 0.0f, add = 0.0f;
         if (ncol < g.NC) {
@@ -271,18 +285,18 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_ge
     const bool vec_store = !g.y_f32 && (g.NC % 8 == 0) && (g.ldy % 8 == 0);
     if (vec_store) {
         // bf16 output: finish each value in fp32, round once, transpose 64-channel chunks through
-        // LDS (this wave's own region) and write 16 bytes per lane, 128 contiguous bytes per pixel
+        // LDS (this wave's own region) and write 16 bytes per lane, 64-128 contiguous bytes per pixel
         unsigned char* stg = smem + wave * (TM * EPI_ROW);
         const uint16_t* res = static_cast<const uint16_t*>(g.residual);
         uint16_t* Yb = static_cast<uint16_t*>(g.Y);
 #pragma unroll
-        for (int nc = 0; nc < NI / 2; ++nc) {
+        for (int nc = 0; nc < NI / EPI_NI; ++nc) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 const int64_t m = m0 + wm * TM + mi * 32 + lrow;
 #pragma unroll
-                for (int nh = 0; nh < 2; ++nh) {
-                    const int ni = nc * 2 + nh;
+                for (int nh = 0; nh < EPI_NI; ++nh) {
+                    const int ni = nc * EPI_NI + nh;
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4) {
                         const int nl = wn * TN + ni * 32 + q4 * 8 + lh * 4;     // column within the block tile
@@ -310,13 +324,14 @@ __global__ __launch_bounds__(256, (BM * BN <= 128 * 256) ? 2 : 1) void gather_ge
                 }
             }
             // same wave wrote and reads: LDS executes a wave's operations in order
+            constexpr int LPR = EPI_CH / 8;          // lanes per staged row (16 bytes each)
 #pragma unroll
-            for (int it = 0; it < TM / 8; ++it) {
-                const int row = it * 8 + (lane >> 3);
-                const int c16 = lane & 7;
+            for (int it = 0; it < TM * LPR / 64; ++it) {
+                const int row = it * (64 / LPR) + lane / LPR;
+                const int c16 = lane % LPR;
                 const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
                 const int64_t m = m0 + wm * TM + row;
-                const int ncol = n0 + wn * TN + nc * 64 + c16 * 8;
+                const int ncol = n0 + wn * TN + nc * EPI_CH + c16 * 8;
                 if (m < g.M && ncol < g.NC) *reinterpret_cast<u32x4*>(Yb + m * g.ldy + ncol) = val;
             }
         }
@@ -368,7 +383,7 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
                                     SMEM) != hipSuccess) return TWN_ERR_HIP;
             allowed[0] = true;
         }
-        k<<<dim3(static_cast<unsigned>(blocks)), dim3(256), SMEM, st>>>(a);
+        k<<<dim3(static_cast<unsigned>(blocks)), dim3(64 * WM * WN), SMEM, st>>>(a);
     } else {
         auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, false>;
         if (!allowed[1]) {
@@ -376,7 +391,7 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
                                     SMEM) != hipSuccess) return TWN_ERR_HIP;
             allowed[1] = true;
         }
-        k<<<dim3(static_cast<unsigned>(blocks)), dim3(256), SMEM, st>>>(a);
+        k<<<dim3(static_cast<unsigned>(blocks)), dim3(64 * WM * WN), SMEM, st>>>(a);
     }
     return launch_status();
 }
@@ -390,6 +405,13 @@ int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
         case 14: return launch_dma_tile<256, 256, 2, 2, 4>(g, st);
         case 15: return launch_dma_tile<128, 256, 2, 2, 4>(g, st);
         case 16: return launch_dma_tile<256, 128, 2, 2, 3>(g, st);
+        case 17: return launch_dma_tile<128, 256, 1, 4, 4>(g, st);
+        case 18: return launch_dma_tile<256, 256, 2, 4, 4>(g, st);
+        case 19: return launch_dma_tile<256, 256, 4, 2, 4>(g, st);
+        case 20: return launch_dma_tile<256, 128, 2, 2, 2>(g, st);
+        case 21: return launch_dma_tile<128, 128, 1, 2, 4>(g, st);
+        case 22: return launch_dma_tile<256, 64, 4, 1, 3>(g, st);
+        case 23: return launch_dma_tile<256, 64, 2, 1, 3>(g, st);
         default: return TWN_ERR_UNSUPPORTED;
     }
 }
