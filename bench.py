@@ -78,6 +78,8 @@ def main():
                                dtype=torch.uint8, device=dev))
     tern_ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
     geo = [((L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2) for L in layers]
+    wsf = [torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tws[li], *geo[li])), dtype=torch.uint8,
+                       device=dev) for li, L in enumerate(layers)]
 
     flops_fwd = sum(L.flops for L in layers)
     flops_dx = sum(L.flops for L in layers[1:])
@@ -92,7 +94,8 @@ def main():
     def do_fwd():
         for li in range(len(layers)):
             st, pd, dl = geo[li]
-            api.twn_conv2d_fwd(X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li], relu=True, out=Y[li])
+            api.twn_conv2d_fwd(X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li], relu=True, out=Y[li],
+                               workspace=wsf[li])
 
     def do_dx():
         for li in range(len(layers) - 1, 0, -1):
@@ -161,7 +164,7 @@ def main():
     for li, L in enumerate(layers):
         st, pd, dl = geo[li]
         tf = time_call(lambda: api.twn_conv2d_fwd(X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li],
-                                                  relu=True, out=Y[li]))
+                                                  relu=True, out=Y[li], workspace=wsf[li]))
         tdx = time_call(lambda: api.twn_conv2d_bwd_ste(None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False,
                                                        dX=dX[li], x_shape=L.x_shape, workspace=wsb[li])) if li else float("nan")
         tdw = time_call(lambda: api.twn_conv2d_bwd_ste(X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True,
@@ -210,7 +213,10 @@ def main():
             sc = torch.ones(L.O, dtype=torch.float32, device=dev)
             sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
             st, pd, dl = (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2
-            t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y), reps=10)
+            ws = torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tw, st, pd, dl)), dtype=torch.uint8,
+                             device=dev)
+            t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y,
+                                                     workspace=ws), reps=10)
             tot += t
             log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq" % (L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
             del x, y

@@ -197,8 +197,16 @@ def _epilogue(scale, shift, residual, relu):
                     None if residual is None else residual.data_ptr(), 1 if relu else 0)
 
 
+def twn_gemm_fwd_workspace_bytes(m, tw, x_dtype=torch.bfloat16, y_dtype=torch.bfloat16, variant=None):
+    if variant is None:
+        variant = TWN_VAR_FP32 if x_dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
+    code = {torch.float32: TWN_F32, torch.bfloat16: TWN_BF16}
+    d = GemmDesc(m, tw.rows, tw.K, code[x_dtype], code[y_dtype], variant, 0, 0, tw.groups)
+    return int(lib().twn_gemm_fwd_workspace_bytes(ctypes.byref(d)))
+
+
 def twn_gemm_fwd(X, tw, y_dtype=torch.bfloat16, variant=None, scale=None, shift=None, residual=None,
-                 relu=False, out=None, stream=None):
+                 relu=False, out=None, workspace=None, stream=None):
     """Y[M][N] = alpha * X[M][K] . W~[N][K]^T; X bf16 (MFMA) or float32 (fp32 variant)."""
     m, k = X.shape
     if k != tw.K:
@@ -208,8 +216,13 @@ def twn_gemm_fwd(X, tw, y_dtype=torch.bfloat16, variant=None, scale=None, shift=
     Y = out if out is not None else torch.empty((m, tw.rows), dtype=y_dtype, device=X.device)
     d = GemmDesc(m, tw.rows, k, _dtype_code(X), _dtype_code(Y), variant, X.stride(0), Y.stride(0), tw.groups)
     ep = _epilogue(scale, shift, residual, relu)
-    rc = lib().twn_gemm_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
-                            None if ep is None else ctypes.byref(ep), _ptr(Y), None, 0, _stream(stream))
+    L = lib()
+    if workspace is None:
+        need = L.twn_gemm_fwd_workspace_bytes(ctypes.byref(d))
+        workspace = _workspace(need, X.device) if need else None
+    rc = L.twn_gemm_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
+                        None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
+                        0 if workspace is None else workspace.numel(), _stream(stream))
     _check(rc, "twn_gemm_fwd")
     return Y
 
@@ -229,8 +242,17 @@ def conv_out_shape(x_shape, tw, stride, pad, dil):
     return (n, p, q, tw.rows)
 
 
+def twn_conv2d_fwd_workspace_bytes(x_shape, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), x_dtype=torch.bfloat16,
+                                   y_dtype=torch.bfloat16, variant=None):
+    if variant is None:
+        variant = TWN_VAR_FP32 if x_dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
+    code = {torch.float32: TWN_F32, torch.bfloat16: TWN_BF16}
+    d = _conv_desc(x_shape, tw, stride, pad, dil, code[x_dtype], code[y_dtype], variant)
+    return int(lib().twn_conv2d_fwd_workspace_bytes(ctypes.byref(d)))
+
+
 def twn_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), y_dtype=torch.bfloat16, variant=None,
-                   scale=None, shift=None, residual=None, relu=False, out=None, stream=None):
+                   scale=None, shift=None, residual=None, relu=False, out=None, workspace=None, stream=None):
     """X NHWC; returns Y NHWC [N][P][Q][O]."""
     if variant is None:
         variant = TWN_VAR_FP32 if X.dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
@@ -238,8 +260,13 @@ def twn_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), y_dtype=torch.b
                                                 device=X.device)
     d = _conv_desc(X.shape, tw, stride, pad, dil, _dtype_code(X), _dtype_code(Y), variant)
     ep = _epilogue(scale, shift, residual, relu)
-    rc = lib().twn_conv2d_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
-                              None if ep is None else ctypes.byref(ep), _ptr(Y), None, 0, _stream(stream))
+    L = lib()
+    if workspace is None:
+        need = L.twn_conv2d_fwd_workspace_bytes(ctypes.byref(d))
+        workspace = _workspace(need, X.device) if need else None
+    rc = L.twn_conv2d_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
+                          None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
+                          0 if workspace is None else workspace.numel(), _stream(stream))
     _check(rc, "twn_conv2d_fwd")
     return Y
 

@@ -5,7 +5,15 @@
 //
 // Dense bf16 x bf16 -> fp32 MFMA GEMM  D[o][j] = sum_pix dY[pix][o] * Xg[pix][j],
 // j = (r*S+s)*C + c.  The reduction index (pixels) is the slow index of both
-// NHWC operands, so tiles are transposed on their way into LDS: a thread loads
+// NHWC operands, so MFMA fragments (8 consecutive pixels of one channel per
+// lane) need a transpose.  Main kernel (weight_grad_dma_kernel, channel counts
+// multiples of 8): both tiles go global -> LDS untransposed with direct 16-byte
+// LDS loads, two slabs of 64 pixels deep, and fragments are fetched with the
+// gfx950 transposing LDS read ds_read_tr16_b64 (a 16-lane group reads a 4 pixel
+// x 16 channel block and each lane receives 4 consecutive pixels of its own
+// channel); 16-byte chunks are XOR-swizzled by 2*(pixel & 3) so the four pixel
+// rows of a block fall in different banks.  Fallback kernel (weight_grad_kernel,
+// any channel count): tiles are transposed on their way into LDS: a thread loads
 // the same 8 channels of two neighbouring pixels (2 x 16 bytes, coalesced
 // across lanes along the channel axis), interleaves them into eight 32-bit
 // words {pixel, pixel+1} and writes those to rows [channel][pixel].  MFMA
@@ -225,22 +233,182 @@ __global__ __launch_bounds__(256) void weight_grad_kernel(const WGArgs a) {
         }
 }
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __attribute__((aligned(16))) const uint32_t kWgZeroBlock[4] = {0u, 0u, 0u, 0u};
+
+constexpr int wg_vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+__device__ __forceinline__ void wg_dma16(const void* gsrc, void* lds_dst) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
+}
+
+// 8 consecutive pixels of one channel for this lane: two transposing reads of 4 pixels each.
+// `base` points at (pixel of this lane's group row, channel block) as described in the file header.
+__device__ __forceinline__ bf16x8 wg_frag(const unsigned char* p0, const unsigned char* p1) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int STAGES>
+__global__ __launch_bounds__(256, 2) void weight_grad_dma_kernel(const WGArgs a) {
+    constexpr int TILE_BYTES = 64 * 256;            // 64 pixels x 128 channels bf16
+    constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+    constexpr int PD = STAGES - 1;
+    constexpr int PER_STAGE = 8;                    // direct LDS loads per wave per slab
+    extern __shared__ __attribute__((aligned(1024))) unsigned char wsm[];
+
+    const WeightGrad& w = a.w;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lh = lane >> 5;
+
+    const int tiles_j = (a.J + kWgTile - 1) / kWgTile;
+    const int o0 = static_cast<int>(blockIdx.x / tiles_j) * kWgTile;
+    const int j0 = static_cast<int>(blockIdx.x % tiles_j) * kWgTile;
+    const int split = blockIdx.y;
+    const int64_t slab_begin = static_cast<int64_t>(split) * a.slabs_per_split;
+    const int64_t total_slabs = (a.pixels + 63) / 64;
+    int64_t slab_end = slab_begin + a.slabs_per_split;
+    if (slab_end > total_slabs) slab_end = total_slabs;
+    const int nslab = static_cast<int>(slab_end - slab_begin);
+    const void* zero = kWgZeroBlock;
+
+    // ---- loader: one wave-level load covers 4 pixel rows x 256 bytes; lane -> (row, 16-byte slot) ----
+    const int prow = lane >> 4;
+    const int qch = (lane & 15) ^ (2 * (prow & 3));     // logical 8-channel chunk fetched by this lane
+    const int oo = o0 + qch * 8;
+    const int jj = j0 + qch * 8;
+    const uint32_t rs = fdiv(jj, a.divC);
+    const int tc = jj - static_cast<int>(rs) * w.C;
+    const int tr = static_cast<int>(fdiv(rs, a.divS));
+    const int ts = static_cast<int>(rs) - tr * w.S;
+    const bool ook = oo < w.O, jok = jj < a.J;
+
+    auto issue = [&](int64_t slab, int stage, bool live) {
+        unsigned char* sA = wsm + stage * STAGE_BYTES;
+        unsigned char* sB = sA + TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t pix = slab * 64 + (i * 4 + wave) * 4 + prow;
+            const bool pok = live && pix < a.pixels;
+            const void* srcA = (pok && ook) ? static_cast<const void*>(w.dY + pix * w.O + oo) : zero;
+            const void* srcB = zero;
+            if (pok && jok) {
+                const uint32_t n = fdiv(static_cast<uint32_t>(pix), a.divPQ);
+                const uint32_t rem = static_cast<uint32_t>(pix) - n * a.divPQ.d;
+                const uint32_t p = fdiv(rem, a.divQ);
+                const uint32_t q = rem - p * w.Q;
+                const int ih = static_cast<int>(p) * w.sh - w.ph + tr * w.dh;
+                const int iw = static_cast<int>(q) * w.sw - w.pw + ts * w.dw;
+                if (static_cast<unsigned>(ih) < static_cast<unsigned>(w.H) &&
+                    static_cast<unsigned>(iw) < static_cast<unsigned>(w.W))
+                    srcB = w.X + ((static_cast<int64_t>(n) * w.H + ih) * w.W + iw) * w.C + tc;
+            }
+            wg_dma16(srcA, sA + (i * 4 + wave) * 1024);
+            wg_dma16(srcB, sB + (i * 4 + wave) * 1024);
+        }
+    };
+
+    // ---- fragment addressing (transposing read): lane -> (pixel row in its 4-row block, 4-channel sub-block) ----
+    const int li = lane & 15;
+    const int fpix = 8 * lh + (li >> 2);                 // + 16*kk (+4 for the second read)
+    const int fch = 16 * ((lane >> 4) & 1) + 4 * (li & 3);   // + wave tile offset + 32*mi
+    auto frag_addr = [&](const unsigned char* tile, int chan0, int pixel) -> const unsigned char* {
+        const int ch = chan0 + fch;
+        const int chunk = (ch >> 3) ^ (2 * (pixel & 3));
+        return tile + pixel * 256 + chunk * 16 + (ch & 7) * 2;
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
+
+#pragma unroll
+    for (int s = 0; s < PD; ++s) issue(slab_begin + s, s, s < nslab);
+    __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 1) * PER_STAGE));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    int stage = 0, fill = PD;
+    for (int it = 0; it < nslab; ++it) {
+        issue(slab_begin + it + PD, fill, it + PD < nslab);
+        const unsigned char* sA = wsm + stage * STAGE_BYTES;
+        const unsigned char* sB = sA + TILE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int pixel = kk * 16 + fpix;
+            bf16x8 af[2], bfr[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+                af[mi] = wg_frag(frag_addr(sA, wm * 64 + mi * 32, pixel), frag_addr(sA, wm * 64 + mi * 32, pixel + 4));
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                bfr[ni] = wg_frag(frag_addr(sB, wn * 64 + ni * 32, pixel), frag_addr(sB, wn * 64 + ni * 32, pixel + 4));
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 1) * PER_STAGE));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+        fill = (fill + 1 == STAGES) ? 0 : fill + 1;
+    }
+    __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm(0));
+
+    float* out = w.partial + static_cast<int64_t>(split) * w.O * a.J;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int j = j0 + wn * 64 + ni * 32 + lrow;
+            if (j >= a.J) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int o = o0 + wm * 64 + mi * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+                if (o < w.O) out[static_cast<int64_t>(o) * a.J + j] = acc[mi][ni][e];
+            }
+        }
+}
+
 // dW[o][c][r][s] = beta*dW + sum over splits (fixed order) of partial[split][o][(r*S+s)*C + c]
 __global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __restrict__ partial, int splits,
                                                                  int O, int C, int RS, float beta,
                                                                  float* __restrict__ dW) {
-    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    // 64 consecutive partial elements per block (coalesced over the large input), 4 thread rows that
+    // each sum every 4th split; the rows are combined in a fixed order and the small output is scattered
+    __shared__ float red[4][64];
+    const int col = threadIdx.x & 63, rowi = threadIdx.x >> 6;
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * 64 + col;
     const int64_t J = static_cast<int64_t>(RS) * C;
     const int64_t total = J * O;
-    if (id >= total) return;
-    const int64_t o = id / J;
-    const int64_t rem = id - o * J;      // = c*RS + rs in the [O][C][R][S] layout
-    const int64_t c = rem / RS;
-    const int64_t rs = rem - c * RS;
-    const int64_t src = o * J + rs * C + c;
     float s = 0.0f;
-    for (int sp = 0; sp < splits; ++sp) s += partial[static_cast<int64_t>(sp) * total + src];
-    dW[id] = (beta != 0.0f) ? beta * dW[id] + s : s;
+    if (id < total)
+        for (int sp = rowi; sp < splits; sp += 4) s += partial[static_cast<int64_t>(sp) * total + id];
+    red[rowi][col] = s;
+    __syncthreads();
+    if (rowi != 0 || id >= total) return;
+    s = ((red[0][col] + red[1][col]) + red[2][col]) + red[3][col];
+    const int64_t o = id / J;
+    const int64_t j = id - o * J;        // = rs*C + c in the partial tiles
+    const int64_t rs = j / C;
+    const int64_t c = j - rs * C;
+    const int64_t dst = o * J + c * RS + rs;   // [O][C][R][S]
+    dW[dst] = (beta != 0.0f) ? beta * dW[dst] + s : s;
 }
 
 // dbias partials: block (x = 64-channel group, y = pixel split) sums its pixel range.
@@ -274,7 +442,7 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float* __res
 int32_t weight_grad_splits(int64_t pixels, int32_t O, int64_t J) {
     const int64_t tiles = ((O + kWgTile - 1) / kWgTile) * ((J + kWgTile - 1) / kWgTile);
     const int64_t slabs = (pixels + 63) / 64;
-    int64_t want = env_int("TWN_WG_BLOCKS", 1024);
+    int64_t want = env_int("TWN_WG_BLOCKS", 512);
     int64_t splits = (want + tiles - 1) / tiles;
     if (splits > slabs) splits = slabs;
     if (splits > 1024) splits = 1024;
@@ -301,10 +469,24 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
         const int tiles = ((w.O + kWgTile - 1) / kWgTile) * ((a.J + kWgTile - 1) / kWgTile);
         const dim3 grid(tiles, w.splits);
         const bool vec = (w.C % 8 == 0) && (w.O % 8 == 0);
-        if (vec) weight_grad_kernel<true><<<grid, 256, 0, st>>>(a);
-        else weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
+        if (vec && env_int("TWN_WG_DMA", 1)) {
+            constexpr int kStages = 2;
+            constexpr int kSmem = kStages * 2 * 64 * 256;
+            static bool allowed = false;
+            auto k = weight_grad_dma_kernel<kStages>;
+            if (!allowed) {
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        kSmem) != hipSuccess) return TWN_ERR_HIP;
+                allowed = true;
+            }
+            k<<<grid, 256, kSmem, st>>>(a);
+        } else if (vec) {
+            weight_grad_kernel<true><<<grid, 256, 0, st>>>(a);
+        } else {
+            weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
+        }
         const int64_t total = static_cast<int64_t>(w.O) * a.J;
-        weight_grad_reduce_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(
+        weight_grad_reduce_kernel<<<static_cast<unsigned>((total + 63) / 64), 256, 0, st>>>(
             w.partial, w.splits, w.O, w.C, w.R * w.S, w.beta, w.dW);
     }
     if (w.dbias) {

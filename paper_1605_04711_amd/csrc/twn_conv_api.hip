@@ -51,47 +51,29 @@ void set_epilogue(GatherGemm& g, const twn_epilogue* ep) {
     g.relu = ep ? (ep->relu != 0) : 0;
 }
 
-int32_t dispatch(const GatherGemm& g, int variant, hipStream_t st) {
+size_t splitk_bytes(const GatherGemm& g, int variant) {
+    if (variant == TWN_VAR_FP32) return 0;
+    const int32_t splits = gather_gemm_splits(g);
+    return splits > 1 ? static_cast<size_t>(splits) * static_cast<size_t>(g.M) * g.NC * sizeof(float) : 0;
+}
+
+// Attaches the split-K workspace (if the problem uses one) and launches.
+int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_bytes, hipStream_t st) {
     if (variant == TWN_VAR_FP32) return launch_gather_gemm_fp32(g, st);
+    g.splits = gather_gemm_splits(g);
+    g.partial = nullptr;
+    if (g.splits > 1) {
+        const size_t need = static_cast<size_t>(g.splits) * static_cast<size_t>(g.M) * g.NC * sizeof(float);
+        if (!workspace || workspace_bytes < need || !aligned(workspace, 16)) return TWN_ERR_WORKSPACE;
+        g.partial = static_cast<float*>(workspace);
+    }
     return launch_gather_gemm_mfma(g, variant, st);
 }
 
-}  // namespace
-
-extern "C" size_t twn_gemm_fwd_workspace_bytes(const twn_gemm_desc* d) {
-    (void)d;
-    return 0;
-}
-
-extern "C" int32_t twn_gemm_fwd(const twn_gemm_desc* d, const void* X, const void* weights,
-                                const float* alpha, const twn_epilogue* ep, void* Y,
-                                void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
-    if (!d || !X || !weights || !alpha || !Y) return TWN_ERR_NULL;
-    if (d->M <= 0 || d->N <= 0 || d->K <= 0 || d->M >= (1LL << 31) || d->K >= (1 << 30)) return TWN_ERR_SHAPE;
-    if (d->alpha_groups < 1 || d->N % d->alpha_groups != 0) return TWN_ERR_SHAPE;
-    int32_t rc = check_dtype(d->x_dtype);
-    if (rc == TWN_OK) rc = check_dtype(d->y_dtype);
-    if (rc == TWN_OK) rc = check_variant(d->variant, d->x_dtype);
-    if (rc != TWN_OK) return rc;
-    const int64_t ldx = d->ldx ? d->ldx : d->K;
-    const int64_t ldy = d->ldy ? d->ldy : d->N;
-    if (ldx < d->K || ldy < d->N) return TWN_ERR_SHAPE;
-    if (!aligned(weights, 16)) return TWN_ERR_ALIGN;
-    if (d->x_dtype == TWN_BF16 && !aligned(X, 2)) return TWN_ERR_ALIGN;
-    if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
-    if (d->x_dtype == TWN_BF16 && d->K % 8 == 0 && ldx % 8 == 0 && !aligned(X, 16)) return TWN_ERR_ALIGN;
-
-    GatherGemm g{};
-    g.X = X;
-    g.Wq = weights;
-    g.alpha = alpha;
-    set_epilogue(g, ep);
-    g.Y = Y;
+void fill_gemm(GatherGemm& g, const twn_gemm_desc* d) {
     g.M = d->M;
-    g.xs = ldx;
-    g.ldy = ldy;
+    g.xs = d->ldx ? d->ldx : d->K;
+    g.ldy = d->ldy ? d->ldy : d->N;
     g.IH = g.IW = g.OH = g.OW = 1;
     g.IC = d->K;
     g.NC = d->N;
@@ -103,37 +85,9 @@ extern "C" int32_t twn_gemm_fwd(const twn_gemm_desc* d, const void* X, const voi
     g.rows_per_group = d->N / d->alpha_groups;
     g.y_f32 = (d->y_dtype == TWN_F32);
     g.plain_gemm = 1;
-    return dispatch(g, d->variant, as_stream(stream));
 }
 
-extern "C" size_t twn_conv2d_fwd_workspace_bytes(const twn_conv_desc* d) {
-    (void)d;
-    return 0;
-}
-
-extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weights,
-                                  const float* alpha, const twn_epilogue* ep, void* Y,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
-    int P, Q;
-    int32_t rc = check_conv_desc(d, &P, &Q);
-    if (rc != TWN_OK) return rc;
-    if (!X || !weights || !alpha || !Y) return TWN_ERR_NULL;
-    rc = check_dtype(d->x_dtype);
-    if (rc == TWN_OK) rc = check_dtype(d->y_dtype);
-    if (rc == TWN_OK) rc = check_variant(d->variant, d->x_dtype);
-    if (rc != TWN_OK) return rc;
-    if (!aligned(weights, 16)) return TWN_ERR_ALIGN;
-    if (d->x_dtype == TWN_BF16 && !aligned(X, (d->C % 8 == 0) ? 16 : 2)) return TWN_ERR_ALIGN;
-    if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
-
-    GatherGemm g{};
-    g.X = X;
-    g.Wq = weights;
-    g.alpha = alpha;
-    set_epilogue(g, ep);
-    g.Y = Y;
+void fill_conv_fwd(GatherGemm& g, const twn_conv_desc* d, int P, int Q) {
     g.M = static_cast<int64_t>(d->N) * P * Q;
     g.xs = d->C;
     g.ldy = d->O;
@@ -158,16 +112,123 @@ extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const v
     g.y_f32 = (d->y_dtype == TWN_F32);
     g.plain_gemm = (d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 &&
                     d->pad_w == 0);
-    return dispatch(g, d->variant, as_stream(stream));
+}
+
+// dX = gather over dY: row (n,h,w), k = (r,s,o):
+//   p = (h + ph - r*dh)/sh when divisible, q likewise; weights = transposed packed copy.
+void fill_conv_bwd_data(GatherGemm& g, const twn_conv_desc* d, int P, int Q) {
+    g.M = static_cast<int64_t>(d->N) * d->H * d->W;
+    g.xs = d->O;
+    g.ldy = d->C;
+    g.IH = P;
+    g.IW = Q;
+    g.IC = d->O;
+    g.OH = d->H;
+    g.OW = d->W;
+    g.NC = d->C;
+    g.R = d->R;
+    g.S = d->S;
+    g.sh = g.sw = 1;
+    g.ph = -d->pad_h;
+    g.pw = -d->pad_w;
+    g.dh = -d->dil_h;
+    g.dw = -d->dil_w;
+    g.divh = d->stride_h;
+    g.divw = d->stride_w;
+    g.K = d->R * d->S * d->O;
+    g.wpr = static_cast<int32_t>(twn_packed_words_per_row(g.K));
+    g.rows_per_group = d->C;
+    g.y_f32 = (d->y_dtype == TWN_F32);
+    g.plain_gemm = (d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 &&
+                    d->pad_w == 0);
+}
+
+size_t weight_grad_bytes(const twn_conv_desc* d, int P, int Q) {
+    const int64_t pixels = static_cast<int64_t>(d->N) * P * Q;
+    const int64_t J = static_cast<int64_t>(d->R) * d->S * d->C;
+    const int64_t splits = weight_grad_splits(pixels, d->O, J);
+    return static_cast<size_t>((splits * d->O * J + 64LL * d->O) * sizeof(float));
+}
+
+}  // namespace
+
+extern "C" size_t twn_gemm_fwd_workspace_bytes(const twn_gemm_desc* d) {
+    if (!d || d->M <= 0 || d->N <= 0 || d->K <= 0 || d->alpha_groups < 1) return 0;
+    GatherGemm g{};
+    fill_gemm(g, d);
+    return splitk_bytes(g, d->variant);
+}
+
+extern "C" int32_t twn_gemm_fwd(const twn_gemm_desc* d, const void* X, const void* weights,
+                                const float* alpha, const twn_epilogue* ep, void* Y,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (!d || !X || !weights || !alpha || !Y) return TWN_ERR_NULL;
+    if (d->M <= 0 || d->N <= 0 || d->K <= 0 || d->M >= (1LL << 31) || d->K >= (1 << 30)) return TWN_ERR_SHAPE;
+    if (d->alpha_groups < 1 || d->N % d->alpha_groups != 0) return TWN_ERR_SHAPE;
+    int32_t rc = check_dtype(d->x_dtype);
+    if (rc == TWN_OK) rc = check_dtype(d->y_dtype);
+    if (rc == TWN_OK) rc = check_variant(d->variant, d->x_dtype);
+    if (rc != TWN_OK) return rc;
+    const int64_t ldx = d->ldx ? d->ldx : d->K;
+    const int64_t ldy = d->ldy ? d->ldy : d->N;
+    if (ldx < d->K || ldy < d->N) return TWN_ERR_SHAPE;
+    if (!aligned(weights, 16)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_BF16 && !aligned(X, 2)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_BF16 && d->K % 8 == 0 && ldx % 8 == 0 && !aligned(X, 16)) return TWN_ERR_ALIGN;
+
+    GatherGemm g{};
+    g.X = X;
+    g.Wq = weights;
+    g.alpha = alpha;
+    set_epilogue(g, ep);
+    g.Y = Y;
+    fill_gemm(g, d);
+    return dispatch(g, d->variant, workspace, workspace_bytes, as_stream(stream));
+}
+
+extern "C" size_t twn_conv2d_fwd_workspace_bytes(const twn_conv_desc* d) {
+    int P, Q;
+    if (check_conv_desc(d, &P, &Q) != TWN_OK) return 0;
+    GatherGemm g{};
+    fill_conv_fwd(g, d, P, Q);
+    return splitk_bytes(g, d->variant);
+}
+
+extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weights,
+                                  const float* alpha, const twn_epilogue* ep, void* Y,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    int P, Q;
+    int32_t rc = check_conv_desc(d, &P, &Q);
+    if (rc != TWN_OK) return rc;
+    if (!X || !weights || !alpha || !Y) return TWN_ERR_NULL;
+    rc = check_dtype(d->x_dtype);
+    if (rc == TWN_OK) rc = check_dtype(d->y_dtype);
+    if (rc == TWN_OK) rc = check_variant(d->variant, d->x_dtype);
+    if (rc != TWN_OK) return rc;
+    if (!aligned(weights, 16)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_BF16 && !aligned(X, (d->C % 8 == 0) ? 16 : 2)) return TWN_ERR_ALIGN;
+    if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
+
+    GatherGemm g{};
+    g.X = X;
+    g.Wq = weights;
+    g.alpha = alpha;
+    set_epilogue(g, ep);
+    g.Y = Y;
+    fill_conv_fwd(g, d, P, Q);
+    return dispatch(g, d->variant, workspace, workspace_bytes, as_stream(stream));
 }
 
 extern "C" size_t twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d) {
     int P, Q;
     if (check_conv_desc(d, &P, &Q) != TWN_OK) return 0;
-    const int64_t pixels = static_cast<int64_t>(d->N) * P * Q;
-    const int64_t J = static_cast<int64_t>(d->R) * d->S * d->C;
-    const int64_t splits = weight_grad_splits(pixels, d->O, J);
-    return static_cast<size_t>((splits * d->O * J + 64LL * d->O) * sizeof(float));
+    // the data-gradient split-K partials and the weight-gradient partials use the workspace one after the other
+    GatherGemm g{};
+    fill_conv_bwd_data(g, d, P, Q);
+    const size_t a = splitk_bytes(g, TWN_VAR_BF16_POSTSCALE);
+    const size_t b = weight_grad_bytes(d, P, Q);
+    return a > b ? a : b;
 }
 
 extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY,
@@ -189,47 +250,22 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
     if (packed_T && !aligned(packed_T, 16)) return TWN_ERR_ALIGN;
     if (dW && !aligned(dW, 4)) return TWN_ERR_ALIGN;
     if (dW || dbias) {
-        const size_t need = twn_conv2d_bwd_ste_workspace_bytes(d);
+        const size_t need = weight_grad_bytes(d, P, Q);
         if (!workspace || workspace_bytes < need || !aligned(workspace, 16)) return TWN_ERR_WORKSPACE;
     }
     hipStream_t st = as_stream(stream);
 
     if (dX) {
-        // dX = gather over dY: row (n,h,w), k = (r,s,o):
-        //   p = (h + ph - r*dh)/sh when divisible, q likewise; weights = transposed packed copy.
+        // alpha multiplies per forward output channel o, which is a K index here: only a
+        // single alpha can be applied after the sum.
+        if (d->alpha_groups != 1) return TWN_ERR_UNSUPPORTED;
         GatherGemm g{};
         g.X = dY;
         g.Wq = packed_T;
         g.alpha = alpha;
         g.Y = dX;
-        g.M = static_cast<int64_t>(d->N) * d->H * d->W;
-        g.xs = d->O;
-        g.ldy = d->C;
-        g.IH = P;
-        g.IW = Q;
-        g.IC = d->O;
-        g.OH = d->H;
-        g.OW = d->W;
-        g.NC = d->C;
-        g.R = d->R;
-        g.S = d->S;
-        g.sh = g.sw = 1;
-        g.ph = -d->pad_h;
-        g.pw = -d->pad_w;
-        g.dh = -d->dil_h;
-        g.dw = -d->dil_w;
-        g.divh = d->stride_h;
-        g.divw = d->stride_w;
-        g.K = d->R * d->S * d->O;
-        g.wpr = static_cast<int32_t>(twn_packed_words_per_row(g.K));
-        // alpha multiplies per forward output channel o, which is a K index here: only a
-        // single alpha can be applied after the sum.
-        if (d->alpha_groups != 1) return TWN_ERR_UNSUPPORTED;
-        g.rows_per_group = d->C;
-        g.y_f32 = (d->y_dtype == TWN_F32);
-        g.plain_gemm = (d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 &&
-                        d->pad_w == 0);
-        rc = launch_gather_gemm_mfma(g, TWN_VAR_BF16_POSTSCALE, st);
+        fill_conv_bwd_data(g, d, P, Q);
+        rc = dispatch(g, TWN_VAR_BF16_POSTSCALE, workspace, workspace_bytes, st);
         if (rc != TWN_OK) return rc;
     }
     if (dW || dbias) {

@@ -269,11 +269,29 @@ static int32_t launch_tile(const GatherGemm& g, int mode, hipStream_t st) {
     return launch_status();
 }
 
+static int gather_mode(const GatherGemm& g) {
+    if (g.IC % 8 != 0 || g.xs % 8 != 0) return kModeScalar;
+    return g.plain_gemm ? kModeGemm : kModeVec8;
+}
+
+int32_t gather_gemm_splits(const GatherGemm& g) {
+    // split K when 128x128 tiles alone cannot fill the chip and K is deep enough to share out
+    if (gather_mode(g) == kModeScalar || env_int("TWN_TILE", 0) != 0) return 1;
+    const int64_t blocks = ((g.M + 127) / 128) * ((g.NC + 127) / 128);
+    const int KT = (g.K + 63) / 64;
+    if (blocks >= 192 || KT < 8) return 1;
+    int64_t splits = (448 + blocks - 1) / blocks;
+    if (splits > KT / 4) splits = KT / 4;
+    if (splits > 32) splits = 32;
+    if (splits < 1) splits = 1;
+    // every range must own at least one slab
+    const int kps = static_cast<int>((KT + splits - 1) / splits);
+    return static_cast<int32_t>((KT + kps - 1) / kps);
+}
+
 int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st) {
     if (variant != TWN_VAR_BF16_POSTSCALE) return TWN_ERR_UNSUPPORTED;
-    int mode;
-    if (g.IC % 8 != 0 || g.xs % 8 != 0) mode = kModeScalar;
-    else mode = g.plain_gemm ? kModeGemm : kModeVec8;
+    const int mode = gather_mode(g);
 
     // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.
     int tile = env_int("TWN_TILE", 0);
@@ -281,7 +299,8 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
         // multi-stage direct-to-LDS kernel
         if (tile == 0) {
             auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
-            if (g.NC <= 64) tile = 13;
+            if (g.splits > 1) tile = 12;
+            else if (g.NC <= 64) tile = 13;
             else if (g.NC <= 128) tile = (blocks(256, 128) >= 512) ? 20 : 12;
             else tile = (blocks(128, 256) >= 512) ? 17 : 12;
         }

@@ -67,7 +67,7 @@ constexpr int dma_min_blocks(int nw, int smem) {
     return b < 1 ? 1 : b;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM>
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK>
 __global__ __launch_bounds__(64 * WM * WN, dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
 void gather_gemm_dma_kernel(const DmaArgs a) {
     constexpr int NW = WM * WN;                    // waves per workgroup
@@ -143,7 +143,11 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     const int bcol = n0 + brow;
     const uint32_t* bsrc = (bcol < g.NC) ? Wq + static_cast<int64_t>(bcol) * g.wpr : nullptr;
 
-    const int KT = (g.K + 63) / 64;
+    // K slabs handled by this workgroup: all of them, or one range of a split-K launch (blockIdx.y)
+    const int KT_all = (g.K + 63) / 64;
+    const int kps = SPLITK ? (KT_all + g.splits - 1) / g.splits : KT_all;
+    const int kt_begin = SPLITK ? static_cast<int>(blockIdx.y) * kps : 0;
+    const int KT = (kt_begin + kps < KT_all) ? kt_begin + kps : KT_all;      // end of this range
 
     auto tap_coord = [&](int base, int tap, int step, int div, int limit, int& out) -> bool {
         int v = base + tap * step;
@@ -195,14 +199,14 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 
     // prologue: PD slabs in flight, the first one landed and visible to every wave
 #pragma unroll
-    for (int s = 0; s < PD; ++s) issue(s, s);
+    for (int s = 0; s < PD; ++s) issue(kt_begin + s, s);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * PER_STAGE));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
     int stage = 0;          // slab kt lives in stage kt % STAGES
     int fill = PD;          // stage that slab kt + PD goes to
-    for (int kt = 0; kt < KT; ++kt) {
+    for (int kt = kt_begin; kt < KT; ++kt) {
         const unsigned char* sa = smem + stage * STAGE_BYTES;
         const unsigned char* sb = sa + A_BYTES;
 
@@ -263,6 +267,34 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+
+    if (SPLITK) {
+        // raw fp32 partial sums; alpha, scale, shift, residual and ReLU are applied by the reduction kernel
+        float* part = g.partial + static_cast<int64_t>(blockIdx.y) * g.M * g.NC;
+        const bool v4 = (g.NC % 4 == 0);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int64_t m = m0 + wm * TM + mi * 32 + lrow;
+            if (m >= g.M) continue;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int ncol = n0 + wn * TN + ni * 32 + q4 * 8 + lh * 4;
+                    float* dst = part + m * g.NC + ncol;
+                    if (v4 && ncol < g.NC) {
+                        *reinterpret_cast<f32x4*>(dst) = f32x4{acc[mi][ni][q4 * 4], acc[mi][ni][q4 * 4 + 1],
+                                                               acc[mi][ni][q4 * 4 + 2], acc[mi][ni][q4 * 4 + 3]};
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (ncol + e < g.NC) dst[e] = acc[mi][ni][q4 * 4 + e];
+                    }
+                }
+            }
+        }
+        return;
+    }
 
     // ---- epilogue: y = relu?((alpha*acc)*scale + shift + residual) ----
     // accumulator element e of tile (mi, ni) in this lane:
@@ -364,36 +396,65 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
-static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
+// Sums the split-K partials in a fixed order and applies the block tail:
+// y = relu?((0.5*alpha*sum)*scale + shift + residual).  One thread per output element.
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const GatherGemm g) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t total = g.M * g.NC;
+    if (id >= total) return;
+    const int64_t m = id / g.NC;
+    const int ncol = static_cast<int>(id - m * g.NC);
+    float s = 0.0f;
+    for (int sp = 0; sp < g.splits; ++sp) s += g.partial[static_cast<int64_t>(sp) * total + id];
+    const float mul = 0.5f * g.alpha[ncol / g.rows_per_group] * (g.scale ? g.scale[ncol] : 1.0f);
+    float v = s * mul + (g.shift ? g.shift[ncol] : 0.0f);
+    const int64_t off = m * g.ldy + ncol;
+    if (g.y_f32) {
+        if (g.residual) v += static_cast<const float*>(g.residual)[off];
+        if (g.relu) v = fmaxf(v, 0.0f);
+        static_cast<float*>(g.Y)[off] = v;
+    } else {
+        if (g.residual) v += bf16_to_f32(static_cast<const uint16_t*>(g.residual)[off]);
+        if (g.relu) v = fmaxf(v, 0.0f);
+        static_cast<uint16_t*>(g.Y)[off] = f32_to_bf16(v);
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK>
+static int32_t launch_dma_kernel(const DmaArgs& a, int64_t blocks, hipStream_t st) {
     constexpr int SMEM = STAGES * (BM * 128 + BN * 16);
     static_assert(SMEM <= 160 * 1024, "LDS budget");
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    static bool allowed = false;
+    auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, GEMM, SPLITK>;
+    if (!allowed) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                SMEM) != hipSuccess) return TWN_ERR_HIP;
+        allowed = true;
+    }
+    k<<<dim3(static_cast<unsigned>(blocks), SPLITK ? a.g.splits : 1), dim3(64 * WM * WN), SMEM, st>>>(a);
+    return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES>
+static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
     const int64_t blocks = ((g.M + BM - 1) / BM) * ((g.NC + BN - 1) / BN);
     if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
     DmaArgs a;
     a.g = g;
     a.divIC = make_fastdiv_u(static_cast<uint32_t>(g.IC));
     a.divS = make_fastdiv_u(static_cast<uint32_t>(g.S));
-    // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    static bool allowed[2] = {false, false};
-    if (g.plain_gemm) {
-        auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, true>;
-        if (!allowed[0]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    SMEM) != hipSuccess) return TWN_ERR_HIP;
-            allowed[0] = true;
-        }
-        k<<<dim3(static_cast<unsigned>(blocks)), dim3(64 * WM * WN), SMEM, st>>>(a);
-    } else {
-        auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, false>;
-        if (!allowed[1]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    SMEM) != hipSuccess) return TWN_ERR_HIP;
-            allowed[1] = true;
-        }
-        k<<<dim3(static_cast<unsigned>(blocks)), dim3(64 * WM * WN), SMEM, st>>>(a);
+    if (g.splits > 1) {
+        if (!g.partial) return TWN_ERR_WORKSPACE;
+        int32_t rc = g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, true>(a, blocks, st)
+                                  : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, true>(a, blocks, st);
+        if (rc != TWN_OK) return rc;
+        const int64_t total = g.M * g.NC;
+        splitk_finish_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(g);
+        return launch_status();
     }
-    return launch_status();
+    return g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, false>(a, blocks, st)
+                        : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, false>(a, blocks, st);
 }
 
 // Tile ids: 11 = 128x256 (3 stages), 12 = 128x128, 13 = 128x64, 14 = 256x256 (4 stages), 15 = 128x256 (4 stages)

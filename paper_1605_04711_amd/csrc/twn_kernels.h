@@ -35,7 +35,13 @@ struct GatherGemm {
     int32_t relu;
     int32_t y_f32;          // 1: Y (and residual) float32, 0: bf16
     int32_t plain_gemm;     // 1: R=S=1, stride 1, no padding, OH*OW pixels == rows of X
+    float* partial;         // split-K workspace [splits][M][NC] float32 (null when splits == 1)
+    int32_t splits;         // K is cut into this many ranges of whole 64-wide slabs
 };
+
+// Number of K ranges the MFMA path uses for this problem (1 = no split); a pure function of the
+// shapes, so the workspace query and the launch agree.
+int32_t gather_gemm_splits(const GatherGemm& g);
 
 int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st);
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
