@@ -143,6 +143,38 @@ void fill_conv_bwd_data(GatherGemm& g, const twn_conv_desc* d, int P, int Q) {
                     d->pad_w == 0);
 }
 
+// ---- small-C forward path (C <= 4, bf16, dilation 1): geometry of the padded copy ----
+struct SmallC {
+    int Hp, Wp, Sp;
+    size_t x_bytes, w_bytes;
+};
+
+bool small_c(const twn_conv_desc* d, SmallC* sc) {
+    if (d->variant != TWN_VAR_BF16_POSTSCALE || d->x_dtype != TWN_BF16) return false;
+    if (d->C > 4 || d->dil_h != 1 || d->dil_w != 1) return false;
+    sc->Sp = (d->S + 1) & ~1;
+    sc->Hp = d->H + 2 * d->pad_h;
+    sc->Wp = d->W + 2 * d->pad_w + (sc->Sp - d->S);
+    sc->x_bytes = round_up(static_cast<size_t>(d->N) * sc->Hp * sc->Wp * 4 * sizeof(uint16_t), 256);
+    sc->w_bytes = round_up(twn_packed_bytes(d->O, static_cast<int64_t>(d->R) * sc->Sp * 4), 256);
+    return static_cast<int64_t>(d->N) * sc->Hp * sc->Wp < (1LL << 31);
+}
+
+void fill_conv_fwd_small_c(GatherGemm& g, const twn_conv_desc* d, const SmallC& sc, int P, int Q) {
+    fill_conv_fwd(g, d, P, Q);
+    g.xs = 4;                    // elements per padded pixel
+    g.IH = sc.Hp;
+    g.IW = sc.Wp;
+    g.IC = 8;                    // one 16-byte chunk = two adjacent taps x 4 channels
+    g.S = sc.Sp / 2;
+    g.ph = g.pw = 0;             // the border is part of the copy
+    g.dw = 2;                    // chunk j of a filter row starts 2 pixels after chunk j-1
+    g.K = d->R * sc.Sp * 4;
+    g.wpr = static_cast<int32_t>(twn_packed_words_per_row(g.K));
+    g.plain_gemm = 0;
+    g.chunk_gather = 1;
+}
+
 size_t weight_grad_bytes(const twn_conv_desc* d, int P, int Q) {
     const int64_t pixels = static_cast<int64_t>(d->N) * P * Q;
     const int64_t J = static_cast<int64_t>(d->R) * d->S * d->C;
@@ -191,6 +223,11 @@ extern "C" size_t twn_conv2d_fwd_workspace_bytes(const twn_conv_desc* d) {
     int P, Q;
     if (check_conv_desc(d, &P, &Q) != TWN_OK) return 0;
     GatherGemm g{};
+    SmallC sc;
+    if (small_c(d, &sc)) {
+        fill_conv_fwd_small_c(g, d, sc, P, Q);
+        return sc.x_bytes + sc.w_bytes + splitk_bytes(g, d->variant);
+    }
     fill_conv_fwd(g, d, P, Q);
     return splitk_bytes(g, d->variant);
 }
@@ -216,6 +253,25 @@ extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const v
     g.alpha = alpha;
     set_epilogue(g, ep);
     g.Y = Y;
+    SmallC sc;
+    if (small_c(d, &sc)) {
+        // first-layer path: padded 4-channel copy of X and re-ordered codes live in the workspace
+        fill_conv_fwd_small_c(g, d, sc, P, Q);
+        const size_t head = sc.x_bytes + sc.w_bytes;
+        if (!workspace || workspace_bytes < head + splitk_bytes(g, d->variant) || !aligned(workspace, 256))
+            return TWN_ERR_WORKSPACE;
+        hipStream_t st = as_stream(stream);
+        uint16_t* Xp = static_cast<uint16_t*>(workspace);
+        uint32_t* Wp = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + sc.x_bytes);
+        rc = launch_pad_c4(static_cast<const uint16_t*>(X), d->N, d->H, d->W, d->C, d->pad_h, d->pad_w, sc.Hp, sc.Wp,
+                           Xp, st);
+        if (rc == TWN_OK)
+            rc = launch_repack_c4(static_cast<const uint32_t*>(weights), d->O, d->C, d->R, d->S, sc.Sp, Wp, st);
+        if (rc != TWN_OK) return rc;
+        g.X = Xp;
+        g.Wq = Wp;
+        return dispatch(g, d->variant, static_cast<unsigned char*>(workspace) + head, workspace_bytes - head, st);
+    }
     fill_conv_fwd(g, d, P, Q);
     return dispatch(g, d->variant, workspace, workspace_bytes, as_stream(stream));
 }

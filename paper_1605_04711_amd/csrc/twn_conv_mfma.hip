@@ -253,6 +253,66 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
     }
 }
 
+__global__ __launch_bounds__(256) void pad_c4_kernel(const uint16_t* __restrict__ X, int N, int H, int W, int C,
+                                                     int ph, int pw, int Hp, int Wp, uint16_t* __restrict__ Xp) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t total = static_cast<int64_t>(N) * Hp * Wp;
+    if (id >= total) return;
+    const int wp = static_cast<int>(id % Wp);
+    const int64_t t = id / Wp;
+    const int hp = static_cast<int>(t % Hp);
+    const int64_t n = t / Hp;
+    const int h = hp - ph, w = wp - pw;
+    uint32_t v[4] = {0, 0, 0, 0};
+    if (static_cast<unsigned>(h) < static_cast<unsigned>(H) && static_cast<unsigned>(w) < static_cast<unsigned>(W)) {
+        const uint16_t* src = X + ((n * H + h) * W + w) * C;
+        for (int c = 0; c < C; ++c) v[c] = src[c];
+    }
+    u32x2 o;
+    o[0] = v[0] | (v[1] << 16);
+    o[1] = v[2] | (v[3] << 16);
+    *reinterpret_cast<u32x2*>(Xp + id * 4) = o;
+}
+
+__global__ __launch_bounds__(256) void repack_c4_kernel(const uint32_t* __restrict__ packed, int rows, int C, int R,
+                                                        int S, int Sp, int wpr, int wpr2, uint32_t* __restrict__ out) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (id >= static_cast<int64_t>(rows) * wpr2) return;
+    const int row = static_cast<int>(id / wpr2), j = static_cast<int>(id % wpr2);
+    uint32_t word = 0;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int k2 = j * 16 + t;
+        const int c = k2 & 3, rs = k2 >> 2;
+        const int s = rs % Sp, r = rs / Sp;
+        if (c < C && s < S && r < R) {
+            const int k = (r * S + s) * C + c;
+            const uint32_t src = packed[static_cast<int64_t>(row) * wpr + (k >> 4)];
+            const int tt = k & 15;
+            const uint32_t fld = (src >> ((tt & 1) * 16 + (tt >> 1) * 2)) & 3u;
+            word |= fld << ((t & 1) * 16 + (t >> 1) * 2);
+        }
+    }
+    out[id] = word;
+}
+
+int32_t launch_pad_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp,
+                      uint16_t* Xp, hipStream_t st) {
+    const int64_t total = static_cast<int64_t>(N) * Hp * Wp;
+    pad_c4_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(X, N, H, W, C, ph, pw, Hp, Wp, Xp);
+    return launch_status();
+}
+
+int32_t launch_repack_c4(const uint32_t* packed, int rows, int C, int R, int S, int Sp, uint32_t* out,
+                         hipStream_t st) {
+    const int wpr = static_cast<int>(twn_packed_words_per_row(static_cast<int64_t>(R) * S * C));
+    const int wpr2 = static_cast<int>(twn_packed_words_per_row(static_cast<int64_t>(R) * Sp * 4));
+    const int64_t total = static_cast<int64_t>(rows) * wpr2;
+    repack_c4_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(packed, rows, C, R, S, Sp, wpr, wpr2,
+                                                                                out);
+    return launch_status();
+}
+
 template <int BM, int BN, int WM, int WN>
 static int32_t launch_tile(const GatherGemm& g, int mode, hipStream_t st) {
     const int64_t tiles_m = (g.M + BM - 1) / BM;
@@ -270,6 +330,7 @@ static int32_t launch_tile(const GatherGemm& g, int mode, hipStream_t st) {
 }
 
 static int gather_mode(const GatherGemm& g) {
+    if (g.chunk_gather) return kModeVec8;
     if (g.IC % 8 != 0 || g.xs % 8 != 0) return kModeScalar;
     return g.plain_gemm ? kModeGemm : kModeVec8;
 }

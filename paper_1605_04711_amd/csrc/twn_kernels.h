@@ -35,6 +35,7 @@ struct GatherGemm {
     int32_t relu;
     int32_t y_f32;          // 1: Y (and residual) float32, 0: bf16
     int32_t plain_gemm;     // 1: R=S=1, stride 1, no padding, OH*OW pixels == rows of X
+    int32_t chunk_gather;   // 1: 16-byte chunks are valid although IC/xs are not multiples of 8 (small-C path)
     float* partial;         // split-K workspace [splits][M][NC] float32 (null when splits == 1)
     int32_t splits;         // K is cut into this many ranges of whole 64-wide slabs
 };
@@ -44,6 +45,15 @@ struct GatherGemm {
 int32_t gather_gemm_splits(const GatherGemm& g);
 
 int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st);
+
+// Small-C first layers (C <= 4, dilation 1): the input is copied once into a zero-bordered
+// [N][H+2ph][Wp][4] bf16 tensor so that two horizontally adjacent taps of 4 channels are one
+// aligned-enough 16-byte chunk, and the packed codes are re-ordered to k' = (r*Sp + s)*4 + c
+// with Sp = S rounded up to even (codes of the phantom tap / channels are zero).
+int32_t launch_pad_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp,
+                      uint16_t* Xp, hipStream_t st);
+int32_t launch_repack_c4(const uint32_t* packed, int rows, int C, int R, int S, int Sp, uint32_t* out,
+                         hipStream_t st);
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 
