@@ -87,66 +87,98 @@ def main():
     flops_step = flops_fwd + flops_dx + flops_dw
     tern_bytes = sum(L.n_weights for L in layers) * 8.5      # two reads + two 2-bit copies
 
-    def do_ternarize():
-        for li in range(len(layers)):
-            api.twn_ternarize(W[li], F, transposed=True, out=tws[li], workspace=tern_ws)
-
-    def do_fwd():
-        for li in range(len(layers)):
-            st, pd, dl = geo[li]
-            api.twn_conv2d_fwd(X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li], relu=True, out=Y[li],
-                               workspace=wsf[li])
-
-    def do_dx():
-        for li in range(len(layers) - 1, 0, -1):
-            st, pd, dl = geo[li]
-            api.twn_conv2d_bwd_ste(None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False, dX=dX[li],
-                                   x_shape=layers[li].x_shape, workspace=wsb[li])
-
-    def do_dw():
-        for li in range(len(layers) - 1, -1, -1):
-            st, pd, dl = geo[li]
-            api.twn_conv2d_bwd_ste(X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True, dW=dW[li],
-                                   workspace=wsb[li])
-
-    phases = [("ternarize", do_ternarize), ("fwd", do_fwd), ("bwd_data", do_dx), ("bwd_weight", do_dw)]
+    # every library call of one step, in order: (phase, layer index, callable)
+    calls = []
+    for li in range(len(layers)):
+        calls.append(("ternarize", li, lambda li=li: api.twn_ternarize(W[li], F, transposed=True, out=tws[li],
+                                                                         workspace=tern_ws)))
+    for li in range(len(layers)):
+        st, pd, dl = geo[li]
+        calls.append(("fwd", li, lambda li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_fwd(
+            X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li], relu=True, out=Y[li], workspace=wsf[li])))
+    for li in range(len(layers) - 1, 0, -1):
+        st, pd, dl = geo[li]
+        calls.append(("bwd_data", li, lambda li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
+            None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False, dX=dX[li], x_shape=layers[li].x_shape,
+            workspace=wsb[li])))
+    for li in range(len(layers) - 1, -1, -1):
+        st, pd, dl = geo[li]
+        calls.append(("bwd_weight", li, lambda li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
+            X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True, dW=dW[li], workspace=wsb[li])))
 
     for _ in range(args.warmup):
-        for _, fn in phases:
+        for _, _, fn in calls:
             fn()
     torch.cuda.synchronize()
 
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in phases]
-          for _ in range(args.steps)]
+    # Timed region.  HIP events on the launch stream (torch's current stream) bracket the four phases and,
+    # inside them, each call that is exactly one launch of the contraction kernel (the roofline sample).
+    # Events around every call would add a bubble per call, so the per-layer table is taken afterwards.
+    name_of = [L.name for L in layers]
+    single = {("fwd", n) for n in ("c2", "c3", "c4", "c5", "c6")} | {("bwd_data", n) for n in ("c2", "c3", "c4", "c6")}
+    phase_names = ["ternarize", "fwd", "bwd_data", "bwd_weight"]
+    is_single = [(c[0], name_of[c[1]]) in single for c in calls]
+    first_of = {ph: min(ci for ci, c in enumerate(calls) if c[0] == ph) for ph in phase_names}
+    last_of = {ph: max(ci for ci, c in enumerate(calls) if c[0] == ph) for ph in phase_names}
+
+    def new_ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    pev = [{ph: (new_ev(), new_ev()) for ph in phase_names} for _ in range(args.steps)]
+    cev = [{ci: (new_ev(), new_ev()) for ci in range(len(calls)) if is_single[ci]} for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        for pi, (_, fn) in enumerate(phases):
-            ev[s][pi][0].record()
+        for ci, (ph, _, fn) in enumerate(calls):
+            if ci == first_of[ph]:
+                pev[s][ph][0].record()
+            if is_single[ci]:
+                cev[s][ci][0].record()
             fn()
-            ev[s][pi][1].record()
+            if is_single[ci]:
+                cev[s][ci][1].record()
+            if ci == last_of[ph]:
+                pev[s][ph][1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    phase_ms = [sum(ev[s][pi][0].elapsed_time(ev[s][pi][1]) for s in range(args.steps)) / args.steps
-                for pi in range(len(phases))]
+    phase_ms = [sum(pev[s][ph][0].elapsed_time(pev[s][ph][1]) for s in range(args.steps)) / args.steps
+                for ph in phase_names]
+    single_ms = {ci: sum(cev[s][ci][0].elapsed_time(cev[s][ci][1]) for s in range(args.steps)) / args.steps
+                 for ci in range(len(calls)) if is_single[ci]}
     value = flops_step / (ms_per_step * 1e-3) / 1e12
-    log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phases[i][0], phase_ms[i]) for i in range(len(phases))))
+    log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phase_names[i], phase_ms[i]) for i in range(4)))
 
-    # the forward/backward-data kernel (one launch per layer) against the bf16 MFMA peak
-    mfma_flops = flops_fwd + flops_dx
-    mfma_ms = phase_ms[1] + phase_ms[2]
-    launches = len(layers) + len(layers) - 1
+    # per-layer detail: a second, untimed pass with events around every call
+    ev = [[(new_ev(), new_ev()) for _ in calls] for _ in range(5)]
+    for s in range(5):
+        for ci, (_, _, fn) in enumerate(calls):
+            ev[s][ci][0].record()
+            fn()
+            ev[s][ci][1].record()
+    torch.cuda.synchronize()
+    call_ms = [sum(ev[s][ci][0].elapsed_time(ev[s][ci][1]) for s in range(5)) / 5 for ci in range(len(calls))]
+
+    per = {(c[0], c[1]): call_ms[ci] for ci, c in enumerate(calls)}
+    log("%-6s %22s %9s %9s %9s %9s %9s %9s" % ("layer", "(M,N,K)", "tern us", "fwd us", "fwd TF/s", "dX TF/s", "dW us", "dW TF/s"))
+    for li, L in enumerate(layers):
+        tf, tdx, tdw = per[("fwd", li)], per.get(("bwd_data", li), float("nan")), per[("bwd_weight", li)]
+        log("%-6s %22s %9.1f %9.1f %9.1f %9.1f %9.1f %9.1f" % (L.name, str(L.gemm_mnk), per[("ternarize", li)] * 1e3,
+                                                             tf * 1e3, L.flops / tf / 1e9, L.flops / tdx / 1e9,
+                                                             tdw * 1e3, L.flops / tdw / 1e9))
+
+    # Roofline of the contraction kernel named by the task (gather_gemm_dma_kernel): the forward and
+    # backward-data calls that consist of exactly ONE launch of it (no split-K finish, no first-layer
+    # copy, no odd-channel fallback): forward c2-c6, backward-data c2-c4 and c6.
+    r_flops = sum(layers[calls[ci][1]].flops for ci in single_ms)
+    r_ms = sum(single_ms.values())
+    gg_tflops = r_flops / (r_ms * 1e-3) / 1e12
+    roof = {"kernel": "gather_gemm_dma_kernel", "bound": "mfma", "achieved": round(gg_tflops, 2),
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gg_tflops / PEAK_BF16_TFLOPS, 4),
+            "traffic": None, "launches_per_step": len(single_ms), "avg_launch_us": round(r_ms * 1e3 / len(single_ms), 2),
+            "flops_per_launch_avg": round(r_flops / len(single_ms) / 1e9, 2),
+            "calls": "fwd c2-c6 + bwd_data c2-c4,c6 (one launch each)"}
     dw_tflops = flops_dw / (phase_ms[3] * 1e-3) / 1e12
-    gg_tflops = mfma_flops / (mfma_ms * 1e-3) / 1e12
-    if phase_ms[3] > mfma_ms:
-        roof = {"kernel": "weight_grad_kernel", "bound": "mfma", "achieved": round(dw_tflops, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(dw_tflops / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "launches_per_step": len(layers), "avg_launch_us": round(phase_ms[3] * 1e3 / len(layers), 2)}
-    else:
-        roof = {"kernel": "gather_gemm_mfma_kernel", "bound": "mfma", "achieved": round(gg_tflops, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gg_tflops / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "launches_per_step": launches, "avg_launch_us": round(mfma_ms * 1e3 / launches, 2)}
 
     def time_call(fn, reps=10, warm=2):
         for _ in range(warm):
@@ -159,20 +191,7 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
-    # per-layer detail (stderr)
-    log("%-6s %22s %10s %10s %10s %10s" % ("layer", "(M,N,K)", "fwd us", "fwd TF/s", "dX TF/s", "dW TF/s"))
-    for li, L in enumerate(layers):
-        st, pd, dl = geo[li]
-        tf = time_call(lambda: api.twn_conv2d_fwd(X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li],
-                                                  relu=True, out=Y[li], workspace=wsf[li]))
-        tdx = time_call(lambda: api.twn_conv2d_bwd_ste(None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False,
-                                                       dX=dX[li], x_shape=L.x_shape, workspace=wsb[li])) if li else float("nan")
-        tdw = time_call(lambda: api.twn_conv2d_bwd_ste(X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True,
-                                                       dW=dW[li], workspace=wsb[li]))
-        log("%-6s %22s %10.1f %10.1f %10.1f %10.1f" % (L.name, str(L.gemm_mnk), tf * 1e3, L.flops / tf / 1e9,
-                                                       L.flops / tdx / 1e9, L.flops / tdw / 1e9))
-
-    extras = {"phase_ms": {phases[i][0]: round(phase_ms[i], 4) for i in range(len(phases))},
+    extras = {"phase_ms": {phase_names[i]: round(phase_ms[i], 4) for i in range(4)},
               "fwd_tflops": round(flops_fwd / (phase_ms[1] * 1e-3) / 1e12, 2),
               "bwd_data_tflops": round(flops_dx / (phase_ms[2] * 1e-3) / 1e12, 2),
               "bwd_weight_tflops": round(dw_tflops, 2),

@@ -114,6 +114,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     // one logical chunk then fall in 16 different 16-byte bank groups (conflict-free ds_read_b128)
     const int kc = (lane & 7) ^ ((wave & 1) * 4 + ((lane >> 4) & 3));   // logical chunk this lane fetches
     int64_t abase[NLOAD];                              // GEMM: element offset of the row; conv: pixel base
+    int64_t off0[NLOAD];                               // conv: element offset of tap (0,0), may be negative
     int ih0[NLOAD], iw0[NLOAD];
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
@@ -137,7 +138,9 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             ih0[i] = -(1 << 28);
             iw0[i] = -(1 << 28);
         }
+        off0[i] = (abase[i] + static_cast<int64_t>(ih0[i]) * g.IW + iw0[i]) * g.xs;
     }
+    const bool undivided = (g.divh == 1 && g.divw == 1);   // everything except strided backward-data
     // ---- B load: this wave stages the packed codes of 64 output channels (one lane per channel) ----
     const int brow = (wave * 64) % BN + lane;
     const int bcol = n0 + brow;
@@ -174,6 +177,18 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             const int c = k - static_cast<int>(rs) * g.IC;
             const int rr = static_cast<int>(fdiv_u(rs, a.divS));
             const int ss = static_cast<int>(rs) - rr * g.S;
+            if (undivided) {
+                // one tap offset per slab for this lane; per row: two bounds tests and one 64-bit add
+                const int dth = rr * g.dh, dtw = ss * g.dw;
+                const int64_t delta = (static_cast<int64_t>(dth) * g.IW + dtw) * g.xs + c;
+#pragma unroll
+                for (int i = 0; i < NLOAD; ++i) {
+                    const bool ok = kok && static_cast<unsigned>(ih0[i] + dth) < static_cast<unsigned>(g.IH) &&
+                                    static_cast<unsigned>(iw0[i] + dtw) < static_cast<unsigned>(g.IW);
+                    const void* src = ok ? static_cast<const void*>(X + off0[i] + delta) : zero;
+                    dma16(src, sbase + (i * NW + wave) * 1024);
+                }
+            } else
 #pragma unroll
             for (int i = 0; i < NLOAD; ++i) {
                 int th, tw;
