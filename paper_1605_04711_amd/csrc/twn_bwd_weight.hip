@@ -32,12 +32,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Exact unsigned division of numerators below 2^31 by a runtime constant.
 struct FastDiv {
-    uint32_t mul, shift, d;
+    uint32_t mul, shift, d, one;   // one = all ones when d == 1 (then mul = 0 and the quotient is n itself)
 };
 
 static FastDiv make_fastdiv(uint32_t d) {
-    FastDiv f{0, 0, d};
+    FastDiv f{0, 0, d, 0xFFFFFFFFu};
     if (d <= 1) return f;
+    f.one = 0;
     uint32_t l = 0;
     while ((1u << l) < d) ++l;
     const uint32_t s = 31 + l;
@@ -47,7 +48,7 @@ static FastDiv make_fastdiv(uint32_t d) {
 }
 
 __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
-    return f.mul ? (__umulhi(n, f.mul) >> f.shift) : n;
+    return (__umulhi(n, f.mul) >> f.shift) | (n & f.one);
 }
 
 struct WGArgs {
@@ -291,26 +292,30 @@ __global__ __launch_bounds__(256, 2) void weight_grad_dma_kernel(const WGArgs a)
     const int ts = static_cast<int>(rs) - tr * w.S;
     const bool ook = oo < w.O, jok = jj < a.J;
 
+    // pixel counts fit 31 bits (checked on the host), so pixel arithmetic is 32-bit; only the final
+    // element offsets are 64-bit
+    const int th0 = tr * w.dh - w.ph, tw0 = ts * w.dw - w.pw;
+    const uint32_t npix = static_cast<uint32_t>(a.pixels);
     auto issue = [&](int64_t slab, int stage, bool live) {
         unsigned char* sA = wsm + stage * STAGE_BYTES;
         unsigned char* sB = sA + TILE_BYTES;
+        const uint32_t pix0 = static_cast<uint32_t>(slab) * 64u + wave * 4 + prow;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int64_t pix = slab * 64 + (i * 4 + wave) * 4 + prow;
-            const bool pok = live && pix < a.pixels;
-            const void* srcA = (pok && ook) ? static_cast<const void*>(w.dY + pix * w.O + oo) : zero;
-            const void* srcB = zero;
-            if (pok && jok) {
-                const uint32_t n = fdiv(static_cast<uint32_t>(pix), a.divPQ);
-                const uint32_t rem = static_cast<uint32_t>(pix) - n * a.divPQ.d;
-                const uint32_t p = fdiv(rem, a.divQ);
-                const uint32_t q = rem - p * w.Q;
-                const int ih = static_cast<int>(p) * w.sh - w.ph + tr * w.dh;
-                const int iw = static_cast<int>(q) * w.sw - w.pw + ts * w.dw;
-                if (static_cast<unsigned>(ih) < static_cast<unsigned>(w.H) &&
-                    static_cast<unsigned>(iw) < static_cast<unsigned>(w.W))
-                    srcB = w.X + ((static_cast<int64_t>(n) * w.H + ih) * w.W + iw) * w.C + tc;
-            }
+            const uint32_t pix = pix0 + i * 16;
+            const bool pok = live && pix < npix;
+            const uint32_t n = fdiv(pix, a.divPQ);
+            const uint32_t rem = pix - n * a.divPQ.d;
+            const uint32_t p = fdiv(rem, a.divQ);
+            const uint32_t q = rem - p * w.Q;
+            const int ih = static_cast<int>(p) * w.sh + th0;
+            const int iw = static_cast<int>(q) * w.sw + tw0;
+            const bool bok = pok && jok && static_cast<unsigned>(ih) < static_cast<unsigned>(w.H) &&
+                             static_cast<unsigned>(iw) < static_cast<unsigned>(w.W);
+            const uint32_t ipix = (n * w.H + ih) * w.W + iw;
+            const void* srcA = (pok && ook) ? static_cast<const void*>(w.dY + static_cast<uint64_t>(pix) * w.O + oo)
+                                            : zero;
+            const void* srcB = bok ? static_cast<const void*>(w.X + static_cast<uint64_t>(ipix) * w.C + tc) : zero;
             wg_dma16(srcA, sA + (i * 4 + wave) * 1024);
             wg_dma16(srcB, sB + (i * 4 + wave) * 1024);
         }
@@ -320,11 +325,21 @@ __global__ __launch_bounds__(256, 2) void weight_grad_dma_kernel(const WGArgs a)
     const int li = lane & 15;
     const int fpix = 8 * lh + (li >> 2);                 // + 16*kk (+4 for the second read)
     const int fch = 16 * ((lane >> 4) & 1) + 4 * (li & 3);   // + wave tile offset + 32*mi
-    auto frag_addr = [&](const unsigned char* tile, int chan0, int pixel) -> const unsigned char* {
+    auto frag_off = [&](int chan0, int pixel) -> int {
         const int ch = chan0 + fch;
         const int chunk = (ch >> 3) ^ (2 * (pixel & 3));
-        return tile + pixel * 256 + chunk * 16 + (ch & 7) * 2;
+        return pixel * 256 + chunk * 16 + (ch & 7) * 2;
     };
+    // byte offsets inside a tile for MFMA step 0; step kk adds kk*16 pixel rows = kk*4096 bytes
+    // (16 is a multiple of 4, so the swizzle term does not change)
+    int offA[2][2], offB[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int hv = 0; hv < 2; ++hv) {
+            offA[t][hv] = frag_off(wm * 64 + t * 32, fpix + 4 * hv);
+            offB[t][hv] = frag_off(wn * 64 + t * 32, fpix + 4 * hv);
+        }
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -347,14 +362,13 @@ __global__ __launch_bounds__(256, 2) void weight_grad_dma_kernel(const WGArgs a)
         const unsigned char* sB = sA + TILE_BYTES;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            const int pixel = kk * 16 + fpix;
             bf16x8 af[2], bfr[2];
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
-                af[mi] = wg_frag(frag_addr(sA, wm * 64 + mi * 32, pixel), frag_addr(sA, wm * 64 + mi * 32, pixel + 4));
+                af[mi] = wg_frag(sA + offA[mi][0] + kk * 4096, sA + offA[mi][1] + kk * 4096);
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni)
-                bfr[ni] = wg_frag(frag_addr(sB, wn * 64 + ni * 32, pixel), frag_addr(sB, wn * 64 + ni * 32, pixel + 4));
+                bfr[ni] = wg_frag(sB + offB[ni][0] + kk * 4096, sB + offB[ni][1] + kk * 4096);
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll

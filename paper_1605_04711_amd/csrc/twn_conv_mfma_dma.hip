@@ -29,12 +29,13 @@ __device__ __attribute__((aligned(16))) const uint32_t kZeroBlock[4] = {0u, 0u, 
 
 // Exact unsigned division of numerators below 2^31 by a runtime constant.
 struct FastDivU {
-    uint32_t mul, shift;
+    uint32_t mul, shift, one;   // one = all ones when d == 1 (then mul = 0 and the quotient is n itself)
 };
 
 static FastDivU make_fastdiv_u(uint32_t d) {
-    FastDivU f{0, 0};
+    FastDivU f{0, 0, 0xFFFFFFFFu};
     if (d <= 1) return f;
+    f.one = 0;
     uint32_t l = 0;
     while ((1u << l) < d) ++l;
     const uint32_t s = 31 + l;
@@ -44,7 +45,7 @@ static FastDivU make_fastdiv_u(uint32_t d) {
 }
 
 __device__ __forceinline__ uint32_t fdiv_u(uint32_t n, const FastDivU& f) {
-    return f.mul ? (__umulhi(n, f.mul) >> f.shift) : n;
+    return (__umulhi(n, f.mul) >> f.shift) | (n & f.one);
 }
 
 struct DmaArgs {

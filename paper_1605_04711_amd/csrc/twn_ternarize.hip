@@ -1,17 +1,22 @@
 // Threshold ternarization on gfx950 (Sec. 2.3: rule of thumb for Delta, Eq. 3
 // codes, Eq. 5 alpha; Alg. 1 steps 3-7).  HBM-streaming kernels:
 //
-//   abs_sum          pass 1: per-block float64 partial sums of |W|
-//   mask_pack_flat   pass 2: Delta from the partials, then one more stream of W:
-//                    masked float64 sum, count, and the 2-bit codes written in
-//                    the same pass (flat layouts: R*S == 1 and K % 128 == 0)
-//   mask_stats       pass 2 without the pack (any layout)
-//   pack_gather      codes for any [rows][C][R][S] layout, normal or transposed
-//   group_stats      one block per group when there are several groups (per filter)
-//   finalize         fixed-order sum of the pass-2 partials -> Delta, alpha, nnz
+//   abs_sum           pass 1: per-block float64 partial sums of |W|
+//   mask_pack_flat    pass 2: Delta from the partials, then one more stream of W:
+//                     masked float64 sum, count, and the 2-bit codes written in
+//                     the same pass (flat layouts: R*S == 1 and K % 128 == 0)
+//   mask_pack_gather  pass 2 for any [rows][C][R][S] layout: one thread per output
+//                     word of the normal and of the transposed copy; the normal
+//                     words also carry the masked sum and count
+//   pack_gather       codes only (transposed copy of flat layouts, per-filter groups)
+//   group_stats       one block per group when there are several groups (per filter)
 //
-// All cross-thread sums run in a fixed order, so results are bit-identical
-// from run to run; no floating-point atomics are used.
+//   finalize          fixed-order sum of the pass-2 partials -> Delta, alpha, nnz
+//
+// (A "last block finishes" variant with a ticket counter was measured and dropped:
+// the device-scope release it needs writes back the L2 of every XCD once per block
+// and cost 75 us on the 2^28 tensor.)  All floating-point sums run in a fixed
+// order: results are bit-identical from run to run; no floating-point atomics.
 #include "twn_common.h"
 
 namespace twn {
@@ -67,6 +72,28 @@ __device__ __forceinline__ float delta_from_partials(const double* __restrict__ 
     return static_cast<float>((static_cast<double>(f) * s1) / static_cast<double>(n));
 }
 
+// Fixed-order sum of the pass-2 partials of `nb2` blocks -> Delta, alpha, nnz (one block).
+__global__ __launch_bounds__(kTernThreads) void finalize_kernel(const TernWorkspace* __restrict__ ws, int nb1, int nb2,
+                                                                float f, int64_t n, float* __restrict__ delta,
+                                                                float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
+    __shared__ double scratch[16];
+    __shared__ unsigned long long scratch_u[16];
+    const float d = delta_from_partials(ws->p1, nb1, f, n, scratch);
+    double acc = 0.0;
+    unsigned long long c = 0;
+    for (int i = threadIdx.x; i < nb2; i += blockDim.x) {
+        acc += ws->p2[i];
+        c += ws->cnt[i];
+    }
+    const double s = block_sum(acc, scratch);
+    const unsigned long long total = block_sum(c, scratch_u);
+    if (threadIdx.x == 0) {
+        delta[0] = d;
+        nnz[0] = total;
+        alpha[0] = total ? static_cast<float>(s / static_cast<double>(total)) : 0.0f;
+    }
+}
+
 __device__ __forceinline__ uint32_t quad_or(uint32_t v) {
     // OR across the 4 lanes of a quad (DPP quad_perm [1,0,3,2] then [2,3,0,1]).
     v |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0xB1, 0xF, 0xF, false));
@@ -81,8 +108,9 @@ __device__ __forceinline__ uint32_t quad_or(uint32_t v) {
 // position in the quad equals the load index, so each wave stores 256
 // contiguous bytes.
 __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
-    const float* __restrict__ W, int64_t n, const double* __restrict__ p1, int nb1, float f,
-    uint32_t* __restrict__ packed, double* __restrict__ p2, uint64_t* __restrict__ cnt, int reverse) {
+    const float* __restrict__ W, int64_t n, TernWorkspace* __restrict__ ws, int nb1, float f,
+    uint32_t* __restrict__ packed, int reverse) {
+    const double* __restrict__ p1 = ws->p1;
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
     const int tid = threadIdx.x;
@@ -126,62 +154,70 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
     }
     const double total = block_sum(acc, scratch);
     const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
-    if (tid == 0) {
-        p2[blockIdx.x] = total;
-        cnt[blockIdx.x] = ctotal;
+    if (threadIdx.x == 0) {
+        ws->p2[blockIdx.x] = total;
+        ws->cnt[blockIdx.x] = ctotal;
     }
 }
 
-__global__ __launch_bounds__(kTernThreads) void mask_stats_kernel(
-    const float* __restrict__ W, int64_t n, const double* __restrict__ p1, int nb1, float f,
-    double* __restrict__ p2, uint64_t* __restrict__ cnt) {
+// Pass 2 for any layout: grid-stride over the output words of the normal copy (which also carry the
+// masked sum and count: every weight belongs to exactly one normal word) and of the transposed copy.
+//   normal:     row = filter o,        k   = (r*S+s)*C + c
+//   transposed: row = input channel c, k_T = (r*S+s)*rows + o   (threads ordered with c fastest)
+__global__ __launch_bounds__(kTernThreads) void mask_pack_gather_kernel(
+    const float* __restrict__ W, int rows, int C, int RS, TernWorkspace* __restrict__ ws, int nb1, float f,
+    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT) {
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
-    const int tid = threadIdx.x;
-    const float delta = delta_from_partials(p1, nb1, f, n, scratch);
-    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    const int64_t n = static_cast<int64_t>(rows) * C * RS;
+    const float delta = delta_from_partials(ws->p1, nb1, f, n, scratch);
+    const int64_t words_n = static_cast<int64_t>(rows) * wpr;
+    const int64_t words_t = packed_T ? static_cast<int64_t>(C) * wprT : 0;
+    const int64_t K = static_cast<int64_t>(RS) * C, KT = static_cast<int64_t>(RS) * rows;
     double acc = 0.0;
     uint32_t count = 0;
-    for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        const int64_t base = c * kChunk;
-        for (int j = 0; j < 16; ++j) {
-            const int64_t idx = base + j * kTernThreads + tid;
-            if (idx < n) {
-                const float a = fabsf(W[idx]);
-                if (a > delta) {
-                    acc += static_cast<double>(a);
-                    ++count;
+    for (int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; id < words_n + words_t;
+         id += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        uint32_t word = 0;
+        if (id < words_n) {
+            const int o = static_cast<int>(id / wpr), j = static_cast<int>(id % wpr);
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                const int64_t k = static_cast<int64_t>(j) * 16 + t;
+                if (k < K) {
+                    const int rs = static_cast<int>(k / C);
+                    const int c = static_cast<int>(k - static_cast<int64_t>(rs) * C);
+                    const float w = W[(static_cast<int64_t>(o) * C + c) * RS + rs];
+                    const uint32_t fld = code_field(w, delta);
+                    if (fld) {
+                        acc += static_cast<double>(fabsf(w));
+                        ++count;
+                    }
+                    word |= fld << ((t & 1) * 16 + (t >> 1) * 2);
                 }
             }
+            packed[id] = word;
+        } else {
+            const int64_t it = id - words_n;
+            const int c = static_cast<int>(it % C), j = static_cast<int>(it / C);
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                const int64_t k = static_cast<int64_t>(j) * 16 + t;
+                if (k < KT) {
+                    const int rs = static_cast<int>(k / rows);
+                    const int o = static_cast<int>(k - static_cast<int64_t>(rs) * rows);
+                    word |= code_field(W[(static_cast<int64_t>(o) * C + c) * RS + rs], delta)
+                            << ((t & 1) * 16 + (t >> 1) * 2);
+                }
+            }
+            packed_T[static_cast<int64_t>(c) * wprT + j] = word;
         }
     }
     const double total = block_sum(acc, scratch);
     const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
-    if (tid == 0) {
-        p2[blockIdx.x] = total;
-        cnt[blockIdx.x] = ctotal;
-    }
-}
-
-__global__ __launch_bounds__(kTernThreads) void finalize_kernel(
-    const double* __restrict__ p1, int nb1, const double* __restrict__ p2,
-    const uint64_t* __restrict__ cnt, int nb2, float f, int64_t n,
-    float* __restrict__ delta, float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
-    __shared__ double scratch[16];
-    __shared__ unsigned long long scratch_u[16];
-    const float d = delta_from_partials(p1, nb1, f, n, scratch);
-    double acc = 0.0;
-    unsigned long long c = 0;
-    for (int i = threadIdx.x; i < nb2; i += blockDim.x) {
-        acc += p2[i];
-        c += cnt[i];
-    }
-    const double s = block_sum(acc, scratch);
-    const unsigned long long total = block_sum(c, scratch_u);
     if (threadIdx.x == 0) {
-        delta[0] = d;
-        nnz[0] = total;
-        alpha[0] = total ? static_cast<float>(s / static_cast<double>(total)) : 0.0f;
+        ws->p2[blockIdx.x] = total;
+        ws->cnt[blockIdx.x] = ctotal;
     }
 }
 
@@ -297,7 +333,6 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
     const int wpr = static_cast<int>(twn_packed_words_per_row(K));
     const int wprT = static_cast<int>(twn_packed_words_per_row(KT));
     const int rows_per_group = wd->rows / groups;
-    bool packed_done = false;
 
     if (groups == 1) {
         TernWorkspace* ws = static_cast<TernWorkspace*>(workspace);
@@ -310,26 +345,33 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
         const bool flat = (RS == 1) && (K % 128 == 0);
         if (flat) {
             const int reverse = env_int("TWN_TERN_REVERSE", 1);
-            mask_pack_flat_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1, nb, delta_factor, packed,
-                                                               ws->p2, ws->cnt, reverse);
-            packed_done = true;
+            mask_pack_flat_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws, nb, delta_factor, packed, reverse);
+            finalize_kernel<<<1, kTernThreads, 0, st>>>(ws, nb, nb, delta_factor, n, delta, alpha, nnz);
+            if (packed_T) {
+                const int64_t words = static_cast<int64_t>(wd->C) * wprT;
+                pack_gather_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(
+                    W, wd->rows, wd->C, static_cast<int>(RS), delta, rows_per_group, packed_T, wprT, 1);
+            }
         } else {
-            mask_stats_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1, nb, delta_factor, ws->p2, ws->cnt);
+            const int64_t words = static_cast<int64_t>(wd->rows) * wpr +
+                                  (packed_T ? static_cast<int64_t>(wd->C) * wprT : 0);
+            int64_t nb2 = (words + kTernThreads - 1) / kTernThreads;
+            if (nb2 > kMaxBlocks) nb2 = kMaxBlocks;
+            mask_pack_gather_kernel<<<static_cast<unsigned>(nb2), kTernThreads, 0, st>>>(
+                W, wd->rows, wd->C, static_cast<int>(RS), ws, nb, delta_factor, packed, wpr, packed_T, wprT);
+            finalize_kernel<<<1, kTernThreads, 0, st>>>(ws, nb, static_cast<int>(nb2), delta_factor, n, delta, alpha,
+                                                        nnz);
         }
-        finalize_kernel<<<1, kTernThreads, 0, st>>>(ws->p1, nb, ws->p2, ws->cnt, nb, delta_factor, n,
-                                                    delta, alpha, nnz);
     } else {
         group_stats_kernel<<<groups, kTernThreads, 0, st>>>(W, n / groups, delta_factor, delta, alpha, nnz);
-    }
-    if (!packed_done) {
         const int64_t words = static_cast<int64_t>(wd->rows) * wpr;
         pack_gather_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(
             W, wd->rows, wd->C, static_cast<int>(RS), delta, rows_per_group, packed, wpr, 0);
-    }
-    if (packed_T) {
-        const int64_t words = static_cast<int64_t>(wd->C) * wprT;
-        pack_gather_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(
-            W, wd->rows, wd->C, static_cast<int>(RS), delta, rows_per_group, packed_T, wprT, 1);
+        if (packed_T) {
+            const int64_t wordsT = static_cast<int64_t>(wd->C) * wprT;
+            pack_gather_kernel<<<static_cast<unsigned>((wordsT + 255) / 256), 256, 0, st>>>(
+                W, wd->rows, wd->C, static_cast<int>(RS), delta, rows_per_group, packed_T, wprT, 1);
+        }
     }
     return launch_status();
 }
