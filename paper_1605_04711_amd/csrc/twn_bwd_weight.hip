@@ -6,9 +6,9 @@
 // Dense bf16 x bf16 -> fp32 MFMA GEMM  D[o][j] = sum_pix dY[pix][o] * Xg[pix][j],
 // j = (r*S+s)*C + c.  The reduction index (pixels) is the slow index of both
 // NHWC operands, so MFMA fragments (8 consecutive pixels of one channel per
-// lane) need a transpose.  Main kernel (weight_grad_dma_kernel, channel counts
+// lane) need a transpose.  Main kernel (weight_grad_patch_kernel, channel counts
 // multiples of 8): both tiles go global -> LDS untransposed with direct 16-byte
-// LDS loads, two slabs of 64 pixels deep, and fragments are fetched with the
+// LDS loads, three slabs of 32 pixels deep, and fragments are fetched with the
 // gfx950 transposing LDS read ds_read_tr16_b64 (a 16-lane group reads a 4 pixel
 // x 16 channel block and each lane receives 4 consecutive pixels of its own
 // channel); 16-byte chunks are XOR-swizzled by 2*(pixel & 3) so the four pixel
@@ -22,6 +22,8 @@
 // keeps both the transposing writes and the fragment reads at the minimum
 // number of LDS bank passes.  The pixel range is split over blockIdx.y; partial
 // tiles go to a workspace and are summed in a fixed order (deterministic).
+#include <type_traits>
+
 #include "twn_kernels.h"
 
 namespace twn {
@@ -29,6 +31,7 @@ namespace twn {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Exact unsigned division of numerators below 2^31 by a runtime constant.
 struct FastDiv {
@@ -54,6 +57,8 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv& f) {
 struct WGArgs {
     WeightGrad w;
     FastDiv divPQ, divQ, divC, divS;
+    FastDiv divSX, divSY;       // patch kernel: slab index -> (batch, row, column) patch coordinates
+    WgPlan plan;
     int64_t pixels;
     int32_t J;
     int32_t slabs_per_split;
@@ -246,106 +251,146 @@ __device__ __forceinline__ void wg_dma16(const void* gsrc, void* lds_dst) {
                                      (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 }
 
-// 8 consecutive pixels of one channel for this lane: two transposing reads of 4 pixels each.
-// `base` points at (pixel of this lane's group row, channel block) as described in the file header.
-__device__ __forceinline__ bf16x8 wg_frag(const unsigned char* p0, const unsigned char* p1) {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
-    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+// Transposing LDS read of 4 pixels x 16 bits for this lane (see the file header).  Issued as inline
+// assembly: the compiler would otherwise order every LDS read after ALL outstanding direct-to-LDS
+// loads (s_waitcnt vmcnt(0)), which serialises the software pipeline.  The caller waits for the data
+// with wg_wait_frags before using it.
+template <int OFFSET>
+__device__ __forceinline__ u32x2 wg_tr_read(uint32_t lds_addr) {
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(OFFSET));
+    return v;
+}
+
+// s_waitcnt lgkmcnt(0) that the consumers of the twelve fragment halves depend on.
+__device__ __forceinline__ void wg_wait_frags(u32x2 (&fa)[2][2], u32x2 (&fb)[4][2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(fa[0][0]), "+v"(fa[0][1]), "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fb[0][0]), "+v"(fb[0][1]),
+                   "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[2][0]), "+v"(fb[2][1]), "+v"(fb[3][0]), "+v"(fb[3][1]));
+}
+
+__device__ __forceinline__ bf16x8 wg_join(const u32x2& lo, const u32x2& hi) {
+    const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// Patch variant: 128 (o) x 256 (j) tile, reduction slabs of 32 pixels that form a pn x ph x pw patch of
+// the output images.  The sum over pixels is order-free, so enumerating them patch by patch instead of
+// linearly costs nothing and makes addressing cheap: the patch origin is uniform per slab (scalar
+// arithmetic), a lane's offsets inside the patch are fixed, and no per-lane division is left.
+// Waves 2 (o) x 2 (j): wave tile 64 x 128; wave column wn owns one 128-column half of the B tile.
 template <int STAGES>
-__global__ __launch_bounds__(256, 2) void weight_grad_dma_kernel(const WGArgs a) {
-    constexpr int TILE_BYTES = 64 * 256;            // 64 pixels x 128 channels bf16
-    constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+__global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs a) {
+    constexpr int A_BYTES = 32 * 256;               // 32 pixels x 128 channels bf16
+    constexpr int B_BYTES = 2 * A_BYTES;            // two 128-column halves
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int PD = STAGES - 1;
-    constexpr int PER_STAGE = 8;                    // direct LDS loads per wave per slab
+    constexpr int PER_STAGE = 6;                    // direct LDS loads per wave per slab
     extern __shared__ __attribute__((aligned(1024))) unsigned char wsm[];
+    // LDS byte address of the dynamic array (low 32 bits of its generic address are the LDS offset)
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) unsigned char*)wsm));
 
     const WeightGrad& w = a.w;
+    const WgPlan& pl = a.plan;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lh = lane >> 5;
 
-    const int tiles_j = (a.J + kWgTile - 1) / kWgTile;
-    const int o0 = static_cast<int>(blockIdx.x / tiles_j) * kWgTile;
-    const int j0 = static_cast<int>(blockIdx.x % tiles_j) * kWgTile;
-    const int split = blockIdx.y;
-    const int64_t slab_begin = static_cast<int64_t>(split) * a.slabs_per_split;
-    const int64_t total_slabs = (a.pixels + 63) / 64;
+    const int tiles_j = (a.J + 255) / 256;
+    const int o0 = static_cast<int>(blockIdx.x / tiles_j) * 128;
+    const int j0 = static_cast<int>(blockIdx.x % tiles_j) * 256;
+    const int64_t slab_begin = static_cast<int64_t>(blockIdx.y) * a.slabs_per_split;
     int64_t slab_end = slab_begin + a.slabs_per_split;
-    if (slab_end > total_slabs) slab_end = total_slabs;
+    if (slab_end > pl.slabs) slab_end = pl.slabs;
     const int nslab = static_cast<int>(slab_end - slab_begin);
     const void* zero = kWgZeroBlock;
 
-    // ---- loader: one wave-level load covers 4 pixel rows x 256 bytes; lane -> (row, 16-byte slot) ----
+    // ---- loader: a wave-level load covers 4 pixel rows x 256 bytes; this wave loads row groups wave and wave+4 ----
     const int prow = lane >> 4;
     const int qch = (lane & 15) ^ (2 * (prow & 3));     // logical 8-channel chunk fetched by this lane
     const int oo = o0 + qch * 8;
-    const int jj = j0 + qch * 8;
-    const uint32_t rs = fdiv(jj, a.divC);
-    const int tc = jj - static_cast<int>(rs) * w.C;
-    const int tr = static_cast<int>(fdiv(rs, a.divS));
-    const int ts = static_cast<int>(rs) - tr * w.S;
-    const bool ook = oo < w.O, jok = jj < a.J;
+    const bool ook = oo < w.O;
+    int tc[2], th0[2], tw0[2];
+    bool jok[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int jj = j0 + h * 128 + qch * 8;
+        const uint32_t rs = fdiv(jj, a.divC);
+        tc[h] = jj - static_cast<int>(rs) * w.C;
+        const int tr = static_cast<int>(fdiv(rs, a.divS));
+        const int ts = static_cast<int>(rs) - tr * w.S;
+        th0[h] = tr * w.dh - w.ph;
+        tw0[h] = ts * w.dw - w.pw;
+        jok[h] = jj < a.J;
+    }
+    // offsets of this lane's two pixels inside a patch (local pixel l = 4*group + prow)
+    const int lpw = __builtin_ctz(pl.pw), lph = __builtin_ctz(pl.ph);
+    int dn[2], dy[2], dx[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int l = 4 * (wave + 4 * t) + prow;
+        dx[t] = l & (pl.pw - 1);
+        dy[t] = (l >> lpw) & (pl.ph - 1);
+        dn[t] = l >> (lpw + lph);
+    }
 
-    // pixel counts fit 31 bits (checked on the host), so pixel arithmetic is 32-bit; only the final
-    // element offsets are 64-bit
-    const int th0 = tr * w.dh - w.ph, tw0 = ts * w.dw - w.pw;
-    const uint32_t npix = static_cast<uint32_t>(a.pixels);
     auto issue = [&](int64_t slab, int stage, bool live) {
         unsigned char* sA = wsm + stage * STAGE_BYTES;
-        unsigned char* sB = sA + TILE_BYTES;
-        const uint32_t pix0 = static_cast<uint32_t>(slab) * 64u + wave * 4 + prow;
+        unsigned char* sB = sA + A_BYTES;
+        // patch origin: uniform over the workgroup
+        const uint32_t su = static_cast<uint32_t>(slab);
+        const uint32_t t1 = fdiv(su, a.divSX);
+        const uint32_t sx = su - t1 * pl.sx;
+        const uint32_t sn = fdiv(t1, a.divSY);
+        const uint32_t sy = t1 - sn * pl.sy;
+        const int n0 = static_cast<int>(sn) * pl.pn, p0 = static_cast<int>(sy) * pl.ph, q0 = static_cast<int>(sx) * pl.pw;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t pix = pix0 + i * 16;
-            const bool pok = live && pix < npix;
-            const uint32_t n = fdiv(pix, a.divPQ);
-            const uint32_t rem = pix - n * a.divPQ.d;
-            const uint32_t p = fdiv(rem, a.divQ);
-            const uint32_t q = rem - p * w.Q;
-            const int ih = static_cast<int>(p) * w.sh + th0;
-            const int iw = static_cast<int>(q) * w.sw + tw0;
-            const bool bok = pok && jok && static_cast<unsigned>(ih) < static_cast<unsigned>(w.H) &&
-                             static_cast<unsigned>(iw) < static_cast<unsigned>(w.W);
-            const uint32_t ipix = (n * w.H + ih) * w.W + iw;
-            const void* srcA = (pok && ook) ? static_cast<const void*>(w.dY + static_cast<uint64_t>(pix) * w.O + oo)
+        for (int t = 0; t < 2; ++t) {
+            const int n = n0 + dn[t], p = p0 + dy[t], q = q0 + dx[t];
+            const bool pok = live && n < w.N && p < w.P && q < w.Q;
+            const uint32_t opix = (static_cast<uint32_t>(n) * w.P + p) * w.Q + q;
+            const void* srcA = (pok && ook) ? static_cast<const void*>(w.dY + static_cast<uint64_t>(opix) * w.O + oo)
                                             : zero;
-            const void* srcB = bok ? static_cast<const void*>(w.X + static_cast<uint64_t>(ipix) * w.C + tc) : zero;
-            wg_dma16(srcA, sA + (i * 4 + wave) * 1024);
-            wg_dma16(srcB, sB + (i * 4 + wave) * 1024);
+            wg_dma16(srcA, sA + (wave + 4 * t) * 1024);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int ih = p * w.sh + th0[h], iw = q * w.sw + tw0[h];
+                const bool bok = pok && jok[h] && static_cast<unsigned>(ih) < static_cast<unsigned>(w.H) &&
+                                 static_cast<unsigned>(iw) < static_cast<unsigned>(w.W);
+                const uint32_t ipix = (static_cast<uint32_t>(n) * w.H + ih) * w.W + iw;
+                const void* srcB = bok ? static_cast<const void*>(w.X + static_cast<uint64_t>(ipix) * w.C + tc[h])
+                                       : zero;
+                wg_dma16(srcB, sB + h * A_BYTES + (wave + 4 * t) * 1024);
+            }
         }
     };
 
-    // ---- fragment addressing (transposing read): lane -> (pixel row in its 4-row block, 4-channel sub-block) ----
+    // ---- fragment addressing (transposing read), as in the linear kernel ----
     const int li = lane & 15;
-    const int fpix = 8 * lh + (li >> 2);                 // + 16*kk (+4 for the second read)
-    const int fch = 16 * ((lane >> 4) & 1) + 4 * (li & 3);   // + wave tile offset + 32*mi
+    const int fpix = 8 * lh + (li >> 2);
+    const int fch = 16 * ((lane >> 4) & 1) + 4 * (li & 3);
     auto frag_off = [&](int chan0, int pixel) -> int {
         const int ch = chan0 + fch;
         const int chunk = (ch >> 3) ^ (2 * (pixel & 3));
         return pixel * 256 + chunk * 16 + (ch & 7) * 2;
     };
-    // byte offsets inside a tile for MFMA step 0; step kk adds kk*16 pixel rows = kk*4096 bytes
-    // (16 is a multiple of 4, so the swizzle term does not change)
-    int offA[2][2], offB[2][2];
+    int offA[2][2], offB[4][2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int hv = 0; hv < 2; ++hv) {
 #pragma unroll
-        for (int hv = 0; hv < 2; ++hv) {
-            offA[t][hv] = frag_off(wm * 64 + t * 32, fpix + 4 * hv);
-            offB[t][hv] = frag_off(wn * 64 + t * 32, fpix + 4 * hv);
-        }
+        for (int mi = 0; mi < 2; ++mi) offA[mi][hv] = frag_off(wm * 64 + mi * 32, fpix + 4 * hv);
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) offB[ni][hv] = wn * A_BYTES + frag_off(ni * 32, fpix + 4 * hv);
+    }
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][4];
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
 
@@ -358,23 +403,30 @@ __global__ __launch_bounds__(256, 2) void weight_grad_dma_kernel(const WGArgs a)
     int stage = 0, fill = PD;
     for (int it = 0; it < nslab; ++it) {
         issue(slab_begin + it + PD, fill, it + PD < nslab);
-        const unsigned char* sA = wsm + stage * STAGE_BYTES;
-        const unsigned char* sB = sA + TILE_BYTES;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 af[2], bfr[2];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                af[mi] = wg_frag(sA + offA[mi][0] + kk * 4096, sA + offA[mi][1] + kk * 4096);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                bfr[ni] = wg_frag(sB + offB[ni][0] + kk * 4096, sB + offB[ni][1] + kk * 4096);
+        const uint32_t sA = lds_base + stage * STAGE_BYTES;
+        const uint32_t sB = sA + A_BYTES;
+        auto step = [&](auto kk_tag) {
+            constexpr int KK = decltype(kk_tag)::value;
+            u32x2 fa[2][2], fb[4][2];
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-        }
+                for (int hv = 0; hv < 2; ++hv) fa[mi][hv] = wg_tr_read<KK * 4096>(sA + offA[mi][hv]);
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                for (int hv = 0; hv < 2; ++hv) fb[ni][hv] = wg_tr_read<KK * 4096>(sB + offB[ni][hv]);
+            wg_wait_frags(fa, fb);
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg_join(fa[mi][0], fa[mi][1]),
+                                                                          wg_join(fb[ni][0], fb[ni][1]), acc[mi][ni],
+                                                                          0, 0, 0);
+        };
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 1) * PER_STAGE));
         __builtin_amdgcn_s_barrier();
@@ -384,12 +436,12 @@ __global__ __launch_bounds__(256, 2) void weight_grad_dma_kernel(const WGArgs a)
     }
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm(0));
 
-    float* out = w.partial + static_cast<int64_t>(split) * w.O * a.J;
+    float* out = w.partial + static_cast<int64_t>(blockIdx.y) * w.O * a.J;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const int j = j0 + wn * 64 + ni * 32 + lrow;
+        for (int ni = 0; ni < 4; ++ni) {
+            const int j = j0 + wn * 128 + ni * 32 + lrow;
             if (j >= a.J) continue;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
@@ -453,9 +505,7 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float* __res
     dbias[ch] = s;
 }
 
-int32_t weight_grad_splits(int64_t pixels, int32_t O, int64_t J) {
-    const int64_t tiles = ((O + kWgTile - 1) / kWgTile) * ((J + kWgTile - 1) / kWgTile);
-    const int64_t slabs = (pixels + 63) / 64;
+static int32_t choose_splits(int64_t tiles, int64_t slabs) {
     int64_t want = env_int("TWN_WG_BLOCKS", 512);
     int64_t splits = (want + tiles - 1) / tiles;
     if (splits > slabs) splits = slabs;
@@ -463,8 +513,37 @@ int32_t weight_grad_splits(int64_t pixels, int32_t O, int64_t J) {
     if (splits < 1) splits = 1;
     // every split must own at least one slab
     const int64_t per = (slabs + splits - 1) / splits;
-    splits = (slabs + per - 1) / per;
-    return static_cast<int32_t>(splits);
+    return static_cast<int32_t>((slabs + per - 1) / per);
+}
+
+WgPlan plan_weight_grad(int32_t N, int32_t P, int32_t Q, int32_t C, int32_t O, int32_t R, int32_t S) {
+    WgPlan pl{};
+    const int64_t J = static_cast<int64_t>(R) * S * C;
+    const int64_t pixels = static_cast<int64_t>(N) * P * Q;
+    pl.patch = (C % 8 == 0) && (O % 8 == 0);
+    if (!pl.patch) {
+        pl.tiles = static_cast<int32_t>(((O + kWgTile - 1) / kWgTile) * ((J + kWgTile - 1) / kWgTile));
+        pl.slabs = (pixels + 63) / 64;
+        pl.splits = choose_splits(pl.tiles, pl.slabs);
+        return pl;
+    }
+    // 32-pixel patch pn x ph x pw (powers of two) that wastes the fewest padded pixels; ties go to wide rows
+    int64_t best = -1;
+    for (int lw = 5; lw >= 0; --lw)
+        for (int lh = 5 - lw; lh >= 0; --lh) {
+            const int pw = 1 << lw, ph = 1 << lh, pn = 32 / (pw * ph);
+            const int64_t sx = (Q + pw - 1) / pw, sy = (P + ph - 1) / ph, sn = (N + pn - 1) / pn;
+            const int64_t padded = sx * sy * sn;
+            if (best < 0 || padded < best) {
+                best = padded;
+                pl.pn = pn; pl.ph = ph; pl.pw = pw;
+                pl.sn = static_cast<int32_t>(sn); pl.sy = static_cast<int32_t>(sy); pl.sx = static_cast<int32_t>(sx);
+            }
+        }
+    pl.slabs = best;
+    pl.tiles = static_cast<int32_t>(((O + 127) / 128) * ((J + 255) / 256));
+    pl.splits = choose_splits(pl.tiles, pl.slabs);
+    return pl;
 }
 
 int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
@@ -477,34 +556,33 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
     a.divC = make_fastdiv(w.C);
     a.divS = make_fastdiv(w.S);
     if (a.pixels >= (1LL << 31)) return TWN_ERR_SHAPE;
-    const int64_t slabs = (a.pixels + 63) / 64;
-    a.slabs_per_split = static_cast<int32_t>((slabs + w.splits - 1) / w.splits);
+    a.plan = plan_weight_grad(w.N, w.P, w.Q, w.C, w.O, w.R, w.S);
+    a.divSX = make_fastdiv(a.plan.patch ? a.plan.sx : 1);
+    a.divSY = make_fastdiv(a.plan.patch ? a.plan.sy : 1);
+    const int32_t splits = a.plan.splits;
+    a.slabs_per_split = static_cast<int32_t>((a.plan.slabs + splits - 1) / splits);
     if (w.dW) {
-        const int tiles = ((w.O + kWgTile - 1) / kWgTile) * ((a.J + kWgTile - 1) / kWgTile);
-        const dim3 grid(tiles, w.splits);
-        const bool vec = (w.C % 8 == 0) && (w.O % 8 == 0);
-        if (vec && env_int("TWN_WG_DMA", 1)) {
-            constexpr int kStages = 2;
-            constexpr int kSmem = kStages * 2 * 64 * 256;
+        const dim3 grid(a.plan.tiles, splits);
+        if (a.plan.patch) {
+            constexpr int kStages = 3;
+            constexpr int kSmem = kStages * 3 * 32 * 256;
             static bool allowed = false;
-            auto k = weight_grad_dma_kernel<kStages>;
+            auto k = weight_grad_patch_kernel<kStages>;
             if (!allowed) {
                 if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         kSmem) != hipSuccess) return TWN_ERR_HIP;
                 allowed = true;
             }
             k<<<grid, 256, kSmem, st>>>(a);
-        } else if (vec) {
-            weight_grad_kernel<true><<<grid, 256, 0, st>>>(a);
         } else {
             weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
         }
         const int64_t total = static_cast<int64_t>(w.O) * a.J;
         weight_grad_reduce_kernel<<<static_cast<unsigned>((total + 63) / 64), 256, 0, st>>>(
-            w.partial, w.splits, w.O, w.C, w.R * w.S, w.beta, w.dW);
+            w.partial, splits, w.O, w.C, w.R * w.S, w.beta, w.dW);
     }
     if (w.dbias) {
-        float* bp = w.partial + static_cast<int64_t>(w.splits) * w.O * a.J;
+        float* bp = w.partial + static_cast<int64_t>(splits) * w.O * a.J;
         bias_grad_partial_kernel<<<dim3((w.O + 63) / 64, kBiasSplits), 256, 0, st>>>(w.dY, a.pixels, w.O, bp);
         bias_grad_final_kernel<<<(w.O + 255) / 256, 256, 0, st>>>(bp, w.O, w.dbias);
     }

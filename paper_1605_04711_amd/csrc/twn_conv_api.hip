@@ -176,9 +176,8 @@ void fill_conv_fwd_small_c(GatherGemm& g, const twn_conv_desc* d, const SmallC& 
 }
 
 size_t weight_grad_bytes(const twn_conv_desc* d, int P, int Q) {
-    const int64_t pixels = static_cast<int64_t>(d->N) * P * Q;
     const int64_t J = static_cast<int64_t>(d->R) * d->S * d->C;
-    const int64_t splits = weight_grad_splits(pixels, d->O, J);
+    const int64_t splits = plan_weight_grad(d->N, P, Q, d->C, d->O, d->R, d->S).splits;
     return static_cast<size_t>((splits * d->O * J + 64LL * d->O) * sizeof(float));
 }
 
@@ -336,8 +335,7 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
         w.P = P; w.Q = Q;
         w.sh = d->stride_h; w.sw = d->stride_w; w.ph = d->pad_h; w.pw = d->pad_w;
         w.dh = d->dil_h; w.dw = d->dil_w;
-        w.splits = weight_grad_splits(static_cast<int64_t>(d->N) * P * Q, d->O,
-                                      static_cast<int64_t>(d->R) * d->S * d->C);
+        w.splits = plan_weight_grad(d->N, P, Q, d->C, d->O, d->R, d->S).splits;
         rc = launch_weight_grad(w, st);
     }
     return rc;

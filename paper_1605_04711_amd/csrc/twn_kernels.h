@@ -70,7 +70,17 @@ struct WeightGrad {
     int32_t splits;
 };
 
-int32_t weight_grad_splits(int64_t pixels, int32_t O, int64_t J);
+// How the weight gradient of one layer is cut up; a pure function of the shapes, shared by the
+// workspace query and the launch.
+struct WgPlan {
+    int32_t patch;          // 1: 128x256 tiles over 32-pixel patches (channel counts multiples of 8); 0: 128x128 tiles over 64 consecutive pixels
+    int32_t pn, ph, pw;     // patch = pn images x ph rows x pw columns (pn*ph*pw = 32), powers of two
+    int32_t sn, sy, sx;     // patches along batch, rows, columns
+    int64_t slabs;          // reduction slabs in total
+    int32_t splits;         // blockIdx.y ranges of slabs
+    int32_t tiles;          // output tiles (blockIdx.x)
+};
+WgPlan plan_weight_grad(int32_t N, int32_t P, int32_t Q, int32_t C, int32_t O, int32_t R, int32_t S);
 int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st);
 
 }  // namespace twn
