@@ -361,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
                 const bool bok = pok && jok[h] && static_cast<unsigned>(ih) < static_cast<unsigned>(w.H) &&
                                  static_cast<unsigned>(iw) < static_cast<unsigned>(w.W);
                 const uint32_t ipix = (static_cast<uint32_t>(n) * w.H + ih) * w.W + iw;
-                const void* srcB = bok ? static_cast<const void*>(w.X + static_cast<uint64_t>(ipix) * w.C + tc[h])
+                const void* srcB = bok ? static_cast<const void*>(w.X + static_cast<uint64_t>(ipix) * w.xc + tc[h])
                                        : zero;
                 wg_dma16(srcB, sB + h * A_BYTES + (wave + 4 * t) * 1024);
             }
@@ -436,6 +436,28 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
     }
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm(0));
 
+    if (pl.splits == 1 && !w.pad_sp) {
+        // the only range: write the gradient itself, [O][C][R][S], without a reduction pass
+        const int RS = w.R * w.S;
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            const int j = j0 + wn * 128 + ni * 32 + lrow;
+            if (j >= a.J) continue;
+            const uint32_t rs = fdiv(j, a.divC);
+            const int c = j - static_cast<int>(rs) * w.C;
+            const int64_t col = static_cast<int64_t>(c) * RS + rs;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int o = o0 + wm * 64 + mi * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+                    if (o >= w.O) continue;
+                    float* dst = w.dW + static_cast<int64_t>(o) * a.J + col;
+                    *dst = (w.beta != 0.0f) ? w.beta * *dst + acc[mi][ni][e] : acc[mi][ni][e];
+                }
+        }
+        return;
+    }
     float* out = w.partial + static_cast<int64_t>(blockIdx.y) * w.O * a.J;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
@@ -452,28 +474,46 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
 }
 
 // dW[o][c][r][s] = beta*dW + sum over splits (fixed order) of partial[split][o][(r*S+s)*C + c]
+// `pad_sp` = 0: partial tiles are [O][(r*S+s)*C + c].  First-layer mode (`pad_sp` = Sp > 0): tiles are
+// [O][(r*Sp+s)*4 + c] and entries with s >= S or c >= C are phantom (dropped).
+// 32 consecutive partial elements per block (coalesced over the large input) x 8 thread rows that each
+// sum every 8th split; the rows are combined in a fixed order and the small output is scattered.
 __global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __restrict__ partial, int splits,
-                                                                 int O, int C, int RS, float beta,
+                                                                 int O, int C, int R, int S, int pad_sp, float beta,
                                                                  float* __restrict__ dW) {
-    // 64 consecutive partial elements per block (coalesced over the large input), 4 thread rows that
-    // each sum every 4th split; the rows are combined in a fixed order and the small output is scattered
-    __shared__ float red[4][64];
-    const int col = threadIdx.x & 63, rowi = threadIdx.x >> 6;
-    const int64_t id = static_cast<int64_t>(blockIdx.x) * 64 + col;
-    const int64_t J = static_cast<int64_t>(RS) * C;
-    const int64_t total = J * O;
+    __shared__ float red[8][32];
+    const int col = threadIdx.x & 31, rowi = threadIdx.x >> 5;
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * 32 + col;
+    const int64_t Jsrc = pad_sp ? static_cast<int64_t>(R) * pad_sp * 4 : static_cast<int64_t>(R) * S * C;
+    const int64_t total = Jsrc * O;
     float s = 0.0f;
-    if (id < total)
-        for (int sp = rowi; sp < splits; sp += 4) s += partial[static_cast<int64_t>(sp) * total + id];
+    if (id < total) {
+#pragma unroll 4
+        for (int sp = rowi; sp < splits; sp += 8) s += partial[static_cast<int64_t>(sp) * total + id];
+    }
     red[rowi][col] = s;
     __syncthreads();
     if (rowi != 0 || id >= total) return;
-    s = ((red[0][col] + red[1][col]) + red[2][col]) + red[3][col];
-    const int64_t o = id / J;
-    const int64_t j = id - o * J;        // = rs*C + c in the partial tiles
-    const int64_t rs = j / C;
-    const int64_t c = j - rs * C;
-    const int64_t dst = o * J + c * RS + rs;   // [O][C][R][S]
+    s = red[0][col];
+#pragma unroll
+    for (int r8 = 1; r8 < 8; ++r8) s += red[r8][col];
+    const int64_t o = id / Jsrc;
+    const int64_t j = id - o * Jsrc;
+    int64_t rs, c;
+    int r, sx;
+    if (pad_sp) {
+        c = j & 3;
+        rs = j >> 2;
+        r = static_cast<int>(rs / pad_sp);
+        sx = static_cast<int>(rs - static_cast<int64_t>(r) * pad_sp);
+        if (c >= C || sx >= S) return;
+    } else {
+        rs = j / C;                  // = r*S + s
+        c = j - rs * C;
+        r = static_cast<int>(rs / S);
+        sx = static_cast<int>(rs - static_cast<int64_t>(r) * S);
+    }
+    const int64_t dst = ((o * C + c) * R + r) * S + sx;   // [O][C][R][S]
     dW[dst] = (beta != 0.0f) ? beta * dW[dst] + s : s;
 }
 
@@ -507,9 +547,9 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float* __res
 
 static int32_t choose_splits(int64_t tiles, int64_t slabs) {
     int64_t want = env_int("TWN_WG_BLOCKS", 512);
-    int64_t splits = (want + tiles - 1) / tiles;
+    int64_t splits = (tiles >= 256) ? 1 : (want + tiles - 1) / tiles;
     if (splits > slabs) splits = slabs;
-    if (splits > 1024) splits = 1024;
+    if (splits > 256) splits = 256;
     if (splits < 1) splits = 1;
     // every split must own at least one slab
     const int64_t per = (slabs + splits - 1) / splits;
@@ -577,9 +617,12 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
         } else {
             weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
         }
-        const int64_t total = static_cast<int64_t>(w.O) * a.J;
-        weight_grad_reduce_kernel<<<static_cast<unsigned>((total + 63) / 64), 256, 0, st>>>(
-            w.partial, splits, w.O, w.C, w.R * w.S, w.beta, w.dW);
+        if (w.pad_sp || !(a.plan.patch && splits == 1)) {   // a single-range patch launch writes dW itself
+            const int64_t total = static_cast<int64_t>(w.O) * a.J;
+            const int C = w.pad_sp ? w.c_real : w.C, S = w.pad_sp ? w.s_real : w.S;
+            weight_grad_reduce_kernel<<<static_cast<unsigned>((total + 31) / 32), 256, 0, st>>>(
+                w.partial, splits, w.O, C, w.R, S, w.pad_sp, w.beta, w.dW);
+        }
     }
     if (w.dbias) {
         float* bp = w.partial + static_cast<int64_t>(splits) * w.O * a.J;

@@ -175,7 +175,14 @@ void fill_conv_fwd_small_c(GatherGemm& g, const twn_conv_desc* d, const SmallC& 
     g.chunk_gather = 1;
 }
 
+// Weight-gradient workspace: [padded copy of X in first-layer mode] + split partials + bias partials.
 size_t weight_grad_bytes(const twn_conv_desc* d, int P, int Q) {
+    SmallC sc;
+    if (small_c(d, &sc) && d->O % 8 == 0) {
+        const int64_t Jp = static_cast<int64_t>(d->R) * sc.Sp * 4;
+        const int64_t splits = plan_weight_grad(d->N, P, Q, 8, d->O, d->R, sc.Sp / 2).splits;
+        return sc.x_bytes + static_cast<size_t>((splits * d->O * Jp + 64LL * d->O) * sizeof(float));
+    }
     const int64_t J = static_cast<int64_t>(d->R) * d->S * d->C;
     const int64_t splits = plan_weight_grad(d->N, P, Q, d->C, d->O, d->R, d->S).splits;
     return static_cast<size_t>((splits * d->O * J + 64LL * d->O) * sizeof(float));
@@ -306,7 +313,7 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
     if (dW && !aligned(dW, 4)) return TWN_ERR_ALIGN;
     if (dW || dbias) {
         const size_t need = weight_grad_bytes(d, P, Q);
-        if (!workspace || workspace_bytes < need || !aligned(workspace, 16)) return TWN_ERR_WORKSPACE;
+        if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return TWN_ERR_WORKSPACE;
     }
     hipStream_t st = as_stream(stream);
 
@@ -335,7 +342,22 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
         w.P = P; w.Q = Q;
         w.sh = d->stride_h; w.sw = d->stride_w; w.ph = d->pad_h; w.pw = d->pad_w;
         w.dh = d->dil_h; w.dw = d->dil_w;
-        w.splits = plan_weight_grad(d->N, P, Q, d->C, d->O, d->R, d->S).splits;
+        w.xc = d->C;
+        SmallC sc;
+        if (dW && small_c(d, &sc) && d->O % 8 == 0) {
+            // first-layer mode: gather from the zero-bordered 4-channel copy (rebuilt here: the call is stateless)
+            uint16_t* Xp = static_cast<uint16_t*>(workspace);
+            rc = launch_pad_c4(static_cast<const uint16_t*>(X), d->N, d->H, d->W, d->C, d->pad_h, d->pad_w, sc.Hp,
+                               sc.Wp, Xp, st);
+            if (rc != TWN_OK) return rc;
+            w.X = Xp;
+            w.partial = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + sc.x_bytes);
+            w.H = sc.Hp; w.W = sc.Wp; w.C = 8; w.S = sc.Sp / 2;
+            w.ph = w.pw = 0; w.dw = 2;
+            w.xc = 4;
+            w.pad_sp = sc.Sp; w.c_real = d->C; w.s_real = d->S;
+        }
+        w.splits = plan_weight_grad(d->N, P, Q, w.C, d->O, d->R, w.S).splits;
         rc = launch_weight_grad(w, st);
     }
     return rc;

@@ -68,6 +68,11 @@ struct WeightGrad {
     int32_t N, H, W, C, O, R, S, P, Q;
     int32_t sh, sw, ph, pw, dh, dw;
     int32_t splits;
+    // First-layer mode (0 = off): X is the zero-bordered 4-channel copy, a "channel" chunk of 8 is two
+    // adjacent taps x 4 channels (C = 8, S = pad_sp/2, dw = 2 above), and the reduction maps
+    // j' = (r*pad_sp + s)*4 + c back to [O][c_real][R][s_real], dropping the phantom tap and channels.
+    int32_t pad_sp, c_real, s_real;
+    int32_t xc;             // elements between consecutive pixels of X (C, or 4 in first-layer mode)
 };
 
 // How the weight gradient of one layer is cut up; a pure function of the shapes, shared by the
