@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the GEMM / ternarize-2^28 / ResNet-18 side measurements")
     ap.add_argument("--cpu-batch", type=int, default=16)
+    ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18"], default=None,
+                    help="run one side measurement alone (used for the rocprofv3 summaries in profiles/)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -56,6 +58,77 @@ def main():
 
     def dev_bf16(a):
         return torch.from_numpy(wl.f32_to_bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16).reshape(a.shape)
+
+    def time_call(fn, reps=10, warm=2):
+        for _ in range(warm):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+
+    def side_gemm():
+        # stand-alone GEMM: X [8192 x 4096] bf16, W [4096 x 4096] N(0, 0.02^2)
+        g = wl.gemm_config()
+        gx = dev_bf16(wl.normal(3, wl.IDX_INPUT, (g.N, g.C)))
+        gw = torch.from_numpy(wl.normal(3, 1, (g.O, g.C), std=0.02)).to(dev)
+        gtw = api.twn_ternarize(gw, F)
+        gy = torch.empty((g.N, g.O), dtype=torch.bfloat16, device=dev)
+        t = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=20, warm=3)
+        log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq" % (t * 1e3, g.flops / t / 1e9))
+        return {"us": round(t * 1e3, 1), "tflops": round(g.flops / t / 1e9, 1),
+                "frac_mfma_peak": round(g.flops / t / 1e9 / PEAK_BF16_TFLOPS, 4)}
+
+    def side_ternarize(calibrate=False):
+        # ternarize-only: 2^28 float32 N(0,1) shaped [16384][16384]
+        rows = 1 << 14
+        big = torch.from_numpy(wl.normal(3, 0, (rows, rows))).to(dev)
+        ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
+        if calibrate:
+            # plain copy of known size (1 GiB read + 1 GiB written): calibrates the HBM byte counters
+            dst = torch.empty_like(big)
+            for _ in range(3):
+                dst.copy_(big)
+            torch.cuda.synchronize()
+            del dst
+        btw = api.twn_ternarize(big, F)
+        t = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=ws), reps=20, warm=3)
+        nbytes = (1 << 28) * 8.25
+        log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight)" % (t * 1e3, nbytes / t / 1e6))
+        return {"us": round(t * 1e3, 1), "GBps": round(nbytes / t / 1e6, 1),
+                "frac_hbm_peak": round(nbytes / t / 1e6 / PEAK_HBM_GBPS, 4)}
+
+    def side_resnet18():
+        # ResNet-18 forward, batch 64 (per-layer synthetic inputs, fused scale/shift/ReLU tail)
+        rl = wl.resnet18(64)
+        tot = 0.0
+        for li, L in enumerate(rl):
+            x = dev_bf16(wl.normal(2, wl.IDX_INPUT + li, L.x_shape))
+            tw = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev), F)
+            y = torch.empty(L.y_shape, dtype=torch.bfloat16, device=dev)
+            sc = torch.ones(L.O, dtype=torch.float32, device=dev)
+            sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
+            st, pd, dl = (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2
+            ws = torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tw, st, pd, dl)), dtype=torch.uint8,
+                             device=dev)
+            t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y,
+                                                     workspace=ws), reps=10)
+            tot += t
+            log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq" % (L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
+            del x, y
+        rflops = sum(L.flops for L in rl)
+        log("resnet18 b64 conv/fc layers: %.3f ms, %.0f img/s" % (tot, 64 / (tot * 1e-3)))
+        return {"ms": round(tot, 4), "img_per_s": round(64 / (tot * 1e-3), 1), "tflops": round(rflops / tot / 1e9, 1),
+                "frac_mfma_peak": round(rflops / tot / 1e9 / PEAK_BF16_TFLOPS, 4)}
+
+    if args.only:
+        res = {"gemm": side_gemm, "ternarize": lambda: side_ternarize(calibrate=True), "resnet18": side_resnet18}[args.only]()
+        print(json.dumps({"only": args.only, **res}), flush=True)
+        return
 
     # ---------------- workload: VGG-7, batch 128 ----------------
     CFG = 1
@@ -180,17 +253,6 @@ def main():
             "calls": "fwd c2-c6 + bwd_data c2-c4,c6 (one launch each)"}
     dw_tflops = flops_dw / (phase_ms[3] * 1e-3) / 1e12
 
-    def time_call(fn, reps=10, warm=2):
-        for _ in range(warm):
-            fn()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            fn()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps
-
     extras = {"phase_ms": {phase_names[i]: round(phase_ms[i], 4) for i in range(4)},
               "fwd_tflops": round(flops_fwd / (phase_ms[1] * 1e-3) / 1e12, 2),
               "bwd_data_tflops": round(flops_dx / (phase_ms[2] * 1e-3) / 1e12, 2),
@@ -200,50 +262,9 @@ def main():
     if not args.no_extras:
         del X, dY, Y, dX, dW
         torch.cuda.empty_cache()
-        # stand-alone GEMM: X [8192 x 4096] bf16, W [4096 x 4096] N(0, 0.02^2)
-        g = wl.gemm_config()
-        gx = dev_bf16(wl.normal(3, wl.IDX_INPUT, (g.N, g.C)))
-        gw = torch.from_numpy(wl.normal(3, 1, (g.O, g.C), std=0.02)).to(dev)
-        gtw = api.twn_ternarize(gw, F)
-        gy = torch.empty((g.N, g.O), dtype=torch.bfloat16, device=dev)
-        t = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=20, warm=3)
-        extras["gemm_8192x4096x4096"] = {"us": round(t * 1e3, 1), "tflops": round(g.flops / t / 1e9, 1),
-                                         "frac_mfma_peak": round(g.flops / t / 1e9 / PEAK_BF16_TFLOPS, 4)}
-        log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq" % (t * 1e3, g.flops / t / 1e9))
-        del gx, gw, gy
-        # ternarize-only: 2^28 float32 N(0,1)
-        rows = 1 << 14
-        big = torch.from_numpy(wl.normal(3, 0, (rows, rows))).to(dev)
-        btw = api.twn_ternarize(big, F)
-        t = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=tern_ws), reps=20, warm=3)
-        nbytes = (1 << 28) * 8.25
-        extras["ternarize_2p28"] = {"us": round(t * 1e3, 1), "GBps": round(nbytes / t / 1e6, 1),
-                                    "frac_hbm_peak": round(nbytes / t / 1e6 / PEAK_HBM_GBPS, 4)}
-        log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight)" % (t * 1e3, nbytes / t / 1e6))
-        del big, btw
-        torch.cuda.empty_cache()
-        # ResNet-18 forward, batch 64 (per-layer synthetic inputs, fused scale/shift/ReLU tail)
-        rl = wl.resnet18(64)
-        tot = 0.0
-        for li, L in enumerate(rl):
-            x = dev_bf16(wl.normal(2, wl.IDX_INPUT + li, L.x_shape))
-            tw = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev), F)
-            y = torch.empty(L.y_shape, dtype=torch.bfloat16, device=dev)
-            sc = torch.ones(L.O, dtype=torch.float32, device=dev)
-            sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
-            st, pd, dl = (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2
-            ws = torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tw, st, pd, dl)), dtype=torch.uint8,
-                             device=dev)
-            t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y,
-                                                     workspace=ws), reps=10)
-            tot += t
-            log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq" % (L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
-            del x, y
-        rflops = sum(L.flops for L in rl)
-        extras["resnet18_b64_fwd"] = {"ms": round(tot, 4), "img_per_s": round(64 / (tot * 1e-3), 1),
-                                      "tflops": round(rflops / tot / 1e9, 1),
-                                      "frac_mfma_peak": round(rflops / tot / 1e9 / PEAK_BF16_TFLOPS, 4)}
-        log("resnet18 b64 conv/fc layers: %.3f ms, %.0f img/s" % (tot, 64 / (tot * 1e-3)))
+        extras["gemm_8192x4096x4096"] = side_gemm()
+        extras["ternarize_2p28"] = side_ternarize()
+        extras["resnet18_b64_fwd"] = side_resnet18()
 
     cpu = None
     if not args.no_cpu:

@@ -35,29 +35,42 @@ __global__ __launch_bounds__(kTernThreads) void abs_sum_kernel(const float* __re
                                                                double* __restrict__ partial) {
     __shared__ double scratch[16];
     const int tid = threadIdx.x;
-    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    const int64_t nfull = n / kChunk;          // chunks that need no bounds test
     double acc = 0.0;
-    for (int64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        const int64_t base = c * kChunk;
-        if (base + kChunk <= n) {
-            const float4* src = reinterpret_cast<const float4*>(W + base);
-            float4 v[4];
+    auto load4 = [&](int64_t c, float4* v) {
+        const float4* src = reinterpret_cast<const float4*>(W + c * kChunk);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = src[j * kTernThreads + tid];
+        for (int j = 0; j < 4; ++j) v[j] = src[j * kTernThreads + tid];
+    };
+    // software pipeline: the next chunk's loads are in flight while this one is summed
+    int64_t c = blockIdx.x;
+    float4 cur[4];
+    if (c < nfull) load4(c, cur);
+    while (c < nfull) {
+        const int64_t nx = c + gridDim.x;
+        float4 nxt[4];
+        if (nx < nfull) load4(nx, nxt);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                acc += static_cast<double>(fabsf(v[j].x));
-                acc += static_cast<double>(fabsf(v[j].y));
-                acc += static_cast<double>(fabsf(v[j].z));
-                acc += static_cast<double>(fabsf(v[j].w));
-            }
-        } else {
-            for (int j = 0; j < 4; ++j)
-                for (int e = 0; e < 4; ++e) {
-                    const int64_t idx = base + (int64_t)(j * kTernThreads + tid) * 4 + e;
-                    if (idx < n) acc += static_cast<double>(fabsf(W[idx]));
-                }
+        for (int j = 0; j < 4; ++j) {
+            acc += static_cast<double>(fabsf(cur[j].x));
+            acc += static_cast<double>(fabsf(cur[j].y));
+            acc += static_cast<double>(fabsf(cur[j].z));
+            acc += static_cast<double>(fabsf(cur[j].w));
         }
+        if (nx < nfull) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cur[j] = nxt[j];
+        }
+        c = nx;
+    }
+    // ragged tail (at most one chunk), taken by one block after its full chunks
+    if (nfull * kChunk < n && static_cast<int64_t>(blockIdx.x) == nfull % gridDim.x) {
+        const int64_t base = nfull * kChunk;
+        for (int j = 0; j < 4; ++j)
+            for (int e = 0; e < 4; ++e) {
+                const int64_t idx = base + static_cast<int64_t>(j * kTernThreads + tid) * 4 + e;
+                if (idx < n) acc += static_cast<double>(fabsf(W[idx]));
+            }
     }
     const double total = block_sum(acc, scratch);
     if (tid == 0) partial[blockIdx.x] = total;
@@ -78,13 +91,18 @@ __global__ __launch_bounds__(kTernThreads) void finalize_kernel(const TernWorksp
                                                                 float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
-    const float d = delta_from_partials(ws->p1, nb1, f, n, scratch);
-    double acc = 0.0;
+    // all loads of the three partial arrays are issued before any sum is formed
+    double a1 = 0.0, acc = 0.0;
     unsigned long long c = 0;
+#pragma unroll 4
+    for (int i = threadIdx.x; i < nb1; i += blockDim.x) a1 += ws->p1[i];
+#pragma unroll 4
     for (int i = threadIdx.x; i < nb2; i += blockDim.x) {
         acc += ws->p2[i];
         c += ws->cnt[i];
     }
+    const double s1 = block_sum(a1, scratch);
+    const float d = static_cast<float>((static_cast<double>(f) * s1) / static_cast<double>(n));
     const double s = block_sum(acc, scratch);
     const unsigned long long total = block_sum(c, scratch_u);
     if (threadIdx.x == 0) {
@@ -120,37 +138,80 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
     const float delta = delta_from_partials(p1, nb1, f, n, scratch);
 
     const int64_t nchunks = (n + kChunk - 1) / kChunk;
-    const int64_t n4 = n >> 2;       // n % 16 == 0 here
+    const int64_t nfull = n / kChunk;   // chunks that need no bounds test
+    const int64_t n4 = n >> 2;          // n % 16 == 0 here
     const int64_t nwords = n >> 4;
     double acc = 0.0;
     uint32_t count = 0;
-    for (int64_t it = blockIdx.x; it < nchunks; it += gridDim.x) {
+
+    auto wave_base = [&](int64_t it) -> int64_t {
         const int64_t c = reverse ? (nchunks - 1 - it) : it;
-        const int64_t wbase = c * kChunk + wave * 1024;   // first weight of this wave's span
+        return c * kChunk + wave * 1024;   // first weight of this wave's span
+    };
+    auto load4 = [&](int64_t wbase, float4* v, bool guard) {
         const float4* src = reinterpret_cast<const float4*>(W + wbase);
-        const int64_t f4base = wbase >> 2;
-        float4 v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int64_t i4 = f4base + j * 64 + lane;
-            v[j] = (i4 < n4) ? src[j * 64 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (guard) {
+                const int64_t i4 = (wbase >> 2) + j * 64 + lane;
+                v[j] = (i4 < n4) ? src[j * 64 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+                v[j] = src[j * 64 + lane];
+            }
         }
+    };
+    auto process = [&](const float4* v, int64_t wbase, bool guard) {
         uint32_t mine = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t f0 = code_field(v[j].x, delta), f1 = code_field(v[j].y, delta);
             const uint32_t f2 = code_field(v[j].z, delta), f3 = code_field(v[j].w, delta);
-            if (f0) acc += static_cast<double>(fabsf(v[j].x));
-            if (f1) acc += static_cast<double>(fabsf(v[j].y));
-            if (f2) acc += static_cast<double>(fabsf(v[j].z));
-            if (f3) acc += static_cast<double>(fabsf(v[j].w));
+            // adding +0.0 for the masked-out weights leaves the float64 sum unchanged
+            acc += static_cast<double>(f0 ? fabsf(v[j].x) : 0.0f);
+            acc += static_cast<double>(f1 ? fabsf(v[j].y) : 0.0f);
+            acc += static_cast<double>(f2 ? fabsf(v[j].z) : 0.0f);
+            acc += static_cast<double>(f3 ? fabsf(v[j].w) : 0.0f);
             count += (f0 & 1u) + (f1 & 1u) + (f2 & 1u) + (f3 & 1u);
             uint32_t word = ((f0 | (f2 << 2)) << (4 * ql)) | ((f1 | (f3 << 2)) << (16 + 4 * ql));
             word = quad_or(word);
             if (ql == j) mine = word;
         }
         const int64_t widx = (wbase >> 4) + (lane >> 2) + 16 * ql;
-        if (widx < nwords) packed[widx] = mine;
+        if (!guard || widx < nwords) packed[widx] = mine;
+    };
+
+    // iteration `it` maps to chunk it (or nchunks-1-it when walking backwards); a chunk is ragged only
+    // if it is the last one in memory order, i.e. it == nchunks-1 forwards or it == 0 backwards
+    const bool has_tail = nfull < nchunks;
+    const int64_t tail_it = reverse ? 0 : nchunks - 1;
+    int64_t it = blockIdx.x;
+    if (has_tail && it == tail_it) {            // only possible for the first iteration of one block
+        float4 v[4];
+        const int64_t wb = wave_base(it);
+        load4(wb, v, true);
+        process(v, wb, true);
+        it += gridDim.x;
+    }
+    const int64_t it_end = (has_tail && !reverse) ? nchunks - 1 : nchunks;
+    // software pipeline over the full chunks: next loads in flight while this chunk is processed
+    float4 cur[4];
+    if (it < it_end) load4(wave_base(it), cur, false);
+    while (it < it_end) {
+        const int64_t nx = it + gridDim.x;
+        float4 nxt[4];
+        if (nx < it_end) load4(wave_base(nx), nxt, false);
+        process(cur, wave_base(it), false);
+        if (nx < it_end) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cur[j] = nxt[j];
+        }
+        it = nx;
+    }
+    if (has_tail && !reverse && static_cast<int64_t>(blockIdx.x) == tail_it % gridDim.x && tail_it >= gridDim.x) {
+        float4 v[4];
+        const int64_t wb = wave_base(tail_it);
+        load4(wb, v, true);
+        process(v, wb, true);
     }
     const double total = block_sum(acc, scratch);
     const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
@@ -337,7 +398,7 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
     if (groups == 1) {
         TernWorkspace* ws = static_cast<TernWorkspace*>(workspace);
         const int64_t nchunks = (n + kChunk - 1) / kChunk;
-        int want = env_int("TWN_TERN_BLOCKS", 2048);
+        int want = env_int("TWN_TERN_BLOCKS", 512);   // two persistent blocks per CU measured best with the prefetch
         if (want < 1) want = 1;
         if (want > kMaxBlocks) want = kMaxBlocks;
         const int nb = static_cast<int>(nchunks < want ? nchunks : want);
