@@ -31,8 +31,8 @@ def log(*a):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the GEMM / ternarize-2^28 / ResNet-18 side measurements")
     ap.add_argument("--cpu-batch", type=int, default=16)
@@ -78,7 +78,7 @@ def main():
         gw = torch.from_numpy(wl.normal(3, 1, (g.O, g.C), std=0.02)).to(dev)
         gtw = api.twn_ternarize(gw, F)
         gy = torch.empty((g.N, g.O), dtype=torch.bfloat16, device=dev)
-        t = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=20, warm=3)
+        t = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=300, warm=100)
         log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq" % (t * 1e3, g.flops / t / 1e9))
         return {"us": round(t * 1e3, 1), "tflops": round(g.flops / t / 1e9, 1),
                 "frac_mfma_peak": round(g.flops / t / 1e9 / PEAK_BF16_TFLOPS, 4)}
@@ -96,7 +96,7 @@ def main():
             torch.cuda.synchronize()
             del dst
         btw = api.twn_ternarize(big, F)
-        t = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=ws), reps=20, warm=3)
+        t = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=ws), reps=100, warm=20)
         nbytes = (1 << 28) * 8.25
         log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight)" % (t * 1e3, nbytes / t / 1e6))
         return {"us": round(t * 1e3, 1), "GBps": round(nbytes / t / 1e6, 1),
@@ -116,7 +116,7 @@ def main():
             ws = torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tw, st, pd, dl)), dtype=torch.uint8,
                              device=dev)
             t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y,
-                                                     workspace=ws), reps=10)
+                                                     workspace=ws), reps=100, warm=20)
             tot += t
             log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq" % (L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
             del x, y
@@ -223,14 +223,15 @@ def main():
     log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phase_names[i], phase_ms[i]) for i in range(4)))
 
     # per-layer detail: a second, untimed pass with events around every call
-    ev = [[(new_ev(), new_ev()) for _ in calls] for _ in range(5)]
-    for s in range(5):
+    NP = 20
+    ev = [[(new_ev(), new_ev()) for _ in calls] for _ in range(NP)]
+    for s in range(NP):
         for ci, (_, _, fn) in enumerate(calls):
             ev[s][ci][0].record()
             fn()
             ev[s][ci][1].record()
     torch.cuda.synchronize()
-    call_ms = [sum(ev[s][ci][0].elapsed_time(ev[s][ci][1]) for s in range(5)) / 5 for ci in range(len(calls))]
+    call_ms = [sum(ev[s][ci][0].elapsed_time(ev[s][ci][1]) for s in range(NP)) / NP for ci in range(len(calls))]
 
     per = {(c[0], c[1]): call_ms[ci] for ci, c in enumerate(calls)}
     log("%-6s %22s %9s %9s %9s %9s %9s %9s" % ("layer", "(M,N,K)", "tern us", "fwd us", "fwd TF/s", "dX TF/s", "dW us", "dW TF/s"))

@@ -15,6 +15,9 @@
 //   * lanes outside the image / beyond M, N or K fetch from a 16-byte zero
 //     block instead, so padding costs no branches and slabs past the end of K
 //     are harmless zero loads that keep the outstanding-load count constant.
+#include <type_traits>
+#include <utility>
+
 #include "twn_kernels.h"
 
 namespace twn {
@@ -61,6 +64,58 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
                                      (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 }
 
+// LDS reads of the main loop are written as inline assembly with hand-placed s_waitcnt lgkmcnt(n): the
+// compiler's own wait insertion falls back to lgkmcnt(0) in this loop, which also waits for the reads
+// issued one MFMA step ahead and so exposes the whole LDS latency at every step.  LDS operations
+// complete in issue order, so "at most n outstanding" is exact.  A value read this way may only be
+// consumed after lds_wait<n>() followed by lds_ready() on its registers.
+template <int OFFSET>
+__device__ __forceinline__ void lds_read128(u32x4& d, uint32_t addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFFSET));
+}
+template <int OFFSET>
+__device__ __forceinline__ void lds_read64(u32x2& d, uint32_t addr) {
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFFSET));
+}
+// N reads (N <= 4) at addr, addr + STRIDE, ...
+template <int N, int STRIDE>
+__device__ __forceinline__ void lds_read128_n(u32x4* d, uint32_t addr) {
+    static_assert(N >= 1 && N <= 4 && 3 * STRIDE < 65536, "immediate offsets");
+    lds_read128<0>(d[0], addr);
+    if constexpr (N > 1) lds_read128<STRIDE>(d[1], addr);
+    if constexpr (N > 2) lds_read128<2 * STRIDE>(d[2], addr);
+    if constexpr (N > 3) lds_read128<3 * STRIDE>(d[3], addr);
+}
+template <int N, int STRIDE>
+__device__ __forceinline__ void lds_read64_n(u32x2* d, uint32_t addr) {
+    static_assert(N >= 1 && N <= 4 && 3 * STRIDE < 65536, "immediate offsets");
+    lds_read64<0>(d[0], addr);
+    if constexpr (N > 1) lds_read64<STRIDE>(d[1], addr);
+    if constexpr (N > 2) lds_read64<2 * STRIDE>(d[2], addr);
+    if constexpr (N > 3) lds_read64<3 * STRIDE>(d[3], addr);
+}
+template <int N>
+__device__ __forceinline__ void lds_wait() {
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+}
+// ties the consumers of r[0..N) to the preceding lds_wait (volatile asm statements keep their order)
+template <int N, class T>
+__device__ __forceinline__ void lds_ready(T* r) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(r[i]));
+}
+
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 // workgroups per CU the register allocation should allow: two waves per SIMD where LDS permits
 constexpr int dma_min_blocks(int nw, int smem) {
     int by_waves = 8 / nw, by_lds = (160 * 1024) / smem;
@@ -87,6 +142,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     constexpr int EPI_NI = EPI_CH / 32;            // 32-channel MFMA tiles per staged chunk
     constexpr int EPI_STAGE_BYTES = NW * TM * EPI_ROW;
     static_assert(BM % (8 * NW) == 0 && BN % 64 == 0 && TN % 64 == 0 && TM % 32 == 0, "tile shape");
+    static_assert(STAGES >= 3, "the mid-slab hand-over needs two slabs in flight");
     static_assert(EPI_STAGE_BYTES + 2 * BN * 4 <= STAGES * STAGE_BYTES, "epilogue staging must fit in the pipeline LDS");
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -153,7 +209,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     const int kt_begin = SPLITK ? static_cast<int>(blockIdx.y) * kps : 0;
     const int KT = (kt_begin + kps < KT_all) ? kt_begin + kps : KT_all;      // end of this range
 
-    auto tap_coord = [&](int base, int tap, int step, int div, int limit, int& out) -> bool {
+    auto tap_coord = [&](int base, int tap, int step, int div, int limit, int& out) __attribute__((always_inline)) -> bool {
         int v = base + tap * step;
         if (div > 1) {
             if (v < 0 || (v % div) != 0) return false;
@@ -163,46 +219,57 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         return static_cast<unsigned>(v) < static_cast<unsigned>(limit);
     };
 
-    auto issue = [&](int kt, int stage) {
-        unsigned char* sbase = smem + stage * STAGE_BYTES;
-        const int k = kt * 64 + kc * 8;
-        const bool kok = (kt < KT) && (k < g.K);
-        if (GEMM) {
-#pragma unroll
-            for (int i = 0; i < NLOAD; ++i) {
-                const void* src = (kok && ih0[i] == 0) ? static_cast<const void*>(X + abase[i] + k) : zero;
-                dma16(src, sbase + (i * NW + wave) * 1024);
-            }
-        } else {
-            const uint32_t rs = fdiv_u(static_cast<uint32_t>(k), a.divIC);
-            const int c = k - static_cast<int>(rs) * g.IC;
-            const int rr = static_cast<int>(fdiv_u(rs, a.divS));
-            const int ss = static_cast<int>(rs) - rr * g.S;
-            if (undivided) {
-                // one tap offset per slab for this lane; per row: two bounds tests and one 64-bit add
-                const int dth = rr * g.dh, dtw = ss * g.dw;
-                const int64_t delta = (static_cast<int64_t>(dth) * g.IW + dtw) * g.xs + c;
-#pragma unroll
-                for (int i = 0; i < NLOAD; ++i) {
-                    const bool ok = kok && static_cast<unsigned>(ih0[i] + dth) < static_cast<unsigned>(g.IH) &&
-                                    static_cast<unsigned>(iw0[i] + dtw) < static_cast<unsigned>(g.IW);
-                    const void* src = ok ? static_cast<const void*>(X + off0[i] + delta) : zero;
-                    dma16(src, sbase + (i * NW + wave) * 1024);
-                }
-            } else
-#pragma unroll
-            for (int i = 0; i < NLOAD; ++i) {
-                int th, tw;
-                bool ok = tap_coord(ih0[i], rr, g.dh, g.divh, g.IH, th);
-                ok = tap_coord(iw0[i], ss, g.dw, g.divw, g.IW, tw) && ok && kok;
-                const void* src = ok ? static_cast<const void*>(
-                                           X + (abase[i] + static_cast<int64_t>(th) * g.IW + tw) * g.xs + c)
-                                     : zero;
-                dma16(src, sbase + (i * NW + wave) * 1024);
-            }
+    // Loads of one slab, cut into pieces so that the main loop can spread them between MFMAs:
+    // issue_setup fixes the slab (per-lane k offset, tap), issue_load<I> issues load I of NLOAD + 1
+    // (the last one stages the packed codes).
+    struct {
+        unsigned char* sbase;
+        int kt, k, c, rr, ss, dth, dtw;
+        int64_t delta;
+        bool kok;
+    } si;
+    auto issue_setup = [&](int kt, int stage) __attribute__((always_inline)) {
+        si.sbase = smem + stage * STAGE_BYTES;
+        si.kt = kt;
+        si.k = kt * 64 + kc * 8;
+        si.kok = (kt < KT) && (si.k < g.K);
+        if (!GEMM) {
+            const uint32_t rs = fdiv_u(static_cast<uint32_t>(si.k), a.divIC);
+            si.c = si.k - static_cast<int>(rs) * g.IC;
+            si.rr = static_cast<int>(fdiv_u(rs, a.divS));
+            si.ss = static_cast<int>(rs) - si.rr * g.S;
+            // one tap offset per slab for this lane; per row: two bounds tests and one 64-bit add
+            si.dth = si.rr * g.dh;
+            si.dtw = si.ss * g.dw;
+            si.delta = (static_cast<int64_t>(si.dth) * g.IW + si.dtw) * g.xs + si.c;
         }
-        const void* bs = (bsrc && kt < KT) ? static_cast<const void*>(bsrc + kt * 4) : zero;
-        dma16(bs, sbase + A_BYTES + ((wave * 64) % BN) * 16);
+    };
+    auto issue_load = [&](auto i_tag) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_tag)::value;
+        if constexpr (i == NLOAD) {
+            const void* bs = (bsrc && si.kt < KT) ? static_cast<const void*>(bsrc + si.kt * 4) : zero;
+            dma16(bs, si.sbase + A_BYTES + ((wave * 64) % BN) * 16);
+        } else {
+            const void* src;
+            if (GEMM) {
+                src = (si.kok && ih0[i] == 0) ? static_cast<const void*>(X + abase[i] + si.k) : zero;
+            } else if (undivided) {
+                const bool ok = si.kok && static_cast<unsigned>(ih0[i] + si.dth) < static_cast<unsigned>(g.IH) &&
+                                static_cast<unsigned>(iw0[i] + si.dtw) < static_cast<unsigned>(g.IW);
+                src = ok ? static_cast<const void*>(X + off0[i] + si.delta) : zero;
+            } else {
+                int th, tw;
+                bool ok = tap_coord(ih0[i], si.rr, g.dh, g.divh, g.IH, th);
+                ok = tap_coord(iw0[i], si.ss, g.dw, g.divw, g.IW, tw) && ok && si.kok;
+                src = ok ? static_cast<const void*>(X + (abase[i] + static_cast<int64_t>(th) * g.IW + tw) * g.xs + si.c)
+                         : zero;
+            }
+            dma16(src, si.sbase + (i * NW + wave) * 1024);
+        }
+    };
+    auto issue = [&](int kt, int stage) __attribute__((always_inline)) {
+        issue_setup(kt, stage);
+        static_for<NLOAD + 1>(issue_load);
     };
 
     f32x16 acc[MI][NI];
@@ -213,72 +280,130 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
 
+    // ---- software pipeline ---------------------------------------------------------------------
+    // Slab kt lives in stage kt % STAGES and is multiplied in four MFMA steps kk = 0..3 of MI*NI MFMAs.
+    // Everything that is not an MFMA is cut into small pieces and placed BETWEEN the MFMAs of a step, so
+    // that a wave never has an MFMA-free stretch (two waves share a SIMD's matrix pipe and tend to fall
+    // into step with each other, so such stretches are not filled by the other wave):
+    //   * the LDS reads of the next step's activation fragments (one step ahead, other register set),
+    //   * the expansion of the next step's packed codes to bf16 {0, +2, -2},
+    //   * in steps 2 and 3, the direct-to-LDS loads of slab kt+PD and the read of slab kt+1's codes.
+    // The hand-over point sits between steps 1 and 2: wait until slab kt+1 has landed, barrier; the stage
+    // of slab kt-1 is then free for slab kt+PD and slab kt+1 may be read.
+    static_assert(MI <= 4 && NI <= 4, "fragment reads use immediate offsets for up to four tiles");
+    // LDS byte address of the dynamic array (the low 32 bits of its generic address are the LDS offset)
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) unsigned char*)smem));
+    // per-lane byte offsets inside a stage; the swizzle term does not depend on mi because TM % 32 == 0
+    uint32_t aoff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        aoff[kk] = (wm * TM + lrow) * 128 + (((lh * 4 + kk) ^ ((lrow >> 1) & 7)) * 16);
+    const uint32_t boff = A_BYTES + (wn * TN + lrow) * 16 + lh * 8;
+
+    u32x2 breg[2][NI];      // packed codes of the slab being multiplied / of the next slab
+    u32x4 afrag[2][MI];     // activation fragments of step kk in set kk & 1
+    u32x4 bfrag[2][NI];     // expanded codes of step kk in set kk & 1
+
+    // code field i of every 32-bit half lands in bits [14,15] of a bf16: 0 / +2.0 / -2.0
+    auto expand = [&](auto kk_tag, auto ni_tag, auto e_tag, const u32x2* br, u32x4* out) __attribute__((always_inline)) {
+        constexpr int kk = decltype(kk_tag)::value, ni = decltype(ni_tag)::value, e = decltype(e_tag)::value;
+        constexpr int i = (kk & 1) * 4 + e;
+        out[ni][e] = (br[ni][kk >> 1] << (14 - 2 * i)) & 0xC000C000u;
+    };
+
+    // One MFMA step.  Weights are the MFMA row operand, activations the column operand: a lane then owns
+    // 4 consecutive output channels of one pixel per accumulator quad.
+    auto step = [&](auto kk_tag, auto cur_tag, int kt, int stage, int next, int fill) __attribute__((always_inline)) {
+        constexpr int KK = decltype(kk_tag)::value;
+        constexpr int CUR = decltype(cur_tag)::value;
+        constexpr int NM = MI * NI;
+        constexpr int SET = KK & 1, NSET = SET ^ 1;
+        constexpr int KN = (KK + 1) & 3;                         // the step being prepared
+        constexpr int BSRC = (KK == 3) ? (CUR ^ 1) : CUR;        // its codes: next slab's after the last step
+        constexpr int HALF = (NLOAD + 2) / 2;                    // loads issued in step 2, the rest in step 3
+        constexpr int G0 = (KK == 2) ? 0 : HALF;
+        constexpr int P_RA = MI;                                 // pieces: fragment reads,
+        constexpr int P_RB = (KK == 2) ? 1 : 0;                  //   codes of the next slab,
+        constexpr int P_D = 4 * NI;                              //   code expansion,
+        constexpr int P_G = (KK == 2) ? HALF : (KK == 3) ? NLOAD + 1 - HALF : 0;   //   global loads
+        constexpr int P = P_RA + P_RB + P_D + P_G;
+        const uint32_t a_addr = lds_base + ((KK == 3) ? next : stage) * STAGE_BYTES + aoff[KN];
+        auto piece = [&](auto p_tag) __attribute__((always_inline)) {
+            constexpr int p = decltype(p_tag)::value;
+            if constexpr (p < P_RA) {
+                lds_read128<p * 32 * 128>(afrag[NSET][p], a_addr);
+            } else if constexpr (p < P_RA + P_RB) {
+                lds_read64_n<NI, 32 * 16>(breg[CUR ^ 1], lds_base + next * STAGE_BYTES + boff);
+            } else if constexpr (p < P_RA + P_RB + P_D) {
+                constexpr int q = p - P_RA - P_RB;
+                expand(std::integral_constant<int, KN>{}, std::integral_constant<int, q / 4>{},
+                       std::integral_constant<int, q % 4>{}, breg[BSRC], bfrag[NSET]);
+            } else {
+                constexpr int gi = G0 + p - (P_RA + P_RB + P_D);
+                if constexpr (gi == 0) issue_setup(kt + PD, fill);
+                issue_load(std::integral_constant<int, gi>{});
+            }
+        };
+        static_for<NM>([&](auto j_tag) __attribute__((always_inline)) {
+            constexpr int j = decltype(j_tag)::value;
+            constexpr int mi = j / NI, ni = j % NI;
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[SET][ni]),
+                                                                  __builtin_bit_cast(bf16x8, afrag[SET][mi]),
+                                                                  acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<P>([&](auto p_tag) __attribute__((always_inline)) {
+                constexpr int p = decltype(p_tag)::value;
+                if constexpr (p * NM / P == j) piece(p_tag);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // everything read during this step is needed by the next one
+        lds_wait<0>();
+        lds_ready<MI>(afrag[NSET]);
+        if constexpr (KK == 2) lds_ready<NI>(breg[CUR ^ 1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
     // prologue: PD slabs in flight, the first one landed and visible to every wave
 #pragma unroll
     for (int s = 0; s < PD; ++s) issue(kt_begin + s, s);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * PER_STAGE));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    lds_read64_n<NI, 32 * 16>(breg[0], lds_base + boff);
+    lds_read128_n<MI, 32 * 128>(afrag[0], lds_base + aoff[0]);
+    lds_wait<0>();
+    lds_ready<NI>(breg[0]);
+    lds_ready<MI>(afrag[0]);
+    static_for<4 * NI>([&](auto q_tag) __attribute__((always_inline)) {
+        constexpr int q = decltype(q_tag)::value;
+        expand(std::integral_constant<int, 0>{}, std::integral_constant<int, q / 4>{},
+               std::integral_constant<int, q % 4>{}, breg[0], bfrag[0]);
+    });
 
-    int stage = 0;          // slab kt lives in stage kt % STAGES
-    int fill = PD;          // stage that slab kt + PD goes to
-    for (int kt = kt_begin; kt < KT; ++kt) {
-        const unsigned char* sa = smem + stage * STAGE_BYTES;
-        const unsigned char* sb = sa + A_BYTES;
-
-        // LDS reads of this slab go out first; the address arithmetic and issue of the
-        // next global loads run while they are in flight
-        u32x2 breg[NI];
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            breg[ni] = *reinterpret_cast<const u32x2*>(sb + (wn * TN + ni * 32 + lrow) * 16 + lh * 8);
-
-        bf16x8 afrag[2][MI];
-        auto read_a = [&](int kk, bf16x8* dst) {
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                const int row = wm * TM + mi * 32 + lrow;
-                const int chunk = (lh * 4 + kk) ^ ((row >> 1) & 7);
-                dst[mi] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(sa + row * 128 + chunk * 16));
-            }
-        };
-        read_a(0, afrag[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        issue(kt + PD, fill);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk + 1 < 4) read_a(kk + 1, afrag[(kk + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this step's MFMAs
-            bf16x8 bfrag[NI];
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const uint32_t word = breg[ni][kk >> 1];
-                u32x4 bb;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = (kk & 1) * 4 + e;
-                    bb[e] = (word << (14 - 2 * i)) & 0xC000C000u;
-                }
-                bfrag[ni] = __builtin_bit_cast(bf16x8, bb);
-            }
-            // weights are the row operand, activations the column operand: a lane then owns
-            // 4 consecutive output channels of one pixel per accumulator quad
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ni], afrag[kk & 1][mi], acc[mi][ni], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // slab kt+1 (issued PD-1 iterations ago) must have landed; the PD-1 younger slabs may stay in flight
+    int stage = 0;          // stage of the slab being multiplied
+    int fill = PD % STAGES; // stage that slab kt + PD goes to
+    // one slab; CUR selects the register set holding this slab's packed codes
+    auto slab = [&](int kt, auto cur_tag) __attribute__((always_inline)) {
+        const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
+        step(std::integral_constant<int, 0>{}, cur_tag, kt, stage, next, fill);
+        step(std::integral_constant<int, 1>{}, cur_tag, kt, stage, next, fill);
+        // hand-over: slab kt+1 landed (the PD-2 younger slabs may stay in flight), stage of slab kt-1 is free
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * PER_STAGE));
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 2) * PER_STAGE));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+        step(std::integral_constant<int, 2>{}, cur_tag, kt, stage, next, fill);
+        step(std::integral_constant<int, 3>{}, cur_tag, kt, stage, next, fill);
+        stage = next;
         fill = (fill + 1 == STAGES) ? 0 : fill + 1;
+    };
+    for (int kt = kt_begin; kt < KT; kt += 2) {
+        slab(kt, std::integral_constant<int, 0>{});
+        if (kt + 1 < KT) slab(kt + 1, std::integral_constant<int, 1>{});
     }
+
     // the trailing zero loads still target LDS: drain them in every wave before LDS is reused
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
@@ -479,16 +604,16 @@ int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
         case 11: return launch_dma_tile<128, 256, 2, 2, 3>(g, st);
         case 12: return launch_dma_tile<128, 128, 2, 2, 3>(g, st);
         case 13: return launch_dma_tile<128, 64, 4, 1, 3>(g, st);
-        case 14: return launch_dma_tile<256, 256, 2, 2, 4>(g, st);
         case 15: return launch_dma_tile<128, 256, 2, 2, 4>(g, st);
         case 16: return launch_dma_tile<256, 128, 2, 2, 3>(g, st);
         case 17: return launch_dma_tile<128, 256, 1, 4, 4>(g, st);
         case 18: return launch_dma_tile<256, 256, 2, 4, 4>(g, st);
         case 19: return launch_dma_tile<256, 256, 4, 2, 4>(g, st);
-        case 20: return launch_dma_tile<256, 128, 2, 2, 2>(g, st);
+        case 20: return launch_dma_tile<256, 128, 2, 2, 3>(g, st);
         case 21: return launch_dma_tile<128, 128, 1, 2, 4>(g, st);
         case 22: return launch_dma_tile<256, 64, 4, 1, 3>(g, st);
         case 23: return launch_dma_tile<256, 64, 2, 1, 3>(g, st);
+        case 24: return launch_dma_tile<128, 512, 1, 8, 4>(g, st);
         default: return TWN_ERR_UNSUPPORTED;
     }
 }
