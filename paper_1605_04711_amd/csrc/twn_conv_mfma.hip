@@ -362,7 +362,7 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
             auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
             if (g.splits > 1) tile = 12;
             else if (g.NC <= 64) tile = 13;
-            else if (g.NC <= 128) tile = (blocks(256, 128) >= 512) ? 20 : 12;
+            else if (g.NC <= 128) tile = 12;
             else tile = (blocks(128, 256) >= 512) ? 17 : 12;
         }
         return launch_gather_gemm_dma(g, tile, st);
