@@ -38,6 +38,7 @@ def main():
     ap.add_argument("--cpu-batch", type=int, default=16)
     ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18"], default=None,
                     help="run one side measurement alone (used for the rocprofv3 summaries in profiles/)")
+    ap.add_argument("--variants", action="store_true", help="with --only gemm: also time the comparison weight formats")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -80,8 +81,22 @@ def main():
         gy = torch.empty((g.N, g.O), dtype=torch.bfloat16, device=dev)
         t = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=300, warm=100)
         log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq" % (t * 1e3, g.flops / t / 1e9))
-        return {"us": round(t * 1e3, 1), "tflops": round(g.flops / t / 1e9, 1),
-                "frac_mfma_peak": round(g.flops / t / 1e9 / PEAK_BF16_TFLOPS, 4)}
+        res = {"us": round(t * 1e3, 1), "tflops": round(g.flops / t / 1e9, 1),
+               "frac_mfma_peak": round(g.flops / t / 1e9 / PEAK_BF16_TFLOPS, 4)}
+        if args.only == "gemm" and not args.variants:
+            return res
+        # The two comparison variants live in the register-staged 128x128 kernel only; the product format is
+        # timed in that same kernel (TWN_TILE=4 selects it) so that only the weight format differs.
+        os.environ["TWN_TILE"] = "4"
+        same = {"postscale_2bit": time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=60, warm=20)}
+        del os.environ["TWN_TILE"]
+        for name, var in (("alpha_at_expansion_2bit", api.TWN_VAR_BF16_ALPHA_LDS),
+                          ("int8_stored", api.TWN_VAR_I8_STORED_POSTSCALE)):
+            same[name] = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy, variant=var), reps=60, warm=20)
+        for k, v in same.items():
+            log("gemm weight format %-24s %.1f us, %.1f TFLOP/s-eq (register-staged 128x128 kernel)" % (k, v * 1e3, g.flops / v / 1e9))
+        res["weight_formats_same_kernel_us"] = {k: round(v * 1e3, 1) for k, v in same.items()}
+        return res
 
     def side_ternarize(calibrate=False):
         # ternarize-only: 2^28 float32 N(0,1) shaped [16384][16384]

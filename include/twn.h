@@ -66,8 +66,12 @@ typedef enum { TWN_F32 = 0, TWN_BF16 = 1 } twn_dtype;
  * on the weights, on the inputs or on the outputs). */
 typedef enum {
     TWN_VAR_BF16_POSTSCALE = 0,     /* 2-bit codes -> exact bf16 in registers, bf16 MFMA, alpha in the fp32 epilogue */
-    TWN_VAR_BF16_ALPHA_LDS = 1,     /* 2-bit codes -> bf16 {-alpha,0,+alpha} staged in LDS, bf16 MFMA (comparison) */
-    TWN_VAR_I8_STORED_POSTSCALE = 2,/* weights stored as int8 {-1,0,1} (8 bits/weight), bf16 MFMA, alpha afterwards (comparison) */
+    TWN_VAR_BF16_ALPHA_LDS = 1,     /* comparison: 2-bit codes -> the paper's operand alpha*W~ itself, bf16 {-alpha,0,+alpha}
+                                       with alpha rounded to bf16, built when the codes are expanded; bf16 MFMA; no scaling
+                                       of the sum afterwards.  Forward and backward-data. */
+    TWN_VAR_I8_STORED_POSTSCALE = 2,/* comparison: weights stored as int8 {-1,0,1} [rows][K] (8 bits per weight, from
+                                       twn_unpack_i8), bf16 MFMA, alpha afterwards.  Forward only; K % 8 == 0 and the
+                                       weights 8-byte aligned, else TWN_ERR_UNSUPPORTED. */
     TWN_VAR_FP32 = 3                /* float32 activations and outputs, vector-ALU FMAs with float64 running sums */
 } twn_variant;
 
@@ -170,7 +174,8 @@ int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weight
  * y_dtype.  packed_T is the transposed copy from twn_ternarize.  Any of dX
  * (with packed_T/alpha), dW (with X), dbias may be NULL to skip that part.
  * dW_beta is 0 (overwrite) or 1 (accumulate).  A fully-connected layer is the
- * case H=W=R=S=1. */
+ * case H=W=R=S=1.  d->variant may be TWN_VAR_BF16_POSTSCALE or
+ * TWN_VAR_BF16_ALPHA_LDS (it only affects dX); others: TWN_ERR_UNSUPPORTED. */
 size_t  twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d);
 int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY,
                            const uint32_t* packed_T, const float* alpha,

@@ -149,10 +149,19 @@ class TernaryWeights:
     delta: torch.Tensor                  # float32 [groups]
     alpha: torch.Tensor                  # float32 [groups]
     nnz: torch.Tensor                    # int64 [groups]
+    codes_i8: Optional[torch.Tensor] = None   # int8 [rows][K], the weights of TWN_VAR_I8_STORED_POSTSCALE
 
     @property
     def K(self):
         return self.R * self.S * self.C
+
+    def weights_for(self, variant):
+        """Device tensor a forward call reads as its `weights` argument."""
+        if variant != TWN_VAR_I8_STORED_POSTSCALE:
+            return self.packed
+        if self.codes_i8 is None:
+            self.codes_i8 = twn_unpack_i8(self.packed, self.rows, self.K)
+        return self.codes_i8
 
 
 def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, workspace=None, stream=None):
@@ -220,7 +229,7 @@ def twn_gemm_fwd(X, tw, y_dtype=torch.bfloat16, variant=None, scale=None, shift=
     if workspace is None:
         need = L.twn_gemm_fwd_workspace_bytes(ctypes.byref(d))
         workspace = _workspace(need, X.device) if need else None
-    rc = L.twn_gemm_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
+    rc = L.twn_gemm_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.weights_for(variant)), _ptr(tw.alpha),
                         None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
                         0 if workspace is None else workspace.numel(), _stream(stream))
     _check(rc, "twn_gemm_fwd")
@@ -264,7 +273,7 @@ def twn_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), y_dtype=torch.b
     if workspace is None:
         need = L.twn_conv2d_fwd_workspace_bytes(ctypes.byref(d))
         workspace = _workspace(need, X.device) if need else None
-    rc = L.twn_conv2d_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.packed), _ptr(tw.alpha),
+    rc = L.twn_conv2d_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.weights_for(variant)), _ptr(tw.alpha),
                           None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
                           0 if workspace is None else workspace.numel(), _stream(stream))
     _check(rc, "twn_conv2d_fwd")
@@ -278,7 +287,7 @@ def twn_conv2d_bwd_ste_workspace_bytes(x_shape, tw, stride=(1, 1), pad=(0, 0), d
 
 def twn_conv2d_bwd_ste(X, dY, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), need_dx=True, need_dw=True,
                        need_dbias=False, dx_dtype=torch.bfloat16, dW=None, accumulate=False, dX=None,
-                       workspace=None, x_shape=None, stream=None):
+                       workspace=None, x_shape=None, stream=None, variant=TWN_VAR_BF16_POSTSCALE):
     """Returns (dX or None, dW float32 [O][C][R][S] or None, dbias or None)."""
     xs = tuple(X.shape) if X is not None else tuple(x_shape)
     dev = dY.device
@@ -287,8 +296,7 @@ def twn_conv2d_bwd_ste(X, dY, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), need_dx
     if need_dw and dW is None:
         dW = torch.empty((tw.rows, tw.C, tw.R, tw.S), dtype=torch.float32, device=dev)
     dbias = torch.empty(tw.rows, dtype=torch.float32, device=dev) if need_dbias else None
-    d = _conv_desc(xs, tw, stride, pad, dil, TWN_BF16, _dtype_code(dX) if need_dx else TWN_BF16,
-                   TWN_VAR_BF16_POSTSCALE)
+    d = _conv_desc(xs, tw, stride, pad, dil, TWN_BF16, _dtype_code(dX) if need_dx else TWN_BF16, variant)
     L = lib()
     if workspace is None:
         workspace = _workspace(L.twn_conv2d_bwd_ste_workspace_bytes(ctypes.byref(d)), dev)

@@ -39,7 +39,7 @@ int32_t check_variant(int32_t variant, int32_t x_dtype) {
         case TWN_VAR_BF16_POSTSCALE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         case TWN_VAR_FP32: return x_dtype == TWN_F32 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         case TWN_VAR_BF16_ALPHA_LDS:
-        case TWN_VAR_I8_STORED_POSTSCALE: return TWN_ERR_UNSUPPORTED;
+        case TWN_VAR_I8_STORED_POSTSCALE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         default: return TWN_ERR_UNSUPPORTED;
     }
 }
@@ -52,7 +52,7 @@ void set_epilogue(GatherGemm& g, const twn_epilogue* ep) {
 }
 
 size_t splitk_bytes(const GatherGemm& g, int variant) {
-    if (variant == TWN_VAR_FP32) return 0;
+    if (variant != TWN_VAR_BF16_POSTSCALE) return 0;   // the other variants never split K
     const int32_t splits = gather_gemm_splits(g);
     return splits > 1 ? static_cast<size_t>(splits) * static_cast<size_t>(g.M) * g.NC * sizeof(float) : 0;
 }
@@ -60,6 +60,12 @@ size_t splitk_bytes(const GatherGemm& g, int variant) {
 // Attaches the split-K workspace (if the problem uses one) and launches.
 int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_bytes, hipStream_t st) {
     if (variant == TWN_VAR_FP32) return launch_gather_gemm_fp32(g, st);
+    if (variant != TWN_VAR_BF16_POSTSCALE) {
+        if (variant == TWN_VAR_I8_STORED_POSTSCALE && (g.K % 8 != 0 || !aligned(g.Wq, 8))) return TWN_ERR_UNSUPPORTED;
+        g.splits = 1;
+        g.partial = nullptr;
+        return launch_gather_gemm_mfma(g, variant, st);
+    }
     g.splits = gather_gemm_splits(g);
     g.partial = nullptr;
     if (g.splits > 1) {
@@ -288,7 +294,7 @@ extern "C" size_t twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d) {
     // the data-gradient split-K partials and the weight-gradient partials use the workspace one after the other
     GatherGemm g{};
     fill_conv_bwd_data(g, d, P, Q);
-    const size_t a = splitk_bytes(g, TWN_VAR_BF16_POSTSCALE);
+    const size_t a = splitk_bytes(g, d->variant);
     const size_t b = weight_grad_bytes(d, P, Q);
     return a > b ? a : b;
 }
@@ -303,7 +309,9 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
     if (!dY) return TWN_ERR_NULL;
     if (dX && (!packed_T || !alpha)) return TWN_ERR_NULL;
     if (dW && !X) return TWN_ERR_NULL;
-    if (d->x_dtype != TWN_BF16 || d->variant != TWN_VAR_BF16_POSTSCALE) return TWN_ERR_UNSUPPORTED;
+    // the int8-stored comparison variant is forward-only: the transposed codes of this call are 2-bit packed
+    if (d->x_dtype != TWN_BF16 ||
+        (d->variant != TWN_VAR_BF16_POSTSCALE && d->variant != TWN_VAR_BF16_ALPHA_LDS)) return TWN_ERR_UNSUPPORTED;
     rc = check_dtype(d->y_dtype);
     if (rc != TWN_OK) return rc;
     if (dW_beta != 0.0f && dW_beta != 1.0f) return TWN_ERR_UNSUPPORTED;
@@ -327,7 +335,7 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
         g.alpha = alpha;
         g.Y = dX;
         fill_conv_bwd_data(g, d, P, Q);
-        rc = dispatch(g, TWN_VAR_BF16_POSTSCALE, workspace, workspace_bytes, st);
+        rc = dispatch(g, d->variant, workspace, workspace_bytes, st);
         if (rc != TWN_OK) return rc;
     }
     if (dW || dbias) {

@@ -24,10 +24,16 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 enum { kModeGemm = 0, kModeVec8 = 1, kModeScalar = 2 };
 
-template <int BM, int BN, int WM, int WN, int MODE>
+// Weight operand formats.  kFmtPacked is the product path; the other two exist to be measured against it:
+// kFmtAlpha builds the paper's operand alpha*W~ itself (bf16 {-alpha, 0, +alpha}, alpha rounded to bf16)
+// at expansion time instead of scaling the fp32 sum, kFmtInt8 reads weights stored one int8 per weight.
+enum { kFmtPacked = 0, kFmtAlpha = 1, kFmtInt8 = 2 };
+
+template <int BM, int BN, int WM, int WN, int MODE, int BFMT>
 __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const GatherGemm g) {
     constexpr int T = 64 * WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -84,7 +90,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
     }
 
     u32x4 areg[NLOAD];
-    u32x2 breg[NI], breg_next[NI];
+    constexpr int BW = (BFMT == kFmtInt8) ? 4 : 1;   // 8-byte words of weights per lane, row and slab
+    u32x2 breg[NI][BW], breg_next[NI][BW];
 
     auto tap_coord = [&](int base, int tap, int step, int div, int limit, int& out) -> bool {
         int t = base + tap * step;
@@ -152,14 +159,63 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
         }
     };
 
-    auto load_b = [&](int kt, u32x2* dst) {
+    auto load_b = [&](int kt, u32x2 (*dst)[BW]) {
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
             const int ncol = n0 + wn * TN + ni * 32 + lrow;
-            dst[ni] = (ncol < g.NC)
-                          ? *reinterpret_cast<const u32x2*>(Wq + static_cast<int64_t>(ncol) * g.wpr + kt * 4 + 2 * lh)
-                          : u32x2{0, 0};
+            if (BFMT == kFmtInt8) {
+                // int8 [NC][K], K % 8 == 0: this lane's 8 weights of each of the four MFMA steps
+                const uint8_t* wrow = reinterpret_cast<const uint8_t*>(g.Wq) + static_cast<int64_t>(ncol) * g.K;
+#pragma unroll
+                for (int kk = 0; kk < BW; ++kk) {
+                    const int k = kt * 64 + lh * 32 + kk * 8;   // the k range of this lane's A fragment at step kk
+                    dst[ni][kk] = (ncol < g.NC && k < g.K) ? *reinterpret_cast<const u32x2*>(wrow + k) : u32x2{0, 0};
+                }
+            } else {
+                dst[ni][0] = (ncol < g.NC)
+                                 ? *reinterpret_cast<const u32x2*>(Wq + static_cast<int64_t>(ncol) * g.wpr + kt * 4 + 2 * lh)
+                                 : u32x2{0, 0};
+            }
         }
+    };
+
+    // kFmtAlpha: bf16(alpha) of this lane's output channels, in both halves of a register
+    uint32_t alpha2[NI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int ncol = n0 + wn * TN + ni * 32 + lrow;
+        const uint32_t ab = (BFMT == kFmtAlpha && ncol < g.NC) ? f32_to_bf16(g.alpha[ncol / g.rows_per_group]) : 0u;
+        alpha2[ni] = ab | (ab << 16);
+    }
+
+    // the 8 weights of (channel tile ni, MFMA step kk) as four registers of two bf16 each
+    auto expand = [&](int ni, int kk) -> u32x4 {
+        u32x4 b;
+        if (BFMT == kFmtInt8) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                // bytes 0x01 / 0xFF / 0x00 -> 0x40 / 0xC0 / 0x00, the high byte of bf16 +2 / -2 / 0
+                const uint32_t x = breg[ni][kk][h];
+                const uint32_t y = ((x << 6) & 0x40404040u) | (x & 0x80808080u);
+                b[2 * h] = __builtin_amdgcn_perm(0u, y, 0x010C000Cu);       // [0, y.b0, 0, y.b1]
+                b[2 * h + 1] = __builtin_amdgcn_perm(0u, y, 0x030C020Cu);   // [0, y.b2, 0, y.b3]
+            }
+        } else {
+            const uint32_t word = breg[ni][0][kk >> 1];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = (kk & 1) * 4 + r;
+                if (BFMT == kFmtAlpha) {
+                    // sign from bit 1 of the field; bit 0 (nonzero) widened to a 16-bit mask that gates alpha
+                    const uint32_t sign = (word << (14 - 2 * i)) & 0x80008000u;
+                    const s16x2 nz = __builtin_bit_cast(s16x2, word << (15 - 2 * i)) >> 15;
+                    b[r] = (__builtin_bit_cast(uint32_t, nz) & alpha2[ni]) | sign;
+                } else {
+                    b[r] = (word << (14 - 2 * i)) & 0xC000C000u;
+                }
+            }
+        }
+        return b;
     };
 
     f32x16 acc[MI][NI];
@@ -179,7 +235,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) breg[ni] = breg_next[ni];
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int w = 0; w < BW; ++w) breg[ni][w] = breg_next[ni][w];
         const bool more = (kt + 1 < KT);
         if (more) {
             load_a(kt + 1);
@@ -202,16 +260,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
             __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of this step's MFMAs
             bf16x8 bfrag[NI];
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) {
-                const uint32_t word = breg[ni][kk >> 1];
-                u32x4 b;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int i = (kk & 1) * 4 + r;
-                    b[r] = (word << (14 - 2 * i)) & 0xC000C000u;
-                }
-                bfrag[ni] = __builtin_bit_cast(bf16x8, b);
-            }
+            for (int ni = 0; ni < NI; ++ni) bfrag[ni] = __builtin_bit_cast(bf16x8, expand(ni, kk));
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -228,7 +277,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
     for (int ni = 0; ni < NI; ++ni) {
         const int ncol = n0 + wn * TN + ni * 32 + lrow;
         if (ncol >= g.NC) continue;
-        const float al = 0.5f * g.alpha[ncol / g.rows_per_group];   // codes were expanded to +-2
+        // codes were expanded to +-2 (or, for kFmtAlpha, to +-alpha already)
+        const float al = (BFMT == kFmtAlpha) ? 1.0f : 0.5f * g.alpha[ncol / g.rows_per_group];
         const float sc = g.scale ? g.scale[ncol] : 1.0f;
         const float sf = g.shift ? g.shift[ncol] : 0.0f;
 #pragma unroll
@@ -313,7 +363,7 @@ int32_t launch_repack_c4(const uint32_t* packed, int rows, int C, int R, int S, 
     return launch_status();
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BFMT = kFmtPacked>
 static int32_t launch_tile(const GatherGemm& g, int mode, hipStream_t st) {
     const int64_t tiles_m = (g.M + BM - 1) / BM;
     const int64_t tiles_n = (g.NC + BN - 1) / BN;
@@ -322,9 +372,9 @@ static int32_t launch_tile(const GatherGemm& g, int mode, hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(blocks));
     const dim3 block(64 * WM * WN);
     switch (mode) {
-        case kModeGemm: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeGemm><<<grid, block, 0, st>>>(g); break;
-        case kModeVec8: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeVec8><<<grid, block, 0, st>>>(g); break;
-        default: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeScalar><<<grid, block, 0, st>>>(g); break;
+        case kModeGemm: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeGemm, BFMT><<<grid, block, 0, st>>>(g); break;
+        case kModeVec8: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeVec8, BFMT><<<grid, block, 0, st>>>(g); break;
+        default: gather_gemm_mfma_kernel<BM, BN, WM, WN, kModeScalar, BFMT><<<grid, block, 0, st>>>(g); break;
     }
     return launch_status();
 }
@@ -351,8 +401,14 @@ int32_t gather_gemm_splits(const GatherGemm& g) {
 }
 
 int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st) {
-    if (variant != TWN_VAR_BF16_POSTSCALE) return TWN_ERR_UNSUPPORTED;
     const int mode = gather_mode(g);
+    // the comparison variants run in the register-staged 128x128 kernel only
+    if (variant == TWN_VAR_BF16_ALPHA_LDS) return launch_tile<128, 128, 2, 2, kFmtAlpha>(g, mode, st);
+    if (variant == TWN_VAR_I8_STORED_POSTSCALE) {
+        if (g.K % 8 != 0) return TWN_ERR_UNSUPPORTED;
+        return launch_tile<128, 128, 2, 2, kFmtInt8>(g, mode, st);
+    }
+    if (variant != TWN_VAR_BF16_POSTSCALE) return TWN_ERR_UNSUPPORTED;
 
     // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.
     int tile = env_int("TWN_TILE", 0);

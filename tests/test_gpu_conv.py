@@ -88,6 +88,59 @@ CONV_CASES = [
 ]
 
 
+VARIANTS = [api.TWN_VAR_BF16_ALPHA_LDS, api.TWN_VAR_I8_STORED_POSTSCALE]
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("m,n,k", [(300, 200, 320), (513, 257, 136), (64, 40, 104), (1, 10, 1024)])
+def test_gemm_fwd_comparison_variants(variant, m, n, k):
+    # alpha-at-expansion rounds alpha to bf16 (one more 2^-9 relative error); int8-stored is exact like the product path
+    x, w, tw, codes, alpha = make_layer(m + n + k + variant, (m, k), (n, k), groups=(n if m == 300 else 1))
+    y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32, variant=variant)
+    ref = oc.gemm_fwd(x, codes.reshape(n, k), alpha)
+    assert rel_err(to_host_f64(y), ref) <= (BF16_TOL if variant == api.TWN_VAR_BF16_ALPHA_LDS else 1e-4)
+    yb = api.twn_gemm_fwd(to_dev_bf16(x), tw, variant=variant)
+    assert rel_err(to_host_f64(yb), ref) <= BF16_TOL
+
+
+def test_int8_codes_match_oracle_codes():
+    n, k = 70, 200
+    x, w, tw, codes, alpha = make_layer(77, (4, k), (n, k))
+    i8 = tw.weights_for(api.TWN_VAR_I8_STORED_POSTSCALE).cpu().numpy()
+    assert i8.dtype == np.int8 and np.array_equal(i8, codes.reshape(n, k))
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("ci", [0, 2, 3, 5, 8, 9])
+def test_conv2d_fwd_comparison_variants(variant, ci):
+    n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
+    x, w, tw, codes, alpha = make_layer(300 + ci, (n, h, w_, c), (o, c, r, s))
+    if variant == api.TWN_VAR_I8_STORED_POSTSCALE and (r * s * c) % 8:
+        with pytest.raises(api.TwnError):      # int8 rows must be 8-byte multiples
+            api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, variant=variant)
+        return
+    g = np.random.default_rng(ci)
+    scale = g.uniform(0.5, 1.5, o).astype(np.float32)
+    # alpha-at-expansion carries bf16(alpha)'s 2^-9 relative error through the whole sum; a shift that cancels
+    # the sum would turn that into an unbounded relative error of the result, so that variant is checked unshifted
+    shift = g.standard_normal(o).astype(np.float32) if variant == api.TWN_VAR_I8_STORED_POSTSCALE else None
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, variant=variant, scale=to_dev_f32(scale),
+                           shift=None if shift is None else to_dev_f32(shift), relu=True)
+    ref = oc.epilogue(oc.conv2d_fwd(x, codes, alpha, st, pd, dl), scale, shift, None, relu=True)
+    assert rel_err(to_host_f64(y), ref) <= BF16_TOL
+
+
+def test_conv2d_bwd_data_alpha_at_expansion_variant():
+    n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[1]
+    x, w, tw, codes, alpha = make_layer(401, (n, h, w_, c), (o, c, r, s), transposed=True)
+    yshape = api.conv_out_shape((n, h, w_, c), tw, st, pd, dl)
+    dy = wl.bf16_round(np.random.default_rng(5).standard_normal(yshape).astype(np.float32))
+    dx, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dx=True, need_dw=False,
+                                      x_shape=(n, h, w_, c), variant=api.TWN_VAR_BF16_ALPHA_LDS)
+    ref = oc.conv2d_bwd_data(dy, codes, alpha, (n, h, w_, c), st, pd, dl)
+    assert rel_err(to_host_f64(dx), ref) <= BF16_TOL
+
+
 @pytest.mark.parametrize("ci", range(len(CONV_CASES)))
 def test_conv2d_fwd_bf16(ci):
     n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
