@@ -141,6 +141,28 @@ int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int32_t groups,
                       float* delta, float* alpha, uint64_t* nnz,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- 1b. several tensors per call (same passages as above) ------------------
+ * The per-layer form of twn_ternarize (groups = 1) for `count` <= 32 weight
+ * tensors at once, in three launches in total: meant for the weight tensors of
+ * a network, which are too small to fill the chip one at a time.  `items` is a
+ * host array (read during the call, not retained); the pointers inside are
+ * device pointers with the meaning and alignment of twn_ternarize's arguments
+ * (packed_T may be NULL).  Results equal those of `count` separate calls up to
+ * the order of the float64 partial sums.  Workspace: device memory, 8-byte
+ * aligned, at least twn_ternarize_batch_workspace_bytes(count) bytes. */
+typedef struct {
+    const float* W;
+    twn_weight_desc wd;
+    uint32_t* packed;
+    uint32_t* packed_T;
+    float* delta;
+    float* alpha;
+    uint64_t* nnz;
+} twn_ternarize_item;
+size_t  twn_ternarize_batch_workspace_bytes(int32_t count);
+int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t count, float delta_factor,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Expand a packed matrix [rows][words_per_row(K)] to int8 codes [rows][K]
  * (the input of TWN_VAR_I8_STORED_POSTSCALE; also lets a caller inspect codes). */
 int32_t twn_unpack_i8(const uint32_t* packed, int32_t rows, int64_t K, int8_t* codes, void* stream);

@@ -21,7 +21,8 @@ _lib = None
 
 EXPORTS = [
     "twn_status_str", "twn_abi_version", "twn_packed_words_per_row", "twn_packed_bytes",
-    "twn_ternarize_workspace_bytes", "twn_ternarize", "twn_unpack_i8",
+    "twn_ternarize_workspace_bytes", "twn_ternarize", "twn_ternarize_batch_workspace_bytes", "twn_ternarize_batch",
+    "twn_unpack_i8",
     "twn_gemm_fwd_workspace_bytes", "twn_gemm_fwd",
     "twn_conv2d_fwd_workspace_bytes", "twn_conv2d_fwd",
     "twn_conv2d_bwd_ste_workspace_bytes", "twn_conv2d_bwd_ste",
@@ -36,6 +37,11 @@ class TwnError(RuntimeError):
 
 class WeightDesc(ctypes.Structure):
     _fields_ = [("rows", ctypes.c_int32), ("C", ctypes.c_int32), ("R", ctypes.c_int32), ("S", ctypes.c_int32)]
+
+
+class TernarizeItem(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p), ("wd", WeightDesc), ("packed", ctypes.c_void_p), ("packed_T", ctypes.c_void_p),
+                ("delta", ctypes.c_void_p), ("alpha", ctypes.c_void_p), ("nnz", ctypes.c_void_p)]
 
 
 class GemmDesc(ctypes.Structure):
@@ -79,6 +85,10 @@ def lib():
         L.twn_ternarize_workspace_bytes.argtypes = [ctypes.POINTER(WeightDesc), i32]
         L.twn_ternarize.restype = i32
         L.twn_ternarize.argtypes = [vp, ctypes.POINTER(WeightDesc), i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.twn_ternarize_batch_workspace_bytes.restype = sz
+        L.twn_ternarize_batch_workspace_bytes.argtypes = [i32]
+        L.twn_ternarize_batch.restype = i32
+        L.twn_ternarize_batch.argtypes = [ctypes.POINTER(TernarizeItem), i32, f32, vp, sz, vp]
         L.twn_unpack_i8.restype = i32
         L.twn_unpack_i8.argtypes = [vp, i32, i64, vp, vp]
         L.twn_gemm_fwd_workspace_bytes.restype = sz
@@ -190,6 +200,39 @@ def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, wor
                          _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha), _ptr(out.nnz),
                          _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "twn_ternarize")
+    return out
+
+
+def _new_ternary_weights(rows, c, r, s, groups, transposed, dev):
+    k, kt = r * s * c, r * s * rows
+    packed = torch.empty((rows, twn_packed_words_per_row(k)), dtype=torch.int32, device=dev)
+    packed_t = torch.empty((c, twn_packed_words_per_row(kt)), dtype=torch.int32, device=dev) if transposed else None
+    return TernaryWeights(rows, c, r, s, groups, packed, packed_t,
+                          torch.empty(groups, dtype=torch.float32, device=dev),
+                          torch.empty(groups, dtype=torch.float32, device=dev),
+                          torch.empty(groups, dtype=torch.int64, device=dev))
+
+
+def twn_ternarize_batch(Ws, delta_factor=0.7, transposed=False, out=None, workspace=None, stream=None):
+    """Per-layer ternarization of up to 32 weight tensors in one call; returns a list of TernaryWeights."""
+    L = lib()
+    shapes = []
+    for W in Ws:
+        if not W.is_contiguous() or W.dtype != torch.float32 or not W.is_cuda:
+            raise TypeError("every W must be a contiguous float32 CUDA tensor")
+        shapes.append(tuple(W.shape) + (1, 1) if W.dim() == 2 else tuple(W.shape))
+    dev = Ws[0].device
+    if out is None:
+        out = [_new_ternary_weights(r_, c, r, s, 1, transposed, dev) for (r_, c, r, s) in shapes]
+    items = (TernarizeItem * len(Ws))()
+    for i, (W, o, (rows, c, r, s)) in enumerate(zip(Ws, out, shapes)):
+        items[i] = TernarizeItem(_ptr(W), WeightDesc(rows, c, r, s), _ptr(o.packed), _ptr(o.packed_T), _ptr(o.delta),
+                                 _ptr(o.alpha), _ptr(o.nnz))
+    if workspace is None:
+        workspace = _workspace(L.twn_ternarize_batch_workspace_bytes(len(Ws)), dev)
+    rc = L.twn_ternarize_batch(items, len(Ws), ctypes.c_float(delta_factor), _ptr(workspace), workspace.numel(),
+                               _stream(stream))
+    _check(rc, "twn_ternarize_batch")
     return out
 
 

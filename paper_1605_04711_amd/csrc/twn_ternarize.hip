@@ -31,8 +31,9 @@ struct TernWorkspace {
     uint64_t cnt[kMaxBlocks];  // pass-2 partial counts
 };
 
-__global__ __launch_bounds__(kTernThreads) void abs_sum_kernel(const float* __restrict__ W, int64_t n,
-                                                               double* __restrict__ partial) {
+// Pass 1 of block `bid` out of `nblk` cooperating blocks: float64 partial sum of |W| -> partial[bid].
+__device__ __forceinline__ void abs_sum_body(const float* __restrict__ W, int64_t n, double* __restrict__ partial,
+                                             int bid, int nblk) {
     __shared__ double scratch[16];
     const int tid = threadIdx.x;
     const int64_t nfull = n / kChunk;          // chunks that need no bounds test
@@ -43,11 +44,11 @@ __global__ __launch_bounds__(kTernThreads) void abs_sum_kernel(const float* __re
         for (int j = 0; j < 4; ++j) v[j] = src[j * kTernThreads + tid];
     };
     // software pipeline: the next chunk's loads are in flight while this one is summed
-    int64_t c = blockIdx.x;
+    int64_t c = bid;
     float4 cur[4];
     if (c < nfull) load4(c, cur);
     while (c < nfull) {
-        const int64_t nx = c + gridDim.x;
+        const int64_t nx = c + nblk;
         float4 nxt[4];
         if (nx < nfull) load4(nx, nxt);
 #pragma unroll
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(kTernThreads) void abs_sum_kernel(const float* __re
         c = nx;
     }
     // ragged tail (at most one chunk), taken by one block after its full chunks
-    if (nfull * kChunk < n && static_cast<int64_t>(blockIdx.x) == nfull % gridDim.x) {
+    if (nfull * kChunk < n && static_cast<int64_t>(bid) == nfull % nblk) {
         const int64_t base = nfull * kChunk;
         for (int j = 0; j < 4; ++j)
             for (int e = 0; e < 4; ++e) {
@@ -73,7 +74,12 @@ __global__ __launch_bounds__(kTernThreads) void abs_sum_kernel(const float* __re
             }
     }
     const double total = block_sum(acc, scratch);
-    if (tid == 0) partial[blockIdx.x] = total;
+    if (tid == 0) partial[bid] = total;
+}
+
+__global__ __launch_bounds__(kTernThreads) void abs_sum_kernel(const float* __restrict__ W, int64_t n,
+                                                               double* __restrict__ partial) {
+    abs_sum_body(W, n, partial, blockIdx.x, gridDim.x);
 }
 
 // Delta = (float)((double)f * S1 / n), S1 = fixed-order sum of the pass-1 partials.
@@ -86,9 +92,9 @@ __device__ __forceinline__ float delta_from_partials(const double* __restrict__ 
 }
 
 // Fixed-order sum of the pass-2 partials of `nb2` blocks -> Delta, alpha, nnz (one block).
-__global__ __launch_bounds__(kTernThreads) void finalize_kernel(const TernWorkspace* __restrict__ ws, int nb1, int nb2,
-                                                                float f, int64_t n, float* __restrict__ delta,
-                                                                float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
+__device__ __forceinline__ void finalize_body(const TernWorkspace* __restrict__ ws, int nb1, int nb2,
+                                              float f, int64_t n, float* __restrict__ delta,
+                                              float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
     // all loads of the three partial arrays are issued before any sum is formed
@@ -110,6 +116,12 @@ __global__ __launch_bounds__(kTernThreads) void finalize_kernel(const TernWorksp
         nnz[0] = total;
         alpha[0] = total ? static_cast<float>(s / static_cast<double>(total)) : 0.0f;
     }
+}
+
+__global__ __launch_bounds__(kTernThreads) void finalize_kernel(const TernWorkspace* __restrict__ ws, int nb1, int nb2,
+                                                                float f, int64_t n, float* __restrict__ delta,
+                                                                float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
+    finalize_body(ws, nb1, nb2, f, n, delta, alpha, nnz);
 }
 
 __device__ __forceinline__ uint32_t quad_or(uint32_t v) {
@@ -225,9 +237,9 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
 // masked sum and count: every weight belongs to exactly one normal word) and of the transposed copy.
 //   normal:     row = filter o,        k   = (r*S+s)*C + c
 //   transposed: row = input channel c, k_T = (r*S+s)*rows + o   (threads ordered with c fastest)
-__global__ __launch_bounds__(kTernThreads) void mask_pack_gather_kernel(
+__device__ __forceinline__ void mask_pack_gather_body(
     const float* __restrict__ W, int rows, int C, int RS, TernWorkspace* __restrict__ ws, int nb1, float f,
-    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT) {
+    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT, int bid, int nblk) {
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
     const int64_t n = static_cast<int64_t>(rows) * C * RS;
@@ -237,8 +249,8 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_gather_kernel(
     const int64_t K = static_cast<int64_t>(RS) * C, KT = static_cast<int64_t>(RS) * rows;
     double acc = 0.0;
     uint32_t count = 0;
-    for (int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; id < words_n + words_t;
-         id += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    for (int64_t id = static_cast<int64_t>(bid) * blockDim.x + threadIdx.x; id < words_n + words_t;
+         id += static_cast<int64_t>(nblk) * blockDim.x) {
         uint32_t word = 0;
         if (id < words_n) {
             const int o = static_cast<int>(id / wpr), j = static_cast<int>(id % wpr);
@@ -277,9 +289,62 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_gather_kernel(
     const double total = block_sum(acc, scratch);
     const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
     if (threadIdx.x == 0) {
-        ws->p2[blockIdx.x] = total;
-        ws->cnt[blockIdx.x] = ctotal;
+        ws->p2[bid] = total;
+        ws->cnt[bid] = ctotal;
     }
+}
+
+__global__ __launch_bounds__(kTernThreads) void mask_pack_gather_kernel(
+    const float* __restrict__ W, int rows, int C, int RS, TernWorkspace* __restrict__ ws, int nb1, float f,
+    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT) {
+    mask_pack_gather_body(W, rows, C, RS, ws, nb1, f, packed, wpr, packed_T, wprT, blockIdx.x, gridDim.x);
+}
+
+// ---- several tensors per launch --------------------------------------------------------------
+// The weight tensors of a network are small (at most a few MB): ternarizing them one call at a time is
+// bound by launch latency and by kernels too small to fill the chip.  The batch entry point runs the same
+// three passes once for up to kBatchMax tensors; a block finds its tensor in a table passed by value.
+constexpr int kBatchMax = 32;
+struct BatchItem {
+    const float* W;
+    uint32_t* packed;
+    uint32_t* packed_T;
+    float* delta;
+    float* alpha;
+    uint64_t* nnz;
+    int32_t rows, C, RS, wpr, wprT;
+    int32_t nb1, nb2;           // blocks of pass 1 / pass 2 working on this tensor
+    int32_t first1, first2;     // index of its first block in the pass-1 / pass-2 launch
+};
+struct BatchTable {
+    BatchItem item[kBatchMax];
+    int32_t count;
+    float f;
+};
+
+__device__ __forceinline__ int batch_find(const BatchTable& tb, int block, bool pass2) {
+    int i = 0;
+    while (i + 1 < tb.count && block >= (pass2 ? tb.item[i + 1].first2 : tb.item[i + 1].first1)) ++i;
+    return i;
+}
+
+__global__ __launch_bounds__(kTernThreads) void batch_abs_sum_kernel(const BatchTable tb, TernWorkspace* __restrict__ ws) {
+    const int i = batch_find(tb, blockIdx.x, false);
+    const BatchItem& it = tb.item[i];
+    abs_sum_body(it.W, static_cast<int64_t>(it.rows) * it.C * it.RS, ws[i].p1, blockIdx.x - it.first1, it.nb1);
+}
+
+__global__ __launch_bounds__(kTernThreads) void batch_mask_pack_kernel(const BatchTable tb, TernWorkspace* __restrict__ ws) {
+    const int i = batch_find(tb, blockIdx.x, true);
+    const BatchItem& it = tb.item[i];
+    mask_pack_gather_body(it.W, it.rows, it.C, it.RS, ws + i, it.nb1, tb.f, it.packed, it.wpr, it.packed_T, it.wprT,
+                          blockIdx.x - it.first2, it.nb2);
+}
+
+__global__ __launch_bounds__(kTernThreads) void batch_finalize_kernel(const BatchTable tb, const TernWorkspace* __restrict__ ws) {
+    const BatchItem& it = tb.item[blockIdx.x];
+    finalize_body(ws + blockIdx.x, it.nb1, it.nb2, tb.f, static_cast<int64_t>(it.rows) * it.C * it.RS, it.delta, it.alpha,
+                  it.nnz);
 }
 
 // One block per group: both passes over the group's contiguous weights.
@@ -434,6 +499,69 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
                 W, wd->rows, wd->C, static_cast<int>(RS), delta, rows_per_group, packed_T, wprT, 1);
         }
     }
+    return launch_status();
+}
+
+extern "C" size_t twn_ternarize_batch_workspace_bytes(int32_t count) {
+    if (count < 1 || count > kBatchMax) return 0;
+    return static_cast<size_t>(count) * sizeof(TernWorkspace);
+}
+
+extern "C" int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t count, float delta_factor,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+    if (!items) return TWN_ERR_NULL;
+    if (count < 1 || count > kBatchMax) return TWN_ERR_SHAPE;
+    if (!(delta_factor > 0.0f) || delta_factor > 1.0f) return TWN_ERR_SHAPE;
+    if (!workspace || workspace_bytes < static_cast<size_t>(count) * sizeof(TernWorkspace) || !aligned(workspace, 8))
+        return TWN_ERR_WORKSPACE;
+    BatchTable tb{};
+    tb.count = count;
+    tb.f = delta_factor;
+    int64_t total_n = 0;
+    for (int i = 0; i < count; ++i) {
+        const twn_ternarize_item& in = items[i];
+        if (!in.W || !in.packed || !in.delta || !in.alpha || !in.nnz) return TWN_ERR_NULL;
+        const twn_weight_desc& wd = in.wd;
+        if (wd.rows <= 0 || wd.C <= 0 || wd.R <= 0 || wd.S <= 0) return TWN_ERR_SHAPE;
+        const int64_t RS = static_cast<int64_t>(wd.R) * wd.S;
+        const int64_t K = RS * wd.C, KT = RS * wd.rows, n = K * wd.rows;
+        if (RS > (1 << 15) || K >= (1LL << 31) || KT >= (1LL << 31) || n >= (1LL << 40)) return TWN_ERR_SHAPE;
+        if (!aligned(in.W, 16) || !aligned(in.packed, 16) || (in.packed_T && !aligned(in.packed_T, 16))) return TWN_ERR_ALIGN;
+        total_n += n;
+    }
+    // blocks are shared out in proportion to the tensor sizes: about 1024 per pass in total
+    int first1 = 0, first2 = 0;
+    for (int i = 0; i < count; ++i) {
+        const twn_ternarize_item& in = items[i];
+        const twn_weight_desc& wd = in.wd;
+        const int64_t RS = static_cast<int64_t>(wd.R) * wd.S;
+        const int64_t K = RS * wd.C, KT = RS * wd.rows, n = K * wd.rows;
+        BatchItem& it = tb.item[i];
+        it.W = in.W; it.packed = in.packed; it.packed_T = in.packed_T;
+        it.delta = in.delta; it.alpha = in.alpha; it.nnz = in.nnz;
+        it.rows = wd.rows; it.C = wd.C; it.RS = static_cast<int32_t>(RS);
+        it.wpr = static_cast<int32_t>(twn_packed_words_per_row(K));
+        it.wprT = static_cast<int32_t>(twn_packed_words_per_row(KT));
+        int64_t share = (1024 * n + total_n - 1) / total_n;
+        if (share < 1) share = 1;
+        const int64_t nchunks = (n + kChunk - 1) / kChunk;
+        it.nb1 = static_cast<int32_t>(nchunks < share ? nchunks : share);
+        const int64_t words = static_cast<int64_t>(wd.rows) * it.wpr + (in.packed_T ? static_cast<int64_t>(wd.C) * it.wprT : 0);
+        int64_t nb2 = (words + kTernThreads - 1) / kTernThreads;
+        if (nb2 > 4 * share) nb2 = 4 * share;
+        if (nb2 > kMaxBlocks) nb2 = kMaxBlocks;
+        if (it.nb1 > kMaxBlocks) it.nb1 = kMaxBlocks;
+        it.nb2 = static_cast<int32_t>(nb2);
+        it.first1 = first1;
+        it.first2 = first2;
+        first1 += it.nb1;
+        first2 += it.nb2;
+    }
+    hipStream_t st = as_stream(stream);
+    TernWorkspace* ws = static_cast<TernWorkspace*>(workspace);
+    batch_abs_sum_kernel<<<first1, kTernThreads, 0, st>>>(tb, ws);
+    batch_mask_pack_kernel<<<first2, kTernThreads, 0, st>>>(tb, ws);
+    batch_finalize_kernel<<<count, kTernThreads, 0, st>>>(tb, ws);
     return launch_status();
 }
 

@@ -58,6 +58,49 @@ def test_per_filter_groups(shape, groups):
     check_against_oracle(w, 0.75, groups=g)
 
 
+def check_batch(shapes, f, transposed):
+    ws = [wl.normal(9, 10 * i + len(sh), sh, std=0.02 * (i + 1)) for i, sh in enumerate(shapes)]
+    tws = api.twn_ternarize_batch([to_dev_f32(w) for w in ws], f, transposed=transposed)
+    torch.cuda.synchronize()
+    for w, tw in zip(ws, tws):
+        w4 = w if w.ndim == 4 else w.reshape(w.shape[0], w.shape[1], 1, 1)
+        codes, delta, alpha, nnz = ot.ternarize(w4, f)
+        assert np.array_equal(tw.nnz.cpu().numpy(), nnz)
+        assert np.all(np.abs(tw.delta.cpu().numpy() - delta) <= REL * np.abs(delta))
+        assert np.all(np.abs(tw.alpha.cpu().numpy() - alpha) <= REL * np.abs(alpha))
+        assert np.array_equal(packed_to_host(tw.packed), op.pack_weights(codes))
+        if transposed:
+            assert np.array_equal(packed_to_host(tw.packed_T), op.pack_weights_t(codes))
+        # and the one-tensor entry point gives the same bytes
+        one = api.twn_ternarize(to_dev_f32(w), f, transposed=transposed)
+        assert torch.equal(one.packed, tw.packed) and torch.equal(one.nnz, tw.nnz)
+        assert torch.allclose(one.delta, tw.delta, rtol=REL, atol=0) and torch.allclose(one.alpha, tw.alpha, rtol=REL, atol=0)
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+def test_batch_of_mixed_tensors(transposed):
+    check_batch([(5, 3, 3, 3), (64, 32, 5, 5), (1000, 128 * 33), (17, 24), (1, 1), (128, 128, 3, 3), (64, 3, 7, 7),
+                 (10, 1024)], 0.7, transposed)
+
+
+def test_batch_of_one_and_of_the_maximum():
+    check_batch([(33, 1152)], 0.75, True)
+    check_batch([(4 + i, 8 + 3 * i, 1 + i % 3, 1 + i % 2) for i in range(32)], 2.0 / 3.0, True)
+
+
+def test_batch_vgg7_weight_tensors():
+    layers = wl.vgg7(128)
+    check_batch([L.w_shape for L in layers], 0.7, True)
+
+
+def test_batch_rejects_bad_arguments():
+    w = to_dev_f32(wl.normal(9, 1, (8, 16), std=0.1))
+    with pytest.raises(api.TwnError):
+        api.twn_ternarize_batch([w] * 33, 0.7)
+    with pytest.raises(api.TwnError):
+        api.twn_ternarize_batch([w], 1.5)
+
+
 def test_ties_zeros_and_constant_magnitude():
     # sum|W| = 16*16 over 128 weights, f = 0.5 -> Delta = 1.0 exactly; entries equal to 1 are ties -> 0
     base = np.array([4, -4, 2, -2, 0.0, -0.0, 1, 3], dtype=np.float32)
