@@ -547,7 +547,9 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float* __res
 
 static int32_t choose_splits(int64_t tiles, int64_t slabs) {
     int64_t want = env_int("TWN_WG_BLOCKS", 512);
-    int64_t splits = (tiles >= 256) ? 1 : (want + tiles - 1) / tiles;
+    // tiles x splits must not exceed the workgroups that are resident at once (two per CU), or the launch
+    // grows a second, nearly empty round
+    int64_t splits = (tiles >= 256) ? 1 : want / tiles;
     if (splits > slabs) splits = slabs;
     if (splits > 256) splits = 256;
     if (splits < 1) splits = 1;

@@ -420,6 +420,8 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
             else if (g.NC <= 64) tile = 13;
             else if (g.NC <= 128) tile = 12;
             else tile = (blocks(128, 256) >= 512) ? 17 : 12;
+            // at most one 128x128 workgroup per CU: eight waves per workgroup (two per SIMD) instead of four
+            if (tile == 12 && g.splits == 1 && blocks(128, 128) <= 256) tile = 27;
         }
         return launch_gather_gemm_dma(g, tile, st);
     }

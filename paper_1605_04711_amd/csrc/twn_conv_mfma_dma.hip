@@ -614,6 +614,7 @@ int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
         case 22: return launch_dma_tile<256, 64, 4, 1, 3>(g, st);
         case 23: return launch_dma_tile<256, 64, 2, 1, 3>(g, st);
         case 24: return launch_dma_tile<128, 512, 1, 8, 4>(g, st);
+        case 27: return launch_dma_tile<128, 128, 4, 2, 3>(g, st);
         default: return TWN_ERR_UNSUPPORTED;
     }
 }

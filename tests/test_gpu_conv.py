@@ -57,6 +57,23 @@ def test_gemm_fwd_every_tile_shape(tile, monkeypatch):
     assert rel_err(to_host_f64(y), ref) <= 1e-4
 
 
+DMA_TILES = [11, 12, 13, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 27]
+
+
+@pytest.mark.parametrize("tile", DMA_TILES)
+def test_every_direct_to_lds_tile_shape(tile, monkeypatch):
+    # every instantiated tile of the direct-to-LDS kernel: a ragged GEMM and a padded, strided convolution
+    monkeypatch.setenv("TWN_TILE", str(tile))
+    m, n, k = 520, 300, 448
+    x, w, tw, codes, alpha = make_layer(tile, (m, k), (n, k))
+    y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
+    assert rel_err(to_host_f64(y), oc.gemm_fwd(x, codes.reshape(n, k), alpha)) <= 1e-4
+    nb, h, w_, c, o, r, s, st, pd, dl = (3, 15, 13, 24, 72, 3, 3, (2, 1), (1, 2), (1, 1))
+    x, w, tw, codes, alpha = make_layer(50 + tile, (nb, h, w_, c), (o, c, r, s))
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, y_dtype=torch.float32)
+    assert rel_err(to_host_f64(y), oc.conv2d_fwd(x, codes, alpha, st, pd, dl)) <= 1e-4
+
+
 def test_gemm_epilogue_groups_and_strides():
     m, n, k = 200, 96, 256
     x, w, tw, codes, alpha = make_layer(11, (m, k), (n, k), groups=n)
