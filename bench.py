@@ -200,9 +200,9 @@ def main():
             fn()
     torch.cuda.synchronize()
 
-    # Timed region.  HIP events on the launch stream (torch's current stream) bracket the four phases and,
-    # inside them, each call that is exactly one launch of the contraction kernel (the roofline sample).
-    # Events around every call would add a bubble per call, so the per-layer table is taken afterwards.
+    # Timed region.  HIP events on the launch stream (torch's current stream) bracket each call that is
+    # exactly one launch of the contraction kernel (the roofline sample); phases and the per-layer table
+    # are taken in separate passes afterwards.
     name_of = [L.name for L in layers]
     single = {("fwd", n) for n in ("c2", "c3", "c4", "c5", "c6")} | {("bwd_data", n) for n in ("c2", "c3", "c4", "c6")}
     phase_names = ["ternarize", "fwd", "bwd_data", "bwd_weight"]
@@ -213,28 +213,40 @@ def main():
     def new_ev():
         return torch.cuda.Event(enable_timing=True)
 
-    pev = [{ph: (new_ev(), new_ev()) for ph in phase_names} for _ in range(args.steps)]
-    cev = [{ci: (new_ev(), new_ev()) for ci in range(len(calls)) if is_single[ci]} for _ in range(args.steps)]
+    # An event between two launches costs a few microseconds of idle GPU, so the timed region records as few
+    # as possible: one event at every boundary of a run of consecutive single-launch calls (the end of one
+    # call is the start of the next), i.e. run_len + 1 events per run.  Phase times come from a separate,
+    # untimed pass below.
+    marks = [ci for ci in range(len(calls) + 1)
+             if (ci < len(calls) and is_single[ci]) or (ci > 0 and is_single[ci - 1])]
+    mev = [{ci: new_ev() for ci in marks} for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
         for ci, (ph, _, fn) in enumerate(calls):
-            if ci == first_of[ph]:
-                pev[s][ph][0].record()
-            if is_single[ci]:
-                cev[s][ci][0].record()
+            if ci in mev[s]:
+                mev[s][ci].record()
             fn()
-            if is_single[ci]:
-                cev[s][ci][1].record()
-            if ci == last_of[ph]:
-                pev[s][ph][1].record()
+        if len(calls) in mev[s]:
+            mev[s][len(calls)].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    phase_ms = [sum(pev[s][ph][0].elapsed_time(pev[s][ph][1]) for s in range(args.steps)) / args.steps
-                for ph in phase_names]
-    single_ms = {ci: sum(cev[s][ci][0].elapsed_time(cev[s][ci][1]) for s in range(args.steps)) / args.steps
+    single_ms = {ci: sum(mev[s][ci].elapsed_time(mev[s][ci + 1]) for s in range(args.steps)) / args.steps
                  for ci in range(len(calls)) if is_single[ci]}
+
+    # phase times: a second pass with one event pair per phase
+    NPH = max(5, min(50, args.steps))
+    pev = [{ph: (new_ev(), new_ev()) for ph in phase_names} for _ in range(NPH)]
+    for s in range(NPH):
+        for ci, (ph, _, fn) in enumerate(calls):
+            if ci == first_of[ph]:
+                pev[s][ph][0].record()
+            fn()
+            if ci == last_of[ph]:
+                pev[s][ph][1].record()
+    torch.cuda.synchronize()
+    phase_ms = [sum(pev[s][ph][0].elapsed_time(pev[s][ph][1]) for s in range(NPH)) / NPH for ph in phase_names]
     value = flops_step / (ms_per_step * 1e-3) / 1e12
     log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phase_names[i], phase_ms[i]) for i in range(4)))
 
