@@ -126,6 +126,20 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
                                    X + (pixbase[i] + static_cast<int64_t>(th) * g.IW + tw) * g.xs + c)
                              : u32x4{0, 0, 0, 0};
             }
+        } else if (g.plain_gemm) {
+            // rows of X with a length that is not a multiple of 8: element loads, no tap arithmetic
+#pragma unroll
+            for (int i = 0; i < NLOAD; ++i) {
+                uint32_t w4[4] = {0, 0, 0, 0};
+                const int64_t m = m0 + (tid >> 3) + i * ROWSTEP;      // GEMM row = pixel index
+                const uint16_t* src = X + m * g.xs + k;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t v = (m < g.M && k + e < g.K) ? src[e] : 0u;
+                    w4[e >> 1] |= v << ((e & 1) * 16);
+                }
+                areg[i] = u32x4{w4[0], w4[1], w4[2], w4[3]};
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < NLOAD; ++i) {
