@@ -476,27 +476,42 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
 // dW[o][c][r][s] = beta*dW + sum over splits (fixed order) of partial[split][o][(r*S+s)*C + c]
 // `pad_sp` = 0: partial tiles are [O][(r*S+s)*C + c].  First-layer mode (`pad_sp` = Sp > 0): tiles are
 // [O][(r*Sp+s)*4 + c] and entries with s >= S or c >= C are phantom (dropped).
-// 32 consecutive partial elements per block (coalesced over the large input) x 8 thread rows that each
-// sum every 8th split; the rows are combined in a fixed order and the small output is scattered.
+// A block covers 64*VEC consecutive partial elements (one float4 or one float per lane); its four waves
+// each sum every fourth split with several loads in flight, and the four sums are combined in a fixed
+// order; the small output is scattered.  VEC = 4 needs the tile size O*J to be a multiple of 4.
+template <int VEC>
 __global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __restrict__ partial, int splits,
                                                                  int O, int C, int R, int S, int pad_sp, float beta,
                                                                  float* __restrict__ dW) {
-    __shared__ float red[8][32];
-    const int col = threadIdx.x & 31, rowi = threadIdx.x >> 5;
-    const int64_t id = static_cast<int64_t>(blockIdx.x) * 32 + col;
+    __shared__ float red[4][64 * VEC];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t id0 = (static_cast<int64_t>(blockIdx.x) * 64 + lane) * VEC;
     const int64_t Jsrc = pad_sp ? static_cast<int64_t>(R) * pad_sp * 4 : static_cast<int64_t>(R) * S * C;
     const int64_t total = Jsrc * O;
-    float s = 0.0f;
-    if (id < total) {
-#pragma unroll 4
-        for (int sp = rowi; sp < splits; sp += 8) s += partial[static_cast<int64_t>(sp) * total + id];
-    }
-    red[rowi][col] = s;
-    __syncthreads();
-    if (rowi != 0 || id >= total) return;
-    s = red[0][col];
+    float acc[VEC];
 #pragma unroll
-    for (int r8 = 1; r8 < 8; ++r8) s += red[r8][col];
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
+    if (id0 < total) {
+#pragma unroll 8
+        for (int sp = wave; sp < splits; sp += 4) {
+            const float* src = partial + static_cast<int64_t>(sp) * total + id0;
+            if (VEC == 4) {
+                const float4 t = *reinterpret_cast<const float4*>(src);
+                acc[0] += t.x; acc[1 % VEC] += t.y; acc[2 % VEC] += t.z; acc[3 % VEC] += t.w;
+            } else {
+                acc[0] += src[0];
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) red[wave][lane * VEC + v] = acc[v];
+    __syncthreads();
+    // one element per thread: element `el` of the block's 64*VEC (VEC = 1: the first wave only)
+    const int el = threadIdx.x;
+    if (el >= 64 * VEC) return;
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * 64 * VEC + el;
+    if (id >= total) return;
+    const float sum = ((red[0][el] + red[1][el]) + red[2][el]) + red[3][el];
     const int64_t o = id / Jsrc;
     const int64_t j = id - o * Jsrc;
     int64_t rs, c;
@@ -514,7 +529,7 @@ __global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __
         sx = static_cast<int>(rs - static_cast<int64_t>(r) * S);
     }
     const int64_t dst = ((o * C + c) * R + r) * S + sx;   // [O][C][R][S]
-    dW[dst] = (beta != 0.0f) ? beta * dW[dst] + s : s;
+    dW[dst] = (beta != 0.0f) ? beta * dW[dst] + sum : sum;
 }
 
 // dbias partials: block (x = 64-channel group, y = pixel split) sums its pixel range.
@@ -622,8 +637,12 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
         if (w.pad_sp || !(a.plan.patch && splits == 1)) {   // a single-range patch launch writes dW itself
             const int64_t total = static_cast<int64_t>(w.O) * a.J;
             const int C = w.pad_sp ? w.c_real : w.C, S = w.pad_sp ? w.s_real : w.S;
-            weight_grad_reduce_kernel<<<static_cast<unsigned>((total + 31) / 32), 256, 0, st>>>(
-                w.partial, splits, w.O, C, w.R, S, w.pad_sp, w.beta, w.dW);
+            if (total % 4 == 0)
+                weight_grad_reduce_kernel<4><<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(
+                    w.partial, splits, w.O, C, w.R, S, w.pad_sp, w.beta, w.dW);
+            else
+                weight_grad_reduce_kernel<1><<<static_cast<unsigned>((total + 63) / 64), 256, 0, st>>>(
+                    w.partial, splits, w.O, C, w.R, S, w.pad_sp, w.beta, w.dW);
         }
     }
     if (w.dbias) {
