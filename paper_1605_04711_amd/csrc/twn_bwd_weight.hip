@@ -254,7 +254,7 @@ __device__ __forceinline__ void wg_dma16(const void* gsrc, void* lds_dst) {
 // Transposing LDS read of 4 pixels x 16 bits for this lane (see the file header).  Issued as inline
 // assembly: the compiler would otherwise order every LDS read after ALL outstanding direct-to-LDS
 // loads (s_waitcnt vmcnt(0)), which serialises the software pipeline.  The caller waits for the data
-// with wg_wait_frags before using it.
+// with wg_wait<N>() + wg_ready() before using it.
 template <int OFFSET>
 __device__ __forceinline__ u32x2 wg_tr_read(uint32_t lds_addr) {
     u32x2 v;
@@ -262,11 +262,18 @@ __device__ __forceinline__ u32x2 wg_tr_read(uint32_t lds_addr) {
     return v;
 }
 
-// s_waitcnt lgkmcnt(0) that the consumers of the twelve fragment halves depend on.
-__device__ __forceinline__ void wg_wait_frags(u32x2 (&fa)[2][2], u32x2 (&fb)[4][2]) {
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(fa[0][0]), "+v"(fa[0][1]), "+v"(fa[1][0]), "+v"(fa[1][1]), "+v"(fb[0][0]), "+v"(fb[0][1]),
-                   "+v"(fb[1][0]), "+v"(fb[1][1]), "+v"(fb[2][0]), "+v"(fb[2][1]), "+v"(fb[3][0]), "+v"(fb[3][1]));
+// s_waitcnt lgkmcnt(N): at most N of the LDS reads issued so far are still outstanding (they complete in
+// issue order).  wg_ready ties the consumers of fragment registers to the preceding wait.
+template <int N>
+__device__ __forceinline__ void wg_wait() {
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+}
+__device__ __forceinline__ void wg_ready(u32x2 (&f)[2][2]) {
+    asm volatile("" : "+v"(f[0][0]), "+v"(f[0][1]), "+v"(f[1][0]), "+v"(f[1][1]));
+}
+__device__ __forceinline__ void wg_ready_b(u32x2 (&f)[2]) {
+    asm volatile("" : "+v"(f[0]), "+v"(f[1]));
 }
 
 __device__ __forceinline__ bf16x8 wg_join(const u32x2& lo, const u32x2& hi) {
@@ -394,46 +401,80 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
 
+    // ---- software pipeline ---------------------------------------------------------------------
+    // A slab is two MFMA steps of eight MFMAs, taken as four pairs (mi = 0, 1) per channel tile ni.  The
+    // fragments of the NEXT step are fetched while this one multiplies: the four dY fragments into the
+    // other register set right after the first pair, the two halves of X fragment ni as soon as pair ni
+    // has consumed the old ones.  LDS reads complete in issue order, so s_waitcnt lgkmcnt(n) with the
+    // number of younger reads is exact: 6 before the first pair of a step, 10 before the others.
+    // Hand-over between the steps of slab `it`: slab it+1 has landed (its step 0 is prefetched during step
+    // 1), and the stage of slab it-1, whose reads were all issued during step 0 of that slab, is refilled.
+    u32x2 fa[2][2][2], fb[4][2];
+    auto read_fa = [&](auto off_tag, uint32_t base, u32x2 (*dst)[2]) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(off_tag)::value;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int hv = 0; hv < 2; ++hv) dst[mi][hv] = wg_tr_read<OFF>(base + offA[mi][hv]);
+    };
+    auto read_fb = [&](auto off_tag, uint32_t base, int ni) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(off_tag)::value;
+#pragma unroll
+        for (int hv = 0; hv < 2; ++hv) fb[ni][hv] = wg_tr_read<OFF>(base + A_BYTES + offB[ni][hv]);
+    };
+
 #pragma unroll
     for (int s = 0; s < PD; ++s) issue(slab_begin + s, s, s < nslab);
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 1) * PER_STAGE));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    read_fa(std::integral_constant<int, 0>{}, lds_base, fa[0]);
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) read_fb(std::integral_constant<int, 0>{}, lds_base, ni);
 
-    int stage = 0, fill = PD;
+    int stage = 0, fill = PD % STAGES;
     for (int it = 0; it < nslab; ++it) {
-        issue(slab_begin + it + PD, fill, it + PD < nslab);
-        const uint32_t sA = lds_base + stage * STAGE_BYTES;
-        const uint32_t sB = sA + A_BYTES;
-        auto step = [&](auto kk_tag) {
+        const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
+        auto step = [&](auto kk_tag) __attribute__((always_inline)) {
             constexpr int KK = decltype(kk_tag)::value;
-            u32x2 fa[2][2], fb[4][2];
+            // where the next step's fragments live: second half of this slab, or first half of the next one
+            const uint32_t nbase = lds_base + ((KK == 0) ? stage : next) * STAGE_BYTES;
+            using NOff = std::integral_constant<int, (KK == 0) ? 4096 : 0>;
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int ni = 0; ni < 4; ++ni) {
+                if (ni == 0) wg_wait<6>(); else wg_wait<10>();
+                if (ni == 0) wg_ready(fa[KK]);
+                wg_ready_b(fb[ni]);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int hv = 0; hv < 2; ++hv) fa[mi][hv] = wg_tr_read<KK * 4096>(sA + offA[mi][hv]);
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-                for (int hv = 0; hv < 2; ++hv) fb[ni][hv] = wg_tr_read<KK * 4096>(sB + offB[ni][hv]);
-            wg_wait_frags(fa, fb);
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg_join(fa[mi][0], fa[mi][1]),
+                for (int mi = 0; mi < 2; ++mi)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg_join(fa[KK][mi][0], fa[KK][mi][1]),
                                                                           wg_join(fb[ni][0], fb[ni][1]), acc[mi][ni],
                                                                           0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ni == 0) read_fa(NOff{}, nbase, fa[KK ^ 1]);
+                read_fb(NOff{}, nbase, ni);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         };
         step(std::integral_constant<int, 0>{});
-        step(std::integral_constant<int, 1>{});
         asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 1) * PER_STAGE));
+        __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 2) * PER_STAGE));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        stage = (stage + 1 == STAGES) ? 0 : stage + 1;
+        issue(slab_begin + it + PD, fill, it + PD < nslab);
+        __builtin_amdgcn_sched_barrier(0);
+        step(std::integral_constant<int, 1>{});
+        stage = next;
         fill = (fill + 1 == STAGES) ? 0 : fill + 1;
     }
+    // the fragments fetched ahead for the slab after the last one are never used: let them land, and drain
+    // the trailing zero loads, before registers and LDS are reused
+    wg_wait<0>();
+    wg_ready(fa[0]);
+    wg_ready(fa[1]);
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) wg_ready_b(fb[ni]);
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm(0));
 
     if (pl.splits == 1 && !w.pad_sp) {
