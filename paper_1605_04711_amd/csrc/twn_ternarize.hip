@@ -137,9 +137,9 @@ __device__ __forceinline__ uint32_t quad_or(uint32_t v) {
 // word, which is assembled with two DPP ORs and written by the lane whose
 // position in the quad equals the load index, so each wave stores 256
 // contiguous bytes.
-__global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
+__device__ __forceinline__ void mask_pack_flat_body(
     const float* __restrict__ W, int64_t n, TernWorkspace* __restrict__ ws, int nb1, float f,
-    uint32_t* __restrict__ packed, int reverse) {
+    uint32_t* __restrict__ packed, int reverse, int bid, int nblk) {
     const double* __restrict__ p1 = ws->p1;
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
@@ -196,20 +196,20 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
     // if it is the last one in memory order, i.e. it == nchunks-1 forwards or it == 0 backwards
     const bool has_tail = nfull < nchunks;
     const int64_t tail_it = reverse ? 0 : nchunks - 1;
-    int64_t it = blockIdx.x;
+    int64_t it = bid;
     if (has_tail && it == tail_it) {            // only possible for the first iteration of one block
         float4 v[4];
         const int64_t wb = wave_base(it);
         load4(wb, v, true);
         process(v, wb, true);
-        it += gridDim.x;
+        it += nblk;
     }
     const int64_t it_end = (has_tail && !reverse) ? nchunks - 1 : nchunks;
     // software pipeline over the full chunks: next loads in flight while this chunk is processed
     float4 cur[4];
     if (it < it_end) load4(wave_base(it), cur, false);
     while (it < it_end) {
-        const int64_t nx = it + gridDim.x;
+        const int64_t nx = it + nblk;
         float4 nxt[4];
         if (nx < it_end) load4(wave_base(nx), nxt, false);
         process(cur, wave_base(it), false);
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
         }
         it = nx;
     }
-    if (has_tail && !reverse && static_cast<int64_t>(blockIdx.x) == tail_it % gridDim.x && tail_it >= gridDim.x) {
+    if (has_tail && !reverse && static_cast<int64_t>(bid) == tail_it % nblk && tail_it >= nblk) {
         float4 v[4];
         const int64_t wb = wave_base(tail_it);
         load4(wb, v, true);
@@ -228,9 +228,15 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
     const double total = block_sum(acc, scratch);
     const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
     if (threadIdx.x == 0) {
-        ws->p2[blockIdx.x] = total;
-        ws->cnt[blockIdx.x] = ctotal;
+        ws->p2[bid] = total;
+        ws->cnt[bid] = ctotal;
     }
+}
+
+__global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
+    const float* __restrict__ W, int64_t n, TernWorkspace* __restrict__ ws, int nb1, float f,
+    uint32_t* __restrict__ packed, int reverse) {
+    mask_pack_flat_body(W, n, ws, nb1, f, packed, reverse, blockIdx.x, gridDim.x);
 }
 
 // Pass 2 for any layout: grid-stride over the output words of the normal copy (which also carry the
@@ -239,12 +245,13 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_flat_kernel(
 //   transposed: row = input channel c, k_T = (r*S+s)*rows + o   (threads ordered with c fastest)
 __device__ __forceinline__ void mask_pack_gather_body(
     const float* __restrict__ W, int rows, int C, int RS, TernWorkspace* __restrict__ ws, int nb1, float f,
-    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT, int bid, int nblk) {
+    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT, int bid, int nblk,
+    bool only_transposed = false, int slot0 = 0) {
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
     const int64_t n = static_cast<int64_t>(rows) * C * RS;
     const float delta = delta_from_partials(ws->p1, nb1, f, n, scratch);
-    const int64_t words_n = static_cast<int64_t>(rows) * wpr;
+    const int64_t words_n = only_transposed ? 0 : static_cast<int64_t>(rows) * wpr;
     const int64_t words_t = packed_T ? static_cast<int64_t>(C) * wprT : 0;
     const int64_t K = static_cast<int64_t>(RS) * C, KT = static_cast<int64_t>(RS) * rows;
     double acc = 0.0;
@@ -289,8 +296,8 @@ __device__ __forceinline__ void mask_pack_gather_body(
     const double total = block_sum(acc, scratch);
     const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
     if (threadIdx.x == 0) {
-        ws->p2[bid] = total;
-        ws->cnt[bid] = ctotal;
+        ws->p2[slot0 + bid] = total;
+        ws->cnt[slot0 + bid] = ctotal;
     }
 }
 
@@ -298,6 +305,100 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_gather_kernel(
     const float* __restrict__ W, int rows, int C, int RS, TernWorkspace* __restrict__ ws, int nb1, float f,
     uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT) {
     mask_pack_gather_body(W, rows, C, RS, ws, nb1, f, packed, wpr, packed_T, wprT, blockIdx.x, gridDim.x);
+}
+
+// Pass 2 for filter banks with R*S > 1, rows % 16 == 0 and C % 16 == 0, staged through LDS: block `bid`
+// owns 16 consecutive filters x CT consecutive channels x all taps.  Its weights are 16 contiguous runs
+// of CT*R*S floats, read once with coalesced float4 loads; the 2-bit fields go to LDS as bytes in memory
+// order, and the words of both copies are assembled from LDS (16 byte reads per word), so no thread
+// gathers from global memory.  Words written: per filter and tap CT/16 normal words; per channel and tap
+// one transposed word (its 16 codes are the block's 16 filters).  Row padding words are written by the
+// blocks with channel tile 0 (normal) and filter tile 0 (transposed).
+constexpr int kTileRows = 16;
+constexpr int kTileLdsBytes = 16 * 64 * 25;   // CT <= 64, R*S <= 25
+__host__ __device__ inline int tile_ct(int C) { return (C % 64 == 0) ? 64 : (C % 32 == 0) ? 32 : 16; }
+__host__ __device__ inline bool tile_ok(int rows, int C, int RS) {
+    return RS > 1 && RS <= 25 && rows % 16 == 0 && C % 16 == 0 &&
+           static_cast<int64_t>(rows / 16) * (C / tile_ct(C)) <= kMaxBlocks;
+}
+
+__device__ __forceinline__ void mask_pack_tile_body(
+    const float* __restrict__ W, int rows, int C, int RS, TernWorkspace* __restrict__ ws, int nb1, float f,
+    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT, int bid) {
+    __shared__ double scratch[16];
+    __shared__ unsigned long long scratch_u[16];
+    __shared__ __attribute__((aligned(16))) unsigned char codes[kTileLdsBytes];
+    const int64_t n = static_cast<int64_t>(rows) * C * RS;
+    const float delta = delta_from_partials(ws->p1, nb1, f, n, scratch);
+    const int CT = tile_ct(C), ctiles = C / CT;
+    const int o0 = (bid / ctiles) * kTileRows, c0 = (bid % ctiles) * CT;
+    const int seg = CT * RS;                       // floats (and code bytes) per filter in this block
+    const int tid = threadIdx.x;
+    double acc = 0.0;
+    uint32_t count = 0;
+    for (int ol = 0; ol < kTileRows; ++ol) {
+        const float4* src = reinterpret_cast<const float4*>(W + (static_cast<int64_t>(o0 + ol) * C + c0) * RS);
+        for (int p = tid; p < seg / 4; p += kTernThreads) {
+            const float4 v = src[p];
+            const float w4[4] = {v.x, v.y, v.z, v.w};
+            uint32_t four = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t fld = code_field(w4[e], delta);
+                if (fld) {
+                    acc += static_cast<double>(fabsf(w4[e]));
+                    ++count;
+                }
+                four |= fld << (8 * e);
+            }
+            *reinterpret_cast<uint32_t*>(codes + ol * seg + 4 * p) = four;
+        }
+    }
+    __syncthreads();
+    // normal copy: word (ol, rs, g) holds channels c0 + 16g .. +15 of tap rs
+    const int groups = CT / 16;
+    for (int wi = tid; wi < kTileRows * RS * groups; wi += kTernThreads) {
+        const int g = wi % groups, t1 = wi / groups;
+        const int rs = t1 % RS, ol = t1 / RS;
+        const unsigned char* src = codes + ol * seg + (16 * g) * RS + rs;
+        uint32_t word = 0;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) word |= static_cast<uint32_t>(src[t * RS]) << ((t & 1) * 16 + (t >> 1) * 2);
+        packed[static_cast<int64_t>(o0 + ol) * wpr + (rs * C + c0) / 16 + g] = word;
+    }
+    if (c0 == 0) {
+        const int kw = RS * C / 16, pad = wpr - kw;
+        for (int wi = tid; wi < kTileRows * pad; wi += kTernThreads)
+            packed[static_cast<int64_t>(o0 + wi / pad) * wpr + kw + wi % pad] = 0u;
+    }
+    if (packed_T) {
+        // transposed copy: word (cl, rs) holds filters o0 .. o0+15
+        for (int wi = tid; wi < CT * RS; wi += kTernThreads) {
+            const int rs = wi % RS, cl = wi / RS;
+            const unsigned char* src = codes + cl * RS + rs;
+            uint32_t word = 0;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) word |= static_cast<uint32_t>(src[t * seg]) << ((t & 1) * 16 + (t >> 1) * 2);
+            packed_T[static_cast<int64_t>(c0 + cl) * wprT + (rs * rows + o0) / 16] = word;
+        }
+        if (o0 == 0) {
+            const int kw = RS * rows / 16, pad = wprT - kw;
+            for (int wi = tid; wi < CT * pad; wi += kTernThreads)
+                packed_T[static_cast<int64_t>(c0 + wi / pad) * wprT + kw + wi % pad] = 0u;
+        }
+    }
+    const double total = block_sum(acc, scratch);
+    const unsigned long long ctotal = block_sum(static_cast<unsigned long long>(count), scratch_u);
+    if (tid == 0) {
+        ws->p2[bid] = total;
+        ws->cnt[bid] = ctotal;
+    }
+}
+
+__global__ __launch_bounds__(kTernThreads) void mask_pack_tile_kernel(
+    const float* __restrict__ W, int rows, int C, int RS, TernWorkspace* __restrict__ ws, int nb1, float f,
+    uint32_t* __restrict__ packed, int wpr, uint32_t* __restrict__ packed_T, int wprT) {
+    mask_pack_tile_body(W, rows, C, RS, ws, nb1, f, packed, wpr, packed_T, wprT, blockIdx.x);
 }
 
 // ---- several tensors per launch --------------------------------------------------------------
@@ -314,6 +415,8 @@ struct BatchItem {
     uint64_t* nnz;
     int32_t rows, C, RS, wpr, wprT;
     int32_t nb1, nb2;           // blocks of pass 1 / pass 2 working on this tensor
+    int32_t tiled;              // pass 2 through the LDS-staged tile body
+    int32_t flat_blocks;        // > 0: flat layout, the first flat_blocks pass-2 blocks stream W, the rest gather the transposed copy
     int32_t first1, first2;     // index of its first block in the pass-1 / pass-2 launch
 };
 struct BatchTable {
@@ -337,8 +440,20 @@ __global__ __launch_bounds__(kTernThreads) void batch_abs_sum_kernel(const Batch
 __global__ __launch_bounds__(kTernThreads) void batch_mask_pack_kernel(const BatchTable tb, TernWorkspace* __restrict__ ws) {
     const int i = batch_find(tb, blockIdx.x, true);
     const BatchItem& it = tb.item[i];
-    mask_pack_gather_body(it.W, it.rows, it.C, it.RS, ws + i, it.nb1, tb.f, it.packed, it.wpr, it.packed_T, it.wprT,
-                          blockIdx.x - it.first2, it.nb2);
+    if (it.flat_blocks > 0) {
+        const int local = blockIdx.x - it.first2;
+        const int64_t n = static_cast<int64_t>(it.rows) * it.C;
+        if (local < it.flat_blocks)
+            mask_pack_flat_body(it.W, n, ws + i, it.nb1, tb.f, it.packed, 1, local, it.flat_blocks);
+        else
+            mask_pack_gather_body(it.W, it.rows, it.C, it.RS, ws + i, it.nb1, tb.f, it.packed, it.wpr, it.packed_T, it.wprT,
+                                  local - it.flat_blocks, it.nb2 - it.flat_blocks, true, it.flat_blocks);
+    } else if (it.tiled)
+        mask_pack_tile_body(it.W, it.rows, it.C, it.RS, ws + i, it.nb1, tb.f, it.packed, it.wpr, it.packed_T, it.wprT,
+                            blockIdx.x - it.first2);
+    else
+        mask_pack_gather_body(it.W, it.rows, it.C, it.RS, ws + i, it.nb1, tb.f, it.packed, it.wpr, it.packed_T, it.wprT,
+                              blockIdx.x - it.first2, it.nb2);
 }
 
 __global__ __launch_bounds__(kTernThreads) void batch_finalize_kernel(const BatchTable tb, const TernWorkspace* __restrict__ ws) {
@@ -483,6 +598,11 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
                                   (packed_T ? static_cast<int64_t>(wd->C) * wprT : 0);
             int64_t nb2 = (words + kTernThreads - 1) / kTernThreads;
             if (nb2 > kMaxBlocks) nb2 = kMaxBlocks;
+            if (tile_ok(wd->rows, wd->C, static_cast<int>(RS))) {
+                nb2 = static_cast<int64_t>(wd->rows / kTileRows) * (wd->C / tile_ct(wd->C));
+                mask_pack_tile_kernel<<<static_cast<unsigned>(nb2), kTernThreads, 0, st>>>(
+                    W, wd->rows, wd->C, static_cast<int>(RS), ws, nb, delta_factor, packed, wpr, packed_T, wprT);
+            } else
             mask_pack_gather_kernel<<<static_cast<unsigned>(nb2), kTernThreads, 0, st>>>(
                 W, wd->rows, wd->C, static_cast<int>(RS), ws, nb, delta_factor, packed, wpr, packed_T, wprT);
             finalize_kernel<<<1, kTernThreads, 0, st>>>(ws, nb, static_cast<int>(nb2), delta_factor, n, delta, alpha,
@@ -551,6 +671,17 @@ extern "C" int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t 
         if (nb2 > 4 * share) nb2 = 4 * share;
         if (nb2 > kMaxBlocks) nb2 = kMaxBlocks;
         if (it.nb1 > kMaxBlocks) it.nb1 = kMaxBlocks;
+        it.tiled = tile_ok(wd.rows, wd.C, static_cast<int>(RS)) ? 1 : 0;
+        if (it.tiled) nb2 = static_cast<int64_t>(wd.rows / kTileRows) * (wd.C / tile_ct(wd.C));
+        it.flat_blocks = 0;
+        if (RS == 1 && K % 128 == 0) {
+            // flat layout: the normal copy is written while W streams by; only the transposed copy gathers
+            it.flat_blocks = it.nb1;
+            int64_t nbT = in.packed_T ? (static_cast<int64_t>(wd.C) * it.wprT + kTernThreads - 1) / kTernThreads : 0;
+            if (nbT > 4 * share) nbT = 4 * share;
+            if (nbT > kMaxBlocks - it.flat_blocks) nbT = kMaxBlocks - it.flat_blocks;
+            nb2 = it.flat_blocks + nbT;
+        }
         it.nb2 = static_cast<int32_t>(nb2);
         it.first1 = first1;
         it.first2 = first2;

@@ -44,6 +44,7 @@ def check_against_oracle(w, f, groups=1, transposed=True):
     (64, 256), (33, 1152), (1000, 128 * 33),       # flat layouts (fused pack), ragged over blocks
     (17, 24), (10, 1024), (1, 1),                  # K not a multiple of 128
     (5, 3, 3, 3), (64, 32, 5, 5), (128, 128, 3, 3), (64, 3, 7, 7), (32, 1, 5, 5),
+    (32, 48, 3, 3), (16, 16, 7, 7), (48, 80, 1, 3), (256, 192, 3, 3),   # LDS-staged tiles: channel tiles of 16/64, and too many taps
 ])
 def test_per_layer(shape, f):
     w = wl.normal(7, len(shape) * 1000 + shape[0] + shape[1], shape, std=0.05)
