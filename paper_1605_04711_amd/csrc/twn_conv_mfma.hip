@@ -426,6 +426,7 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
 
     // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.
     int tile = env_int("TWN_TILE", 0);
+    if (mode != kModeScalar && tile == 0 && conv_halo_applicable(g)) return launch_conv_halo(g, st);
     if (mode != kModeScalar && (tile == 0 || tile > 10)) {
         // multi-stage direct-to-LDS kernel
         if (tile == 0) {

@@ -57,6 +57,11 @@ int32_t launch_repack_c4(const uint32_t* packed, int rows, int C, int R, int S, 
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 
+// Halo-tiled kernel for stride-1 filters with several taps (activations staged once per 64-channel slab and
+// reused by every tap); `applicable` is a pure function of the problem.
+bool conv_halo_applicable(const GatherGemm& g);
+int32_t launch_conv_halo(const GatherGemm& g, hipStream_t st);
+
 // dW[o][c][r][s] = beta*dW + sum_{n,p,q} X[n,ih,iw,c] * dY[n,p,q,o]; dbias[o] = sum dY.
 struct WeightGrad {
     const uint16_t* X;      // bf16 NHWC [N][H][W][C]

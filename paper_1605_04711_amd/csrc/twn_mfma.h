@@ -1,0 +1,45 @@
+// Device helpers shared by the MFMA contraction kernels (gfx950).
+#pragma once
+
+#include "twn_common.h"
+
+namespace twn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Exact unsigned division of numerators below 2^31 by a runtime constant.
+struct FastDivU {
+    uint32_t mul, shift, one;   // one = all ones when d == 1 (then mul = 0 and the quotient is n itself)
+};
+
+static inline FastDivU make_fastdiv_u(uint32_t d) {
+    FastDivU f{0, 0, 0xFFFFFFFFu};
+    if (d <= 1) return f;
+    f.one = 0;
+    uint32_t l = 0;
+    while ((1u << l) < d) ++l;
+    const uint32_t s = 31 + l;
+    f.mul = static_cast<uint32_t>(((1ULL << s) + d - 1) / d);
+    f.shift = s - 32;
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fdiv_u(uint32_t n, const FastDivU& f) {
+    return (__umulhi(n, f.mul) >> f.shift) | (n & f.one);
+}
+
+// s_waitcnt immediate that waits only for vmcnt <= n (gfx9 encoding).
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+// One direct global -> LDS load of 16 bytes per lane: lane j of the wave writes LDS at lds_dst + 16*j
+// (lds_dst is wave-uniform); counted by vmcnt.
+__device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
+}
+
+}  // namespace twn

@@ -74,6 +74,40 @@ def test_every_direct_to_lds_tile_shape(tile, monkeypatch):
     assert rel_err(to_host_f64(y), oc.conv2d_fwd(x, codes, alpha, st, pd, dl)) <= 1e-4
 
 
+HALO_CASES = [
+    # N  H   W   C    O    R  S  pad     dil      (stride 1: the halo-tiled kernel's domain)
+    (3, 17, 17, 64, 128, 3, 3, (1, 1), (1, 1)),
+    (5, 8, 8, 128, 72, 3, 3, (1, 1), (1, 1)),
+    (2, 20, 33, 64, 64, 3, 3, (0, 2), (1, 1)),
+    (1, 19, 19, 64, 48, 3, 3, (2, 2), (2, 2)),
+    (2, 12, 12, 192, 136, 5, 5, (2, 2), (1, 1)),
+    (3, 9, 30, 64, 256, 1, 3, (0, 1), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(HALO_CASES)))
+def test_halo_tiled_kernel_forward_and_backward_data(ci, monkeypatch):
+    monkeypatch.setenv("TWN_HALO", "1")
+    n, h, w_, c, o, r, s, pd, dl = HALO_CASES[ci]
+    st = (1, 1)
+    x, w, tw, codes, alpha = make_layer(600 + ci, (n, h, w_, c), (o, c, r, s), transposed=True)
+    g = np.random.default_rng(ci)
+    scale = g.uniform(0.5, 1.5, o).astype(np.float32)
+    shift = g.standard_normal(o).astype(np.float32)
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, y_dtype=torch.float32)
+    ref = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    assert rel_err(to_host_f64(y), ref) <= 1e-4
+    res = wl.bf16_round(g.standard_normal(ref.shape).astype(np.float32))
+    yb = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, scale=to_dev_f32(scale), shift=to_dev_f32(shift),
+                            residual=to_dev_bf16(res), relu=True)
+    assert rel_err(to_host_f64(yb), oc.epilogue(ref, scale, shift, res, relu=True)) <= BF16_TOL
+    if o % 64 == 0:
+        dy = wl.bf16_round(g.standard_normal(ref.shape).astype(np.float32))
+        dx, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dx=True, need_dw=False,
+                                          x_shape=(n, h, w_, c), dx_dtype=torch.float32)
+        assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, (n, h, w_, c), st, pd, dl)) <= 1e-4
+
+
 def test_gemm_epilogue_groups_and_strides():
     m, n, k = 200, 96, 256
     x, w, tw, codes, alpha = make_layer(11, (m, k), (n, k), groups=n)
