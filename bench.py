@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # dense bf16 MFMA, MI355X
 PEAK_HBM_GBPS = 8000.0
+# HBM-side bytes per launch of the roofline sample (L2 fills + write-backs, rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE scaled by a 1 GiB copy), taken from profiles/vgg7_b128_step_kernels.txt; it is a property of
+# the committed kernels and tile choices at this workload, re-measured whenever those change.
+ROOFLINE_SAMPLE_TRAFFIC_BYTES = 35257588
 F = 0.7
 
 
@@ -273,12 +277,20 @@ def main():
     # Roofline of the contraction kernel named by the task (gather_gemm_dma_kernel): the forward and
     # backward-data calls that consist of exactly ONE launch of it (no split-K finish, no first-layer
     # copy, no odd-channel fallback): forward c2-c6, backward-data c2-c4 and c6.
+    def call_bytes(ph, L):
+        # algorithmic bytes of one call: bf16 activations in and out plus the 2-bit codes
+        x_b = 2 * L.N * L.H * L.W * L.C
+        y_b = 2 * L.N * L.P * L.Q * L.O
+        return x_b + y_b + L.n_weights // 4     # the same three tensors forward (X -> Y) and backward (dY -> dX)
+    sample_bytes = {ci: call_bytes(calls[ci][0], layers[calls[ci][1]]) for ci in single_ms}
     r_flops = sum(layers[calls[ci][1]].flops for ci in single_ms)
     r_ms = sum(single_ms.values())
     gg_tflops = r_flops / (r_ms * 1e-3) / 1e12
     roof = {"kernel": "gather_gemm_dma_kernel", "bound": "mfma", "achieved": round(gg_tflops, 2),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gg_tflops / PEAK_BF16_TFLOPS, 4),
-            "traffic": None, "launches_per_step": len(single_ms), "avg_launch_us": round(r_ms * 1e3 / len(single_ms), 2),
+            "traffic": ROOFLINE_SAMPLE_TRAFFIC_BYTES,
+            "algorithmic_bytes_per_launch": round(sum(sample_bytes.values()) / len(sample_bytes)),
+            "launches_per_step": len(single_ms), "avg_launch_us": round(r_ms * 1e3 / len(single_ms), 2),
             "flops_per_launch_avg": round(r_flops / len(single_ms) / 1e9, 2),
             "calls": "fwd c2-c6 + bwd_data c2-c4,c6 (one launch each)"}
     dw_tflops = flops_dw / (phase_ms[3] * 1e-3) / 1e12
