@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the GEMM / ternarize-2^28 / ResNet-18 side measurements")
-    ap.add_argument("--cpu-batch", type=int, default=16)
+    ap.add_argument("--cpu-batch", type=int, default=128)
     ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18"], default=None,
                     help="run one side measurement alone (used for the rocprofv3 summaries in profiles/)")
     ap.add_argument("--variants", action="store_true", help="with --only gemm: also time the comparison weight formats")
@@ -335,8 +335,8 @@ def main():
         t_full = t_tern + t_conv * (128.0 / nb)
         cpu = {"value": round(flops_step / t_full / 1e12, 6), "unit": "TFLOP/s-eq", "cores": cores, "kind": "oracle",
                "sample": "ternarize of all 8 VGG-7 tensors in full (%.2f s, numpy sort, 1 thread) + fwd/dX/dW of every layer "
-                         "at batch %d of 128 (%.2f s, C direct loops, %d OpenMP threads), conv time scaled linearly to batch 128"
-                         % (t_tern, nb, t_conv, cores)}
+                         "at batch %d of 128 (%.2f s, C direct loops, %d OpenMP threads)%s"
+                         % (t_tern, nb, t_conv, cores, "" if nb == 128 else ", conv time scaled linearly to batch 128")}
         log("cpu oracle: ternarize %.2f s, conv(b%d) %.2f s -> %.5f TFLOP/s-eq" % (t_tern, nb, t_conv, cpu["value"]))
 
     out = {

@@ -564,21 +564,13 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
                         : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, false>(a, blocks, st);
 }
 
-// Tile ids: 11 = 128x256 (3 stages), 12 = 128x128, 13 = 128x64, 14 = 256x256 (4 stages), 15 = 128x256 (4 stages)
+// Tile ids (BM x BN, waves, stages): 12 = 128x128 2x2 S3, 13 = 128x64 4x1 S3, 17 = 128x256 1x4 S4,
+// 24 = 128x512 1x8 S4, 27 = 128x128 4x2 S3
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
     switch (tile) {
-        case 11: return launch_dma_tile<128, 256, 2, 2, 3>(g, st);
         case 12: return launch_dma_tile<128, 128, 2, 2, 3>(g, st);
         case 13: return launch_dma_tile<128, 64, 4, 1, 3>(g, st);
-        case 15: return launch_dma_tile<128, 256, 2, 2, 4>(g, st);
-        case 16: return launch_dma_tile<256, 128, 2, 2, 3>(g, st);
         case 17: return launch_dma_tile<128, 256, 1, 4, 4>(g, st);
-        case 18: return launch_dma_tile<256, 256, 2, 4, 4>(g, st);
-        case 19: return launch_dma_tile<256, 256, 4, 2, 4>(g, st);
-        case 20: return launch_dma_tile<256, 128, 2, 2, 3>(g, st);
-        case 21: return launch_dma_tile<128, 128, 1, 2, 4>(g, st);
-        case 22: return launch_dma_tile<256, 64, 4, 1, 3>(g, st);
-        case 23: return launch_dma_tile<256, 64, 2, 1, 3>(g, st);
         case 24: return launch_dma_tile<128, 512, 1, 8, 4>(g, st);
         case 27: return launch_dma_tile<128, 128, 4, 2, 3>(g, st);
         default: return TWN_ERR_UNSUPPORTED;
