@@ -5,7 +5,7 @@ A step is one pass of the whole hot path over one batch of the VGG-7 / CIFAR
 workload (batch 128, bf16 activations): ternarize all 8 weight tensors
 (Delta, alpha, 2-bit codes and the transposed copy), forward every conv / FC
 layer with the fused scale-shift-ReLU tail, then the straight-through backward
-(dX and dW) of every layer.  Inputs are seeded synthetic tensors already
+of every layer (dX and dW on two streams, they are independent of each other).  Inputs are seeded synthetic tensors already
 resident in HBM.  Prints ONE JSON line on stdout; per-layer detail goes to stderr.
 """
 
@@ -24,7 +24,7 @@ PEAK_HBM_GBPS = 8000.0
 # HBM-side bytes per launch of the roofline sample (L2 fills + write-backs, rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 1 GiB copy), taken from profiles/vgg7_b128_step_kernels.txt; it is a property of
 # the committed kernels and tile choices at this workload, re-measured whenever those change.
-ROOFLINE_SAMPLE_TRAFFIC_BYTES = 35257588
+ROOFLINE_SAMPLE_TRAFFIC_BYTES = 33279280
 F = 0.7
 
 
@@ -152,7 +152,7 @@ def main():
     # ---------------- workload: VGG-7, batch 128 ----------------
     CFG = 1
     layers = wl.vgg7(128)
-    W, X, dY, Y, dX, dW, tws, wsb, scale, shift = [], [], [], [], [], [], [], [], [], []
+    W, X, dY, Y, dX, dW, tws, wsb, wsw, scale, shift = [], [], [], [], [], [], [], [], [], [], []
     tern_ws = None
     for li, L in enumerate(layers):
         w = wl.kaiming_weights(CFG, li, L)
@@ -165,9 +165,10 @@ def main():
         scale.append(torch.ones(L.O, dtype=torch.float32, device=dev))
         shift.append(torch.zeros(L.O, dtype=torch.float32, device=dev))
         tws.append(api.twn_ternarize(W[li], F, transposed=True))
-        wsb.append(torch.empty(max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, tws[li], (L.stride,) * 2,
-                                                                              (L.pad,) * 2, (L.dil,) * 2)),
-                               dtype=torch.uint8, device=dev))
+        nws = max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, tws[li], (L.stride,) * 2, (L.pad,) * 2,
+                                                             (L.dil,) * 2))
+        wsb.append(torch.empty(nws, dtype=torch.uint8, device=dev))      # backward-data (split-K partials)
+        wsw.append(torch.empty(nws, dtype=torch.uint8, device=dev))      # backward-weight (split partials)
     tern_ws = torch.empty(api.lib().twn_ternarize_batch_workspace_bytes(len(layers)), dtype=torch.uint8, device=dev)
     geo = [((L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2) for L in layers]
     wsf = [torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tws[li], *geo[li])), dtype=torch.uint8,
@@ -179,80 +180,106 @@ def main():
     flops_step = flops_fwd + flops_dx + flops_dw
     tern_bytes = sum(L.n_weights for L in layers) * 8.5      # two reads + two 2-bit copies
 
-    # every library call of one step, in order: (phase, layer index, callable)
-    # The eight weight tensors are ternarized by ONE multi-tensor call (three launches in all); the
-    # one-tensor entry point is timed per layer in the detail pass below.
-    calls = [("ternarize", 0, lambda: api.twn_ternarize_batch(W, F, transposed=True, out=tws, workspace=tern_ws))]
+    # One step.  Main stream: ONE multi-tensor ternarize call (three launches for the eight tensors), then the
+    # forward of every layer.  Backward: the data gradients and the weight gradients of a layer do not depend
+    # on each other, so they run on two streams forked from the main stream after the forward and joined at
+    # the end (the tail of one kernel is filled by the other stream's work).  `calls` lists every library
+    # call as (phase, layer index, callable(stream)); the one-tensor ternarize entry point is timed per
+    # layer in the detail pass below.
+    calls = [("ternarize", 0, lambda st_=None: api.twn_ternarize_batch(W, F, transposed=True, out=tws, workspace=tern_ws))]
     tern_single = [lambda li=li: api.twn_ternarize(W[li], F, transposed=True, out=tws[li], workspace=tern_ws)
                    for li in range(len(layers))]
     for li in range(len(layers)):
         st, pd, dl = geo[li]
-        calls.append(("fwd", li, lambda li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_fwd(
+        calls.append(("fwd", li, lambda st_=None, li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_fwd(
             X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li], relu=True, out=Y[li], workspace=wsf[li])))
+    n_main = len(calls)
     for li in range(len(layers) - 1, 0, -1):
         st, pd, dl = geo[li]
-        calls.append(("bwd_data", li, lambda li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
+        calls.append(("bwd_data", li, lambda st_=None, li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
             None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False, dX=dX[li], x_shape=layers[li].x_shape,
-            workspace=wsb[li])))
+            workspace=wsb[li], stream=st_)))
     for li in range(len(layers) - 1, -1, -1):
         st, pd, dl = geo[li]
-        calls.append(("bwd_weight", li, lambda li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
-            X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True, dW=dW[li], workspace=wsb[li])))
+        calls.append(("bwd_weight", li, lambda st_=None, li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
+            X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True, dW=dW[li], workspace=wsw[li], stream=st_)))
+    dx_calls = [c for c in calls if c[0] == "bwd_data"]
+    dw_calls = [c for c in calls if c[0] == "bwd_weight"]
+    side_a, side_b = torch.cuda.Stream(), torch.cuda.Stream()     # default priority
+
+    def backward():
+        cur = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(cur)
+        side_a.wait_event(fork)
+        side_b.wait_event(fork)
+        # interleave the launches layer by layer so neither stream runs ahead of the host
+        for i in range(len(dw_calls)):
+            if i < len(dx_calls):
+                dx_calls[i][2](side_a)
+            dw_calls[i][2](side_b)
+        ja, jb = torch.cuda.Event(), torch.cuda.Event()
+        ja.record(side_a)
+        jb.record(side_b)
+        cur.wait_event(ja)
+        cur.wait_event(jb)
+
+    def one_step(marks=None):
+        for ci in range(n_main):
+            if marks is not None and ci in marks:
+                marks[ci].record()
+            calls[ci][2]()
+        if marks is not None and n_main in marks:
+            marks[n_main].record()
+        backward()
 
     for _ in range(args.warmup):
-        for _, _, fn in calls:
-            fn()
+        one_step()
     torch.cuda.synchronize()
 
-    # Timed region.  HIP events on the launch stream (torch's current stream) bracket each call that is
-    # exactly one launch of the contraction kernel (the roofline sample); phases and the per-layer table
-    # are taken in separate passes afterwards.
+    # Timed region.  HIP events on the launch stream (torch's current stream) bracket each forward call that is
+    # exactly one launch of the contraction kernel (the roofline sample: forward c2-c6, which run alone on
+    # the GPU); phases and the per-layer table are taken in separate passes afterwards.
     name_of = [L.name for L in layers]
-    single = {("fwd", n) for n in ("c2", "c3", "c4", "c5", "c6")} | {("bwd_data", n) for n in ("c2", "c3", "c4", "c6")}
-    phase_names = ["ternarize", "fwd", "bwd_data", "bwd_weight"]
+    single = {("fwd", n) for n in ("c2", "c3", "c4", "c5", "c6")}
     is_single = [(c[0], name_of[c[1]]) in single for c in calls]
-    first_of = {ph: min(ci for ci, c in enumerate(calls) if c[0] == ph) for ph in phase_names}
-    last_of = {ph: max(ci for ci, c in enumerate(calls) if c[0] == ph) for ph in phase_names}
 
     def new_ev():
         return torch.cuda.Event(enable_timing=True)
 
     # An event between two launches costs a few microseconds of idle GPU, so the timed region records as few
-    # as possible: one event at every boundary of a run of consecutive single-launch calls (the end of one
-    # call is the start of the next), i.e. run_len + 1 events per run.  Phase times come from a separate,
-    # untimed pass below.
-    marks = [ci for ci in range(len(calls) + 1)
-             if (ci < len(calls) and is_single[ci]) or (ci > 0 and is_single[ci - 1])]
+    # as possible: one event at every boundary of the run of consecutive single-launch calls (the end of one
+    # call is the start of the next).
+    marks = [ci for ci in range(n_main + 1)
+             if (ci < n_main and is_single[ci]) or (ci > 0 and is_single[ci - 1])]
     mev = [{ci: new_ev() for ci in marks} for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        for ci, (ph, _, fn) in enumerate(calls):
-            if ci in mev[s]:
-                mev[s][ci].record()
-            fn()
-        if len(calls) in mev[s]:
-            mev[s][len(calls)].record()
+        one_step(mev[s])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     single_ms = {ci: sum(mev[s][ci].elapsed_time(mev[s][ci + 1]) for s in range(args.steps)) / args.steps
-                 for ci in range(len(calls)) if is_single[ci]}
+                 for ci in range(n_main) if is_single[ci]}
 
-    # phase times: a second pass with one event pair per phase
+    # phase times: a second pass with one event pair per phase (the two backward streams form one phase)
+    phase_names = ["ternarize", "fwd", "bwd_two_streams"]
     NPH = max(5, min(50, args.steps))
-    pev = [{ph: (new_ev(), new_ev()) for ph in phase_names} for _ in range(NPH)]
+    pev = [[new_ev() for _ in range(4)] for _ in range(NPH)]
     for s in range(NPH):
-        for ci, (ph, _, fn) in enumerate(calls):
-            if ci == first_of[ph]:
-                pev[s][ph][0].record()
-            fn()
-            if ci == last_of[ph]:
-                pev[s][ph][1].record()
+        pev[s][0].record()
+        calls[0][2]()
+        pev[s][1].record()
+        for ci in range(1, n_main):
+            calls[ci][2]()
+        pev[s][2].record()
+        backward()
+        pev[s][3].record()
     torch.cuda.synchronize()
-    phase_ms = [sum(pev[s][ph][0].elapsed_time(pev[s][ph][1]) for s in range(NPH)) / NPH for ph in phase_names]
+    phase_ms = [sum(pev[s][i].elapsed_time(pev[s][i + 1]) for s in range(NPH)) / NPH for i in range(3)]
     value = flops_step / (ms_per_step * 1e-3) / 1e12
-    log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phase_names[i], phase_ms[i]) for i in range(4)))
+    log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phase_names[i], phase_ms[i]) for i in range(3)))
 
     # per-layer detail: a second, untimed pass with events around every call
     NP = 20
@@ -274,9 +301,9 @@ def main():
                                                              tf * 1e3, L.flops / tf / 1e9, L.flops / tdx / 1e9,
                                                              tdw * 1e3, L.flops / tdw / 1e9))
 
-    # Roofline of the contraction kernel named by the task (gather_gemm_dma_kernel): the forward and
-    # backward-data calls that consist of exactly ONE launch of it (no split-K finish, no first-layer
-    # copy, no odd-channel fallback): forward c2-c6, backward-data c2-c4 and c6.
+    # Roofline of the contraction kernel named by the task (gather_gemm_dma_kernel): the forward calls that
+    # consist of exactly ONE launch of it (no split-K finish, no first-layer copy, no odd-channel fallback)
+    # and run alone on the GPU: forward c2-c6.
     def call_bytes(ph, L):
         # algorithmic bytes of one call: bf16 activations in and out plus the 2-bit codes
         x_b = 2 * L.N * L.H * L.W * L.C
@@ -292,13 +319,14 @@ def main():
             "algorithmic_bytes_per_launch": round(sum(sample_bytes.values()) / len(sample_bytes)),
             "launches_per_step": len(single_ms), "avg_launch_us": round(r_ms * 1e3 / len(single_ms), 2),
             "flops_per_launch_avg": round(r_flops / len(single_ms) / 1e9, 2),
-            "calls": "fwd c2-c6 + bwd_data c2-c4,c6 (one launch each)"}
-    dw_tflops = flops_dw / (phase_ms[3] * 1e-3) / 1e12
-
-    extras = {"phase_ms": {phase_names[i]: round(phase_ms[i], 4) for i in range(4)},
+            "calls": "fwd c2-c6 (one launch each)"}
+    # serial per-layer times of the detail pass give the per-phase rates of the two backward parts
+    dx_ms = sum(per[("bwd_data", li)] for li in range(1, len(layers)))
+    dw_ms = sum(per[("bwd_weight", li)] for li in range(len(layers)))
+    extras = {"phase_ms": {phase_names[i]: round(phase_ms[i], 4) for i in range(3)},
               "fwd_tflops": round(flops_fwd / (phase_ms[1] * 1e-3) / 1e12, 2),
-              "bwd_data_tflops": round(flops_dx / (phase_ms[2] * 1e-3) / 1e12, 2),
-              "bwd_weight_tflops": round(dw_tflops, 2),
+              "bwd_tflops": round((flops_dx + flops_dw) / (phase_ms[2] * 1e-3) / 1e12, 2),
+              "bwd_data_serial_ms": round(dx_ms, 4), "bwd_weight_serial_ms": round(dw_ms, 4),
               "ternarize_layers_GBps": round(tern_bytes / (phase_ms[0] * 1e-3) / 1e9, 1)}
 
     if not args.no_extras:
