@@ -7,8 +7,10 @@
 // 2^ltx columns = BM pixels) and, per slab of 64 input channels, stages the patch plus its halo ONCE:
 // every tap then reads its shifted window of the same LDS data (a lane's A-fragment address is just the
 // halo pixel of its row plus a wave-uniform tap offset).  Global -> LDS traffic per 64 channels drops from
-// R*S*BM pixel rows to (rows+R-1)*(cols+S-1), about 6x for 3x3 filters; the 2-bit codes of all taps of the
-// slab (R*S*BN*16 bytes) travel as before.
+// R*S*BM pixel rows to (rows+R-1)*(cols+S-1), about 6x for 3x3 filters.  The 2-bit codes do not pass through
+// LDS at all: each lane loads the 32 codes of its output channel and tap (8 bytes, L2-resident) straight
+// into registers one tap ahead, which keeps the LDS footprint at two halo stages (about 49 KB for a 128-pixel
+// patch) so that three workgroups share a CU.
 //
 // Pipeline: two stages; the slab after the current one is in flight while all R*S*4 MFMA steps of the
 // current one run, so a single s_waitcnt vmcnt(0) + s_barrier per slab hands over.  LDS rows are 128 bytes
@@ -39,10 +41,11 @@ struct HaloArgs {
     FastDivU divHW, divHH, divTN, divTX, divTY;
 };
 
-template <int BM, int BN>
-__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv_halo_kernel(const HaloArgs a) {
-    constexpr int WM = BM / 64, WN = BN / 64, NW = WM * WN;
-    constexpr int MI = 2, NI = 2;
+template <int BM, int BN, int MI>
+__global__ __launch_bounds__((BM / (32 * MI)) * (BN / 64) * 64) void conv_halo_kernel(const HaloArgs a) {
+    constexpr int WM = BM / (32 * MI), WN = BN / 64, NW = WM * WN;
+    constexpr int TM = 32 * MI;         // pixels per wave
+    constexpr int NI = 2;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const GatherGemm& g = a.g;
@@ -52,8 +55,7 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv_halo_kernel(c
     const int wm = wave / WN, wn = wave % WN;
     const int lrow = lane & 31, lh = lane >> 5;
     const int RS = g.R * g.S;
-    const int a_bytes = a.nla * NW * 1024;
-    const int stage_bytes = a_bytes + RS * BN * 16;
+    const int stage_bytes = a.nla * NW * 1024;
 
     // workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles
     const uint32_t nb = gridDim.x, b = blockIdx.x;
@@ -90,11 +92,9 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv_halo_kernel(c
                         static_cast<unsigned>(ix) < static_cast<unsigned>(g.IW);
         pix[i] = ok ? (img * g.IH + iy) * g.IW + ix : -1;
     }
-    const int brow = n0 + lane;     // + 64 * (channel sub-tile): the output channel whose codes this lane stages
 
     auto issue = [&](int cs, int stage) __attribute__((always_inline)) {
         unsigned char* sA = smem + stage * stage_bytes;
-        unsigned char* sB = sA + a_bytes;
 #pragma unroll
         for (int i = 0; i < kHaloMaxLoads; ++i) {
             if (i < a.nla) {
@@ -106,22 +106,13 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv_halo_kernel(c
                 dma16(src, sA + (i * NW + wave) * 1024);
             }
         }
-        // packed codes of the slab: tap `tap`, 64 output channels per load
-        for (int j = wave; j < RS * WN; j += NW) {
-            const int tap = j / WN, sub = j - tap * WN;
-            const int ncol = brow + sub * 64;
-            const void* src = (ncol < g.NC) ? static_cast<const void*>(Wq + static_cast<int64_t>(ncol) * g.wpr +
-                                                                       ((tap * g.IC + cs * 64) >> 4))
-                                            : zero;
-            dma16(src, sB + (tap * BN + sub * 64) * 16);
-        }
     };
 
     // ---- this lane's rows: halo pixel of output pixel m_local at tap (0,0) with roff = soff = 0 ----
     int hp0[MI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        const int ml = wm * 64 + mi * 32 + lrow;
+        const int ml = wm * TM + mi * 32 + lrow;
         const int xl = ml & ((1 << a.ltx) - 1);
         const int yl = (ml >> a.ltx) & ((1 << a.lty) - 1);
         const int nl = ml >> (a.ltx + a.lty);
@@ -136,8 +127,24 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv_halo_kernel(c
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
 
+    // ---- packed codes: this lane's output channel of tile ni, the 8 bytes (32 codes) of its k half ----
+    const uint32_t* wrow[NI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+        const int ncol = n0 + wn * 64 + ni * 32 + lrow;
+        wrow[ni] = (ncol < g.NC) ? Wq + static_cast<int64_t>(ncol) * g.wpr + 2 * lh : nullptr;
+    }
+    auto load_codes = [&](int cs, int tap, u32x2* dst) __attribute__((always_inline)) {
+        const int word = (tap * g.IC + cs * 64) >> 4;
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+            dst[ni] = wrow[ni] ? *reinterpret_cast<const u32x2*>(wrow[ni] + word) : u32x2{0u, 0u};
+    };
+
     const int ncs = g.IC / 64;
     issue(0, 0);
+    u32x2 bnext[NI];
+    load_codes(0, 0, bnext);
     int stage = 0;
     for (int cs = 0; cs < ncs; ++cs) {
         // slab cs has landed for every wave, and every wave is done with the other stage
@@ -148,14 +155,15 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv_halo_kernel(c
         if (cs + 1 < ncs) issue(cs + 1, stage ^ 1);
 
         const unsigned char* sA = smem + stage * stage_bytes;
-        const unsigned char* sB = sA + a_bytes + (wn * 64 + lrow) * 16 + lh * 8;
         int r = 0, s = 0;
         for (int tap = 0; tap < RS; ++tap) {
             const int toff = (a.roff + r * g.dh) * a.hw + (a.soff + s * g.dw);
             u32x2 breg[NI];
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                breg[ni] = *reinterpret_cast<const u32x2*>(sB + (tap * BN + ni * 32) * 16);
+            for (int ni = 0; ni < NI; ++ni) breg[ni] = bnext[ni];
+            // the codes of the next tap (or of the next slab's first tap) are fetched one tap ahead
+            if (tap + 1 < RS) load_codes(cs, tap + 1, bnext);
+            else if (cs + 1 < ncs) load_codes(cs + 1, 0, bnext);
             const unsigned char* rowp[MI];
             int sw[MI];
 #pragma unroll
@@ -206,11 +214,11 @@ __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64) void conv_halo_kernel(c
     }
 
     // ---- epilogue: y = relu?((0.5*alpha*acc)*scale + shift + residual) ----
-    // accumulator element e of tile (mi, ni): pixel m_local = wm*64 + mi*32 + lrow,
+    // accumulator element e of tile (mi, ni): pixel m_local = wm*TM + mi*32 + lrow,
     // channel n0 + wn*64 + ni*32 + (e>>2)*8 + lh*4 + (e&3)
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        const int ml = wm * 64 + mi * 32 + lrow;
+        const int ml = wm * TM + mi * 32 + lrow;
         const int ox = x0 + (ml & ((1 << a.ltx) - 1));
         const int oy = y0 + ((ml >> a.ltx) & ((1 << a.lty) - 1));
         const int img = img0 + (ml >> (a.ltx + a.lty));
@@ -269,12 +277,11 @@ static int abs_i(int v) { return v < 0 ? -v : v; }
 
 // Patch of BM = 2^k output pixels (powers of two along batch, rows, columns) that wastes the fewest padded
 // pixels and whose halo fits the LDS and load budgets; false if none does.
-template <int BM, int BN>
+template <int BM, int BN, int MI>
 static bool halo_plan(const GatherGemm& g, HaloArgs* a) {
-    constexpr int NW = (BM / 64) * (BN / 64);
+    constexpr int NW = (BM / (32 * MI)) * (BN / 64);
     int lbm = 0;
     while ((1 << lbm) < BM) ++lbm;
-    const int RS = g.R * g.S;
     const int eh = (g.R - 1) * abs_i(g.dh), ew = (g.S - 1) * abs_i(g.dw);
     const int64_t batch = g.M / (static_cast<int64_t>(g.OH) * g.OW);
     int64_t best = -1;
@@ -290,7 +297,7 @@ static bool halo_plan(const GatherGemm& g, HaloArgs* a) {
             const int64_t hp = static_cast<int64_t>(tn) * hh * hw;
             const int64_t nla = (hp + 8 * NW - 1) / (8 * NW);
             if (nla > kHaloMaxLoads) continue;
-            const int64_t stage = nla * NW * 1024 + static_cast<int64_t>(RS) * BN * 16;
+            const int64_t stage = nla * NW * 1024;
             if (2 * stage > kHaloLdsBudget) continue;
             const int64_t tiles = ((g.OW + tx - 1) / tx) * static_cast<int64_t>((g.OH + ty - 1) / ty) * ((batch + tn - 1) / tn);
             // fewest padded pixels first, then the smallest halo
@@ -326,14 +333,14 @@ static int64_t halo_blocks(const HaloArgs& a) {
     return groups * a.tiles_y * a.tiles_x * a.tiles_n;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int MI>
 static int32_t launch_halo(const HaloArgs& a, hipStream_t st) {
-    constexpr int NW = (BM / 64) * (BN / 64);
-    const int smem = 2 * (a.nla * NW * 1024 + a.g.R * a.g.S * BN * 16);
+    constexpr int NW = (BM / (32 * MI)) * (BN / 64);
+    const int smem = 2 * a.nla * NW * 1024;
     const int64_t blocks = halo_blocks(a);
     if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
     static bool allowed = false;
-    auto k = conv_halo_kernel<BM, BN>;
+    auto k = conv_halo_kernel<BM, BN, MI>;
     if (!allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kHaloLdsBudget) != hipSuccess) return TWN_ERR_HIP;
@@ -354,16 +361,18 @@ bool conv_halo_applicable(const GatherGemm& g) {
     if (g.M % (static_cast<int64_t>(g.OH) * g.OW) != 0) return false;
     if (static_cast<int64_t>(g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW >= (1LL << 31)) return false;
     HaloArgs a;
-    return halo_plan<128, 128>(g, &a);
+    return halo_plan<128, 128, 2>(g, &a);
 }
 
 int32_t launch_conv_halo(const GatherGemm& g, hipStream_t st) {
     HaloArgs a;
-    // the larger patch when it still gives every CU a workgroup
-    if (g.NC > 64 && halo_plan<256, 128>(g, &a) && halo_blocks(a) >= 256) return launch_halo<256, 128>(a, st);
-    if (g.NC <= 64 && halo_plan<256, 64>(g, &a) && halo_blocks(a) >= 256) return launch_halo<256, 64>(a, st);
-    if (!halo_plan<128, 128>(g, &a)) return TWN_ERR_UNSUPPORTED;
-    return launch_halo<128, 128>(a, st);
+    if (g.NC <= 64) {
+        // 64 output channels: four waves of 32 pixels each
+        if (!halo_plan<128, 64, 1>(g, &a)) return TWN_ERR_UNSUPPORTED;
+        return launch_halo<128, 64, 1>(a, st);
+    }
+    if (!halo_plan<128, 128, 2>(g, &a)) return TWN_ERR_UNSUPPORTED;
+    return launch_halo<128, 128, 2>(a, st);
 }
 
 }  // namespace twn

@@ -313,6 +313,25 @@ def test_full_size_resnet18_layers_sampled(name):
     assert rel_err(to_host_f64(y).ravel()[idx], ref) <= BF16_TOL
 
 
+@pytest.mark.parametrize("name", ["conv1", "conv5", "conv8", "fc6", "fc7"])
+def test_full_size_detection_backbone_layers_sampled(name):
+    # the 300x300 detection stand-in at batch 32: odd image sizes, the dilated 3x3 (dilation 6) and the 1x1 layer
+    layers = {l.name: (i, l) for i, l in enumerate(wl.vgg16_ssd(32))}
+    li, layer = layers[name]
+    x = wl.bf16_round(wl.normal(4, wl.IDX_INPUT + li, layer.x_shape))
+    w = wl.kaiming_weights(4, li, layer)
+    tw = api.twn_ternarize(to_dev_f32(w), F)
+    codes, delta, alpha, nnz = ot.ternarize(w, F)
+    st, pd, dl = (layer.stride,) * 2, (layer.pad,) * 2, (layer.dil,) * 2
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl)
+    total = int(np.prod(layer.y_shape))
+    n_, p_, q_, o_ = layer.y_shape
+    corners = [((b * p_ + pp) * q_ + qq) * o_ for b in (0, n_ - 1) for pp in (0, p_ - 1) for qq in (0, q_ - 1)]
+    idx = np.concatenate([_sample(total, 20000, li), np.array(corners)])
+    ref = oc.conv2d_fwd_at(x, codes, alpha, idx, st, pd, dl)
+    assert rel_err(to_host_f64(y).ravel()[idx], ref) <= BF16_TOL
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c4", "c6", "fc1"])
 def test_full_size_vgg7_backward_sampled(name):
     layers = {l.name: (i, l) for i, l in enumerate(wl.vgg7(128))}
