@@ -41,11 +41,17 @@ struct HaloArgs {
     FastDivU divHW, divHH, divTN, divTX, divTY;
 };
 
-template <int BM, int BN, int MI>
-__global__ __launch_bounds__((BM / (32 * MI)) * (BN / 64) * 64) void conv_halo_kernel(const HaloArgs a) {
+// CS = input channels per slab (64 or 32).  An LDS row is one halo pixel of CS channels (CS*2 bytes, CP = CS/8
+// chunks of 16 bytes), a wave-level load covers 64/CP pixels, a tap takes KS = CS/16 MFMA steps, and a lane
+// needs CS/2 codes per tap and channel tile (one or two 32-bit words).
+template <int BM, int BN, int MI, int CS>
+__global__ __launch_bounds__((BM / (32 * MI)) * (BN / 64) * 64, (MI == 4) ? 2 : 3) void conv_halo_kernel(const HaloArgs a) {
     constexpr int WM = BM / (32 * MI), WN = BN / 64, NW = WM * WN;
     constexpr int TM = 32 * MI;         // pixels per wave
     constexpr int NI = 2;
+    constexpr int CP = CS / 8, PPL = 64 / CP, KS = CS / 16, ROWB = CS * 2, CW = CS / 32;
+    constexpr int LCP = (CP == 8) ? 3 : 2;            // log2(CP)
+    static_assert(CS == 64 || CS == 32, "slab width");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     const GatherGemm& g = a.g;
@@ -76,11 +82,15 @@ __global__ __launch_bounds__((BM / (32 * MI)) * (BN / 64) * 64) void conv_halo_k
     const uint32_t* __restrict__ Wq = static_cast<const uint32_t*>(g.Wq);
     const void* zero = kHaloZeroBlock;
 
-    // ---- activation loads: wave-level load i of this wave covers halo pixels (i*NW + wave)*8 .. +7 ----
+    // 16-byte chunk c of halo pixel hp sits at chunk position c ^ swz(hp): 16 consecutive pixels then spread
+    // one logical chunk over all 64 banks
+    auto swz = [](int hp) __attribute__((always_inline)) { return (CP == 8) ? ((hp >> 1) & 7) : ((hp >> 2) & 3); };
+
+    // ---- activation loads: wave-level load i of this wave covers halo pixels (i*NW + wave)*PPL .. +PPL-1 ----
     int32_t pix[kHaloMaxLoads];     // input pixel index of this lane's halo pixel, -1 = outside (zero)
 #pragma unroll
     for (int i = 0; i < kHaloMaxLoads; ++i) {
-        const uint32_t hpi = static_cast<uint32_t>((i * NW + wave) * 8 + (lane >> 3));
+        const uint32_t hpi = static_cast<uint32_t>((i * NW + wave) * PPL + (lane >> LCP));
         const uint32_t t1 = fdiv_u(hpi, a.divHW);
         const int hx = static_cast<int>(hpi - t1 * a.hw);
         const uint32_t nl = fdiv_u(t1, a.divHH);
@@ -98,10 +108,11 @@ __global__ __launch_bounds__((BM / (32 * MI)) * (BN / 64) * 64) void conv_halo_k
 #pragma unroll
         for (int i = 0; i < kHaloMaxLoads; ++i) {
             if (i < a.nla) {
-                // physical chunk lane&7 of halo pixel hp holds logical chunk (lane&7) ^ ((hp >> 1) & 7)
-                const int chunk = (lane & 7) ^ ((((i * NW + wave) * 4) + (lane >> 4)) & 7);
+                // this lane fills chunk position lane % CP of its halo pixel: fetch the logical chunk that lives there
+                const int hpi = (i * NW + wave) * PPL + (lane >> LCP);
+                const int chunk = (lane & (CP - 1)) ^ swz(hpi);
                 const void* src = pix[i] >= 0
-                                      ? static_cast<const void*>(X + static_cast<int64_t>(pix[i]) * g.xs + cs * 64 + chunk * 8)
+                                      ? static_cast<const void*>(X + static_cast<int64_t>(pix[i]) * g.xs + cs * CS + chunk * 8)
                                       : zero;
                 dma16(src, sA + (i * NW + wave) * 1024);
             }
@@ -127,21 +138,23 @@ __global__ __launch_bounds__((BM / (32 * MI)) * (BN / 64) * 64) void conv_halo_k
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
 
-    // ---- packed codes: this lane's output channel of tile ni, the 8 bytes (32 codes) of its k half ----
+    // ---- packed codes: this lane's output channel of tile ni, the CS/2 codes (CW words) of its k half ----
     const uint32_t* wrow[NI];
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
         const int ncol = n0 + wn * 64 + ni * 32 + lrow;
-        wrow[ni] = (ncol < g.NC) ? Wq + static_cast<int64_t>(ncol) * g.wpr + 2 * lh : nullptr;
+        wrow[ni] = (ncol < g.NC) ? Wq + static_cast<int64_t>(ncol) * g.wpr + CW * lh : nullptr;
     }
     auto load_codes = [&](int cs, int tap, u32x2* dst) __attribute__((always_inline)) {
-        const int word = (tap * g.IC + cs * 64) >> 4;
+        const int word = (tap * g.IC + cs * CS) >> 4;
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            dst[ni] = wrow[ni] ? *reinterpret_cast<const u32x2*>(wrow[ni] + word) : u32x2{0u, 0u};
+        for (int ni = 0; ni < NI; ++ni) {
+            if (CW == 2) dst[ni] = wrow[ni] ? *reinterpret_cast<const u32x2*>(wrow[ni] + word) : u32x2{0u, 0u};
+            else dst[ni] = u32x2{wrow[ni] ? wrow[ni][word] : 0u, 0u};
+        }
     };
 
-    const int ncs = g.IC / 64;
+    const int ncs = g.IC / CS;
     issue(0, 0);
     u32x2 bnext[NI];
     load_codes(0, 0, bnext);
@@ -169,25 +182,27 @@ __global__ __launch_bounds__((BM / (32 * MI)) * (BN / 64) * 64) void conv_halo_k
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 const int hpm = hp0[mi] + toff;
-                rowp[mi] = sA + hpm * 128;
-                sw[mi] = (hpm >> 1) & 7;
+                rowp[mi] = sA + hpm * ROWB;
+                sw[mi] = swz(hpm);
             }
+            // lane (row, lh) holds at MFMA step kk the 8 channels of logical chunk lh*KS + kk
             u32x4 afrag[2][MI];
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
-                afrag[0][mi] = *reinterpret_cast<const u32x4*>(rowp[mi] + (((lh * 4) ^ sw[mi]) << 4));
+                afrag[0][mi] = *reinterpret_cast<const u32x4*>(rowp[mi] + (((lh * KS) ^ sw[mi]) << 4));
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                if (kk + 1 < 4) {
+            for (int kk = 0; kk < KS; ++kk) {
+                if (kk + 1 < KS) {
 #pragma unroll
                     for (int mi = 0; mi < MI; ++mi)
                         afrag[(kk + 1) & 1][mi] =
-                            *reinterpret_cast<const u32x4*>(rowp[mi] + (((lh * 4 + kk + 1) ^ sw[mi]) << 4));
+                            *reinterpret_cast<const u32x4*>(rowp[mi] + (((lh * KS + kk + 1) ^ sw[mi]) << 4));
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 u32x4 bfrag[NI];
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni) {
+                    // codes of this lane's k half in k order: step kk uses fields 4*kk .. 4*kk+3 of its word(s)
                     const uint32_t word = breg[ni][kk >> 1];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -277,9 +292,11 @@ static int abs_i(int v) { return v < 0 ? -v : v; }
 
 // Patch of BM = 2^k output pixels (powers of two along batch, rows, columns) that wastes the fewest padded
 // pixels and whose halo fits the LDS and load budgets; false if none does.
-template <int BM, int BN, int MI>
+template <int BM, int BN, int MI, int CS>
 static bool halo_plan(const GatherGemm& g, HaloArgs* a) {
     constexpr int NW = (BM / (32 * MI)) * (BN / 64);
+    constexpr int PPL = 64 / (CS / 8);      // halo pixels per wave-level load
+    if (g.IC % CS != 0) return false;
     int lbm = 0;
     while ((1 << lbm) < BM) ++lbm;
     const int eh = (g.R - 1) * abs_i(g.dh), ew = (g.S - 1) * abs_i(g.dw);
@@ -295,7 +312,7 @@ static bool halo_plan(const GatherGemm& g, HaloArgs* a) {
             if ((tn >> 1) >= batch && ltn > 0) continue;
             const int hh = ty + eh, hw = tx + ew;
             const int64_t hp = static_cast<int64_t>(tn) * hh * hw;
-            const int64_t nla = (hp + 8 * NW - 1) / (8 * NW);
+            const int64_t nla = (hp + PPL * NW - 1) / (PPL * NW);
             if (nla > kHaloMaxLoads) continue;
             const int64_t stage = nla * NW * 1024;
             if (2 * stage > kHaloLdsBudget) continue;
@@ -333,14 +350,14 @@ static int64_t halo_blocks(const HaloArgs& a) {
     return groups * a.tiles_y * a.tiles_x * a.tiles_n;
 }
 
-template <int BM, int BN, int MI>
+template <int BM, int BN, int MI, int CS>
 static int32_t launch_halo(const HaloArgs& a, hipStream_t st) {
     constexpr int NW = (BM / (32 * MI)) * (BN / 64);
     const int smem = 2 * a.nla * NW * 1024;
     const int64_t blocks = halo_blocks(a);
     if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
     static bool allowed = false;
-    auto k = conv_halo_kernel<BM, BN, MI>;
+    auto k = conv_halo_kernel<BM, BN, MI, CS>;
     if (!allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 kHaloLdsBudget) != hipSuccess) return TWN_ERR_HIP;
@@ -361,18 +378,22 @@ bool conv_halo_applicable(const GatherGemm& g) {
     if (g.M % (static_cast<int64_t>(g.OH) * g.OW) != 0) return false;
     if (static_cast<int64_t>(g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW >= (1LL << 31)) return false;
     HaloArgs a;
-    return halo_plan<128, 128, 2>(g, &a);
+    return halo_plan<128, 128, 2, 64>(g, &a);
 }
 
 int32_t launch_conv_halo(const GatherGemm& g, hipStream_t st) {
     HaloArgs a;
     if (g.NC <= 64) {
         // 64 output channels: four waves of 32 pixels each
-        if (!halo_plan<128, 64, 1>(g, &a)) return TWN_ERR_UNSUPPORTED;
-        return launch_halo<128, 64, 1>(a, st);
+        if (!halo_plan<128, 64, 1, 64>(g, &a)) return TWN_ERR_UNSUPPORTED;
+        return launch_halo<128, 64, 1, 64>(a, st);
     }
-    if (!halo_plan<128, 128, 2>(g, &a)) return TWN_ERR_UNSUPPORTED;
-    return launch_halo<128, 128, 2>(a, st);
+    // TWN_HALO_SHAPE=1: 256-pixel patches, 128-pixel wave tiles (four MFMAs per expanded code fragment) and
+    // 32-channel slabs (two halo stages stay near 48 KB, two workgroups per CU); measured slower than the
+    // 128-pixel shape on every benchmark layer except the largest grids, where it ties
+    if (env_int("TWN_HALO_SHAPE", 0) == 1 && halo_plan<256, 128, 4, 32>(g, &a)) return launch_halo<256, 128, 4, 32>(a, st);
+    if (!halo_plan<128, 128, 2, 64>(g, &a)) return TWN_ERR_UNSUPPORTED;
+    return launch_halo<128, 128, 2, 64>(a, st);
 }
 
 }  // namespace twn

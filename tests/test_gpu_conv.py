@@ -85,9 +85,11 @@ HALO_CASES = [
 ]
 
 
+@pytest.mark.parametrize("shape", ["0", "1"])
 @pytest.mark.parametrize("ci", range(len(HALO_CASES)))
-def test_halo_tiled_kernel_forward_and_backward_data(ci, monkeypatch):
+def test_halo_tiled_kernel_forward_and_backward_data(ci, shape, monkeypatch):
     monkeypatch.setenv("TWN_HALO", "1")
+    monkeypatch.setenv("TWN_HALO_SHAPE", shape)      # 1: 256-pixel patches with 32-channel slabs
     n, h, w_, c, o, r, s, pd, dl = HALO_CASES[ci]
     st = (1, 1)
     x, w, tw, codes, alpha = make_layer(600 + ci, (n, h, w_, c), (o, c, r, s), transposed=True)
