@@ -311,6 +311,8 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                 issue_load(std::integral_constant<int, gi>{});
             }
         };
+        // while this wave is in its MFMA chain it goes first at issue: the SIMD's other wave fills the gaps
+        __builtin_amdgcn_s_setprio(2);
         static_for<NM>([&](auto j_tag) __attribute__((always_inline)) {
             constexpr int j = decltype(j_tag)::value;
             constexpr int mi = j / NI, ni = j % NI;
@@ -324,6 +326,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             });
             __builtin_amdgcn_sched_barrier(0);
         });
+        __builtin_amdgcn_s_setprio(0);
         // everything read during this step is needed by the next one
         lds_wait<0>();
         lds_ready<MI>(afrag[NSET]);
