@@ -28,6 +28,10 @@ __device__ __attribute__((aligned(16))) const uint32_t kZeroBlock[4] = {0u, 0u, 
 struct DmaArgs {
     GatherGemm g;
     FastDivU divIC, divS;
+    // 1: loads go through buffer descriptors (x_bytes, w_bytes < 2 GiB; plain GEMM with K % 64 == 0, or a
+    // convolution without tap division whose channel count is a multiple of 64, so that a slab is one tap)
+    int32_t use_buf;
+    uint32_t x_bytes, w_bytes;
 };
 
 // LDS reads of the main loop are written as inline assembly with hand-placed s_waitcnt lgkmcnt(n): the
@@ -89,7 +93,7 @@ constexpr int dma_min_blocks(int nw, int smem) {
     return b < 1 ? 1 : b;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK>
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF>
 __global__ __launch_bounds__(64 * WM * WN, dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
 void gather_gemm_dma_kernel(const DmaArgs a) {
     constexpr int NW = WM * WN;                    // waves per workgroup
@@ -164,10 +168,20 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         off0[i] = (abase[i] + static_cast<int64_t>(ih0[i]) * g.IW + iw0[i]) * g.xs;
     }
     const bool undivided = (g.divh == 1 && g.divw == 1);   // everything except strided backward-data
+    // buffer-descriptor path: per-lane byte offsets that stay fixed for the whole K loop
+    constexpr bool use_buf = BUF;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(X, a.x_bytes), rw = make_rsrc(Wq, a.w_bytes);
+    uint32_t voffA[NLOAD];      // GEMM: the row's offset (or kBufOutside); convolution: offset of tap (0,0), any sign
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int64_t bytes = ((GEMM ? abase[i] : off0[i]) + kc * 8) * 2;
+        voffA[i] = (GEMM && ih0[i] != 0) ? kBufOutside : static_cast<uint32_t>(static_cast<int32_t>(bytes));
+    }
     // ---- B load: this wave stages the packed codes of 64 output channels (one lane per channel) ----
     const int brow = (wave * 64) % BN + lane;
     const int bcol = n0 + brow;
     const uint32_t* bsrc = (bcol < g.NC) ? Wq + static_cast<int64_t>(bcol) * g.wpr : nullptr;
+    const uint32_t voffB = (bcol < g.NC) ? static_cast<uint32_t>(bcol) * static_cast<uint32_t>(g.wpr) * 4u : kBufOutside;
 
     // K slabs handled by this workgroup: all of them, or one range of a split-K launch (blockIdx.y)
     const int KT_all = (g.K + 63) / 64;
@@ -193,10 +207,27 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         int kt, k, c, rr, ss, dth, dtw;
         int64_t delta;
         bool kok;
+        int ktc;            // buffer path: slab index clamped to the range (slabs past the end re-read the last one)
+        int32_t delta_b;    // buffer path, convolution: byte offset of this slab's tap and channel base (wave-uniform)
     } si;
     auto issue_setup = [&](int kt, int stage) __attribute__((always_inline)) {
         si.sbase = smem + stage * STAGE_BYTES;
         si.kt = kt;
+        if constexpr (use_buf) {
+            // everything here is wave-uniform: scalar instructions only
+            si.ktc = (kt < KT) ? kt : KT - 1;
+            if (!GEMM) {
+                const uint32_t kb = static_cast<uint32_t>(si.ktc) * 64u;
+                const uint32_t rs = fdiv_u(kb, a.divIC);
+                const int c0 = static_cast<int>(kb - rs * g.IC);
+                const int rr = static_cast<int>(fdiv_u(rs, a.divS));
+                const int ss = static_cast<int>(rs) - rr * g.S;
+                si.dth = rr * g.dh;
+                si.dtw = ss * g.dw;
+                si.delta_b = ((si.dth * g.IW + si.dtw) * static_cast<int>(g.xs) + c0) * 2;
+            }
+            return;
+        }
         si.k = kt * 64 + kc * 8;
         si.kok = (kt < KT) && (si.k < g.K);
         if (!GEMM) {
@@ -212,6 +243,19 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     };
     auto issue_load = [&](auto i_tag) __attribute__((always_inline)) {
         constexpr int i = decltype(i_tag)::value;
+        if constexpr (use_buf) {
+            if constexpr (i == NLOAD) {
+                buf_dma16(rw, voffB, static_cast<uint32_t>(si.ktc) * 16u, si.sbase + A_BYTES + ((wave * 64) % BN) * 16);
+            } else if (GEMM) {
+                buf_dma16(rx, voffA[i], static_cast<uint32_t>(si.ktc) * 128u, si.sbase + (i * NW + wave) * 1024);
+            } else {
+                const bool ok = static_cast<unsigned>(ih0[i] + si.dth) < static_cast<unsigned>(g.IH) &&
+                                static_cast<unsigned>(iw0[i] + si.dtw) < static_cast<unsigned>(g.IW);
+                buf_dma16(rx, ok ? voffA[i] + static_cast<uint32_t>(si.delta_b) : kBufOutside, 0u,
+                          si.sbase + (i * NW + wave) * 1024);
+            }
+            return;
+        }
         if constexpr (i == NLOAD) {
             const void* bs = (bsrc && si.kt < KT) ? static_cast<const void*>(bsrc + si.kt * 4) : zero;
             dma16(bs, si.sbase + A_BYTES + ((wave * 64) % BN) * 16);
@@ -530,13 +574,13 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const GatherGemm g) 
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK>
-static int32_t launch_dma_kernel(const DmaArgs& a, int64_t blocks, hipStream_t st) {
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF>
+static int32_t launch_dma_kernel_b(const DmaArgs& a, int64_t blocks, hipStream_t st) {
     constexpr int SMEM = STAGES * (BM * 128 + BN * 16);
     static_assert(SMEM <= 160 * 1024, "LDS budget");
     // more than 64 KB of dynamic LDS has to be allowed once per kernel
     static bool allowed = false;
-    auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, GEMM, SPLITK>;
+    auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, GEMM, SPLITK, BUF>;
     if (!allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 SMEM) != hipSuccess) return TWN_ERR_HIP;
@@ -544,6 +588,12 @@ static int32_t launch_dma_kernel(const DmaArgs& a, int64_t blocks, hipStream_t s
     }
     k<<<dim3(static_cast<unsigned>(blocks), SPLITK ? a.g.splits : 1), dim3(64 * WM * WN), SMEM, st>>>(a);
     return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK>
+static int32_t launch_dma_kernel(const DmaArgs& a, int64_t blocks, hipStream_t st) {
+    return a.use_buf ? launch_dma_kernel_b<BM, BN, WM, WN, STAGES, GEMM, SPLITK, true>(a, blocks, st)
+                     : launch_dma_kernel_b<BM, BN, WM, WN, STAGES, GEMM, SPLITK, false>(a, blocks, st);
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES>
@@ -554,6 +604,18 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
     a.g = g;
     a.divIC = make_fastdiv_u(static_cast<uint32_t>(g.IC));
     a.divS = make_fastdiv_u(static_cast<uint32_t>(g.S));
+    {
+        // whole-tensor sizes for the buffer descriptors (the last pixel row ends after its IC / K values)
+        const int64_t in_rows = g.plain_gemm ? g.M : (g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW;
+        const int64_t xb = ((in_rows - 1) * g.xs + (g.plain_gemm ? g.K : g.IC)) * 2;
+        const int64_t wb = static_cast<int64_t>(g.NC) * g.wpr * 4;
+        const bool shape_ok = g.plain_gemm ? (g.K % 64 == 0)
+                                           : (g.divh == 1 && g.divw == 1 && g.IC % 64 == 0 && !g.chunk_gather &&
+                                              g.M % (static_cast<int64_t>(g.OH) * g.OW) == 0);
+        a.use_buf = (env_int("TWN_BUFLOAD", 1) != 0 && shape_ok && xb > 0 && xb < (1LL << 31) && wb < (1LL << 31)) ? 1 : 0;
+        a.x_bytes = static_cast<uint32_t>(xb < (1LL << 31) ? xb : 0);
+        a.w_bytes = static_cast<uint32_t>(wb < (1LL << 31) ? wb : 0);
+    }
     if (g.splits > 1) {
         if (!g.partial) return TWN_ERR_WORKSPACE;
         int32_t rc = g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, true>(a, blocks, st)

@@ -42,4 +42,16 @@ __device__ __forceinline__ void dma16(const void* gsrc, void* lds_dst) {
                                      (__attribute__((address_space(3))) void*)lds_dst, 16, 0, 0);
 }
 
+// The same through a raw buffer descriptor: address = base + voffset (per lane) + soffset (wave-uniform, so
+// advancing along K costs no vector instruction); a lane whose voffset is at or beyond the descriptor's
+// size reads zeros, which replaces the select against a zero block for rows and taps outside the tensor.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ void buf_dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset, void* lds_dst) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds_dst, 16,
+                                             static_cast<int>(voffset), static_cast<int>(soffset), 0, 0);
+}
+constexpr uint32_t kBufOutside = 0x80000000u;   // voffset of a lane that must read zeros (tensors stay below 2 GiB)
+
 }  // namespace twn
