@@ -18,6 +18,7 @@
 #include <type_traits>
 #include <utility>
 
+#include "twn_agpr_tiles.h"
 #include "twn_kernels.h"
 #include "twn_mfma.h"
 
@@ -47,14 +48,18 @@ template <int OFFSET>
 __device__ __forceinline__ void lds_read64(u32x2& d, uint32_t addr) {
     asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFFSET));
 }
-// N reads (N <= 4) at addr, addr + STRIDE, ...
+// N reads (N <= 8) at addr, addr + STRIDE, ...
 template <int N, int STRIDE>
 __device__ __forceinline__ void lds_read128_n(u32x4* d, uint32_t addr) {
-    static_assert(N >= 1 && N <= 4 && 3 * STRIDE < 65536, "immediate offsets");
+    static_assert(N >= 1 && N <= 8 && (N - 1) * STRIDE < 65536, "immediate offsets");
     lds_read128<0>(d[0], addr);
     if constexpr (N > 1) lds_read128<STRIDE>(d[1], addr);
     if constexpr (N > 2) lds_read128<2 * STRIDE>(d[2], addr);
     if constexpr (N > 3) lds_read128<3 * STRIDE>(d[3], addr);
+    if constexpr (N > 4) lds_read128<4 * STRIDE>(d[4], addr);
+    if constexpr (N > 5) lds_read128<5 * STRIDE>(d[5], addr);
+    if constexpr (N > 6) lds_read128<6 * STRIDE>(d[6], addr);
+    if constexpr (N > 7) lds_read128<7 * STRIDE>(d[7], addr);
 }
 template <int N, int STRIDE>
 __device__ __forceinline__ void lds_read64_n(u32x2* d, uint32_t addr) {
@@ -74,6 +79,14 @@ template <int N, class T>
 __device__ __forceinline__ void lds_ready(T* r) {
 #pragma unroll
     for (int i = 0; i < N; ++i) asm volatile("" : "+v"(r[i]));
+}
+
+// a constant the compiler keeps in a scalar register (it cannot fold it back into a literal operand)
+template <int V>
+__device__ __forceinline__ uint32_t sgpr_const() {
+    uint32_t r;
+    asm volatile("s_mov_b32 %0, %1" : "=s"(r) : "n"(V));
+    return r;
 }
 
 // compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
@@ -106,6 +119,8 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int PD = STAGES - 1;                 // slabs in flight ahead of the one being multiplied
     constexpr int PER_STAGE = NLOAD + 1;           // vector-memory loads per wave per slab
+    // 16 accumulator tiles per wave fill the accumulation registers exactly: they are then pinned by hand
+    constexpr bool PINNED = (MI * NI == 16);
     // epilogue staging: EPI_CH channels of every pixel row of a wave's tile at a time (64 when LDS allows)
     constexpr int EPI_CH = (NW * TM * 144 + 2 * BN * 4 <= STAGES * STAGE_BYTES) ? 64 : 32;
     constexpr int EPI_ROW = EPI_CH * 2 + 16;       // bytes per staged pixel row (pad keeps 16-byte reads conflict-free)
@@ -282,13 +297,25 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         static_for<NLOAD + 1>(issue_load);
     };
 
-    f32x16 acc[MI][NI];
+    f32x16 acc[PINNED ? 1 : MI][PINNED ? 1 : NI];
+    if constexpr (PINNED) {
+        static_for<16>([&](auto j_tag) __attribute__((always_inline)) { AgprTile<decltype(j_tag)::value>::zero(); });
+    } else {
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+            for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
+                for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
+    }
+    // accumulator tile (mi, ni) as a value, for the epilogue
+    auto acc_tile = [&](int mi, int ni) __attribute__((always_inline)) -> f32x16 {
+        if constexpr (PINNED) {
+            return agpr_read(mi * NI + ni);
+        } else {
+            return acc[mi][ni];
+        }
+    };
 
     // ---- software pipeline ---------------------------------------------------------------------
     // Slab kt lives in stage kt % STAGES and is multiplied in four MFMA steps kk = 0..3 of MI*NI MFMAs.
@@ -300,7 +327,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     //   * in steps 2 and 3, the direct-to-LDS loads of slab kt+PD and the read of slab kt+1's codes.
     // The hand-over point sits between steps 1 and 2: wait until slab kt+1 has landed, barrier; the stage
     // of slab kt-1 is then free for slab kt+PD and slab kt+1 may be read.
-    static_assert(MI <= 4 && NI <= 4, "fragment reads use immediate offsets for up to four tiles");
+    static_assert(MI <= 8 && NI <= 4, "fragment reads use immediate offsets");
     // LDS byte address of the dynamic array (the low 32 bits of its generic address are the LDS offset)
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) unsigned char*)smem));
@@ -315,11 +342,21 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     u32x4 afrag[2][MI];     // activation fragments of step kk in set kk & 1
     u32x4 bfrag[2][NI];     // expanded codes of step kk in set kk & 1
 
-    // code field i of every 32-bit half lands in bits [14,15] of a bf16: 0 / +2.0 / -2.0
+    // code field i of every 32-bit half lands in bits [14,15] of a bf16: 0 / +2.0 / -2.0.  The field is
+    // masked first (masks held in scalar registers), then shifted: the intermediate is mostly zero bits.
+    uint32_t kmask[8];
+    kmask[0] = sgpr_const<static_cast<int>(0xC000C000u >> 14)>();
+    kmask[1] = sgpr_const<static_cast<int>(0xC000C000u >> 12)>();
+    kmask[2] = sgpr_const<static_cast<int>(0xC000C000u >> 10)>();
+    kmask[3] = sgpr_const<static_cast<int>(0xC000C000u >> 8)>();
+    kmask[4] = sgpr_const<static_cast<int>(0xC000C000u >> 6)>();
+    kmask[5] = sgpr_const<static_cast<int>(0xC000C000u >> 4)>();
+    kmask[6] = sgpr_const<static_cast<int>(0xC000C000u >> 2)>();
+    kmask[7] = sgpr_const<static_cast<int>(0xC000C000u)>();
     auto expand = [&](auto kk_tag, auto ni_tag, auto e_tag, const u32x2* br, u32x4* out) __attribute__((always_inline)) {
         constexpr int kk = decltype(kk_tag)::value, ni = decltype(ni_tag)::value, e = decltype(e_tag)::value;
         constexpr int i = (kk & 1) * 4 + e;
-        out[ni][e] = (br[ni][kk >> 1] << (14 - 2 * i)) & 0xC000C000u;
+        out[ni][e] = (br[ni][kk >> 1] & kmask[i]) << (14 - 2 * i);
     };
 
     // One MFMA step.  Weights are the MFMA row operand, activations the column operand: a lane then owns
@@ -360,9 +397,13 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         static_for<NM>([&](auto j_tag) __attribute__((always_inline)) {
             constexpr int j = decltype(j_tag)::value;
             constexpr int mi = j / NI, ni = j % NI;
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[SET][ni]),
-                                                                  __builtin_bit_cast(bf16x8, afrag[SET][mi]),
-                                                                  acc[mi][ni], 0, 0, 0);
+            if constexpr (PINNED) {
+                AgprTile<j>::mfma(bfrag[SET][ni], afrag[SET][mi]);
+            } else {
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[SET][ni]),
+                                                                      __builtin_bit_cast(bf16x8, afrag[SET][mi]),
+                                                                      acc[mi][ni], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             static_for<P>([&](auto p_tag) __attribute__((always_inline)) {
                 constexpr int p = decltype(p_tag)::value;
@@ -421,6 +462,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    if constexpr (PINNED) agpr_settle();
 
     if (SPLITK) {
         // raw fp32 partial sums; alpha, scale, shift, residual and ReLU are applied by the reduction kernel
@@ -432,17 +474,17 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             if (m >= g.M) continue;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
+                const f32x16 t = acc_tile(mi, ni);
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const int ncol = n0 + wn * TN + ni * 32 + q4 * 8 + lh * 4;
                     float* dst = part + m * g.NC + ncol;
                     if (v4 && ncol < g.NC) {
-                        *reinterpret_cast<f32x4*>(dst) = f32x4{acc[mi][ni][q4 * 4], acc[mi][ni][q4 * 4 + 1],
-                                                               acc[mi][ni][q4 * 4 + 2], acc[mi][ni][q4 * 4 + 3]};
+                        *reinterpret_cast<f32x4*>(dst) = f32x4{t[q4 * 4], t[q4 * 4 + 1], t[q4 * 4 + 2], t[q4 * 4 + 3]};
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (ncol + e < g.NC) dst[e] = acc[mi][ni][q4 * 4 + e];
+                            if (ncol + e < g.NC) dst[e] = t[q4 * 4 + e];
                     }
                 }
             }
@@ -483,6 +525,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 #pragma unroll
                 for (int nh = 0; nh < EPI_NI; ++nh) {
                     const int ni = nc * EPI_NI + nh;
+                    const f32x16 t = acc_tile(mi, ni);
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4) {
                         const int nl = wn * TN + ni * 32 + q4 * 8 + lh * 4;     // column within the block tile
@@ -490,7 +533,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                         const f32x4 add = *reinterpret_cast<const f32x4*>(coladd + nl);
                         float v[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][q4 * 4 + e] * mul[e] + add[e];
+                        for (int e = 0; e < 4; ++e) v[e] = t[q4 * 4 + e] * mul[e] + add[e];
                         if (res && m < g.M && n0 + nl < g.NC) {
                             const u32x2 rr = *reinterpret_cast<const u32x2*>(res + m * g.ldy + n0 + nl);
                             v[0] += __uint_as_float(rr[0] << 16);
@@ -528,12 +571,13 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             if (m >= g.M) continue;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
+                const f32x16 t = acc_tile(mi, ni);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int nl = wn * TN + ni * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
                     const int ncol = n0 + nl;
                     if (ncol >= g.NC) continue;
-                    float v = acc[mi][ni][e] * colmul[nl] + coladd[nl];
+                    float v = t[e] * colmul[nl] + coladd[nl];
                     const int64_t off = m * g.ldy + ncol;
                     if (g.y_f32) {
                         if (g.residual) v += static_cast<const float*>(g.residual)[off];
@@ -617,20 +661,26 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
         a.w_bytes = static_cast<uint32_t>(wb < (1LL << 31) ? wb : 0);
     }
     if (g.splits > 1) {
-        if (!g.partial) return TWN_ERR_WORKSPACE;
-        int32_t rc = g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, true>(a, blocks, st)
-                                  : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, true>(a, blocks, st);
-        if (rc != TWN_OK) return rc;
-        const int64_t total = g.M * g.NC;
-        splitk_finish_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(g);
-        return launch_status();
+        // the dispatcher splits K only for grids of few 128x128 tiles: no other tile has a split-K build
+        if constexpr (BM == 128 && BN == 128 && WM == 2 && WN == 2) {
+            if (!g.partial) return TWN_ERR_WORKSPACE;
+            int32_t rc = g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, true>(a, blocks, st)
+                                      : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, true>(a, blocks, st);
+            if (rc != TWN_OK) return rc;
+            const int64_t total = g.M * g.NC;
+            splitk_finish_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(g);
+            return launch_status();
+        } else {
+            return TWN_ERR_UNSUPPORTED;
+        }
     }
     return g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, false>(a, blocks, st)
                         : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, false>(a, blocks, st);
 }
 
 // Tile ids (BM x BN, waves, stages): 12 = 128x128 2x2 S3, 13 = 128x64 4x1 S3, 17 = 128x256 1x4 S4,
-// 24 = 128x512 1x8 S4, 27 = 128x128 4x2 S3
+// 24 = 128x512 1x8 S4, 27 = 128x128 4x2 S3, 30 = 256x256 2x2 S3
+// (30: 16 accumulator tiles per wave, pinned by hand; only on request, it is not faster than 17)
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
     switch (tile) {
         case 12: return launch_dma_tile<128, 128, 2, 2, 3>(g, st);
@@ -638,6 +688,7 @@ int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
         case 17: return launch_dma_tile<128, 256, 1, 4, 4>(g, st);
         case 24: return launch_dma_tile<128, 512, 1, 8, 4>(g, st);
         case 27: return launch_dma_tile<128, 128, 4, 2, 3>(g, st);
+        case 30: return launch_dma_tile<256, 256, 2, 2, 3>(g, st);
         default: return TWN_ERR_UNSUPPORTED;
     }
 }

@@ -57,7 +57,7 @@ def test_gemm_fwd_every_tile_shape(tile, monkeypatch):
     assert rel_err(to_host_f64(y), ref) <= 1e-4
 
 
-DMA_TILES = [12, 13, 17, 24, 27]
+DMA_TILES = [12, 13, 17, 24, 27, 30]
 
 
 @pytest.mark.parametrize("tile", DMA_TILES)
@@ -72,6 +72,43 @@ def test_every_direct_to_lds_tile_shape(tile, monkeypatch):
     x, w, tw, codes, alpha = make_layer(50 + tile, (nb, h, w_, c), (o, c, r, s))
     y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, y_dtype=torch.float32)
     assert rel_err(to_host_f64(y), oc.conv2d_fwd(x, codes, alpha, st, pd, dl)) <= 1e-4
+
+
+@pytest.mark.parametrize("tile", [30])
+def test_pinned_accumulator_tiles(tile, monkeypatch):
+    # the 256x256 tiles keep their 16 accumulator tiles per wave in hand-assigned registers: both load paths
+    # (K and channel counts that are / are not multiples of 64), both epilogues, and backward-data
+    monkeypatch.setenv("TWN_TILE", str(tile))
+    for seed, (m, n, k) in enumerate([(520, 600, 448), (300, 257, 440), (1100, 512, 1024)]):
+        x, w, tw, codes, alpha = make_layer(300 + seed, (m, k), (n, k))
+        ref = oc.gemm_fwd(x, codes.reshape(n, k), alpha)
+        y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
+        assert rel_err(to_host_f64(y), ref) <= 1e-4
+        yb = api.twn_gemm_fwd(to_dev_bf16(x), tw)
+        assert rel_err(to_host_f64(yb), ref) <= BF16_TOL
+    m, n, k = 700, 320, 256
+    x, w, tw, codes, alpha = make_layer(310, (m, k), (n, k), groups=n)
+    g = np.random.default_rng(4)
+    scale = g.uniform(0.5, 1.5, n).astype(np.float32)
+    shift = g.standard_normal(n).astype(np.float32)
+    res = wl.bf16_round(g.standard_normal((m, n)).astype(np.float32))
+    y = api.twn_gemm_fwd(to_dev_bf16(x), tw, scale=to_dev_f32(scale), shift=to_dev_f32(shift),
+                         residual=to_dev_bf16(res), relu=True)
+    ref = oc.epilogue(oc.gemm_fwd(x, codes.reshape(n, k), alpha), scale, shift, res, relu=True)
+    assert rel_err(to_host_f64(y), ref) <= BF16_TOL
+    for seed, (nb, h, w_, c, o, r, s, st, pd, dl) in enumerate([
+            (3, 17, 17, 64, 320, 3, 3, (1, 1), (1, 1), (1, 1)),
+            (3, 15, 13, 24, 72, 3, 3, (2, 1), (1, 2), (1, 1))]):
+        x, w, tw, codes, alpha = make_layer(320 + seed, (nb, h, w_, c), (o, c, r, s), transposed=True)
+        ref = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+        y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, y_dtype=torch.float32)
+        assert rel_err(to_host_f64(y), ref) <= 1e-4
+        yb = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl)
+        assert rel_err(to_host_f64(yb), ref) <= BF16_TOL
+        dy = wl.bf16_round(g.standard_normal(ref.shape).astype(np.float32))
+        dx, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dx=True, need_dw=False,
+                                          x_shape=(nb, h, w_, c), dx_dtype=torch.float32)
+        assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, (nb, h, w_, c), st, pd, dl)) <= 1e-4
 
 
 HALO_CASES = [
