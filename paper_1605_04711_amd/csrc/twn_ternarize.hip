@@ -307,19 +307,28 @@ __global__ __launch_bounds__(kTernThreads) void mask_pack_gather_kernel(
     mask_pack_gather_body(W, rows, C, RS, ws, nb1, f, packed, wpr, packed_T, wprT, blockIdx.x, gridDim.x);
 }
 
-// Pass 2 for filter banks with R*S > 1, rows % 16 == 0 and C % 16 == 0, staged through LDS: block `bid`
-// owns 16 consecutive filters x CT consecutive channels x all taps.  Its weights are 16 contiguous runs
+// Pass 2 for tensors with rows % 16 == 0 and C % 16 == 0 (filter banks, and matrices that also need the
+// transposed copy), staged through LDS: block `bid` owns 16 consecutive filters x CT consecutive channels
+// x all taps.  Its weights are 16 contiguous runs
 // of CT*R*S floats, read once with coalesced float4 loads; the 2-bit fields go to LDS as bytes in memory
 // order, and the words of both copies are assembled from LDS (16 byte reads per word), so no thread
 // gathers from global memory.  Words written: per filter and tap CT/16 normal words; per channel and tap
 // one transposed word (its 16 codes are the block's 16 filters).  Row padding words are written by the
 // blocks with channel tile 0 (normal) and filter tile 0 (transposed).
 constexpr int kTileRows = 16;
-constexpr int kTileLdsBytes = 16 * 64 * 25;   // CT <= 64, R*S <= 25
-__host__ __device__ inline int tile_ct(int C) { return (C % 64 == 0) ? 64 : (C % 32 == 0) ? 32 : 16; }
+constexpr int kTileLdsBytes = 16 * 64 * 25;   // CT <= 64 with R*S <= 25 taps; CT <= 1024 for matrices
+__host__ __device__ inline int tile_ct(int C, int RS) {
+    if (RS == 1) {
+        // matrices: the largest power of two up to 1024 that divides C (runs of up to 4 KB per filter)
+        int ct = 16;
+        while (ct < 1024 && C % (2 * ct) == 0) ct *= 2;
+        return ct;
+    }
+    return (C % 64 == 0) ? 64 : (C % 32 == 0) ? 32 : 16;
+}
 __host__ __device__ inline bool tile_ok(int rows, int C, int RS) {
-    return RS > 1 && RS <= 25 && rows % 16 == 0 && C % 16 == 0 &&
-           static_cast<int64_t>(rows / 16) * (C / tile_ct(C)) <= kMaxBlocks;
+    return RS >= 1 && RS <= 25 && rows % 16 == 0 && C % 16 == 0 &&
+           static_cast<int64_t>(rows / 16) * (C / tile_ct(C, RS)) <= kMaxBlocks;
 }
 
 __device__ __forceinline__ void mask_pack_tile_body(
@@ -330,7 +339,7 @@ __device__ __forceinline__ void mask_pack_tile_body(
     __shared__ __attribute__((aligned(16))) unsigned char codes[kTileLdsBytes];
     const int64_t n = static_cast<int64_t>(rows) * C * RS;
     const float delta = delta_from_partials(ws->p1, nb1, f, n, scratch);
-    const int CT = tile_ct(C), ctiles = C / CT;
+    const int CT = tile_ct(C, RS), ctiles = C / CT;
     const int o0 = (bid / ctiles) * kTileRows, c0 = (bid % ctiles) * CT;
     const int seg = CT * RS;                       // floats (and code bytes) per filter in this block
     const int tid = threadIdx.x;
@@ -583,7 +592,9 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
         if (want > kMaxBlocks) want = kMaxBlocks;
         const int nb = static_cast<int>(nchunks < want ? nchunks : want);
         abs_sum_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1);
-        const bool flat = (RS == 1) && (K % 128 == 0);
+        // matrices stream through the flat kernel; when the transposed copy is wanted too, the tile kernel
+        // writes both from one read of W instead of a second, gathering pass
+        const bool flat = (RS == 1) && (K % 128 == 0) && !(packed_T && tile_ok(wd->rows, wd->C, 1));
         if (flat) {
             const int reverse = env_int("TWN_TERN_REVERSE", 1);
             mask_pack_flat_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws, nb, delta_factor, packed, reverse);
@@ -599,7 +610,7 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
             int64_t nb2 = (words + kTernThreads - 1) / kTernThreads;
             if (nb2 > kMaxBlocks) nb2 = kMaxBlocks;
             if (tile_ok(wd->rows, wd->C, static_cast<int>(RS))) {
-                nb2 = static_cast<int64_t>(wd->rows / kTileRows) * (wd->C / tile_ct(wd->C));
+                nb2 = static_cast<int64_t>(wd->rows / kTileRows) * (wd->C / tile_ct(wd->C, static_cast<int>(RS)));
                 mask_pack_tile_kernel<<<static_cast<unsigned>(nb2), kTernThreads, 0, st>>>(
                     W, wd->rows, wd->C, static_cast<int>(RS), ws, nb, delta_factor, packed, wpr, packed_T, wprT);
             } else
@@ -671,10 +682,11 @@ extern "C" int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t 
         if (nb2 > 4 * share) nb2 = 4 * share;
         if (nb2 > kMaxBlocks) nb2 = kMaxBlocks;
         if (it.nb1 > kMaxBlocks) it.nb1 = kMaxBlocks;
-        it.tiled = tile_ok(wd.rows, wd.C, static_cast<int>(RS)) ? 1 : 0;
-        if (it.tiled) nb2 = static_cast<int64_t>(wd.rows / kTileRows) * (wd.C / tile_ct(wd.C));
+        const bool flat = (RS == 1) && (K % 128 == 0) && !(in.packed_T && tile_ok(wd.rows, wd.C, 1));
+        it.tiled = (!flat && tile_ok(wd.rows, wd.C, static_cast<int>(RS))) ? 1 : 0;
+        if (it.tiled) nb2 = static_cast<int64_t>(wd.rows / kTileRows) * (wd.C / tile_ct(wd.C, static_cast<int>(RS)));
         it.flat_blocks = 0;
-        if (RS == 1 && K % 128 == 0) {
+        if (flat) {
             // flat layout: the normal copy is written while W streams by; only the transposed copy gathers
             it.flat_blocks = it.nb1;
             int64_t nbT = in.packed_T ? (static_cast<int64_t>(wd.C) * it.wprT + kTernThreads - 1) / kTernThreads : 0;

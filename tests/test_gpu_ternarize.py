@@ -43,6 +43,7 @@ def check_against_oracle(w, f, groups=1, transposed=True):
 @pytest.mark.parametrize("shape", [
     (64, 256), (33, 1152), (1000, 128 * 33),       # flat layouts (fused pack), ragged over blocks
     (17, 24), (10, 1024), (1, 1),                  # K not a multiple of 128
+    (48, 320), (32, 48), (64, 2048), (16, 3072),   # matrices through the LDS-staged tiles (both copies from one read)
     (5, 3, 3, 3), (64, 32, 5, 5), (128, 128, 3, 3), (64, 3, 7, 7), (32, 1, 5, 5),
     (32, 48, 3, 3), (16, 16, 7, 7), (48, 80, 1, 3), (256, 192, 3, 3),   # LDS-staged tiles: channel tiles of 16/64, and too many taps
 ])
