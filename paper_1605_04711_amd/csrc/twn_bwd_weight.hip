@@ -62,6 +62,7 @@ struct WGArgs {
     int64_t pixels;
     int32_t J;
     int32_t slabs_per_split;
+    int32_t xcd_map;            // patch kernel: renumber workgroups so that an XCD owns a contiguous run of (range, tile)
 };
 
 constexpr int kWgTile = 128;
@@ -306,10 +307,21 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lh = lane >> 5;
 
+    // Workgroups are dealt round-robin to the 8 XCDs in dispatch order (x fastest).  The tiles of one pixel
+    // range read the same dY and overlapping X: give each XCD a contiguous run of (range, tile) pairs, tile
+    // fastest, so that those tiles run side by side under one L2 instead of on eight.
+    uint32_t bx = blockIdx.x, by = blockIdx.y;
+    if (a.xcd_map) {
+        const uint32_t nbx = gridDim.x, nb = nbx * gridDim.y, lin = by * nbx + bx;
+        const uint32_t q = nb >> 3, r = nb & 7, xcd = lin & 7, idx = lin >> 3;
+        const uint32_t t = (xcd < r) ? xcd * (q + 1) + idx : r * (q + 1) + (xcd - r) * q + idx;
+        bx = t % nbx;
+        by = t / nbx;
+    }
     const int tiles_j = (a.J + 255) / 256;
-    const int o0 = static_cast<int>(blockIdx.x / tiles_j) * 128;
-    const int j0 = static_cast<int>(blockIdx.x % tiles_j) * 256;
-    const int64_t slab_begin = static_cast<int64_t>(blockIdx.y) * a.slabs_per_split;
+    const int o0 = static_cast<int>(bx / tiles_j) * 128;
+    const int j0 = static_cast<int>(bx % tiles_j) * 256;
+    const int64_t slab_begin = static_cast<int64_t>(by) * a.slabs_per_split;
     int64_t slab_end = slab_begin + a.slabs_per_split;
     if (slab_end > pl.slabs) slab_end = pl.slabs;
     const int nslab = static_cast<int>(slab_end - slab_begin);
@@ -499,7 +511,7 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
         }
         return;
     }
-    float* out = w.partial + static_cast<int64_t>(blockIdx.y) * w.O * a.J;
+    float* out = w.partial + static_cast<int64_t>(by) * w.O * a.J;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -659,6 +671,7 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
     a.divSY = make_fastdiv(a.plan.patch ? a.plan.sy : 1);
     const int32_t splits = a.plan.splits;
     a.slabs_per_split = static_cast<int32_t>((a.plan.slabs + splits - 1) / splits);
+    a.xcd_map = env_int("TWN_WG_XCD", 1);
     if (w.dW) {
         const dim3 grid(a.plan.tiles, splits);
         if (a.plan.patch) {
