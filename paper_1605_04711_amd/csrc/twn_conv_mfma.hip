@@ -400,11 +400,13 @@ static int gather_mode(const GatherGemm& g) {
 }
 
 int32_t gather_gemm_splits(const GatherGemm& g) {
-    // split K when 128x128 tiles alone cannot fill the chip and K is deep enough to share out
+    // split K when even 64x128 tiles leave half the CUs idle and K is deep enough to share out (few workgroups
+    // with two slabs in flight each are bound by memory latency when their input is not in L2)
     if (gather_mode(g) == kModeScalar || env_int("TWN_TILE", 0) != 0) return 1;
     const int64_t blocks = ((g.M + 127) / 128) * ((g.NC + 127) / 128);
+    const int64_t blocks64 = ((g.M + 63) / 64) * ((g.NC + 127) / 128);
     const int KT = (g.K + 63) / 64;
-    if (blocks >= 192 || KT < 8) return 1;
+    if (blocks64 >= 128 || KT < 8) return 1;
     int64_t splits = (448 + blocks - 1) / blocks;
     if (splits > KT / 4) splits = KT / 4;
     if (splits > 32) splits = 32;
@@ -435,8 +437,8 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
             else if (g.NC <= 64) tile = 13;
             else if (g.NC <= 128) tile = 12;
             else tile = (blocks(128, 256) >= 512) ? 17 : 12;
-            // at most one 128x128 workgroup per CU: eight waves per workgroup (two per SIMD) instead of four
-            if (tile == 12 && g.splits == 1 && blocks(128, 128) <= 256) tile = 27;
+            // at most one 128x128 workgroup per CU: 64x128 tiles double the workgroups (layers with few pixels)
+            if (tile == 12 && g.splits == 1 && blocks(128, 128) <= 256) tile = 14;
         }
         return launch_gather_gemm_dma(g, tile, st);
     }

@@ -122,11 +122,11 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     // 16 accumulator tiles per wave fill the accumulation registers exactly: they are then pinned by hand
     constexpr bool PINNED = (MI * NI == 16);
     // epilogue staging: EPI_CH channels of every pixel row of a wave's tile at a time (64 when LDS allows)
-    constexpr int EPI_CH = (NW * TM * 144 + 2 * BN * 4 <= STAGES * STAGE_BYTES) ? 64 : 32;
+    constexpr int EPI_CH = (TN % 64 == 0 && NW * TM * 144 + 2 * BN * 4 <= STAGES * STAGE_BYTES) ? 64 : 32;
     constexpr int EPI_ROW = EPI_CH * 2 + 16;       // bytes per staged pixel row (pad keeps 16-byte reads conflict-free)
     constexpr int EPI_NI = EPI_CH / 32;            // 32-channel MFMA tiles per staged chunk
     constexpr int EPI_STAGE_BYTES = NW * TM * EPI_ROW;
-    static_assert(BM % (8 * NW) == 0 && BN % 64 == 0 && TN % 64 == 0 && TM % 32 == 0, "tile shape");
+    static_assert(BM % (8 * NW) == 0 && BN % 64 == 0 && BN <= 64 * NW && TN % 32 == 0 && TM % 32 == 0, "tile shape");
     static_assert(STAGES >= 3, "the mid-slab hand-over needs two slabs in flight");
     static_assert(EPI_STAGE_BYTES + 2 * BN * 4 <= STAGES * STAGE_BYTES, "epilogue staging must fit in the pipeline LDS");
 
@@ -678,16 +678,16 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
                         : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, false>(a, blocks, st);
 }
 
-// Tile ids (BM x BN, waves, stages): 12 = 128x128 2x2 S3, 13 = 128x64 4x1 S3, 17 = 128x256 1x4 S4,
-// 24 = 128x512 1x8 S4, 27 = 128x128 4x2 S3, 30 = 256x256 2x2 S3
+// Tile ids (BM x BN, waves, stages): 12 = 128x128 2x2 S3, 13 = 128x64 4x1 S3, 14 = 64x128 1x4 S3,
+// 17 = 128x256 1x4 S4, 24 = 128x512 1x8 S4, 30 = 256x256 2x2 S3
 // (30: 16 accumulator tiles per wave, pinned by hand; only on request, it is not faster than 17)
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
     switch (tile) {
         case 12: return launch_dma_tile<128, 128, 2, 2, 3>(g, st);
         case 13: return launch_dma_tile<128, 64, 4, 1, 3>(g, st);
+        case 14: return launch_dma_tile<64, 128, 1, 4, 3>(g, st);
         case 17: return launch_dma_tile<128, 256, 1, 4, 4>(g, st);
         case 24: return launch_dma_tile<128, 512, 1, 8, 4>(g, st);
-        case 27: return launch_dma_tile<128, 128, 4, 2, 3>(g, st);
         case 30: return launch_dma_tile<256, 256, 2, 2, 3>(g, st);
         default: return TWN_ERR_UNSUPPORTED;
     }
