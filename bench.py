@@ -43,6 +43,7 @@ def main():
     ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18"], default=None,
                     help="run one side measurement alone (used for the rocprofv3 summaries in profiles/)")
     ap.add_argument("--variants", action="store_true", help="with --only gemm: also time the comparison weight formats")
+    ap.add_argument("--graph", action="store_true", help="also capture the step into a HIP graph and time its replay")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -328,6 +329,41 @@ def main():
               "bwd_tflops": round((flops_dx + flops_dw) / (phase_ms[2] * 1e-3) / 1e12, 2),
               "bwd_data_serial_ms": round(dx_ms, 4), "bwd_weight_serial_ms": round(dw_ms, 4),
               "ternarize_layers_GBps": round(tern_bytes / (phase_ms[0] * 1e-3) / 1e9, 1)}
+
+    if args.graph:
+        # the same step captured once into a HIP graph and replayed (the library only launches kernels and takes
+        # its workspaces from the caller, so a step captures as is); outputs are compared with the eager step's
+        outs = (Y[1], Y[7], dX[1], dW[1], dW[5], dW[7])
+        one_step()
+        torch.cuda.synchronize()
+        ref = [t.clone() for t in outs]
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap):
+            one_step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap):
+            one_step()
+        torch.cuda.synchronize()
+        same = True
+        for _ in range(3):
+            for t in outs:
+                t.fill_(0.0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            same = same and all(torch.equal(a, b) for a, b in zip(ref, outs))
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+        log("graph replay: %.3f ms per step (eager %.3f), outputs identical to eager: %s" % (g_ms, ms_per_step, same))
+        extras["graph_replay"] = {"ms_per_step": round(g_ms, 4), "outputs_identical_to_eager": bool(same)}
 
     if not args.no_extras:
         del X, dY, Y, dX, dW

@@ -389,3 +389,70 @@ def test_full_size_vgg7_backward_sampled(name):
         i1 = _sample(int(np.prod(layer.x_shape)), 20000, li)
         ref_dx = oc.conv2d_bwd_data_at(dy, codes, alpha, layer.x_shape, i1, st, pd, dl)
         assert rel_err(to_host_f64(dx).ravel()[i1], ref_dx) <= BF16_TOL
+
+
+def test_library_calls_capture_into_a_graph_and_replay():
+    # the library only launches kernels and takes its workspaces from the caller, so a ternarize + forward +
+    # two-stream backward sequence captures into a HIP graph; every replay (with eager work and
+    # synchronisations between the replays) must reproduce the eager results bit for bit
+    n, h, w_, c, o = 4, 12, 12, 64, 128
+    st, pd, dl = (1, 1), (1, 1), (1, 1)
+    g = np.random.default_rng(77)
+    x = to_dev_bf16(wl.bf16_round(g.standard_normal((n, h, w_, c)).astype(np.float32)))
+    dy = to_dev_bf16(wl.bf16_round(g.standard_normal((n, h, w_, o)).astype(np.float32)))
+    wts = [to_dev_f32((g.standard_normal((o, c, 3, 3)) * 0.05).astype(np.float32)),
+           to_dev_f32((g.standard_normal((10, 256)) * 0.05).astype(np.float32))]
+    tws = api.twn_ternarize_batch(wts, F, transposed=True)
+    tern_ws = torch.empty(api.lib().twn_ternarize_batch_workspace_bytes(2), dtype=torch.uint8, device="cuda")
+    y = torch.empty((n, h, w_, o), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((n, h, w_, c), dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((o, c, 3, 3), dtype=torch.float32, device="cuda")
+    nws = max(16, api.twn_conv2d_bwd_ste_workspace_bytes((n, h, w_, c), tws[0], st, pd, dl))
+    ws_a = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(nws, dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes((n, h, w_, c), tws[0], st, pd, dl)),
+                       dtype=torch.uint8, device="cuda")
+    side_a, side_b = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def sequence():
+        api.twn_ternarize_batch(wts, F, transposed=True, out=tws, workspace=tern_ws)
+        api.twn_conv2d_fwd(x, tws[0], st, pd, dl, relu=True, out=y, workspace=ws_f)
+        cur = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(cur)
+        side_a.wait_event(fork)
+        side_b.wait_event(fork)
+        api.twn_conv2d_bwd_ste(None, dy, tws[0], st, pd, dl, need_dx=True, need_dw=False, dX=dx, x_shape=(n, h, w_, c),
+                               workspace=ws_a, stream=side_a)
+        api.twn_conv2d_bwd_ste(x, dy, tws[0], st, pd, dl, need_dx=False, need_dw=True, dW=dw, workspace=ws_b,
+                               stream=side_b)
+        ja, jb = torch.cuda.Event(), torch.cuda.Event()
+        ja.record(side_a)
+        jb.record(side_b)
+        cur.wait_event(ja)
+        cur.wait_event(jb)
+
+    outs = (y, dx, dw, tws[0].packed, tws[0].packed_T, tws[1].packed, tws[0].alpha)
+    sequence()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    cap = torch.cuda.Stream()
+    cap.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(cap):
+        sequence()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=cap):
+        sequence()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for t in outs:
+            t.zero_()
+        if rep % 2:
+            # eager work of the program itself between two replays
+            api.twn_conv2d_fwd(x, api.twn_ternarize(wts[0], F), st, pd, dl)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, outs):
+            assert torch.equal(a, b)
