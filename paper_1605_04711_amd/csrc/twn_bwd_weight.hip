@@ -585,6 +585,40 @@ __global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __
     dW[dst] = (beta != 0.0f) ? beta * dW[dst] + sum : sum;
 }
 
+// The same reduction for few splits and many outputs (C % 64 == 0, no first-layer padding).  The kernel
+// above scatters its sums as single floats, R*S floats apart; with few splits that write pattern is most of
+// its time.  Here a block owns filter o and 64 consecutive channels: per tap it reads one 256-byte run of
+// every split (float4 per lane, several splits in flight, summed in split order), transposes the R*S x 64
+// sums through LDS and writes dW[o][c0..c0+63][:][:] as ONE contiguous run of 64*R*S floats.
+constexpr int kReduceRowsMaxTaps = 25;
+__global__ __launch_bounds__(256) void weight_grad_reduce_rows_kernel(const float* __restrict__ partial, int splits,
+                                                                      int O, int C, int RS, float beta,
+                                                                      float* __restrict__ dW) {
+    __shared__ float tile[64 * kReduceRowsMaxTaps];      // [channel][tap]
+    const int cchunks = C / 64;
+    const int o = blockIdx.x / cchunks, c0 = (blockIdx.x % cchunks) * 64;
+    const int64_t J = static_cast<int64_t>(RS) * C;
+    const int64_t total = J * O;
+    // item = (tap, group of 4 channels): 16 items per tap
+    for (int item = threadIdx.x; item < RS * 16; item += 256) {
+        const int rs = item >> 4, c4 = (item & 15) * 4;
+        const float* src = partial + static_cast<int64_t>(o) * J + static_cast<int64_t>(rs) * C + c0 + c4;
+        float4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 8
+        for (int sp = 0; sp < splits; ++sp) {
+            const float4 t = *reinterpret_cast<const float4*>(src + static_cast<int64_t>(sp) * total);
+            acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+        }
+        tile[(c4 + 0) * RS + rs] = acc.x;
+        tile[(c4 + 1) * RS + rs] = acc.y;
+        tile[(c4 + 2) * RS + rs] = acc.z;
+        tile[(c4 + 3) * RS + rs] = acc.w;
+    }
+    __syncthreads();
+    float* dst = dW + (static_cast<int64_t>(o) * C + c0) * RS;      // [O][C][R][S]: 64*RS contiguous floats
+    for (int i = threadIdx.x; i < 64 * RS; i += 256) dst[i] = (beta != 0.0f) ? beta * dst[i] + tile[i] : tile[i];
+}
+
 // dbias partials: block (x = 64-channel group, y = pixel split) sums its pixel range.
 constexpr int kBiasSplits = 64;
 __global__ __launch_bounds__(256) void bias_grad_partial_kernel(const uint16_t* __restrict__ dY, int64_t pixels,
@@ -691,7 +725,11 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
         if (w.pad_sp || !(a.plan.patch && splits == 1)) {   // a single-range patch launch writes dW itself
             const int64_t total = static_cast<int64_t>(w.O) * a.J;
             const int C = w.pad_sp ? w.c_real : w.C, S = w.pad_sp ? w.s_real : w.S;
-            if (total % 4 == 0)
+            const int RS = w.R * w.S;
+            if (!w.pad_sp && w.C % 64 == 0 && RS <= kReduceRowsMaxTaps && splits <= env_int("TWN_WG_ROWS_SPLITS", 32))
+                weight_grad_reduce_rows_kernel<<<static_cast<unsigned>(w.O * (w.C / 64)), 256, 0, st>>>(
+                    w.partial, splits, w.O, w.C, RS, w.beta, w.dW);
+            else if (total % 4 == 0)
                 weight_grad_reduce_kernel<4><<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(
                     w.partial, splits, w.O, C, w.R, S, w.pad_sp, w.beta, w.dW);
             else
