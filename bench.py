@@ -248,11 +248,12 @@ def main():
     def new_ev():
         return torch.cuda.Event(enable_timing=True)
 
-    # An event between two launches costs a few microseconds of idle GPU, so the timed region records as few
-    # as possible: one event at every boundary of the run of consecutive single-launch calls (the end of one
-    # call is the start of the next).
-    marks = [ci for ci in range(n_main + 1)
-             if (ci < n_main and is_single[ci]) or (ci > 0 and is_single[ci - 1])]
+    # An event between two launches costs several microseconds of idle GPU, so the timed region records only
+    # two per step: before the first and after the last call of the run of consecutive single-launch calls.
+    first_single = min(ci for ci in range(n_main) if is_single[ci])
+    last_single = max(ci for ci in range(n_main) if is_single[ci])
+    assert all(is_single[ci] for ci in range(first_single, last_single + 1))
+    marks = [first_single, last_single + 1]
     mev = [{ci: new_ev() for ci in marks} for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -261,8 +262,8 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    single_ms = {ci: sum(mev[s][ci].elapsed_time(mev[s][ci + 1]) for s in range(args.steps)) / args.steps
-                 for ci in range(n_main) if is_single[ci]}
+    span_ms = sum(mev[s][first_single].elapsed_time(mev[s][last_single + 1]) for s in range(args.steps)) / args.steps
+    single_calls = list(range(first_single, last_single + 1))
 
     # phase times: a second pass with one event pair per phase (the two backward streams form one phase)
     phase_names = ["ternarize", "fwd", "bwd_two_streams"]
@@ -310,16 +311,16 @@ def main():
         x_b = 2 * L.N * L.H * L.W * L.C
         y_b = 2 * L.N * L.P * L.Q * L.O
         return x_b + y_b + L.n_weights // 4     # the same three tensors forward (X -> Y) and backward (dY -> dX)
-    sample_bytes = {ci: call_bytes(calls[ci][0], layers[calls[ci][1]]) for ci in single_ms}
-    r_flops = sum(layers[calls[ci][1]].flops for ci in single_ms)
-    r_ms = sum(single_ms.values())
+    sample_bytes = {ci: call_bytes(calls[ci][0], layers[calls[ci][1]]) for ci in single_calls}
+    r_flops = sum(layers[calls[ci][1]].flops for ci in single_calls)
+    r_ms = span_ms
     gg_tflops = r_flops / (r_ms * 1e-3) / 1e12
     roof = {"kernel": "gather_gemm_dma_kernel", "bound": "mfma", "achieved": round(gg_tflops, 2),
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gg_tflops / PEAK_BF16_TFLOPS, 4),
             "traffic": ROOFLINE_SAMPLE_TRAFFIC_BYTES,
             "algorithmic_bytes_per_launch": round(sum(sample_bytes.values()) / len(sample_bytes)),
-            "launches_per_step": len(single_ms), "avg_launch_us": round(r_ms * 1e3 / len(single_ms), 2),
-            "flops_per_launch_avg": round(r_flops / len(single_ms) / 1e9, 2),
+            "launches_per_step": len(single_calls), "avg_launch_us": round(r_ms * 1e3 / len(single_calls), 2),
+            "flops_per_launch_avg": round(r_flops / len(single_calls) / 1e9, 2),
             "calls": "fwd c2-c6 (one launch each)"}
     # serial per-layer times of the detail pass give the per-phase rates of the two backward parts
     dx_ms = sum(per[("bwd_data", li)] for li in range(1, len(layers)))
