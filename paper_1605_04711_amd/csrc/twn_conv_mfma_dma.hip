@@ -595,26 +595,42 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 }
 
 // Sums the split-K partials in a fixed order and applies the block tail:
-// y = relu?((0.5*alpha*sum)*scale + shift + residual).  One thread per output element.
+// y = relu?((0.5*alpha*sum)*scale + shift + residual).  One thread per VEC consecutive output elements.
+template <int VEC>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const GatherGemm g) {
-    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t id0 = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) * VEC;
     const int64_t total = g.M * g.NC;
-    if (id >= total) return;
-    const int64_t m = id / g.NC;
-    const int ncol = static_cast<int>(id - m * g.NC);
-    float s = 0.0f;
-    for (int sp = 0; sp < g.splits; ++sp) s += g.partial[static_cast<int64_t>(sp) * total + id];
-    const float mul = 0.5f * g.alpha[ncol / g.rows_per_group] * (g.scale ? g.scale[ncol] : 1.0f);
-    float v = s * mul + (g.shift ? g.shift[ncol] : 0.0f);
-    const int64_t off = m * g.ldy + ncol;
-    if (g.y_f32) {
-        if (g.residual) v += static_cast<const float*>(g.residual)[off];
-        if (g.relu) v = fmaxf(v, 0.0f);
-        static_cast<float*>(g.Y)[off] = v;
-    } else {
-        if (g.residual) v += bf16_to_f32(static_cast<const uint16_t*>(g.residual)[off]);
-        if (g.relu) v = fmaxf(v, 0.0f);
-        static_cast<uint16_t*>(g.Y)[off] = f32_to_bf16(v);
+    if (id0 >= total) return;
+    const int64_t m = id0 / g.NC;
+    const int ncol0 = static_cast<int>(id0 - m * g.NC);      // VEC = 4 needs NC % 4 == 0: the group stays in one row
+    float s[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) s[v] = 0.0f;
+#pragma unroll 8
+    for (int sp = 0; sp < g.splits; ++sp) {
+        const float* src = g.partial + static_cast<int64_t>(sp) * total + id0;
+        if (VEC == 4) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(src);
+            s[0] += t[0]; s[1 % VEC] += t[1]; s[2 % VEC] += t[2]; s[3 % VEC] += t[3];
+        } else {
+            s[0] += src[0];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int ncol = ncol0 + e;
+        const float mul = 0.5f * g.alpha[ncol / g.rows_per_group] * (g.scale ? g.scale[ncol] : 1.0f);
+        float v = s[e] * mul + (g.shift ? g.shift[ncol] : 0.0f);
+        const int64_t off = m * g.ldy + ncol;
+        if (g.y_f32) {
+            if (g.residual) v += static_cast<const float*>(g.residual)[off];
+            if (g.relu) v = fmaxf(v, 0.0f);
+            static_cast<float*>(g.Y)[off] = v;
+        } else {
+            if (g.residual) v += bf16_to_f32(static_cast<const uint16_t*>(g.residual)[off]);
+            if (g.relu) v = fmaxf(v, 0.0f);
+            static_cast<uint16_t*>(g.Y)[off] = f32_to_bf16(v);
+        }
     }
 }
 
@@ -668,7 +684,10 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
                                       : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, true>(a, blocks, st);
             if (rc != TWN_OK) return rc;
             const int64_t total = g.M * g.NC;
-            splitk_finish_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(g);
+            if (g.NC % 4 == 0 && (reinterpret_cast<uintptr_t>(g.partial) & 15) == 0)
+                splitk_finish_kernel<4><<<static_cast<unsigned>((total / 4 + 255) / 256), 256, 0, st>>>(g);
+            else
+                splitk_finish_kernel<1><<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(g);
             return launch_status();
         } else {
             return TWN_ERR_UNSUPPORTED;
