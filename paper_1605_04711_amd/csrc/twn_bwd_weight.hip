@@ -25,6 +25,7 @@
 #include <type_traits>
 
 #include "twn_kernels.h"
+#include "twn_mfma.h"
 
 namespace twn {
 
@@ -63,6 +64,10 @@ struct WGArgs {
     int32_t J;
     int32_t slabs_per_split;
     int32_t xcd_map;            // patch kernel: renumber workgroups so that an XCD owns a contiguous run of (range, tile)
+    // patch kernel, buffer-descriptor loads (both tensors below 2 GiB): sizes in bytes; `exact` = every patch
+    // lies inside the output image (N, P, Q are multiples of the patch extents)
+    uint32_t dy_bytes, x_bytes;
+    int32_t exact;
 };
 
 constexpr int kWgTile = 128;
@@ -287,7 +292,10 @@ __device__ __forceinline__ bf16x8 wg_join(const u32x2& lo, const u32x2& hi) {
 // linearly costs nothing and makes addressing cheap: the patch origin is uniform per slab (scalar
 // arithmetic), a lane's offsets inside the patch are fixed, and no per-lane division is left.
 // Waves 2 (o) x 2 (j): wave tile 64 x 128; wave column wn owns one 128-column half of the B tile.
-template <int STAGES>
+// BUF: loads go through buffer descriptors.  A lane's byte offsets inside a patch are fixed; the patch origin
+// is wave-uniform (scalar arithmetic), and a lane whose pixel, tap or channel is outside gets an offset beyond
+// the descriptor's size and reads zeros: no 64-bit address arithmetic and no branches are left in the loop.
+template <int STAGES, bool BUF>
 __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs a) {
     constexpr int A_BYTES = 32 * 256;               // 32 pixels x 128 channels bf16
     constexpr int B_BYTES = 2 * A_BYTES;            // two 128-column halves
@@ -356,7 +364,30 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
         dn[t] = l >> (lpw + lph);
     }
 
-    auto issue = [&](int64_t slab, int stage, bool live) {
+    // buffer path: fixed per-lane byte offsets relative to the patch origin
+    const __amdgpu_buffer_rsrc_t rdy = make_rsrc(w.dY, a.dy_bytes), rx = make_rsrc(w.X, a.x_bytes);
+    uint32_t voffA[2] = {0u, 0u};
+    uint32_t voffB[2][2] = {{0u, 0u}, {0u, 0u}};      // may stand for a negative offset (arithmetic is modulo 2^32)
+    int32_t aH[2][2], aW[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        if constexpr (BUF) {
+            const uint32_t pix = (static_cast<uint32_t>(dn[t]) * w.P + dy[t]) * w.Q + dx[t];
+            voffA[t] = ook ? (pix * w.O + oo) * 2u : kBufOutside;
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            aH[t][h] = dy[t] * w.sh + th0[h];
+            aW[t][h] = dx[t] * w.sw + tw0[h];
+            if constexpr (BUF) {
+                const uint32_t pix = (static_cast<uint32_t>(dn[t]) * w.H + static_cast<uint32_t>(aH[t][h])) * w.W +
+                                     static_cast<uint32_t>(aW[t][h]);
+                voffB[t][h] = (pix * w.xc + tc[h]) * 2u;
+            }
+        }
+    }
+
+    auto issue = [&](int64_t slab, int stage, bool live) __attribute__((always_inline)) {
         unsigned char* sA = wsm + stage * STAGE_BYTES;
         unsigned char* sB = sA + A_BYTES;
         // patch origin: uniform over the workgroup
@@ -366,6 +397,26 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
         const uint32_t sn = fdiv(t1, a.divSY);
         const uint32_t sy = t1 - sn * pl.sy;
         const int n0 = static_cast<int>(sn) * pl.pn, p0 = static_cast<int>(sy) * pl.ph, q0 = static_cast<int>(sx) * pl.pw;
+        if constexpr (BUF) {
+            // a slab past the end of the range (live == false) still issues its loads, all of them reading zeros
+            const uint32_t sA_off = live ? ((static_cast<uint32_t>(n0) * w.P + p0) * w.Q + q0) * w.O * 2u : 0u;
+            const uint32_t sB_off = ((static_cast<uint32_t>(n0) * w.H + p0 * w.sh) * w.W + q0 * w.sw) * w.xc * 2u;
+            const int remN = w.N - n0, remP = w.P - p0, remQ = w.Q - q0;
+            const int hb = p0 * w.sh, wb = q0 * w.sw;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const bool pok = live && (a.exact || (dn[t] < remN && dy[t] < remP && dx[t] < remQ));
+                buf_dma16(rdy, pok ? voffA[t] : kBufOutside, sA_off, sA + (wave + 4 * t) * 1024);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const bool bok = pok && jok[h] && static_cast<unsigned>(hb + aH[t][h]) < static_cast<unsigned>(w.H) &&
+                                     static_cast<unsigned>(wb + aW[t][h]) < static_cast<unsigned>(w.W);
+                    buf_dma16(rx, bok ? voffB[t][h] + sB_off : kBufOutside, 0u,
+                              sB + h * A_BYTES + (wave + 4 * t) * 1024);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int n = n0 + dn[t], p = p0 + dy[t], q = q0 + dx[t];
@@ -422,17 +473,29 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
     // Hand-over between the steps of slab `it`: slab it+1 has landed (its step 0 is prefetched during step
     // 1), and the stage of slab it-1, whose reads were all issued during step 0 of that slab, is refilled.
     u32x2 fa[2][2][2], fb[4][2];
-    auto read_fa = [&](auto off_tag, uint32_t base, u32x2 (*dst)[2]) __attribute__((always_inline)) {
+    // LDS byte addresses of this lane's fragments in stage 0; the stage and the half of the slab go into the
+    // instruction's immediate offset (the loop is unrolled over the three stages), so a read costs no vector
+    // arithmetic
+    static_assert(STAGES == 3 && 2 * STAGE_BYTES + A_BYTES + 4096 < 65536, "immediate offsets of the fragment reads");
+    uint32_t adrA[2][2], adrB[4][2];
+#pragma unroll
+    for (int hv = 0; hv < 2; ++hv) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) adrA[mi][hv] = lds_base + offA[mi][hv];
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) adrB[ni][hv] = lds_base + offB[ni][hv];
+    }
+    auto read_fa = [&](auto off_tag, u32x2 (*dst)[2]) __attribute__((always_inline)) {
         constexpr int OFF = decltype(off_tag)::value;
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int hv = 0; hv < 2; ++hv) dst[mi][hv] = wg_tr_read<OFF>(base + offA[mi][hv]);
+            for (int hv = 0; hv < 2; ++hv) dst[mi][hv] = wg_tr_read<OFF>(adrA[mi][hv]);
     };
-    auto read_fb = [&](auto off_tag, uint32_t base, int ni) __attribute__((always_inline)) {
-        constexpr int OFF = decltype(off_tag)::value;
+    auto read_fb = [&](auto off_tag, int ni) __attribute__((always_inline)) {
+        constexpr int OFF = decltype(off_tag)::value + A_BYTES;
 #pragma unroll
-        for (int hv = 0; hv < 2; ++hv) fb[ni][hv] = wg_tr_read<OFF>(base + A_BYTES + offB[ni][hv]);
+        for (int hv = 0; hv < 2; ++hv) fb[ni][hv] = wg_tr_read<OFF>(adrB[ni][hv]);
     };
 
 #pragma unroll
@@ -440,18 +503,18 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 1) * PER_STAGE));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    read_fa(std::integral_constant<int, 0>{}, lds_base, fa[0]);
+    read_fa(std::integral_constant<int, 0>{}, fa[0]);
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) read_fb(std::integral_constant<int, 0>{}, lds_base, ni);
+    for (int ni = 0; ni < 4; ++ni) read_fb(std::integral_constant<int, 0>{}, ni);
 
-    int stage = 0, fill = PD % STAGES;
-    for (int it = 0; it < nslab; ++it) {
-        const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
+    // one slab that lives in stage STG (compile-time: the loop below walks the stages in order)
+    auto slab = [&](int it, auto stg_tag) __attribute__((always_inline)) {
+        constexpr int STG = decltype(stg_tag)::value;
+        constexpr int NEXT = (STG + 1) % STAGES, FILL = (STG + PD) % STAGES;
         auto step = [&](auto kk_tag) __attribute__((always_inline)) {
             constexpr int KK = decltype(kk_tag)::value;
             // where the next step's fragments live: second half of this slab, or first half of the next one
-            const uint32_t nbase = lds_base + ((KK == 0) ? stage : next) * STAGE_BYTES;
-            using NOff = std::integral_constant<int, (KK == 0) ? 4096 : 0>;
+            using NOff = std::integral_constant<int, (KK == 0) ? STG * STAGE_BYTES + 4096 : NEXT * STAGE_BYTES>;
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni) {
                 if (ni == 0) wg_wait<6>(); else wg_wait<10>();
@@ -464,8 +527,8 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
                                                                           wg_join(fb[ni][0], fb[ni][1]), acc[mi][ni],
                                                                           0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (ni == 0) read_fa(NOff{}, nbase, fa[KK ^ 1]);
-                read_fb(NOff{}, nbase, ni);
+                if (ni == 0) read_fa(NOff{}, fa[KK ^ 1]);
+                read_fb(NOff{}, ni);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -474,11 +537,14 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
         __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 2) * PER_STAGE));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue(slab_begin + it + PD, fill, it + PD < nslab);
+        issue(slab_begin + it + PD, FILL, it + PD < nslab);
         __builtin_amdgcn_sched_barrier(0);
         step(std::integral_constant<int, 1>{});
-        stage = next;
-        fill = (fill + 1 == STAGES) ? 0 : fill + 1;
+    };
+    for (int it = 0; it < nslab; it += 3) {
+        slab(it, std::integral_constant<int, 0>{});
+        if (it + 1 < nslab) slab(it + 1, std::integral_constant<int, 1>{});
+        if (it + 2 < nslab) slab(it + 2, std::integral_constant<int, 2>{});
     }
     // the fragments fetched ahead for the slab after the last one are never used: let them land, and drain
     // the trailing zero loads, before registers and LDS are reused
@@ -706,19 +772,32 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
     const int32_t splits = a.plan.splits;
     a.slabs_per_split = static_cast<int32_t>((a.plan.slabs + splits - 1) / splits);
     a.xcd_map = env_int("TWN_WG_XCD", 1);
+    a.dy_bytes = a.x_bytes = 0;
+    a.exact = 0;
     if (w.dW) {
         const dim3 grid(a.plan.tiles, splits);
         if (a.plan.patch) {
             constexpr int kStages = 3;
             constexpr int kSmem = kStages * 3 * 32 * 256;
             static bool allowed = false;
-            auto k = weight_grad_patch_kernel<kStages>;
+            const int64_t dyb = a.pixels * w.O * 2;
+            const int64_t xb = ((static_cast<int64_t>(w.N) * w.H * w.W - 1) * w.xc + w.C) * 2;
+            const bool buf = env_int("TWN_BUFLOAD", 1) != 0 && dyb < (1LL << 31) && xb < (1LL << 31);
+            a.dy_bytes = static_cast<uint32_t>(buf ? dyb : 0);
+            a.x_bytes = static_cast<uint32_t>(buf ? xb : 0);
+            a.exact = (w.N % a.plan.pn == 0 && w.P % a.plan.ph == 0 && w.Q % a.plan.pw == 0) ? 1 : 0;
             if (!allowed) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        kSmem) != hipSuccess) return TWN_ERR_HIP;
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess ||
+                    hipFuncSetAttribute(reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)
+                    return TWN_ERR_HIP;
                 allowed = true;
             }
-            k<<<grid, 256, kSmem, st>>>(a);
+            if (buf)
+                weight_grad_patch_kernel<kStages, true><<<grid, 256, kSmem, st>>>(a);
+            else
+                weight_grad_patch_kernel<kStages, false><<<grid, 256, kSmem, st>>>(a);
         } else {
             weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
         }
