@@ -295,7 +295,8 @@ __device__ __forceinline__ bf16x8 wg_join(const u32x2& lo, const u32x2& hi) {
 // BUF: loads go through buffer descriptors.  A lane's byte offsets inside a patch are fixed; the patch origin
 // is wave-uniform (scalar arithmetic), and a lane whose pixel, tap or channel is outside gets an offset beyond
 // the descriptor's size and reads zeros: no 64-bit address arithmetic and no branches are left in the loop.
-template <int STAGES, bool BUF>
+// EXACT (buffer path only): every patch lies inside the output image, so no lane tests its output pixel.
+template <int STAGES, bool BUF, bool EXACT>
 __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs a) {
     constexpr int A_BYTES = 32 * 256;               // 32 pixels x 128 channels bf16
     constexpr int B_BYTES = 2 * A_BYTES;            // two 128-column halves
@@ -380,6 +381,8 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
             aH[t][h] = dy[t] * w.sh + th0[h];
             aW[t][h] = dx[t] * w.sw + tw0[h];
             if constexpr (BUF) {
+                // a column beyond J never passes the row test below (no separate test per load)
+                if (!jok[h]) aH[t][h] = 0x40000000;
                 const uint32_t pix = (static_cast<uint32_t>(dn[t]) * w.H + static_cast<uint32_t>(aH[t][h])) * w.W +
                                      static_cast<uint32_t>(aW[t][h]);
                 voffB[t][h] = (pix * w.xc + tc[h]) * 2u;
@@ -387,9 +390,58 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
         }
     }
 
+    // buffer path: the calls of issue() walk consecutive slabs, so the patch coordinates (cx, cy, cn) are kept
+    // as running scalar counters and every uniform offset is three multiplications by a per-launch stride
+    uint32_t cx, cy, cn;
+    {
+        const uint32_t su = static_cast<uint32_t>(slab_begin);
+        const uint32_t t1 = fdiv(su, a.divSX);
+        cx = su - t1 * pl.sx;
+        cn = fdiv(t1, a.divSY);
+        cy = t1 - cn * pl.sy;
+    }
+    const uint32_t strAx = static_cast<uint32_t>(pl.pw) * w.O * 2u, strAy = static_cast<uint32_t>(pl.ph) * w.Q * w.O * 2u,
+                   strAn = static_cast<uint32_t>(pl.pn) * w.P * w.Q * w.O * 2u;
+    const uint32_t strBx = static_cast<uint32_t>(pl.pw) * w.sw * w.xc * 2u,
+                   strBy = static_cast<uint32_t>(pl.ph) * w.sh * w.W * w.xc * 2u,
+                   strBn = static_cast<uint32_t>(pl.pn) * w.H * w.W * w.xc * 2u;
+    const int strH = pl.ph * w.sh, strW = pl.pw * w.sw;
+
     auto issue = [&](int64_t slab, int stage, bool live) __attribute__((always_inline)) {
         unsigned char* sA = wsm + stage * STAGE_BYTES;
         unsigned char* sB = sA + A_BYTES;
+        if constexpr (BUF) {
+            // a slab past the end of the range (live == false) still issues its loads, all of them reading zeros
+            const uint32_t sA_off = live ? cn * strAn + cy * strAy + cx * strAx : 0u;
+            const uint32_t sB_off = cn * strBn + cy * strBy + cx * strBx;
+            const int hb = static_cast<int>(cy) * strH, wb = static_cast<int>(cx) * strW;
+            const int remN = w.N - static_cast<int>(cn) * pl.pn, remP = w.P - static_cast<int>(cy) * pl.ph,
+                      remQ = w.Q - static_cast<int>(cx) * pl.pw;      // unused when EXACT
+            // advance to the next slab's patch
+            ++cx;
+            if (cx == static_cast<uint32_t>(pl.sx)) {
+                cx = 0;
+                ++cy;
+                if (cy == static_cast<uint32_t>(pl.sy)) {
+                    cy = 0;
+                    ++cn;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                // bitwise, not short-circuit: straight-line code (selects), no branches around the loads
+                const bool pok = EXACT ? live : (live & (dn[t] < remN) & (dy[t] < remP) & (dx[t] < remQ));
+                buf_dma16(rdy, pok ? voffA[t] : kBufOutside, sA_off, sA + (wave + 4 * t) * 1024);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const bool bok = pok & (static_cast<unsigned>(hb + aH[t][h]) < static_cast<unsigned>(w.H)) &
+                                     (static_cast<unsigned>(wb + aW[t][h]) < static_cast<unsigned>(w.W));
+                    buf_dma16(rx, bok ? voffB[t][h] + sB_off : kBufOutside, 0u,
+                              sB + h * A_BYTES + (wave + 4 * t) * 1024);
+                }
+            }
+            return;
+        }
         // patch origin: uniform over the workgroup
         const uint32_t su = static_cast<uint32_t>(slab);
         const uint32_t t1 = fdiv(su, a.divSX);
@@ -397,26 +449,6 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
         const uint32_t sn = fdiv(t1, a.divSY);
         const uint32_t sy = t1 - sn * pl.sy;
         const int n0 = static_cast<int>(sn) * pl.pn, p0 = static_cast<int>(sy) * pl.ph, q0 = static_cast<int>(sx) * pl.pw;
-        if constexpr (BUF) {
-            // a slab past the end of the range (live == false) still issues its loads, all of them reading zeros
-            const uint32_t sA_off = live ? ((static_cast<uint32_t>(n0) * w.P + p0) * w.Q + q0) * w.O * 2u : 0u;
-            const uint32_t sB_off = ((static_cast<uint32_t>(n0) * w.H + p0 * w.sh) * w.W + q0 * w.sw) * w.xc * 2u;
-            const int remN = w.N - n0, remP = w.P - p0, remQ = w.Q - q0;
-            const int hb = p0 * w.sh, wb = q0 * w.sw;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const bool pok = live && (a.exact || (dn[t] < remN && dy[t] < remP && dx[t] < remQ));
-                buf_dma16(rdy, pok ? voffA[t] : kBufOutside, sA_off, sA + (wave + 4 * t) * 1024);
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const bool bok = pok && jok[h] && static_cast<unsigned>(hb + aH[t][h]) < static_cast<unsigned>(w.H) &&
-                                     static_cast<unsigned>(wb + aW[t][h]) < static_cast<unsigned>(w.W);
-                    buf_dma16(rx, bok ? voffB[t][h] + sB_off : kBufOutside, 0u,
-                              sB + h * A_BYTES + (wave + 4 * t) * 1024);
-                }
-            }
-            return;
-        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int n = n0 + dn[t], p = p0 + dy[t], q = q0 + dx[t];
@@ -787,17 +819,20 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
             a.x_bytes = static_cast<uint32_t>(buf ? xb : 0);
             a.exact = (w.N % a.plan.pn == 0 && w.P % a.plan.ph == 0 && w.Q % a.plan.pw == 0) ? 1 : 0;
             if (!allowed) {
-                if (hipFuncSetAttribute(reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess ||
-                    hipFuncSetAttribute(reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)
-                    return TWN_ERR_HIP;
+                const void* ks[3] = {reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, true>),
+                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, false>),
+                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false, false>)};
+                for (const void* kp : ks)
+                    if (hipFuncSetAttribute(kp, hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)
+                        return TWN_ERR_HIP;
                 allowed = true;
             }
-            if (buf)
-                weight_grad_patch_kernel<kStages, true><<<grid, 256, kSmem, st>>>(a);
+            if (buf && a.exact)
+                weight_grad_patch_kernel<kStages, true, true><<<grid, 256, kSmem, st>>>(a);
+            else if (buf)
+                weight_grad_patch_kernel<kStages, true, false><<<grid, 256, kSmem, st>>>(a);
             else
-                weight_grad_patch_kernel<kStages, false><<<grid, 256, kSmem, st>>>(a);
+                weight_grad_patch_kernel<kStages, false, false><<<grid, 256, kSmem, st>>>(a);
         } else {
             weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
         }
