@@ -224,7 +224,18 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         bool kok;
         int ktc;            // buffer path: slab index clamped to the range (slabs past the end re-read the last one)
         int32_t delta_b;    // buffer path, convolution: byte offset of this slab's tap and channel base (wave-uniform)
+        // buffer path, convolution: channel base and tap of the NEXT slab to issue (issue_setup is called for
+        // consecutive slabs, so these run as counters instead of being divided out of the slab index)
+        int nc0, nss, nrr;
     } si;
+    if constexpr (use_buf && !GEMM) {
+        const uint32_t kb = static_cast<uint32_t>(kt_begin) * 64u;
+        const uint32_t rs = fdiv_u(kb, a.divIC);
+        si.nc0 = static_cast<int>(kb - rs * g.IC);
+        si.nrr = static_cast<int>(fdiv_u(rs, a.divS));
+        si.nss = static_cast<int>(rs) - si.nrr * g.S;
+    }
+    const int32_t strR = g.dh * g.IW * static_cast<int>(g.xs) * 2, strS = g.dw * static_cast<int>(g.xs) * 2;
     auto issue_setup = [&](int kt, int stage) __attribute__((always_inline)) {
         si.sbase = smem + stage * STAGE_BYTES;
         si.kt = kt;
@@ -232,14 +243,20 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             // everything here is wave-uniform: scalar instructions only
             si.ktc = (kt < KT) ? kt : KT - 1;
             if (!GEMM) {
-                const uint32_t kb = static_cast<uint32_t>(si.ktc) * 64u;
-                const uint32_t rs = fdiv_u(kb, a.divIC);
-                const int c0 = static_cast<int>(kb - rs * g.IC);
-                const int rr = static_cast<int>(fdiv_u(rs, a.divS));
-                const int ss = static_cast<int>(rs) - rr * g.S;
-                si.dth = rr * g.dh;
-                si.dtw = ss * g.dw;
-                si.delta_b = ((si.dth * g.IW + si.dtw) * static_cast<int>(g.xs) + c0) * 2;
+                si.delta_b = si.nrr * strR + si.nss * strS + si.nc0 * 2;
+                si.dth = si.nrr * g.dh;
+                si.dtw = si.nss * g.dw;
+                // a slab past the end re-reads the last one: the counters stop there
+                if (kt < KT - 1) {
+                    si.nc0 += 64;
+                    if (si.nc0 == g.IC) {
+                        si.nc0 = 0;
+                        if (++si.nss == g.S) {
+                            si.nss = 0;
+                            ++si.nrr;
+                        }
+                    }
+                }
             }
             return;
         }
@@ -264,8 +281,8 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             } else if (GEMM) {
                 buf_dma16(rx, voffA[i], static_cast<uint32_t>(si.ktc) * 128u, si.sbase + (i * NW + wave) * 1024);
             } else {
-                const bool ok = static_cast<unsigned>(ih0[i] + si.dth) < static_cast<unsigned>(g.IH) &&
-                                static_cast<unsigned>(iw0[i] + si.dtw) < static_cast<unsigned>(g.IW);
+                const bool ok = (static_cast<unsigned>(ih0[i] + si.dth) < static_cast<unsigned>(g.IH)) &
+                                (static_cast<unsigned>(iw0[i] + si.dtw) < static_cast<unsigned>(g.IW));
                 buf_dma16(rx, ok ? voffA[i] + static_cast<uint32_t>(si.delta_b) : kBufOutside, 0u,
                           si.sbase + (i * NW + wave) * 1024);
             }
@@ -392,8 +409,6 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                 issue_load(std::integral_constant<int, gi>{});
             }
         };
-        // while this wave is in its MFMA chain it goes first at issue: the SIMD's other wave fills the gaps
-        __builtin_amdgcn_s_setprio(2);
         static_for<NM>([&](auto j_tag) __attribute__((always_inline)) {
             constexpr int j = decltype(j_tag)::value;
             constexpr int mi = j / NI, ni = j % NI;
@@ -411,7 +426,6 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             });
             __builtin_amdgcn_sched_barrier(0);
         });
-        __builtin_amdgcn_s_setprio(0);
         // everything read during this step is needed by the next one
         lds_wait<0>();
         lds_ready<MI>(afrag[NSET]);
