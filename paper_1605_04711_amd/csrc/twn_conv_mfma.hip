@@ -434,7 +434,7 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
         if (tile == 0) {
             auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
             if (g.splits > 1) tile = 12;
-            else if (g.NC <= 64) tile = 13;
+            else if (g.NC <= 64) tile = 16;
             else if (g.NC <= 128) tile = 12;
             else tile = (blocks(128, 256) >= 512) ? 17 : 12;
             // at most one 128x128 workgroup per CU: 64x128 tiles double the workgroups (layers with few pixels)

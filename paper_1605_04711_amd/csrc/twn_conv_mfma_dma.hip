@@ -711,16 +711,16 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
                         : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, false>(a, blocks, st);
 }
 
-// Tile ids (BM x BN, waves, stages): 12 = 128x128 2x2 S3, 13 = 128x64 4x1 S3, 14 = 64x128 1x4 S3,
-// 15 = 128x128 1x4 S3,
+// Tile ids (BM x BN, waves, stages): 12 = 128x128 2x2 S3, 14 = 64x128 1x4 S3, 15 = 128x128 1x4 S3,
+// 16 = 128x64 2x2 S3,
 // 17 = 128x256 1x4 S4, 24 = 128x512 1x8 S4, 30 = 256x256 2x2 S3
 // (30: 16 accumulator tiles per wave, pinned by hand; only on request, it is not faster than 17)
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
     switch (tile) {
         case 12: return launch_dma_tile<128, 128, 2, 2, 3>(g, st);
-        case 13: return launch_dma_tile<128, 64, 4, 1, 3>(g, st);
         case 14: return launch_dma_tile<64, 128, 1, 4, 3>(g, st);
         case 15: return launch_dma_tile<128, 128, 1, 4, 3>(g, st);
+        case 16: return launch_dma_tile<128, 64, 2, 2, 3>(g, st);
         case 17: return launch_dma_tile<128, 256, 1, 4, 4>(g, st);
         case 24: return launch_dma_tile<128, 512, 1, 8, 4>(g, st);
         case 30: return launch_dma_tile<256, 256, 2, 2, 3>(g, st);
