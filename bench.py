@@ -183,7 +183,8 @@ def main():
 
     # One step.  Main stream: ONE multi-tensor ternarize call (three launches for the eight tensors), then the
     # forward of every layer.  Backward: the data gradients and the weight gradients of a layer do not depend
-    # on each other, so they run on two streams forked from the main stream after the forward and joined at
+    # on each other (nor do the weight gradients of different layers), so they run on side streams forked from
+    # the main stream after the forward and joined at
     # the end (the tail of one kernel is filled by the other stream's work).  `calls` lists every library
     # call as (phase, layer index, callable(stream)); the one-tensor ternarize entry point is timed per
     # layer in the detail pass below.
@@ -206,24 +207,27 @@ def main():
             X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True, dW=dW[li], workspace=wsw[li], stream=st_)))
     dx_calls = [c for c in calls if c[0] == "bwd_data"]
     dw_calls = [c for c in calls if c[0] == "bwd_weight"]
-    side_a, side_b = torch.cuda.Stream(), torch.cuda.Stream()     # default priority
+    # default priority; the weight gradients of different layers are independent too, so they alternate between
+    # two streams: the reduction pass of one layer overlaps the main pass of the next
+    side_a, side_b, side_c = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    n_dw_streams = int(os.environ.get("TWN_BENCH_DW_STREAMS", "2"))
 
     def backward():
         cur = torch.cuda.current_stream()
         fork = torch.cuda.Event()
         fork.record(cur)
-        side_a.wait_event(fork)
-        side_b.wait_event(fork)
-        # interleave the launches layer by layer so neither stream runs ahead of the host
+        sides = [side_a, side_b] + ([side_c] if n_dw_streams > 1 else [])
+        for st_ in sides:
+            st_.wait_event(fork)
+        # interleave the launches layer by layer so no stream runs ahead of the host
         for i in range(len(dw_calls)):
             if i < len(dx_calls):
                 dx_calls[i][2](side_a)
-            dw_calls[i][2](side_b)
-        ja, jb = torch.cuda.Event(), torch.cuda.Event()
-        ja.record(side_a)
-        jb.record(side_b)
-        cur.wait_event(ja)
-        cur.wait_event(jb)
+            dw_calls[i][2](side_c if (n_dw_streams > 1 and i % 2) else side_b)
+        for st_ in sides:
+            j = torch.cuda.Event()
+            j.record(st_)
+            cur.wait_event(j)
 
     def one_step(marks=None):
         for ci in range(n_main):
