@@ -275,10 +275,8 @@ extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const v
         hipStream_t st = as_stream(stream);
         uint16_t* Xp = static_cast<uint16_t*>(workspace);
         uint32_t* Wp = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + sc.x_bytes);
-        rc = launch_pad_c4(static_cast<const uint16_t*>(X), d->N, d->H, d->W, d->C, d->pad_h, d->pad_w, sc.Hp, sc.Wp,
-                           Xp, st);
-        if (rc == TWN_OK)
-            rc = launch_repack_c4(static_cast<const uint32_t*>(weights), d->O, d->C, d->R, d->S, sc.Sp, Wp, st);
+        rc = launch_pad_repack_c4(static_cast<const uint16_t*>(X), d->N, d->H, d->W, d->C, d->pad_h, d->pad_w, sc.Hp,
+                                  sc.Wp, Xp, static_cast<const uint32_t*>(weights), d->O, d->R, d->S, sc.Sp, Wp, st);
         if (rc != TWN_OK) return rc;
         g.X = Xp;
         g.Wq = Wp;

@@ -317,9 +317,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
     }
 }
 
-__global__ __launch_bounds__(256) void pad_c4_kernel(const uint16_t* __restrict__ X, int N, int H, int W, int C,
-                                                     int ph, int pw, int Hp, int Wp, uint16_t* __restrict__ Xp) {
-    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void pad_c4_body(const uint16_t* __restrict__ X, int N, int H, int W, int C, int ph, int pw,
+                                            int Hp, int Wp, uint16_t* __restrict__ Xp, int64_t block) {
+    const int64_t id = block * blockDim.x + threadIdx.x;
     const int64_t total = static_cast<int64_t>(N) * Hp * Wp;
     if (id >= total) return;
     const int wp = static_cast<int>(id % Wp);
@@ -338,9 +338,14 @@ __global__ __launch_bounds__(256) void pad_c4_kernel(const uint16_t* __restrict_
     *reinterpret_cast<u32x2*>(Xp + id * 4) = o;
 }
 
-__global__ __launch_bounds__(256) void repack_c4_kernel(const uint32_t* __restrict__ packed, int rows, int C, int R,
-                                                        int S, int Sp, int wpr, int wpr2, uint32_t* __restrict__ out) {
-    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void pad_c4_kernel(const uint16_t* __restrict__ X, int N, int H, int W, int C,
+                                                     int ph, int pw, int Hp, int Wp, uint16_t* __restrict__ Xp) {
+    pad_c4_body(X, N, H, W, C, ph, pw, Hp, Wp, Xp, blockIdx.x);
+}
+
+__device__ __forceinline__ void repack_c4_body(const uint32_t* __restrict__ packed, int rows, int C, int R, int S, int Sp,
+                                               int wpr, int wpr2, uint32_t* __restrict__ out, int64_t block) {
+    const int64_t id = block * blockDim.x + threadIdx.x;
     if (id >= static_cast<int64_t>(rows) * wpr2) return;
     const int row = static_cast<int>(id / wpr2), j = static_cast<int>(id % wpr2);
     uint32_t word = 0;
@@ -360,20 +365,37 @@ __global__ __launch_bounds__(256) void repack_c4_kernel(const uint32_t* __restri
     out[id] = word;
 }
 
+// Both preparations of the first-layer path in one launch: the first pad_blocks workgroups copy X, the rest
+// re-order the codes (the two are independent, and a launch costs more than either of them).
+__global__ __launch_bounds__(256) void pad_repack_c4_kernel(const uint16_t* __restrict__ X, int N, int H, int W, int C,
+                                                            int ph, int pw, int Hp, int Wp, uint16_t* __restrict__ Xp,
+                                                            unsigned pad_blocks, const uint32_t* __restrict__ packed,
+                                                            int rows, int R, int S, int Sp, int wpr, int wpr2,
+                                                            uint32_t* __restrict__ out) {
+    if (blockIdx.x < pad_blocks)
+        pad_c4_body(X, N, H, W, C, ph, pw, Hp, Wp, Xp, blockIdx.x);
+    else
+        repack_c4_body(packed, rows, C, R, S, Sp, wpr, wpr2, out, blockIdx.x - pad_blocks);
+}
+
+int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp, uint16_t* Xp,
+                             const uint32_t* packed, int rows, int R, int S, int Sp, uint32_t* out, hipStream_t st) {
+    const int64_t total_x = static_cast<int64_t>(N) * Hp * Wp;
+    const int wpr = static_cast<int>(twn_packed_words_per_row(static_cast<int64_t>(R) * S * C));
+    const int wpr2 = static_cast<int>(twn_packed_words_per_row(static_cast<int64_t>(R) * Sp * 4));
+    const int64_t total_w = static_cast<int64_t>(rows) * wpr2;
+    const int64_t pad_blocks = (total_x + 255) / 256, blocks = pad_blocks + (total_w + 255) / 256;
+    if (blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
+    pad_repack_c4_kernel<<<static_cast<unsigned>(blocks), 256, 0, st>>>(X, N, H, W, C, ph, pw, Hp, Wp, Xp,
+                                                                     static_cast<unsigned>(pad_blocks), packed, rows, R, S,
+                                                                     Sp, wpr, wpr2, out);
+    return launch_status();
+}
+
 int32_t launch_pad_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp,
                       uint16_t* Xp, hipStream_t st) {
     const int64_t total = static_cast<int64_t>(N) * Hp * Wp;
     pad_c4_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(X, N, H, W, C, ph, pw, Hp, Wp, Xp);
-    return launch_status();
-}
-
-int32_t launch_repack_c4(const uint32_t* packed, int rows, int C, int R, int S, int Sp, uint32_t* out,
-                         hipStream_t st) {
-    const int wpr = static_cast<int>(twn_packed_words_per_row(static_cast<int64_t>(R) * S * C));
-    const int wpr2 = static_cast<int>(twn_packed_words_per_row(static_cast<int64_t>(R) * Sp * 4));
-    const int64_t total = static_cast<int64_t>(rows) * wpr2;
-    repack_c4_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(packed, rows, C, R, S, Sp, wpr, wpr2,
-                                                                                out);
     return launch_status();
 }
 
