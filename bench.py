@@ -44,6 +44,7 @@ def main():
                     help="run one side measurement alone (used for the rocprofv3 summaries in profiles/)")
     ap.add_argument("--variants", action="store_true", help="with --only gemm: also time the comparison weight formats")
     ap.add_argument("--graph", action="store_true", help="also capture the step into a HIP graph and time its replay")
+    ap.add_argument("--eager-backward", action="store_true", help="launch the backward eagerly instead of replaying its HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -229,6 +230,8 @@ def main():
             j.record(st_)
             cur.wait_event(j)
 
+    bwd_graph = None
+
     def one_step(marks=None):
         for ci in range(n_main):
             if marks is not None and ci in marks:
@@ -236,11 +239,46 @@ def main():
             calls[ci][2]()
         if marks is not None and n_main in marks:
             marks[n_main].record()
-        backward()
+        if bwd_graph is not None:
+            bwd_graph.replay()
+        else:
+            backward()
 
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
+
+    # The backward (27 launches on three streams) is captured once into a HIP graph and replayed in every step:
+    # the library only launches kernels and takes its workspaces from the caller, so it captures as is.  The
+    # forward stays eager because the roofline events sit between its launches.  Replays are checked against
+    # the eager results (bit for bit) before they are used.
+    if not args.eager_backward:
+        outs_b = [t for t in dX[1:]] + list(dW)
+        ref_b = [t.clone() for t in outs_b]
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap):
+            backward()
+        torch.cuda.synchronize()
+        g_ = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_, stream=cap):
+            backward()
+        torch.cuda.synchronize()
+        ok = True
+        for _ in range(2):
+            for t in outs_b:
+                t.zero_()
+            calls[1][2]()                  # eager work between two replays
+            torch.cuda.synchronize()
+            g_.replay()
+            torch.cuda.synchronize()
+            ok = ok and all(torch.equal(a, b) for a, b in zip(ref_b, outs_b))
+        if not ok:
+            sys.exit("bench.py: the captured backward does not reproduce the eager results")
+        bwd_graph = g_
+        for _ in range(args.warmup):
+            one_step()
+        torch.cuda.synchronize()
 
     # Timed region.  HIP events on the launch stream (torch's current stream) bracket each forward call that is
     # exactly one launch of the contraction kernel (the roofline sample: forward c2-c6, which run alone on
@@ -280,7 +318,10 @@ def main():
         for ci in range(1, n_main):
             calls[ci][2]()
         pev[s][2].record()
-        backward()
+        if bwd_graph is not None:
+            bwd_graph.replay()
+        else:
+            backward()
         pev[s][3].record()
     torch.cuda.synchronize()
     phase_ms = [sum(pev[s][i].elapsed_time(pev[s][i + 1]) for s in range(NPH)) / NPH for i in range(3)]
@@ -339,17 +380,23 @@ def main():
         # the same step captured once into a HIP graph and replayed (the library only launches kernels and takes
         # its workspaces from the caller, so a step captures as is); outputs are compared with the eager step's
         outs = (Y[1], Y[7], dX[1], dW[1], dW[5], dW[7])
-        one_step()
+
+        def full_step():
+            for ci in range(n_main):
+                calls[ci][2]()
+            backward()
+
+        full_step()
         torch.cuda.synchronize()
         ref = [t.clone() for t in outs]
         cap = torch.cuda.Stream()
         cap.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(cap):
-            one_step()
+            full_step()
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=cap):
-            one_step()
+            full_step()
         torch.cuda.synchronize()
         same = True
         for _ in range(3):
