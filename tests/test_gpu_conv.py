@@ -456,3 +456,23 @@ def test_library_calls_capture_into_a_graph_and_replay():
         torch.cuda.synchronize()
         for a, b in zip(ref, outs):
             assert torch.equal(a, b)
+
+
+def test_per_lane_pointer_load_path(monkeypatch):
+    # tensors of 2 GiB and more cannot use buffer descriptors and fall back to per-lane pointers; the switch
+    # that forces that path keeps it covered at test sizes: GEMM, convolution, both gradients
+    monkeypatch.setenv("TWN_BUFLOAD", "0")
+    m, n, k = 520, 300, 448
+    x, w, tw, codes, alpha = make_layer(41, (m, k), (n, k))
+    y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
+    assert rel_err(to_host_f64(y), oc.gemm_fwd(x, codes.reshape(n, k), alpha)) <= 1e-4
+    for ci in (1, 2):
+        nb, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
+        x, w, tw, codes, alpha = make_layer(42 + ci, (nb, h, w_, c), (o, c, r, s), transposed=True)
+        ref = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+        y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, y_dtype=torch.float32)
+        assert rel_err(to_host_f64(y), ref) <= 1e-4
+        dy = wl.bf16_round(np.random.default_rng(45 + ci).standard_normal(ref.shape).astype(np.float32))
+        dx, dw, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, dx_dtype=torch.float32)
+        assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)) <= 1e-4
+        assert rel_err(to_host_f64(dw), oc.conv2d_bwd_weight(x, dy, codes.shape, st, pd, dl)) <= 1e-4
