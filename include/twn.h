@@ -197,7 +197,10 @@ int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weight
  * (with packed_T/alpha), dW (with X), dbias may be NULL to skip that part.
  * dW_beta is 0 (overwrite) or 1 (accumulate).  A fully-connected layer is the
  * case H=W=R=S=1.  d->variant may be TWN_VAR_BF16_POSTSCALE or
- * TWN_VAR_BF16_ALPHA_LDS (it only affects dX); others: TWN_ERR_UNSUPPORTED. */
+ * TWN_VAR_BF16_ALPHA_LDS (it only affects dX); others: TWN_ERR_UNSUPPORTED.
+ * With alpha_groups > 1 (one alpha per filter group, Alg. 1) alpha_o is a
+ * factor inside the sum over o: dX then needs a workspace, where dY is first
+ * scaled per channel (rounded once more to bf16) before the contraction. */
 size_t  twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d);
 int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY,
                            const uint32_t* packed_T, const float* alpha,

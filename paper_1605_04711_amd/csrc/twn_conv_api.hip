@@ -181,6 +181,12 @@ void fill_conv_fwd_small_c(GatherGemm& g, const twn_conv_desc* d, const SmallC& 
     g.chunk_gather = 1;
 }
 
+// Backward-data with one alpha per group of filters: scaled copy of dY + one float (the unit alpha).
+size_t scaled_dy_bytes(const twn_conv_desc* d, int P, int Q) {
+    if (d->alpha_groups == 1) return 0;
+    return round_up(static_cast<size_t>(d->N) * P * Q * d->O * sizeof(uint16_t), 256) + 256;
+}
+
 // Weight-gradient workspace: [padded copy of X in first-layer mode] + split partials + bias partials.
 size_t weight_grad_bytes(const twn_conv_desc* d, int P, int Q) {
     SmallC sc;
@@ -292,7 +298,7 @@ extern "C" size_t twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d) {
     // the data-gradient split-K partials and the weight-gradient partials use the workspace one after the other
     GatherGemm g{};
     fill_conv_bwd_data(g, d, P, Q);
-    const size_t a = splitk_bytes(g, d->variant);
+    const size_t a = scaled_dy_bytes(d, P, Q) + splitk_bytes(g, d->variant);
     const size_t b = weight_grad_bytes(d, P, Q);
     return a > b ? a : b;
 }
@@ -324,16 +330,31 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
     hipStream_t st = as_stream(stream);
 
     if (dX) {
-        // alpha multiplies per forward output channel o, which is a K index here: only a
-        // single alpha can be applied after the sum.
-        if (d->alpha_groups != 1) return TWN_ERR_UNSUPPORTED;
         GatherGemm g{};
         g.X = dY;
         g.Wq = packed_T;
         g.alpha = alpha;
         g.Y = dX;
         fill_conv_bwd_data(g, d, P, Q);
-        rc = dispatch(g, d->variant, workspace, workspace_bytes, st);
+        unsigned char* ws = static_cast<unsigned char*>(workspace);
+        size_t ws_bytes = workspace_bytes;
+        const size_t head = scaled_dy_bytes(d, P, Q);
+        if (head) {
+            // alpha multiplies per forward output channel o, which is a K index here: with several alphas dY is
+            // scaled first (into the workspace) and the contraction runs with alpha = 1
+            if (!workspace || workspace_bytes < head + splitk_bytes(g, d->variant) || !aligned(workspace, 256))
+                return TWN_ERR_WORKSPACE;
+            uint16_t* scaled = static_cast<uint16_t*>(workspace);
+            float* one = reinterpret_cast<float*>(ws + head - 256);
+            rc = launch_scale_channels(static_cast<const uint16_t*>(dY), alpha, d->O / d->alpha_groups, d->O,
+                                       static_cast<int64_t>(d->N) * P * Q, scaled, one, st);
+            if (rc != TWN_OK) return rc;
+            g.X = scaled;
+            g.alpha = one;
+            ws += head;
+            ws_bytes -= head;
+        }
+        rc = dispatch(g, d->variant, ws, ws_bytes, st);
         if (rc != TWN_OK) return rc;
     }
     if (dW || dbias) {

@@ -392,6 +392,29 @@ int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int 
     return launch_status();
 }
 
+// Per-filter alpha in backward-data (Alg. 1 with one alpha per filter): alpha multiplies per forward output
+// channel o, which is a reduction index of dX, so it cannot be applied after the sum.  dY is scaled instead,
+// out[p][o] = bf16(dY[p][o] * alpha[o / rows_per_group]) (one extra rounding to bf16), and the contraction then
+// runs with alpha = 1, which thread 0 writes to `one`.
+__global__ __launch_bounds__(256) void scale_channels_kernel(const uint16_t* __restrict__ dY, const float* __restrict__ alpha,
+                                                             int rows_per_group, int O, int64_t total,
+                                                             uint16_t* __restrict__ out, float* __restrict__ one) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (id == 0) *one = 1.0f;
+    if (id >= total) return;
+    const int o = static_cast<int>(id % O);
+    out[id] = f32_to_bf16(bf16_to_f32(dY[id]) * alpha[o / rows_per_group]);
+}
+
+int32_t launch_scale_channels(const uint16_t* dY, const float* alpha, int rows_per_group, int O, int64_t pixels,
+                              uint16_t* out, float* one, hipStream_t st) {
+    const int64_t total = pixels * O;
+    if (total <= 0 || (total + 255) / 256 >= (1LL << 31)) return TWN_ERR_SHAPE;
+    scale_channels_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(dY, alpha, rows_per_group, O, total,
+                                                                                   out, one);
+    return launch_status();
+}
+
 int32_t launch_pad_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp,
                       uint16_t* Xp, hipStream_t st) {
     const int64_t total = static_cast<int64_t>(N) * Hp * Wp;
