@@ -391,6 +391,35 @@ def test_full_size_vgg7_backward_sampled(name):
         assert rel_err(to_host_f64(dx).ravel()[i1], ref_dx) <= BF16_TOL
 
 
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5", "c6", "fc1", "fc2"])
+def test_full_size_vgg7_forward_sampled(name):
+    """The timed workload's forward calls at full size, as bench.py launches them (fused scale/shift/ReLU tail,
+    weights ternarized by the multi-tensor call); sampled outputs plus the image corners against the oracle."""
+    all_layers = wl.vgg7(128)
+    layers = {l.name: (i, l) for i, l in enumerate(all_layers)}
+    li, layer = layers[name]
+    x = wl.bf16_round(wl.normal(1, wl.IDX_INPUT + li, layer.x_shape))
+    w = wl.kaiming_weights(1, li, layer)
+    tw = api.twn_ternarize_batch([to_dev_f32(w)], F, transposed=True)[0]
+    codes, delta, alpha, nnz = ot.ternarize(w if w.ndim == 4 else w.reshape(w.shape[0], w.shape[1], 1, 1), F)
+    g = np.random.default_rng(900 + li)
+    scale = g.uniform(0.5, 1.5, layer.O).astype(np.float32)
+    shift = (0.1 * g.standard_normal(layer.O)).astype(np.float32)
+    st, pd, dl = (layer.stride,) * 2, (layer.pad,) * 2, (layer.dil,) * 2
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, scale=to_dev_f32(scale), shift=to_dev_f32(shift), relu=True)
+    total = int(np.prod(layer.y_shape))
+    n_, p_, q_, o_ = layer.y_shape
+    corners = [((b * p_ + pp) * q_ + qq) * o_ for b in (0, n_ - 1) for pp in (0, p_ - 1) for qq in (0, q_ - 1)]
+    idx = np.unique(np.concatenate([_sample(total, 20000, li), np.array(corners), np.array([total - 1])]))
+    z = oc.conv2d_fwd_at(x, codes, alpha, idx, st, pd, dl)
+    ch = idx % o_
+    ref = np.maximum(z * scale[ch].astype(np.float64) + shift[ch].astype(np.float64), 0.0)
+    got = to_host_f64(y).ravel()[idx]
+    # relative to the magnitudes before the ReLU cut (a clipped output has no scale of its own)
+    floor = 1e-2 * np.sqrt(np.mean(z * z))
+    assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), floor)) <= BF16_TOL
+
+
 def test_library_calls_capture_into_a_graph_and_replay():
     # the library only launches kernels and takes its workspaces from the caller, so a ternarize + forward +
     # two-stream backward sequence captures into a HIP graph; every replay (with eager work and
