@@ -198,6 +198,10 @@ int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weight
  * dW_beta is 0 (overwrite) or 1 (accumulate).  A fully-connected layer is the
  * case H=W=R=S=1.  d->variant may be TWN_VAR_BF16_POSTSCALE or
  * TWN_VAR_BF16_ALPHA_LDS (it only affects dX); others: TWN_ERR_UNSUPPORTED.
+ * Strided layers with dilation 1 and O % 64 == 0 compute dX as one stride-1
+ * problem per residue class of the output pixels when the workspace of
+ * twn_conv2d_bwd_ste_workspace_bytes is passed (otherwise, and for other
+ * shapes, by the generic gather: same result, slower).
  * With alpha_groups > 1 (one alpha per filter group, Alg. 1) alpha_o is a
  * factor inside the sum over o: dX then needs a workspace, where dY is first
  * scaled per channel (rounded once more to bf16) before the contraction. */

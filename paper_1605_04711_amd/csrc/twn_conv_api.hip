@@ -181,6 +181,79 @@ void fill_conv_fwd_small_c(GatherGemm& g, const twn_conv_desc* d, const SmallC& 
     g.chunk_gather = 1;
 }
 
+// Strided backward-data as stride-1 problems, one per residue class (a, b) of the output pixels
+// (h = a + sh*u, w = b + sw*v): the taps that reach the class are r = r0 + jr*sh with r0 = (a + pad_h) % sh, the
+// coordinate read is p = u + (a + pad_h - r0)/sh - jr, i.e. an undivided gather with dilation -1.  Used for
+// dilation 1, O % 64 == 0 (every tap is whole K slabs), C % 8 == 0, stride products up to 4.
+struct DxClasses {
+    int count;                  // classes that have taps
+    bool any_empty;             // some class has none: those pixels of dX are zero
+    GatherGemm g[4];
+    DxClassTable tb;
+    int64_t code_words;
+};
+
+bool strided_dx_classes(const twn_conv_desc* d, int P, int Q, DxClasses* out) {
+    const int sh = d->stride_h, sw = d->stride_w;
+    if (sh * sw <= 1 || sh * sw > 4 || d->dil_h != 1 || d->dil_w != 1 || d->O % 64 != 0 || d->C % 8 != 0 ||
+        d->variant != TWN_VAR_BF16_POSTSCALE || d->x_dtype != TWN_BF16 || d->alpha_groups != 1)
+        return false;
+    // several small launches only pay when each class still has enough pixels to fill the chip
+    if (static_cast<int64_t>(d->N) * ((d->H + sh - 1) / sh) * ((d->W + sw - 1) / sw) < env_int("TWN_DX_CLASS_MIN_PIXELS", 8192))
+        return false;
+    out->count = 0;
+    out->any_empty = false;
+    out->code_words = 0;
+    for (int a = 0; a < sh; ++a)
+        for (int b = 0; b < sw; ++b) {
+            const int U = (d->H - a + sh - 1) / sh, V = (d->W - b + sw - 1) / sw;
+            if (U <= 0 || V <= 0) continue;         // no pixel in this class
+            const int r0 = (a + d->pad_h) % sh, s0 = (b + d->pad_w) % sw;
+            const int nr = r0 < d->R ? (d->R - r0 + sh - 1) / sh : 0, ns = s0 < d->S ? (d->S - s0 + sw - 1) / sw : 0;
+            if (nr == 0 || ns == 0) {
+                out->any_empty = true;
+                continue;
+            }
+            const int k = out->count++;
+            GatherGemm& g = out->g[k];
+            g = GatherGemm{};
+            fill_conv_bwd_data(g, d, P, Q);
+            g.M = static_cast<int64_t>(d->N) * U * V;
+            g.OH = U;
+            g.OW = V;
+            g.R = nr;
+            g.S = ns;
+            g.ph = -((a + d->pad_h - r0) / sh);
+            g.pw = -((b + d->pad_w - s0) / sw);
+            g.dh = g.dw = -1;
+            g.divh = g.divw = 1;
+            g.K = nr * ns * d->O;
+            g.wpr = static_cast<int32_t>(twn_packed_words_per_row(g.K));
+            g.plain_gemm = 0;
+            g.orU = U; g.orV = V; g.orH = d->H; g.orW = d->W;
+            g.ora = a; g.orb = b; g.orsh = sh; g.orsw = sw;
+            out->tb.r0[k] = r0; out->tb.nr[k] = nr; out->tb.s0[k] = s0; out->tb.ns[k] = ns;
+            out->tb.wpr[k] = g.wpr;
+            out->tb.first_word[k] = out->code_words;
+            out->code_words += static_cast<int64_t>(d->C) * g.wpr;
+        }
+    out->tb.count = out->count;
+    for (int k = out->count; k <= 4; ++k) out->tb.first_word[k] = out->code_words;
+    return out->count > 0;
+}
+
+// Workspace of the class path: gathered codes (256-byte multiple) + the largest split-K need of a class.
+size_t strided_dx_bytes(const twn_conv_desc* d, int P, int Q) {
+    DxClasses cl;
+    if (!strided_dx_classes(d, P, Q, &cl)) return 0;
+    size_t split = 0;
+    for (int k = 0; k < cl.count; ++k) {
+        const size_t b = splitk_bytes(cl.g[k], d->variant);
+        if (b > split) split = b;
+    }
+    return round_up(static_cast<size_t>(cl.code_words) * sizeof(uint32_t), 256) + split;
+}
+
 // Backward-data with one alpha per group of filters: scaled copy of dY + one float (the unit alpha).
 size_t scaled_dy_bytes(const twn_conv_desc* d, int P, int Q) {
     if (d->alpha_groups == 1) return 0;
@@ -298,7 +371,9 @@ extern "C" size_t twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d) {
     // the data-gradient split-K partials and the weight-gradient partials use the workspace one after the other
     GatherGemm g{};
     fill_conv_bwd_data(g, d, P, Q);
-    const size_t a = scaled_dy_bytes(d, P, Q) + splitk_bytes(g, d->variant);
+    size_t a = scaled_dy_bytes(d, P, Q) + splitk_bytes(g, d->variant);
+    const size_t a2 = strided_dx_bytes(d, P, Q);
+    if (a2 > a) a = a2;
     const size_t b = weight_grad_bytes(d, P, Q);
     return a > b ? a : b;
 }
@@ -329,7 +404,32 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
     }
     hipStream_t st = as_stream(stream);
 
-    if (dX) {
+    DxClasses cl;
+    if (dX && env_int("TWN_DX_CLASSES", 1) != 0 && strided_dx_classes(d, P, Q, &cl) && workspace &&
+        workspace_bytes >= strided_dx_bytes(d, P, Q) && aligned(workspace, 256) && aligned(dX, 16)) {
+        // strided layer: one stride-1 contraction per residue class of the output pixels
+        const size_t code_bytes = round_up(static_cast<size_t>(cl.code_words) * sizeof(uint32_t), 256);
+        uint32_t* codes = static_cast<uint32_t*>(workspace);
+        rc = launch_gather_class_codes(packed_T, d->C, static_cast<int>(twn_packed_words_per_row(
+                                           static_cast<int64_t>(d->R) * d->S * d->O)),
+                                       d->S, d->O, d->stride_h, d->stride_w, cl.tb, cl.code_words, codes, st);
+        if (rc != TWN_OK) return rc;
+        if (cl.any_empty) {
+            const int64_t bytes = static_cast<int64_t>(d->N) * d->H * d->W * d->C * (d->y_dtype == TWN_F32 ? 4 : 2);
+            rc = launch_zero_fill(dX, bytes, st);
+            if (rc != TWN_OK) return rc;
+        }
+        for (int k = 0; k < cl.count; ++k) {
+            GatherGemm& g = cl.g[k];
+            g.X = dY;
+            g.Wq = codes + cl.tb.first_word[k];
+            g.alpha = alpha;
+            g.Y = dX;
+            rc = dispatch(g, d->variant, static_cast<unsigned char*>(workspace) + code_bytes,
+                          workspace_bytes - code_bytes, st);
+            if (rc != TWN_OK) return rc;
+        }
+    } else if (dX) {
         GatherGemm g{};
         g.X = dY;
         g.Wq = packed_T;

@@ -415,6 +415,50 @@ int32_t launch_scale_channels(const uint16_t* dY, const float* alpha, int rows_p
     return launch_status();
 }
 
+// Strided backward-data as one stride-1 problem per residue class of the output pixels: the taps that reach
+// class (a, b) are r = r0 + jr*sh, s = s0 + js*sw.  Their codes are gathered from the transposed copy into a
+// contiguous K range per class: out[class][c][(jr*ns + js)*O/16 + t] = packed_T[c][((r0+jr*sh)*S + s0+js*sw)*O/16 + t].
+__global__ __launch_bounds__(256) void gather_class_codes_kernel(const uint32_t* __restrict__ packed_T, int C, int wprT, int S,
+                                                                 int O16, int sh, int sw, DxClassTable tb,
+                                                                 uint32_t* __restrict__ out) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    int k = 0;
+    while (k + 1 < tb.count && id >= tb.first_word[k + 1]) ++k;
+    const int64_t local = id - tb.first_word[k];
+    const int wpr = tb.wpr[k];
+    if (k >= tb.count || local >= static_cast<int64_t>(C) * wpr) return;
+    const int c = static_cast<int>(local / wpr), j = static_cast<int>(local % wpr);
+    uint32_t word = 0u;
+    if (j < tb.nr[k] * tb.ns[k] * O16) {
+        const int tap = j / O16, t = j % O16;
+        const int jr = tap / tb.ns[k], js = tap % tb.ns[k];
+        const int src_tap = (tb.r0[k] + jr * sh) * S + tb.s0[k] + js * sw;
+        word = packed_T[static_cast<int64_t>(c) * wprT + static_cast<int64_t>(src_tap) * O16 + t];
+    }
+    out[id] = word;
+}
+
+int32_t launch_gather_class_codes(const uint32_t* packed_T, int C, int wprT, int S, int O, int sh, int sw,
+                                  const DxClassTable& tb, int64_t total_words, uint32_t* out, hipStream_t st) {
+    if (total_words <= 0 || (total_words + 255) / 256 >= (1LL << 31)) return TWN_ERR_SHAPE;
+    gather_class_codes_kernel<<<static_cast<unsigned>((total_words + 255) / 256), 256, 0, st>>>(packed_T, C, wprT, S, O / 16,
+                                                                                             sh, sw, tb, out);
+    return launch_status();
+}
+
+// Zero fill in 16-byte units (a kernel rather than a memset, so that callers may capture it into a graph).
+__global__ __launch_bounds__(256) void zero_fill_kernel(u32x4* __restrict__ p, int64_t n16) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (id < n16) p[id] = u32x4{0u, 0u, 0u, 0u};
+}
+
+int32_t launch_zero_fill(void* p, int64_t bytes, hipStream_t st) {
+    const int64_t n16 = bytes / 16;
+    if (bytes % 16 != 0 || n16 <= 0 || (n16 + 255) / 256 >= (1LL << 31)) return TWN_ERR_SHAPE;
+    zero_fill_kernel<<<static_cast<unsigned>((n16 + 255) / 256), 256, 0, st>>>(static_cast<u32x4*>(p), n16);
+    return launch_status();
+}
+
 int32_t launch_pad_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp,
                       uint16_t* Xp, hipStream_t st) {
     const int64_t total = static_cast<int64_t>(N) * Hp * Wp;

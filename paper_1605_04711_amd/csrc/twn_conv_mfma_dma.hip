@@ -33,7 +33,19 @@ struct DmaArgs {
     // convolution without tap division whose channel count is a multiple of 64, so that a slab is one tap)
     int32_t use_buf;
     uint32_t x_bytes, w_bytes;
+    FastDivU divUV, divV;       // output row remap (g.orU > 0): row -> (image, u, v)
 };
+
+// Row of Y that GEMM row m is written to (see GatherGemm::orU).
+__device__ __forceinline__ int64_t out_row(const GatherGemm& g, const FastDivU& divUV, const FastDivU& divV, int64_t m) {
+    if (g.orU == 0) return m;
+    const uint32_t mu = static_cast<uint32_t>(m);
+    const uint32_t n = fdiv_u(mu, divUV);
+    const uint32_t rem = mu - n * static_cast<uint32_t>(g.orU * g.orV);
+    const uint32_t u = fdiv_u(rem, divV);
+    const uint32_t v = rem - u * static_cast<uint32_t>(g.orV);
+    return (static_cast<int64_t>(n) * g.orH + g.ora + g.orsh * static_cast<int>(u)) * g.orW + g.orb + g.orsw * static_cast<int>(v);
+}
 
 // LDS reads of the main loop are written as inline assembly with hand-placed s_waitcnt lgkmcnt(n): the
 // compiler's own wait insertion falls back to lgkmcnt(0) in this loop, which also waits for the reads
@@ -549,7 +561,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 #pragma unroll
                         for (int e = 0; e < 4; ++e) v[e] = t[q4 * 4 + e] * mul[e] + add[e];
                         if (res && m < g.M && n0 + nl < g.NC) {
-                            const u32x2 rr = *reinterpret_cast<const u32x2*>(res + m * g.ldy + n0 + nl);
+                            const u32x2 rr = *reinterpret_cast<const u32x2*>(res + out_row(g, a.divUV, a.divV, m) * g.ldy + n0 + nl);
                             v[0] += __uint_as_float(rr[0] << 16);
                             v[1] += __uint_as_float(rr[0] & 0xFFFF0000u);
                             v[2] += __uint_as_float(rr[1] << 16);
@@ -575,7 +587,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                 const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
                 const int64_t m = m0 + wm * TM + row;
                 const int ncol = n0 + wn * TN + nc * EPI_CH + c16 * 8;
-                if (m < g.M && ncol < g.NC) *reinterpret_cast<u32x4*>(Yb + m * g.ldy + ncol) = val;
+                if (m < g.M && ncol < g.NC) *reinterpret_cast<u32x4*>(Yb + out_row(g, a.divUV, a.divV, m) * g.ldy + ncol) = val;
             }
         }
     } else {
@@ -583,6 +595,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         for (int mi = 0; mi < MI; ++mi) {
             const int64_t m = m0 + wm * TM + mi * 32 + lrow;
             if (m >= g.M) continue;
+            const int64_t orow = out_row(g, a.divUV, a.divV, m);
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
                 const f32x16 t = acc_tile(mi, ni);
@@ -592,7 +605,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                     const int ncol = n0 + nl;
                     if (ncol >= g.NC) continue;
                     float v = t[e] * colmul[nl] + coladd[nl];
-                    const int64_t off = m * g.ldy + ncol;
+                    const int64_t off = orow * g.ldy + ncol;
                     if (g.y_f32) {
                         if (g.residual) v += static_cast<const float*>(g.residual)[off];
                         if (g.relu) v = fmaxf(v, 0.0f);
@@ -617,6 +630,13 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const GatherGemm g) 
     if (id0 >= total) return;
     const int64_t m = id0 / g.NC;
     const int ncol0 = static_cast<int>(id0 - m * g.NC);      // VEC = 4 needs NC % 4 == 0: the group stays in one row
+    int64_t orow = m;
+    if (g.orU != 0) {
+        const int64_t uv = static_cast<int64_t>(g.orU) * g.orV;
+        const int64_t n = m / uv, rem = m - n * uv;
+        const int64_t u = rem / g.orV, v = rem - u * g.orV;
+        orow = (n * g.orH + g.ora + g.orsh * u) * g.orW + g.orb + g.orsw * v;
+    }
     float s[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) s[v] = 0.0f;
@@ -635,7 +655,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const GatherGemm g) 
         const int ncol = ncol0 + e;
         const float mul = 0.5f * g.alpha[ncol / g.rows_per_group] * (g.scale ? g.scale[ncol] : 1.0f);
         float v = s[e] * mul + (g.shift ? g.shift[ncol] : 0.0f);
-        const int64_t off = m * g.ldy + ncol;
+        const int64_t off = orow * g.ldy + ncol;
         if (g.y_f32) {
             if (g.residual) v += static_cast<const float*>(g.residual)[off];
             if (g.relu) v = fmaxf(v, 0.0f);
@@ -678,6 +698,8 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
     a.g = g;
     a.divIC = make_fastdiv_u(static_cast<uint32_t>(g.IC));
     a.divS = make_fastdiv_u(static_cast<uint32_t>(g.S));
+    a.divUV = make_fastdiv_u(g.orU ? static_cast<uint32_t>(g.orU) * static_cast<uint32_t>(g.orV) : 1u);
+    a.divV = make_fastdiv_u(g.orU ? static_cast<uint32_t>(g.orV) : 1u);
     {
         // whole-tensor sizes for the buffer descriptors (the last pixel row ends after its IC / K values)
         const int64_t in_rows = g.plain_gemm ? g.M : (g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW;

@@ -36,6 +36,10 @@ struct GatherGemm {
     int32_t y_f32;          // 1: Y (and residual) float32, 0: bf16
     int32_t plain_gemm;     // 1: R=S=1, stride 1, no padding, OH*OW pixels == rows of X
     int32_t chunk_gather;   // 1: 16-byte chunks are valid although IC/xs are not multiples of 8 (small-C path)
+    // Output row remap (strided backward-data as one stride-1 problem per residue class): row m = (n, u, v) of an
+    // [N][orU][orV] grid is written to pixel (n, ora + orsh*u, orb + orsw*v) of an [N][orH][orW] image.
+    // orU == 0: rows are written in order.
+    int32_t orU, orV, orH, orW, ora, orb, orsh, orsw;
     float* partial;         // split-K workspace [splits][M][NC] float32 (null when splits == 1)
     int32_t splits;         // K is cut into this many ranges of whole 64-wide slabs
 };
@@ -52,6 +56,15 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
 // with Sp = S rounded up to even (codes of the phantom tap / channels are zero).
 int32_t launch_pad_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp,
                       uint16_t* Xp, hipStream_t st);
+// Residue classes of a strided backward-data pass (at most 4: stride products up to 4), by value to the kernel.
+struct DxClassTable {
+    int32_t count;
+    int32_t r0[4], nr[4], s0[4], ns[4], wpr[4];
+    int64_t first_word[5];      // offset of each class's codes in the gathered buffer, in 32-bit words
+};
+int32_t launch_gather_class_codes(const uint32_t* packed_T, int C, int wprT, int S, int O, int sh, int sw,
+                                  const DxClassTable& tb, int64_t total_words, uint32_t* out, hipStream_t st);
+int32_t launch_zero_fill(void* p, int64_t bytes, hipStream_t st);
 int32_t launch_scale_channels(const uint16_t* dY, const float* alpha, int rows_per_group, int O, int64_t pixels,
                               uint16_t* out, float* one, hipStream_t st);
 int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp, uint16_t* Xp,

@@ -528,3 +528,57 @@ def test_conv2d_bwd_data_per_filter_alpha(groups):
         ref = oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)
         assert np.max(np.abs(got - ref)) <= BF16_TOL * np.sqrt(np.mean(ref * ref))
         assert rel_err(to_host_f64(dw), oc.conv2d_bwd_weight(x, dy, codes.shape, st, pd, dl)) <= 1e-4
+
+
+STRIDED_DX_CASES = [
+    # N  H   W   C   O    R  S  stride  pad
+    (2, 14, 14, 128, 256, 3, 3, (2, 2), (1, 1)),
+    (2, 15, 13, 16, 64, 3, 3, (2, 2), (1, 1)),      # odd extents: the classes have different numbers of pixels
+    (3, 16, 16, 64, 128, 1, 1, (2, 2), (0, 0)),     # 1x1: three of the four classes have no tap (zeros)
+    (2, 31, 29, 8, 64, 7, 7, (2, 2), (3, 3)),
+    (2, 12, 17, 32, 64, 5, 5, (2, 2), (2, 2)),
+    (2, 13, 12, 24, 128, 3, 3, (2, 1), (1, 1)),
+    (2, 12, 13, 24, 64, 3, 2, (1, 2), (0, 1)),
+    (1, 9, 9, 8, 64, 2, 2, (2, 2), (0, 0)),         # taps and stride coincide: one tap per class
+    (2, 10, 10, 16, 64, 3, 3, (2, 2), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(STRIDED_DX_CASES)))
+def test_strided_backward_data_by_residue_classes(ci, monkeypatch):
+    # strided layers run one stride-1 contraction per residue class of the output pixels (forced here for
+    # small shapes); both output types, and the generic divided gather as a cross-check
+    n, h, w_, c, o, r, s, st, pd = STRIDED_DX_CASES[ci]
+    dl = (1, 1)
+    x, w, tw, codes, alpha = make_layer(700 + ci, (n, h, w_, c), (o, c, r, s), transposed=True)
+    p, q = oc.out_size(h, r, st[0], pd[0], 1), oc.out_size(w_, s, st[1], pd[1], 1)
+    dy = wl.bf16_round(np.random.default_rng(710 + ci).standard_normal((n, p, q, o)).astype(np.float32))
+    ref = oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)
+    monkeypatch.setenv("TWN_DX_CLASS_MIN_PIXELS", "0")
+    dx32, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape,
+                                        dx_dtype=torch.float32)
+    assert rel_err(to_host_f64(dx32), ref) <= 1e-4
+    dxb, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape)
+    assert rel_err(to_host_f64(dxb), ref) <= BF16_TOL
+    monkeypatch.setenv("TWN_DX_CLASSES", "0")
+    dxg, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape,
+                                       dx_dtype=torch.float32)
+    assert rel_err(to_host_f64(dxg), ref) <= 1e-4
+
+
+def test_full_size_resnet18_strided_backward_data_sampled():
+    layers = {l.name: (i, l) for i, l in enumerate(wl.resnet18(64))}
+    for name in ("l2.0.conv1", "l2.0.down"):
+        li, layer = layers[name]
+        dy = wl.bf16_round(wl.normal(2, wl.IDX_DY + 10 * li, layer.y_shape))
+        w = wl.kaiming_weights(2, li, layer)
+        tw = api.twn_ternarize(to_dev_f32(w), F, transposed=True)
+        codes, delta, alpha, nnz = ot.ternarize(w, F)
+        st, pd, dl = (layer.stride,) * 2, (layer.pad,) * 2, (layer.dil,) * 2
+        dx, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=layer.x_shape)
+        n_, h_, w_, c_ = layer.x_shape
+        corners = [((b * h_ + hh) * w_ + ww) * c_ for b in (0, n_ - 1) for hh in (0, 1, h_ - 2, h_ - 1)
+                   for ww in (0, 1, w_ - 2, w_ - 1)]
+        idx = np.unique(np.concatenate([_sample(int(np.prod(layer.x_shape)), 20000, li), np.array(corners)]))
+        ref = oc.conv2d_bwd_data_at(dy, codes, alpha, layer.x_shape, idx, st, pd, dl)
+        assert rel_err(to_host_f64(dx).ravel()[idx], ref) <= BF16_TOL
