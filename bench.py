@@ -24,7 +24,7 @@ PEAK_HBM_GBPS = 8000.0
 # HBM-side bytes per launch of the roofline sample (L2 fills + write-backs, rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 1 GiB copy), taken from profiles/vgg7_b128_step_kernels.txt; it is a property of
 # the committed kernels and tile choices at this workload, re-measured whenever those change.
-ROOFLINE_SAMPLE_TRAFFIC_BYTES = 33154952
+ROOFLINE_SAMPLE_TRAFFIC_BYTES = 33194047
 F = 0.7
 
 
