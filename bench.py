@@ -127,6 +127,7 @@ def main():
         # ResNet-18 forward, batch 64 (per-layer synthetic inputs, fused scale/shift/ReLU tail)
         rl = wl.resnet18(64)
         tot = 0.0
+        tot_b = 0.0
         for li, L in enumerate(rl):
             x = dev_bf16(wl.normal(2, wl.IDX_INPUT + li, L.x_shape))
             tw = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev), F)
@@ -139,12 +140,24 @@ def main():
             t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y,
                                                      workspace=ws), reps=100, warm=20)
             tot += t
-            log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq" % (L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
-            del x, y
+            # straight-through backward of the same layer (serial: data gradient, then weight gradient)
+            twt = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev), F, transposed=True)
+            dy = dev_bf16(wl.normal(2, wl.IDX_DY + 10 * li, L.y_shape))
+            wsb_ = torch.empty(max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, twt, st, pd, dl)),
+                               dtype=torch.uint8, device=dev)
+            dxo = torch.empty(L.x_shape, dtype=torch.bfloat16, device=dev)
+            dwo = torch.empty(L.w_shape, dtype=torch.float32, device=dev)
+            tb = time_call(lambda: api.twn_conv2d_bwd_ste(x, dy, twt, st, pd, dl, need_dx=(li > 0), need_dw=True, dX=dxo,
+                                                          dW=dwo, workspace=wsb_), reps=50, warm=10)
+            tot_b += tb
+            log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq | bwd %8.1f us" % (L.name, str(L.gemm_mnk), t * 1e3,
+                                                                                L.flops / t / 1e9, tb * 1e3))
+            del x, y, dy, dxo, dwo, wsb_
         rflops = sum(L.flops for L in rl)
-        log("resnet18 b64 conv/fc layers: %.3f ms, %.0f img/s" % (tot, 64 / (tot * 1e-3)))
+        log("resnet18 b64 conv/fc layers: fwd %.3f ms, %.0f img/s; STE backward (dX + dW, serial) %.3f ms" %
+            (tot, 64 / (tot * 1e-3), tot_b))
         return {"ms": round(tot, 4), "img_per_s": round(64 / (tot * 1e-3), 1), "tflops": round(rflops / tot / 1e9, 1),
-                "frac_mfma_peak": round(rflops / tot / 1e9 / PEAK_BF16_TFLOPS, 4)}
+                "frac_mfma_peak": round(rflops / tot / 1e9 / PEAK_BF16_TFLOPS, 4), "bwd_serial_ms": round(tot_b, 4)}
 
     if args.only:
         res = {"gemm": side_gemm, "ternarize": lambda: side_ternarize(calibrate=True), "resnet18": side_resnet18}[args.only]()
