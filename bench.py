@@ -24,7 +24,7 @@ PEAK_HBM_GBPS = 8000.0
 # HBM-side bytes per launch of the roofline sample (L2 fills + write-backs, rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE scaled by a 1 GiB copy), taken from profiles/vgg7_b128_step_kernels.txt; it is a property of
 # the committed kernels and tile choices at this workload, re-measured whenever those change.
-ROOFLINE_SAMPLE_TRAFFIC_BYTES = 33194047
+ROOFLINE_SAMPLE_TRAFFIC_BYTES = 33194744
 F = 0.7
 
 
@@ -124,7 +124,7 @@ def main():
                 "frac_hbm_peak": round(nbytes / t / 1e6 / PEAK_HBM_GBPS, 4)}
 
     def side_resnet18():
-        # ResNet-18 forward, batch 64 (per-layer synthetic inputs, fused scale/shift/ReLU tail)
+        # ResNet-18, batch 64: forward (per-layer synthetic inputs, fused scale/shift/ReLU tail) and STE backward
         rl = wl.resnet18(64)
         tot = 0.0
         tot_b = 0.0
