@@ -3,7 +3,9 @@
 Forward: library routine (torch CPU conv2d in float64, numpy matmul), the
 multiplication-free form of Eq. 2, closed forms (all-ones input, unit impulse),
 hand-enumerated tiny case.  Backward (Alg. 1 steps 9-10): adjoint identities,
-central finite differences, torch autograd.  Packing: explicit bit patterns."""
+central finite differences, torch autograd.  Fused block tail: hand case with every term alone and
+together, torch batch_norm + relu.  Bias gradient: hand case, torch autograd, adjoint of the bias term.
+Packing: explicit bit patterns."""
 
 import numpy as np
 import pytest
@@ -199,3 +201,80 @@ def test_packing_round_trip_and_orders():
     assert np.array_equal(back, codes) and not bad and clean
     # 16x smaller than float32 once K is a multiple of 128
     assert op.packed_bytes(64, 1152) * 16 == 64 * 1152 * 4
+
+
+# --- fused block tail (X_next = g(Z) of Eq. 2 behind the folded batch-norm affine of Sec. 2.4) ----------
+
+def test_epilogue_hand_case_each_term_alone_and_together():
+    # Z of shape [1][1][2][2] (two pixels, two channels), channel index last
+    z = np.array([[1.0, -2.0], [-3.0, 4.0]]).reshape(1, 1, 2, 2)
+    scale = np.array([2.0, -1.0])
+    shift = np.array([0.5, 1.0])
+    res = np.array([[-4.0, 1.0], [10.0, -6.0]]).reshape(1, 1, 2, 2)
+    flat = lambda a: a.reshape(2, 2).tolist()
+    assert flat(oc.epilogue(z)) == [[1.0, -2.0], [-3.0, 4.0]]
+    assert flat(oc.epilogue(z, scale=scale)) == [[2.0, 2.0], [-6.0, -4.0]]
+    assert flat(oc.epilogue(z, shift=shift)) == [[1.5, -1.0], [-2.5, 5.0]]
+    assert flat(oc.epilogue(z, residual=res)) == [[-3.0, -1.0], [7.0, -2.0]]
+    assert flat(oc.epilogue(z, relu=True)) == [[1.0, 0.0], [0.0, 4.0]]
+    # affine first (scale, then shift), residual after the affine, ReLU last:
+    # pixel 0: (1*2+0.5-4, -2*-1+1+1) = (-1.5, 4); pixel 1: (-3*2+0.5+10, 4*-1+1-6) = (4.5, -9)
+    assert flat(oc.epilogue(z, scale=scale, shift=shift, residual=res)) == [[-1.5, 4.0], [4.5, -9.0]]
+    assert flat(oc.epilogue(z, scale=scale, shift=shift, residual=res, relu=True)) == [[0.0, 4.0], [4.5, 0.0]]
+    # orders a mistake would produce give different numbers on this case
+    wrong_shift_first = (z + shift) * scale + res
+    wrong_res_first = (z + res) * scale + shift
+    got = oc.epilogue(z, scale=scale, shift=shift, residual=res)
+    assert not np.array_equal(got, wrong_shift_first) and not np.array_equal(got, wrong_res_first)
+    # the input is not modified
+    assert flat(z) == [[1.0, -2.0], [-3.0, 4.0]]
+
+
+def test_epilogue_equals_library_batchnorm_block(oracle_lib):
+    # relu(batch_norm(conv(X, T)) + residual) with the affine folded:
+    # scale = gamma / sqrt(var + eps), shift = beta - mean * scale
+    x, codes, alpha, st, pd, dl = rand_case(CASES[0], 77)
+    g = np.random.default_rng(78)
+    o = codes.shape[0]
+    gamma, beta = g.uniform(0.5, 1.5, o), g.standard_normal(o)
+    mean, var, eps = g.standard_normal(o), g.uniform(0.5, 2.0, o), 1e-5
+    z = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    res = g.standard_normal(z.shape)
+    scale = gamma / np.sqrt(var + eps)
+    shift = beta - mean * scale
+    got = oc.epilogue(z, scale=scale, shift=shift, residual=res, relu=True)
+    zt = torch.from_numpy(np.ascontiguousarray(torch_conv(x, alpha * codes.astype(np.float64), st, pd, dl)
+                                               .transpose(0, 3, 1, 2)))
+    bn = torch.nn.functional.batch_norm(zt, torch.from_numpy(mean), torch.from_numpy(var),
+                                        torch.from_numpy(gamma), torch.from_numpy(beta), False, 0.0, eps)
+    ref = torch.relu(bn + torch.from_numpy(np.ascontiguousarray(res.transpose(0, 3, 1, 2))))
+    ref = ref.permute(0, 2, 3, 1).numpy()
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.abs(ref).max())
+    assert (got == 0).any() and (got > 0).any()
+
+
+# --- bias gradient (Alg. 1 step 9 applied to the additive term of the block) -----------------------------
+
+def test_bias_grad_hand_case_and_autograd(oracle_lib):
+    # two images of 1x2 pixels, three channels: db[o] adds the four pixels of channel o
+    dy = np.array([[[[1, 10, 100], [2, 20, 200]]],
+                   [[[3, 30, 300], [4, 40, 400]]]], dtype=np.float32)
+    assert dy.shape == (2, 1, 2, 3)
+    assert oc.bias_grad(dy).tolist() == [10.0, 100.0, 1000.0]
+    # library cross-check: autograd of a convolution with a bias term
+    x, codes, alpha, st, pd, dl = rand_case(CASES[2], 55)
+    g = np.random.default_rng(56)
+    t = alpha * codes.astype(np.float64)
+    xt = torch.from_numpy(np.ascontiguousarray(x.transpose(0, 3, 1, 2))).double()
+    b = torch.zeros(codes.shape[0], dtype=torch.float64, requires_grad=True)
+    out = torch.nn.functional.conv2d(xt, torch.from_numpy(t), b, stride=st, padding=pd, dilation=dl)
+    dyr = wl.bf16_round(g.standard_normal(tuple(out.permute(0, 2, 3, 1).shape)).astype(np.float32))
+    out.backward(torch.from_numpy(np.ascontiguousarray(dyr.transpose(0, 3, 1, 2))).double())
+    db = oc.bias_grad(dyr)
+    assert db.shape == (codes.shape[0],)
+    assert np.max(np.abs(db - b.grad.numpy())) <= 1e-12 * max(1.0, np.abs(db).max())
+    # the forward's bias term and db are adjoint: <1, dY> per channel
+    y0 = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    y1 = oc.conv2d_fwd(x, codes, alpha, st, pd, dl, bias=np.arange(codes.shape[0], dtype=np.float64))
+    lhs = float(np.sum((y1 - y0) * dyr))
+    assert abs(lhs - float(np.dot(np.arange(codes.shape[0]), db))) <= 1e-10 * max(1.0, abs(lhs))
