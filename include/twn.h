@@ -141,6 +141,24 @@ int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int32_t groups,
                       float* delta, float* alpha, uint64_t* nnz,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- 1a. twn_ternarize for callers that cannot allocate ---------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that
+ * forbid allocation: the same computation, outputs and validation as
+ * twn_ternarize, without the workspace argument.  The per-block partial sums
+ * live in a fixed array of twn_ternarize_static_scratch_bytes() bytes (98304)
+ * inside the library's device image, one copy per GPU, held until the process
+ * ends; the call allocates and frees nothing.  The array serves every tensor
+ * twn_ternarize accepts (fewer than 2^40 weights; larger: TWN_ERR_SHAPE); the
+ * device ordinal must be below 64 (else TWN_ERR_UNSUPPORTED).  The first call
+ * on a device looks the array's address up (host-side, no allocation).  All
+ * calls on one GPU share that array: two calls that overlap on one GPU (two
+ * streams, two threads) race; calls on one stream are ordered and safe. */
+size_t  twn_ternarize_static_scratch_bytes(void);
+int32_t twn_ternarize_static(const float* W, const twn_weight_desc* wd, int32_t groups,
+                             float delta_factor,
+                             uint32_t* packed, uint32_t* packed_T,
+                             float* delta, float* alpha, uint64_t* nnz, void* stream);
+
 /* ---- 1b. several tensors per call (same passages as above) ------------------
  * The per-layer form of twn_ternarize (groups = 1) for `count` <= 32 weight
  * tensors at once, in three launches in total: meant for the weight tensors of

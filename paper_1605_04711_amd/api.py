@@ -21,7 +21,8 @@ _lib = None
 
 EXPORTS = [
     "twn_status_str", "twn_abi_version", "twn_packed_words_per_row", "twn_packed_bytes",
-    "twn_ternarize_workspace_bytes", "twn_ternarize", "twn_ternarize_batch_workspace_bytes", "twn_ternarize_batch",
+    "twn_ternarize_workspace_bytes", "twn_ternarize", "twn_ternarize_static_scratch_bytes", "twn_ternarize_static",
+    "twn_ternarize_batch_workspace_bytes", "twn_ternarize_batch",
     "twn_unpack_i8",
     "twn_gemm_fwd_workspace_bytes", "twn_gemm_fwd",
     "twn_conv2d_fwd_workspace_bytes", "twn_conv2d_fwd",
@@ -85,6 +86,10 @@ def lib():
         L.twn_ternarize_workspace_bytes.argtypes = [ctypes.POINTER(WeightDesc), i32]
         L.twn_ternarize.restype = i32
         L.twn_ternarize.argtypes = [vp, ctypes.POINTER(WeightDesc), i32, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.twn_ternarize_static_scratch_bytes.restype = sz
+        L.twn_ternarize_static_scratch_bytes.argtypes = []
+        L.twn_ternarize_static.restype = i32
+        L.twn_ternarize_static.argtypes = [vp, ctypes.POINTER(WeightDesc), i32, f32, vp, vp, vp, vp, vp, vp]
         L.twn_ternarize_batch_workspace_bytes.restype = sz
         L.twn_ternarize_batch_workspace_bytes.argtypes = [i32]
         L.twn_ternarize_batch.restype = i32
@@ -200,6 +205,19 @@ def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, wor
                          _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha), _ptr(out.nnz),
                          _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "twn_ternarize")
+    return out
+
+
+def twn_ternarize_static(W, out, delta_factor=0.7, stream=None):
+    """twn_ternarize without a workspace: every buffer of `out` (a TernaryWeights) is the caller's, and the call
+    allocates nothing on the device."""
+    if not W.is_contiguous() or W.dtype != torch.float32 or not W.is_cuda:
+        raise TypeError("W must be a contiguous float32 CUDA tensor")
+    wd = WeightDesc(out.rows, out.C, out.R, out.S)
+    rc = lib().twn_ternarize_static(_ptr(W), ctypes.byref(wd), out.groups, ctypes.c_float(delta_factor),
+                                    _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha),
+                                    _ptr(out.nnz), _stream(stream))
+    _check(rc, "twn_ternarize_static")
     return out
 
 

@@ -17,6 +17,8 @@
 // the device-scope release it needs writes back the L2 of every XCD once per block
 // and cost 75 us on the 2^28 tensor.)  All floating-point sums run in a fixed
 // order: results are bit-identical from run to run; no floating-point atomics.
+#include <mutex>
+
 #include "twn_common.h"
 
 namespace twn {
@@ -563,10 +565,10 @@ extern "C" size_t twn_ternarize_workspace_bytes(const twn_weight_desc* wd, int32
     return sizeof(TernWorkspace);
 }
 
-extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int32_t groups,
-                                 float delta_factor, uint32_t* packed, uint32_t* packed_T,
-                                 float* delta, float* alpha, uint64_t* nnz,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
+// Host-side argument checks shared by twn_ternarize and twn_ternarize_static (no GPU call).
+static int32_t ternarize_check(const float* W, const twn_weight_desc* wd, int32_t groups, float delta_factor,
+                               const uint32_t* packed, const uint32_t* packed_T, const float* delta,
+                               const float* alpha, const uint64_t* nnz) {
     if (!W || !wd || !packed || !delta || !alpha || !nnz) return TWN_ERR_NULL;
     if (wd->rows <= 0 || wd->C <= 0 || wd->R <= 0 || wd->S <= 0) return TWN_ERR_SHAPE;
     if (groups < 1 || wd->rows % groups != 0) return TWN_ERR_SHAPE;
@@ -577,6 +579,21 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
     const int64_t n = K * wd->rows;
     if (RS > (1 << 15) || K >= (1LL << 31) || KT >= (1LL << 31) || n >= (1LL << 40)) return TWN_ERR_SHAPE;
     if (!aligned(W, 16) || !aligned(packed, 16) || (packed_T && !aligned(packed_T, 16))) return TWN_ERR_ALIGN;
+    return TWN_OK;
+}
+
+// Launches of one ternarization; `workspace` is device memory of at least sizeof(TernWorkspace) bytes, either
+// the caller's (twn_ternarize) or the library's own per-device array (twn_ternarize_static).
+static int32_t ternarize_impl(const float* W, const twn_weight_desc* wd, int32_t groups,
+                              float delta_factor, uint32_t* packed, uint32_t* packed_T,
+                              float* delta, float* alpha, uint64_t* nnz,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    const int32_t rc = ternarize_check(W, wd, groups, delta_factor, packed, packed_T, delta, alpha, nnz);
+    if (rc != TWN_OK) return rc;
+    const int64_t RS = static_cast<int64_t>(wd->R) * wd->S;
+    const int64_t K = RS * wd->C;
+    const int64_t KT = RS * wd->rows;
+    const int64_t n = K * wd->rows;
     if (!workspace || workspace_bytes < sizeof(TernWorkspace) || !aligned(workspace, 8)) return TWN_ERR_WORKSPACE;
 
     hipStream_t st = as_stream(stream);
@@ -631,6 +648,53 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
         }
     }
     return launch_status();
+}
+
+extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int32_t groups,
+                                 float delta_factor, uint32_t* packed, uint32_t* packed_T,
+                                 float* delta, float* alpha, uint64_t* nnz,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    return ternarize_impl(W, wd, groups, delta_factor, packed, packed_T, delta, alpha, nnz, workspace, workspace_bytes,
+                          stream);
+}
+
+// ---- the entry point that allocates nothing -------------------------------------------------------------
+// The per-block partial sums of twn_ternarize live in a file-scope device array instead of a caller
+// workspace.  Every GPU the library runs on holds its own copy of the array at its own address: the
+// address is looked up once per device (with that device current) and only that pointer is ever handed
+// to kernels.  Nothing in the array has to start at zero: every partial a pass reads was written by the
+// pass before it in the same call.
+namespace twn {
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[sizeof(TernWorkspace)];
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kStaticMaxDevices];      // per device: address of `scratch` there, null until looked up
+}  // namespace twn
+
+extern "C" size_t twn_ternarize_static_scratch_bytes(void) { return sizeof(TernWorkspace); }
+
+extern "C" int32_t twn_ternarize_static(const float* W, const twn_weight_desc* wd, int32_t groups,
+                                        float delta_factor, uint32_t* packed, uint32_t* packed_T,
+                                        float* delta, float* alpha, uint64_t* nnz, void* stream) {
+    // every check that needs no GPU comes first; tensors beyond the 2^40 weights the fixed array is specified
+    // for are rejected here with TWN_ERR_SHAPE
+    const int32_t rc = ternarize_check(W, wd, groups, delta_factor, packed, packed_T, delta, alpha, nnz);
+    if (rc != TWN_OK) return rc;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return TWN_ERR_HIP;
+    if (dev < 0 || dev >= kStaticMaxDevices) return TWN_ERR_UNSUPPORTED;
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TWN_ERR_HIP;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    return ternarize_impl(W, wd, groups, delta_factor, packed, packed_T, delta, alpha, nnz, ptr, sizeof(TernWorkspace),
+                          stream);
 }
 
 extern "C" size_t twn_ternarize_batch_workspace_bytes(int32_t count) {

@@ -68,6 +68,24 @@ def test_ternarize_argument_errors():
     assert call(*a) == -5
 
 
+def test_ternarize_static_argument_errors():
+    # every check that needs no GPU comes before the first GPU call of the entry point
+    L = api.lib()
+    wd = api.WeightDesc(8, 16, 3, 3)
+    assert L.twn_ternarize_static_scratch_bytes() == 98304
+    ok_args = [FAKE, ctypes.byref(wd), 1, ctypes.c_float(0.7), FAKE, None, FAKE, FAKE, FAKE, None]
+    call = lambda *a: L.twn_ternarize_static(*a)
+    a = list(ok_args); a[0] = None
+    assert call(*a) == -1
+    a = list(ok_args); a[2] = 3
+    assert call(*a) == -2
+    a = list(ok_args); a[4] = ODD
+    assert call(*a) == -3
+    big = api.WeightDesc(1 << 20, 1 << 20, 1, 1)     # 2^40 weights: beyond what the fixed array is specified for
+    a = list(ok_args); a[1] = ctypes.byref(big)
+    assert call(*a) == -2
+
+
 def test_gemm_and_conv_argument_errors():
     L = api.lib()
     d = api.GemmDesc(64, 32, 128, api.TWN_BF16, api.TWN_BF16, api.TWN_VAR_BF16_POSTSCALE, 0, 0, 1)
