@@ -532,6 +532,8 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
             // instead of twice; a few percent faster than the 2x2 arrangement, which keeps the split-K builds
             if (tile == 12 && g.splits == 1) tile = 15;
         }
+        if ((tile == 12 || (tile >= 14 && tile <= 17)) && env_int("TWN_STREAM", 1) != 0 && conv_stream_applicable(g))
+            return launch_conv_stream(g, tile, st);
         return launch_gather_gemm_dma(g, tile, st);
     }
     if (tile > 10) tile = 0;   // ids above 10 name tiles of the direct-to-LDS kernel

@@ -15,16 +15,25 @@
 //   * lanes outside the image / beyond M, N or K fetch from a 16-byte zero
 //     block instead, so padding costs no branches and slabs past the end of K
 //     are harmless zero loads that keep the outstanding-load count constant.
-#include <type_traits>
-#include <utility>
-
 #include "twn_agpr_tiles.h"
 #include "twn_kernels.h"
+#include "twn_lds_asm.h"
 #include "twn_mfma.h"
 
 namespace twn {
 
 __device__ __attribute__((aligned(16))) const uint32_t kZeroBlock[4] = {0u, 0u, 0u, 0u};
+
+#ifdef TWN_TRACE
+// development build only: per-workgroup phase timestamps (shader clock) written to a buffer set from the host
+__device__ uint64_t* g_trace = nullptr;
+#define TWN_TRACE_POINT(slot)                                                                         \
+    do {                                                                                              \
+        if (g_trace && threadIdx.x == 0) g_trace[static_cast<size_t>(blockIdx.x) * 8 + (slot)] = __builtin_readcyclecounter(); \
+    } while (0)
+#else
+#define TWN_TRACE_POINT(slot) do {} while (0)
+#endif
 
 struct DmaArgs {
     GatherGemm g;
@@ -34,6 +43,7 @@ struct DmaArgs {
     int32_t use_buf;
     uint32_t x_bytes, w_bytes;
     FastDivU divUV, divV;       // output row remap (g.orU > 0): row -> (image, u, v)
+    FastDivU divOW, divOH;      // GEMM row -> (image, oh, ow) of the gather's output grid (M < 2^31)
 };
 
 // Row of Y that GEMM row m is written to (see GatherGemm::orU).
@@ -47,70 +57,6 @@ __device__ __forceinline__ int64_t out_row(const GatherGemm& g, const FastDivU& 
     return (static_cast<int64_t>(n) * g.orH + g.ora + g.orsh * static_cast<int>(u)) * g.orW + g.orb + g.orsw * static_cast<int>(v);
 }
 
-// LDS reads of the main loop are written as inline assembly with hand-placed s_waitcnt lgkmcnt(n): the
-// compiler's own wait insertion falls back to lgkmcnt(0) in this loop, which also waits for the reads
-// issued one MFMA step ahead and so exposes the whole LDS latency at every step.  LDS operations
-// complete in issue order, so "at most n outstanding" is exact.  A value read this way may only be
-// consumed after lds_wait<n>() followed by lds_ready() on its registers.
-template <int OFFSET>
-__device__ __forceinline__ void lds_read128(u32x4& d, uint32_t addr) {
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFFSET));
-}
-template <int OFFSET>
-__device__ __forceinline__ void lds_read64(u32x2& d, uint32_t addr) {
-    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFFSET));
-}
-// N reads (N <= 8) at addr, addr + STRIDE, ...
-template <int N, int STRIDE>
-__device__ __forceinline__ void lds_read128_n(u32x4* d, uint32_t addr) {
-    static_assert(N >= 1 && N <= 8 && (N - 1) * STRIDE < 65536, "immediate offsets");
-    lds_read128<0>(d[0], addr);
-    if constexpr (N > 1) lds_read128<STRIDE>(d[1], addr);
-    if constexpr (N > 2) lds_read128<2 * STRIDE>(d[2], addr);
-    if constexpr (N > 3) lds_read128<3 * STRIDE>(d[3], addr);
-    if constexpr (N > 4) lds_read128<4 * STRIDE>(d[4], addr);
-    if constexpr (N > 5) lds_read128<5 * STRIDE>(d[5], addr);
-    if constexpr (N > 6) lds_read128<6 * STRIDE>(d[6], addr);
-    if constexpr (N > 7) lds_read128<7 * STRIDE>(d[7], addr);
-}
-template <int N, int STRIDE>
-__device__ __forceinline__ void lds_read64_n(u32x2* d, uint32_t addr) {
-    static_assert(N >= 1 && N <= 4 && 3 * STRIDE < 65536, "immediate offsets");
-    lds_read64<0>(d[0], addr);
-    if constexpr (N > 1) lds_read64<STRIDE>(d[1], addr);
-    if constexpr (N > 2) lds_read64<2 * STRIDE>(d[2], addr);
-    if constexpr (N > 3) lds_read64<3 * STRIDE>(d[3], addr);
-}
-template <int N>
-__device__ __forceinline__ void lds_wait() {
-    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
-    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
-}
-// ties the consumers of r[0..N) to the preceding lds_wait (volatile asm statements keep their order)
-template <int N, class T>
-__device__ __forceinline__ void lds_ready(T* r) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(r[i]));
-}
-
-// a constant the compiler keeps in a scalar register (it cannot fold it back into a literal operand)
-template <int V>
-__device__ __forceinline__ uint32_t sgpr_const() {
-    uint32_t r;
-    asm volatile("s_mov_b32 %0, %1" : "=s"(r) : "n"(V));
-    return r;
-}
-
-// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
 // workgroups per CU the register allocation should allow: two waves per SIMD where LDS permits
 constexpr int dma_min_blocks(int nw, int smem) {
     int by_waves = 8 / nw, by_lds = (160 * 1024) / smem;
@@ -118,8 +64,8 @@ constexpr int dma_min_blocks(int nw, int smem) {
     return b < 1 ? 1 : b;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF>
-__global__ __launch_bounds__(64 * WM * WN, dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF, int OCC = 0>
+__global__ __launch_bounds__(64 * WM * WN, OCC ? OCC : dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
 void gather_gemm_dma_kernel(const DmaArgs a) {
     constexpr int NW = WM * WN;                    // waves per workgroup
     constexpr int NT = 64 * NW;
@@ -144,6 +90,16 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
+    TWN_TRACE_POINT(0);
+#ifdef TWN_TRACE
+    if (g_trace && threadIdx.x == 0) {
+        uint32_t hw, xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        g_trace[static_cast<size_t>(blockIdx.x) * 8 + 6] = (static_cast<uint64_t>(xcc) << 32) | hw;
+        g_trace[static_cast<size_t>(blockIdx.x) * 8 + 7] = wall_clock64();
+    }
+#endif
     const GatherGemm& g = a.g;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -180,10 +136,13 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                 ih0[i] = 0;
                 iw0[i] = 0;
             } else {
-                const int ow = static_cast<int>(m % g.OW);
-                const int64_t tt = m / g.OW;
-                const int oh = static_cast<int>(tt % g.OH);
-                abase[i] = (tt / g.OH) * g.IH * g.IW;
+                // M < 2^31: exact 32-bit division by multiplication instead of 64-bit divisions
+                const uint32_t mu = static_cast<uint32_t>(m);
+                const uint32_t tt = fdiv_u(mu, a.divOW);
+                const int ow = static_cast<int>(mu - tt * static_cast<uint32_t>(g.OW));
+                const uint32_t img = fdiv_u(tt, a.divOH);
+                const int oh = static_cast<int>(tt - img * static_cast<uint32_t>(g.OH));
+                abase[i] = static_cast<int64_t>(img) * (g.IH * g.IW);
                 ih0[i] = oh * g.sh - g.ph;
                 iw0[i] = ow * g.sw - g.pw;
             }
@@ -448,9 +407,11 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     // prologue: PD slabs in flight, the first one landed and visible to every wave
 #pragma unroll
     for (int s = 0; s < PD; ++s) issue(kt_begin + s, s);
+    TWN_TRACE_POINT(1);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * PER_STAGE));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    TWN_TRACE_POINT(2);
     lds_read64_n<NI, 32 * 16>(breg[0], lds_base + boff);
     lds_read128_n<MI, 32 * 128>(afrag[0], lds_base + aoff[0]);
     lds_wait<0>();
@@ -485,9 +446,11 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     }
 
     // the trailing zero loads still target LDS: drain them in every wave before LDS is reused
+    TWN_TRACE_POINT(3);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    TWN_TRACE_POINT(4);
     if constexpr (PINNED) agpr_settle();
 
     if (SPLITK) {
@@ -528,7 +491,8 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
         const int ncol = n0 + i;
         float mul = 0.0f, add = 0.0f;
         if (ncol < g.NC) {
-            mul = 0.5f * g.alpha[ncol / g.rows_per_group] * (g.scale ? g.scale[ncol] : 1.0f);   // codes were +-2
+            const int ag = (g.rows_per_group >= g.NC) ? 0 : ncol / g.rows_per_group;
+            mul = 0.5f * g.alpha[ag] * (g.scale ? g.scale[ncol] : 1.0f);   // codes were +-2
             add = g.shift ? g.shift[ncol] : 0.0f;
         }
         colmul[i] = mul;
@@ -572,8 +536,8 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                             for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
                         }
                         u32x2 pk;
-                        pk[0] = static_cast<uint32_t>(f32_to_bf16(v[0])) | (static_cast<uint32_t>(f32_to_bf16(v[1])) << 16);
-                        pk[1] = static_cast<uint32_t>(f32_to_bf16(v[2])) | (static_cast<uint32_t>(f32_to_bf16(v[3])) << 16);
+                        pk[0] = pack_bf16x2(v[0], v[1]);
+                        pk[1] = pack_bf16x2(v[2], v[3]);
                         *reinterpret_cast<u32x2*>(stg + (mi * 32 + lrow) * EPI_ROW + (nh * 32 + q4 * 8 + lh * 4) * 2) = pk;
                     }
                 }
@@ -619,6 +583,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
             }
         }
     }
+    TWN_TRACE_POINT(5);
 }
 
 // Sums the split-K partials in a fixed order and applies the block tail:
@@ -668,13 +633,13 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const GatherGemm g) 
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF>
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF, int OCC>
 static int32_t launch_dma_kernel_b(const DmaArgs& a, int64_t blocks, hipStream_t st) {
     constexpr int SMEM = STAGES * (BM * 128 + BN * 16);
     static_assert(SMEM <= 160 * 1024, "LDS budget");
     // more than 64 KB of dynamic LDS has to be allowed once per kernel
     static bool allowed = false;
-    auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, GEMM, SPLITK, BUF>;
+    auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, GEMM, SPLITK, BUF, OCC>;
     if (!allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 SMEM) != hipSuccess) return TWN_ERR_HIP;
@@ -684,13 +649,13 @@ static int32_t launch_dma_kernel_b(const DmaArgs& a, int64_t blocks, hipStream_t
     return launch_status();
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK>
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, int OCC>
 static int32_t launch_dma_kernel(const DmaArgs& a, int64_t blocks, hipStream_t st) {
-    return a.use_buf ? launch_dma_kernel_b<BM, BN, WM, WN, STAGES, GEMM, SPLITK, true>(a, blocks, st)
-                     : launch_dma_kernel_b<BM, BN, WM, WN, STAGES, GEMM, SPLITK, false>(a, blocks, st);
+    return a.use_buf ? launch_dma_kernel_b<BM, BN, WM, WN, STAGES, GEMM, SPLITK, true, OCC>(a, blocks, st)
+                     : launch_dma_kernel_b<BM, BN, WM, WN, STAGES, GEMM, SPLITK, false, OCC>(a, blocks, st);
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
+template <int BM, int BN, int WM, int WN, int STAGES, int OCC = 0>
 static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
     const int64_t blocks = ((g.M + BM - 1) / BM) * ((g.NC + BN - 1) / BN);
     if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
@@ -700,6 +665,8 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
     a.divS = make_fastdiv_u(static_cast<uint32_t>(g.S));
     a.divUV = make_fastdiv_u(g.orU ? static_cast<uint32_t>(g.orU) * static_cast<uint32_t>(g.orV) : 1u);
     a.divV = make_fastdiv_u(g.orU ? static_cast<uint32_t>(g.orV) : 1u);
+    a.divOW = make_fastdiv_u(static_cast<uint32_t>(g.OW));
+    a.divOH = make_fastdiv_u(static_cast<uint32_t>(g.OH));
     {
         // whole-tensor sizes for the buffer descriptors (the last pixel row ends after its IC / K values)
         const int64_t in_rows = g.plain_gemm ? g.M : (g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW;
@@ -716,8 +683,8 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
         // the dispatcher splits K only for grids of few 128x128 tiles: no other tile has a split-K build
         if constexpr (BM == 128 && BN == 128 && WM == 2 && WN == 2) {
             if (!g.partial) return TWN_ERR_WORKSPACE;
-            int32_t rc = g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, true>(a, blocks, st)
-                                      : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, true>(a, blocks, st);
+            int32_t rc = g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, true, OCC>(a, blocks, st)
+                                      : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, true, OCC>(a, blocks, st);
             if (rc != TWN_OK) return rc;
             const int64_t total = g.M * g.NC;
             if (g.NC % 4 == 0 && (reinterpret_cast<uintptr_t>(g.partial) & 15) == 0)
@@ -729,14 +696,21 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
             return TWN_ERR_UNSUPPORTED;
         }
     }
-    return g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, false>(a, blocks, st)
-                        : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, false>(a, blocks, st);
+    return g.plain_gemm ? launch_dma_kernel<BM, BN, WM, WN, STAGES, true, false, OCC>(a, blocks, st)
+                        : launch_dma_kernel<BM, BN, WM, WN, STAGES, false, false, OCC>(a, blocks, st);
 }
 
 // Tile ids (BM x BN, waves, stages): 12 = 128x128 2x2 S3, 14 = 64x128 1x4 S3, 15 = 128x128 1x4 S3,
 // 16 = 128x64 2x2 S3,
 // 17 = 128x256 1x4 S4, 24 = 128x512 1x8 S4, 30 = 256x256 2x2 S3
 // (30: 16 accumulator tiles per wave, pinned by hand; only on request, it is not faster than 17)
+#ifdef TWN_TRACE
+extern "C" int32_t twn_debug_set_trace(void* buf) {
+    uint64_t* p = static_cast<uint64_t*>(buf);
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p)) == hipSuccess ? 0 : -6;
+}
+#endif
+
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
     switch (tile) {
         case 12: return launch_dma_tile<128, 128, 2, 2, 3>(g, st);

@@ -1,0 +1,697 @@
+// Persistent implicit-GEMM ternary convolution / inner product on gfx950
+// (Eq. 2, Alg. 1 step 8; also the undivided backward-data pass of Alg. 1 step 9).
+//
+// Same arithmetic and the same per-slab pipeline as gather_gemm_dma_kernel (bf16
+// activations staged global -> LDS by direct 16-byte buffer loads, 2-bit codes
+// expanded in registers to +-2.0 / 0, v_mfma_f32_32x32x16_bf16, alpha/2 in the fp32
+// epilogue), but a workgroup does not end with its tile.  The grid is sized to what
+// the chip holds at once and every workgroup walks a list of tiles; the K slabs of
+// all its tiles form ONE stream:
+//   * the loads of the next tile's first slabs are issued while the last slabs of the
+//     current tile are multiplied, so no tile after the first waits for memory at its
+//     start and nothing is drained at its end;
+//   * the epilogue of a tile (scale, shift, residual, ReLU, rounding, transposition
+//     through LDS, 16-byte stores) runs while those loads are in flight; it stages
+//     through the one pipeline stage that is free at that moment (the stage of the
+//     slab just multiplied; the next load to it is issued only after the following
+//     mid-slab barrier), 32 pixel rows per wave at a time;
+//   * co-resident workgroups drift out of step, so the vector-ALU work of one
+//     workgroup's epilogue and tile set-up overlaps the MFMAs of the others instead
+//     of every workgroup of a launch doing the same phase at the same time;
+//   * per-column parameters (alpha, scale, shift) are loaded one tile ahead.
+// Shapes it takes: bf16 output, channel counts that are multiples of 8, and the
+// loads of the buffer-descriptor path (plain GEMM with K % 64 == 0, or an undivided
+// convolution whose channel count is a multiple of 64; tensors below 2 GiB).  Every
+// other problem stays with gather_gemm_dma_kernel.
+#include <mutex>
+
+#include "twn_kernels.h"
+#include "twn_lds_asm.h"
+#include "twn_mfma.h"
+
+namespace twn {
+
+#ifdef TWN_TRACE
+// development build only: per-workgroup phase timestamps (shader clock), 16 slots per workgroup
+__device__ uint64_t* g_stream_trace = nullptr;
+#define TWN_STRACE(slot)                                                                                   \
+    do {                                                                                                   \
+        if (g_stream_trace && threadIdx.x == 0 && (slot) < 16)                                             \
+            g_stream_trace[static_cast<size_t>(blockIdx.x) * 16 + (slot)] = __builtin_readcyclecounter();  \
+    } while (0)
+extern "C" int32_t twn_debug_set_stream_trace(void* buf) {
+    uint64_t* p = static_cast<uint64_t*>(buf);
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_stream_trace), &p, sizeof(p)) == hipSuccess ? 0 : -6;
+}
+#else
+#define TWN_STRACE(slot) do {} while (0)
+#endif
+
+struct StreamArgs {
+    GatherGemm g;
+    FastDivU divOW, divOH;      // GEMM row -> (image, oh, ow)
+    FastDivU divTN;             // tile -> (row block, column block)
+    uint32_t x_bytes, w_bytes;  // sizes for the buffer descriptors
+    uint32_t tiles, tiles_n;
+    int32_t KT;                 // K / 64
+};
+
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, int OCC, bool DEEP>
+__global__ __launch_bounds__(64 * WM * WN, OCC)
+void conv_stream_kernel(const StreamArgs a) {
+    constexpr int NW = WM * WN;                    // waves per workgroup
+    constexpr int NT = 64 * NW;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int NLOAD = BM / (8 * NW);           // 1 KB (8 rows) per wave-level load
+    constexpr int A_BYTES = BM * 128;
+    constexpr int B_BYTES = BN * 16;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    // slabs in flight ahead of the one being multiplied.  DEEP: activation fragments are read from LDS three MFMA
+    // steps ahead, so a stage is read for the last time in step 0 of its slab and can be refilled for the
+    // rest of that slab: all STAGES stages carry loads, and a load has two slab times to land
+    constexpr int PD = DEEP ? STAGES : STAGES - 1;
+    constexpr int PER_STAGE = NLOAD + 1;           // vector-memory loads per wave per slab
+    constexpr int EPI_CH = TN < 64 ? TN : 64;      // channels staged at a time
+    constexpr int EPI_ROW = EPI_CH * 2 + 16;       // bytes per staged pixel row (pad keeps 16-byte reads conflict-free)
+    constexpr int EPI_NI = EPI_CH / 32;
+    constexpr int EPI_WAVE = 32 * EPI_ROW;         // one block of 32 pixel rows per wave
+    static_assert(BM % (8 * NW) == 0 && BN % 64 == 0 && BN <= 64 * NW && TN % 32 == 0 && TM % 32 == 0, "tile shape");
+    static_assert(NW % 2 == 0, "the swizzle of the staged rows assumes an even number of waves");
+    static_assert(STAGES >= 3, "the mid-slab hand-over needs two slabs in flight");
+    static_assert(NW * EPI_WAVE <= STAGE_BYTES, "epilogue staging must fit in one pipeline stage");
+    // Column parameters of a tile: a region of their own behind the stages (double-buffered, no extra barrier),
+    // unless that region would cost a resident workgroup; then they share the free stage with the staging
+    // rows, at the price of a second barrier per tile.
+    constexpr bool COL_IN_STAGE = (STAGES * STAGE_BYTES + 4 * BN * 4) * OCC > 160 * 1024;
+    static_assert(!COL_IN_STAGE || NW * EPI_WAVE + 2 * BN * 4 <= STAGE_BYTES, "column parameters must fit in the free stage");
+    static_assert(BN <= NT, "one thread per column loads the column parameters");
+    static_assert(MI <= 8 && NI <= 4, "fragment reads use immediate offsets");
+
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    float* colbuf = reinterpret_cast<float*>(smem + STAGES * STAGE_BYTES);   // [2][2][BN]: mul, add of even / odd tiles (unless COL_IN_STAGE)
+
+    TWN_STRACE(0);
+#ifdef TWN_TRACE
+    if (g_stream_trace && threadIdx.x == 0) g_stream_trace[static_cast<size_t>(blockIdx.x) * 16 + 15] = wall_clock64();
+#endif
+    const GatherGemm& g = a.g;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = lane & 31, lh = lane >> 5;
+
+    // ---- this workgroup's tiles ------------------------------------------------------------------
+    // Workgroups are dealt round-robin to the 8 XCDs.  Each XCD owns a contiguous range of tiles and its
+    // workgroups walk that range side by side: the tiles in flight on one XCD are neighbours (shared halos
+    // and codes in its L2).
+    const uint32_t G = gridDim.x, b = blockIdx.x;
+    const uint32_t xcd = b & 7, j = b >> 3;
+    const uint32_t gx = (G + 7 - xcd) >> 3;                 // workgroups on this XCD
+    const uint32_t q = a.tiles >> 3, r = a.tiles & 7;
+    const uint32_t count_x = q + (xcd < r ? 1u : 0u);       // tiles of this XCD
+    const uint32_t start_x = xcd * q + (xcd < r ? xcd : r);
+    if (j >= count_x) return;                               // whole workgroup, before any barrier
+    const uint32_t n_my = (count_x - j + gx - 1) / gx;
+    auto tile_id = [&](uint32_t i) __attribute__((always_inline)) -> uint32_t { return start_x + j + i * gx; };
+
+    const int KT = a.KT;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(g.X, a.x_bytes), rw = make_rsrc(g.Wq, a.w_bytes);
+
+    // ---- per-lane load state of the tile the load stream is in ----------------------------------------
+    // wave-level load i covers rows (i*NW + wave)*8 .. +7 of the tile; LDS row r keeps logical 16-byte chunk
+    // c at position c ^ ((r >> 1) & 7) (conflict-free ds_read_b128 with 64 banks); the swizzle is applied by
+    // choosing which chunk of the row this lane fetches.
+    const int kc = (lane & 7) ^ ((wave & 1) * 4 + ((lane >> 4) & 3));
+    const int brow = (wave * 64) % BN + lane;               // column whose codes this lane stages
+    uint32_t voffA[NLOAD];      // GEMM: byte offset of the row; convolution: byte offset of tap (0,0) (any sign, wraps)
+    int ih0[NLOAD], iw0[NLOAD];
+    uint32_t voffB;
+    auto tile_setup = [&](uint32_t t, bool valid) __attribute__((always_inline)) {
+        const uint32_t tm = fdiv_u(t, a.divTN);
+        const uint32_t tn = t - tm * a.tiles_n;
+        const uint32_t m0 = tm * BM;
+        const uint32_t ncol = tn * BN + static_cast<uint32_t>(brow);
+        voffB = (valid && ncol < static_cast<uint32_t>(g.NC)) ? ncol * static_cast<uint32_t>(g.wpr) * 4u : kBufOutside;
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) {
+            const uint32_t m = m0 + static_cast<uint32_t>((i * NW + wave) * 8 + (lane >> 3));
+            // computed unconditionally and selected afterwards (no memory is touched here)
+            const bool rv = valid && m < static_cast<uint32_t>(g.M);
+            uint32_t vo;
+            int h0 = 0, w0 = 0;
+            if (GEMM) {
+                vo = (m * static_cast<uint32_t>(g.xs) + static_cast<uint32_t>(kc * 8)) * 2u;
+            } else {
+                const uint32_t tt = fdiv_u(m, a.divOW);
+                const int ow = static_cast<int>(m - tt * static_cast<uint32_t>(g.OW));
+                const uint32_t img = fdiv_u(tt, a.divOH);
+                const int oh = static_cast<int>(tt - img * static_cast<uint32_t>(g.OH));
+                h0 = oh * g.sh - g.ph;
+                w0 = ow * g.sw - g.pw;
+                // 32-bit wrapping arithmetic: the true offset of every tap that passes the bounds test
+                // lies in [0, 2^31)
+                const uint32_t pix = (img * static_cast<uint32_t>(g.IH) + static_cast<uint32_t>(h0)) *
+                                         static_cast<uint32_t>(g.IW) + static_cast<uint32_t>(w0);
+                vo = (pix * static_cast<uint32_t>(g.xs) + static_cast<uint32_t>(kc * 8)) * 2u;
+            }
+            voffA[i] = rv ? vo : kBufOutside;
+            ih0[i] = rv ? h0 : -(1 << 28);
+            iw0[i] = rv ? w0 : -(1 << 28);
+        }
+    };
+
+    // ---- the load stream: (tile lt, slab lk), wave-uniform ----------------------------------------------
+    uint32_t lt = 0;
+    int lk = 0;
+    int nc0 = 0, nss = 0, nrr = 0;      // convolution: channel base and tap of the slab to issue next
+    const int32_t strR = g.dh * g.IW * static_cast<int>(g.xs) * 2, strS = g.dw * static_cast<int>(g.xs) * 2;
+    struct {
+        unsigned char* sbase;
+        uint32_t soff;                  // slab index inside the tile
+        int32_t delta_b;                // convolution: byte offset of this slab's tap and channel base
+        int dth, dtw;
+    } si;
+    auto issue_setup = [&](int stage) __attribute__((always_inline)) {
+        si.sbase = smem + stage * STAGE_BYTES;
+        si.soff = static_cast<uint32_t>(lk);
+        if (!GEMM) {
+            si.delta_b = nrr * strR + nss * strS + nc0 * 2;
+            si.dth = nrr * g.dh;
+            si.dtw = nss * g.dw;
+        }
+    };
+    auto issue_load = [&](auto i_tag) __attribute__((always_inline)) {
+        constexpr int i = decltype(i_tag)::value;
+        if constexpr (i == NLOAD) {
+            buf_dma16(rw, voffB, si.soff * 16u, si.sbase + A_BYTES + ((wave * 64) % BN) * 16);
+        } else if (GEMM) {
+            buf_dma16(rx, voffA[i], si.soff * 128u, si.sbase + (i * NW + wave) * 1024);
+        } else {
+            const bool ok = (static_cast<unsigned>(ih0[i] + si.dth) < static_cast<unsigned>(g.IH)) &
+                            (static_cast<unsigned>(iw0[i] + si.dtw) < static_cast<unsigned>(g.IW));
+            buf_dma16(rx, ok ? voffA[i] + static_cast<uint32_t>(si.delta_b) : kBufOutside, 0u,
+                      si.sbase + (i * NW + wave) * 1024);
+        }
+    };
+    // after the last load of a slab: next slab, or the first slab of the next tile (past the last tile every
+    // lane reads zeros: the loads keep their count, which the vmcnt arithmetic below relies on)
+    auto issue_advance = [&]() __attribute__((always_inline)) {
+        ++lk;
+        if (!GEMM) {
+            nc0 += 64;
+            if (nc0 == g.IC) {
+                nc0 = 0;
+                if (++nss == g.S) {
+                    nss = 0;
+                    ++nrr;
+                }
+            }
+        }
+        if (lk == KT) {
+            lk = 0;
+            nc0 = nss = nrr = 0;
+            ++lt;
+            tile_setup(tile_id(lt), lt < n_my);
+        }
+    };
+
+    // ---- per-column parameters, loaded one tile ahead (thread c < BN owns column c of the tile) --------
+    float cp_alpha = 0.0f, cp_scale = 1.0f, cp_shift = 0.0f;
+    auto colparam_load = [&](uint32_t t) __attribute__((always_inline)) {
+        const uint32_t tm = fdiv_u(t, a.divTN);
+        const int ncol = static_cast<int>((t - tm * a.tiles_n) * BN) + tid;
+        cp_alpha = 0.0f;
+        cp_scale = 1.0f;
+        cp_shift = 0.0f;
+        if (tid < BN && ncol < g.NC) {
+            const int ag = (g.rows_per_group >= g.NC) ? 0 : ncol / g.rows_per_group;
+            cp_alpha = g.alpha[ag];
+            if (g.scale) cp_scale = g.scale[ncol];
+            if (g.shift) cp_shift = g.shift[ncol];
+        }
+    };
+
+    f32x16 acc[MI][NI];
+    auto acc_clear = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
+    };
+
+    // ---- software pipeline (see gather_gemm_dma_kernel for the reasoning behind its shape) --------------
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) unsigned char*)smem));
+    uint32_t aoff[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+        aoff[kk] = (wm * TM + lrow) * 128 + (((lh * 4 + kk) ^ ((lrow >> 1) & 7)) * 16);
+    const uint32_t boff = A_BYTES + (wn * TN + lrow) * 16 + lh * 8;
+
+    u32x2 breg[2][NI];      // packed codes of the slab being multiplied / of the next slab
+    u32x4 afrag[DEEP ? 4 : 2][MI];   // activation fragments of step kk in set kk & 1 (DEEP: in set kk)
+    u32x4 bfrag[2][NI];     // expanded codes of step kk in set kk & 1
+
+    uint32_t kmask[8];
+    kmask[0] = sgpr_const<static_cast<int>(0xC000C000u >> 14)>();
+    kmask[1] = sgpr_const<static_cast<int>(0xC000C000u >> 12)>();
+    kmask[2] = sgpr_const<static_cast<int>(0xC000C000u >> 10)>();
+    kmask[3] = sgpr_const<static_cast<int>(0xC000C000u >> 8)>();
+    kmask[4] = sgpr_const<static_cast<int>(0xC000C000u >> 6)>();
+    kmask[5] = sgpr_const<static_cast<int>(0xC000C000u >> 4)>();
+    kmask[6] = sgpr_const<static_cast<int>(0xC000C000u >> 2)>();
+    kmask[7] = sgpr_const<static_cast<int>(0xC000C000u)>();
+    auto expand = [&](auto kk_tag, auto ni_tag, auto e_tag, const u32x2* br, u32x4* out) __attribute__((always_inline)) {
+        constexpr int kk = decltype(kk_tag)::value, ni = decltype(ni_tag)::value, e = decltype(e_tag)::value;
+        constexpr int i = (kk & 1) * 4 + e;
+        out[ni][e] = (br[ni][kk >> 1] & kmask[i]) << (14 - 2 * i);
+    };
+
+    auto step = [&](auto kk_tag, auto cur_tag, int stage, int next, int fill) __attribute__((always_inline)) {
+        constexpr int KK = decltype(kk_tag)::value;
+        constexpr int CUR = decltype(cur_tag)::value;
+        constexpr int NM = MI * NI;
+        constexpr int SET = KK & 1, NSET = SET ^ 1;
+        constexpr int KN = (KK + 1) & 3;                         // the step being prepared
+        constexpr int BSRC = (KK == 3) ? (CUR ^ 1) : CUR;        // its codes: next slab's after the last step
+        constexpr int HALF = (NLOAD + 2) / 2;                    // loads issued in step 2, the rest in step 3
+        constexpr int G0 = (KK == 2) ? 0 : HALF;
+        constexpr int P_RA = MI;                                 // pieces: fragment reads,
+        constexpr int P_RB = (KK == 2) ? 1 : 0;                  //   codes of the next slab,
+        constexpr int P_D = 4 * NI;                              //   code expansion,
+        constexpr int P_G = (KK == 2) ? HALF : (KK == 3) ? NLOAD + 1 - HALF : 0;   //   global loads
+        constexpr int P = P_RA + P_RB + P_D + P_G;
+        const uint32_t a_addr = lds_base + ((KK == 3) ? next : stage) * STAGE_BYTES + aoff[KN];
+        auto piece = [&](auto p_tag) __attribute__((always_inline)) {
+            constexpr int p = decltype(p_tag)::value;
+            if constexpr (p < P_RA) {
+                lds_read128<p * 32 * 128>(afrag[NSET][p], a_addr);
+            } else if constexpr (p < P_RA + P_RB) {
+                lds_read64_n<NI, 32 * 16>(breg[CUR ^ 1], lds_base + next * STAGE_BYTES + boff);
+            } else if constexpr (p < P_RA + P_RB + P_D) {
+                constexpr int qq = p - P_RA - P_RB;
+                expand(std::integral_constant<int, KN>{}, std::integral_constant<int, qq / 4>{},
+                       std::integral_constant<int, qq % 4>{}, breg[BSRC], bfrag[NSET]);
+            } else {
+                constexpr int gi = G0 + p - (P_RA + P_RB + P_D);
+                if constexpr (gi == 0) issue_setup(fill);
+                issue_load(std::integral_constant<int, gi>{});
+                if constexpr (gi == NLOAD) issue_advance();
+            }
+        };
+        static_for<NM>([&](auto j_tag) __attribute__((always_inline)) {
+            constexpr int jj = decltype(j_tag)::value;
+            constexpr int mi = jj / NI, ni = jj % NI;
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[SET][ni]),
+                                                                  __builtin_bit_cast(bf16x8, afrag[SET][mi]),
+                                                                  acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<P>([&](auto p_tag) __attribute__((always_inline)) {
+                constexpr int p = decltype(p_tag)::value;
+                if constexpr (p * NM / P == jj) piece(p_tag);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        lds_wait<0>();
+        lds_ready<MI>(afrag[NSET]);
+        if constexpr (KK == 2) lds_ready<NI>(breg[CUR ^ 1]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // DEEP variant of a step.  With few MFMAs per step (MI*NI of 2 or 4) the one-step-ahead fragment reads above
+    // leave every step waiting for LDS latency (measured: 1300 cycles per slab for 256 cycles of MFMA work).  Here
+    // step kk reads the fragments of step kk+3 into the set that step kk-1 has just consumed, and waits only for
+    // reads issued two steps earlier:
+    //   step 0: fragments (this slab, step 3);  then the hand-over: all reads done (this stage is then free
+    //           in every wave), next slab landed, barrier;
+    //   step 1: codes of the next slab, fragments (next slab, step 0), first half of the global loads, which
+    //           refill THIS slab's stage with the slab STAGES positions ahead;
+    //   step 2: fragments (next, 1), the other global loads;   step 3: fragments (next, 2).
+    // `hold` (last slab of a tile) skips the global loads: the stage is used by the epilogue first.
+    auto step_deep = [&](auto kk_tag, auto cur_tag, int stage, int next, bool hold) __attribute__((always_inline)) {
+        constexpr int KK = decltype(kk_tag)::value;
+        constexpr int CUR = decltype(cur_tag)::value;
+        constexpr int NM = MI * NI;
+        constexpr int SET = KK & 1, NSET = SET ^ 1;              // expanded codes: one step ahead, as above
+        constexpr int KN = (KK + 1) & 3;
+        constexpr int BSRC = (KK == 3) ? (CUR ^ 1) : CUR;
+        constexpr int RS = (KK + 3) & 3;                         // the step whose fragments are read now
+        constexpr int HALF = (NLOAD + 2) / 2;
+        constexpr int G0 = (KK == 1) ? 0 : HALF;
+        constexpr int P_RB = (KK == 1) ? 1 : 0;
+        constexpr int P_RA = MI;
+        constexpr int P_D = 4 * NI;
+        constexpr int P_G = (KK == 1) ? HALF : (KK == 2) ? NLOAD + 1 - HALF : 0;
+        constexpr int P = P_RB + P_RA + P_D + P_G;
+        const uint32_t a_addr = lds_base + ((KK == 0) ? stage : next) * STAGE_BYTES + aoff[RS];
+        auto piece = [&](auto p_tag) __attribute__((always_inline)) {
+            constexpr int p = decltype(p_tag)::value;
+            if constexpr (p < P_RB) {
+                lds_read64_n<NI, 32 * 16>(breg[CUR ^ 1], lds_base + next * STAGE_BYTES + boff);
+            } else if constexpr (p < P_RB + P_RA) {
+                constexpr int idx = p - P_RB;
+                lds_read128<idx * 32 * 128>(afrag[RS][idx], a_addr);
+            } else if constexpr (p < P_RB + P_RA + P_D) {
+                constexpr int qq = p - P_RB - P_RA;
+                expand(std::integral_constant<int, KN>{}, std::integral_constant<int, qq / 4>{},
+                       std::integral_constant<int, qq % 4>{}, breg[BSRC], bfrag[NSET]);
+            } else {
+                constexpr int gi = G0 + p - (P_RB + P_RA + P_D);
+                if (!hold) {
+                    if constexpr (gi == 0) issue_setup(stage);
+                    issue_load(std::integral_constant<int, gi>{});
+                    if constexpr (gi == NLOAD) issue_advance();
+                }
+            }
+        };
+        static_for<NM>([&](auto j_tag) __attribute__((always_inline)) {
+            constexpr int jj = decltype(j_tag)::value;
+            constexpr int mi = jj / NI, ni = jj % NI;
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[SET][ni]),
+                                                                  __builtin_bit_cast(bf16x8, afrag[DEEP ? KK : 0][mi]),
+                                                                  acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<P>([&](auto p_tag) __attribute__((always_inline)) {
+                constexpr int p = decltype(p_tag)::value;
+                if constexpr (p * NM / P == jj) piece(p_tag);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // LDS operations complete in issue order: "at most 2*MI outstanding" leaves the fragment reads of the
+        // last two steps in flight and guarantees everything older
+        if constexpr (KK == 2) {
+            lds_wait<2 * MI>();
+            lds_ready<NI>(breg[CUR ^ 1]);           // issued first in step 1
+        }
+        if constexpr (KK == 3) {
+            lds_wait<2 * MI>();
+            lds_ready<MI>(afrag[0]);                // issued in step 1
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- epilogue of the tile the compute stream has just finished -------------------------------------
+    uint32_t ct = 0;        // tiles finished so far
+    auto epilogue = [&](int free_stage) __attribute__((always_inline)) {
+        float* cmul = colbuf + (ct & 1u) * (2 * BN);
+        if constexpr (COL_IN_STAGE) {
+            // the free stage may still be read by slower waves
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            cmul = reinterpret_cast<float*>(smem + free_stage * STAGE_BYTES + NW * EPI_WAVE);
+        }
+        float* cadd = cmul + BN;
+        if (tid < BN) {
+            cmul[tid] = 0.5f * cp_alpha * cp_scale;      // codes were +-2
+            cadd[tid] = cp_shift;
+        }
+        // every wave has finished reading the stage of the last slab, and the column parameters are visible:
+        // a bare s_barrier does not wait for this wave's LDS writes, so they are waited for first
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const uint32_t t = tile_id(ct);
+        const uint32_t tm = fdiv_u(t, a.divTN);
+        const uint32_t m0 = tm * BM;
+        const int n0 = static_cast<int>((t - tm * a.tiles_n) * BN);
+        unsigned char* stg = smem + free_stage * STAGE_BYTES + wave * EPI_WAVE;
+        const uint16_t* res = static_cast<const uint16_t*>(g.residual);
+        uint16_t* Yb = static_cast<uint16_t*>(g.Y);
+        // accumulator element e of tile (mi, ni) in this lane: pixel wm*TM + mi*32 + lrow,
+        // channel wn*TN + ni*32 + (e>>2)*8 + lh*4 + (e&3)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const uint32_t m = m0 + static_cast<uint32_t>(wm * TM + mi * 32 + lrow);
+#pragma unroll
+            for (int nc = 0; nc < NI / EPI_NI; ++nc) {
+#pragma unroll
+                for (int nh = 0; nh < EPI_NI; ++nh) {
+                    const int ni = nc * EPI_NI + nh;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const int nl = wn * TN + ni * 32 + q4 * 8 + lh * 4;     // column within the block tile
+                        const f32x4 mul = *reinterpret_cast<const f32x4*>(cmul + nl);
+                        const f32x4 add = *reinterpret_cast<const f32x4*>(cadd + nl);
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][q4 * 4 + e] * mul[e] + add[e];
+                        if (res && m < static_cast<uint32_t>(g.M) && n0 + nl < g.NC) {
+                            const u32x2 rr = *reinterpret_cast<const u32x2*>(res + static_cast<int64_t>(m) * g.ldy + n0 + nl);
+                            v[0] += __uint_as_float(rr[0] << 16);
+                            v[1] += __uint_as_float(rr[0] & 0xFFFF0000u);
+                            v[2] += __uint_as_float(rr[1] << 16);
+                            v[3] += __uint_as_float(rr[1] & 0xFFFF0000u);
+                        }
+                        if (g.relu) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
+                        }
+                        u32x2 pk;
+                        pk[0] = pack_bf16x2(v[0], v[1]);
+                        pk[1] = pack_bf16x2(v[2], v[3]);
+                        *reinterpret_cast<u32x2*>(stg + lrow * EPI_ROW + (nh * 32 + q4 * 8 + lh * 4) * 2) = pk;
+                    }
+                }
+                // same wave wrote and reads: LDS executes a wave's operations in order
+                constexpr int LPR = EPI_CH / 8;          // lanes per staged row (16 bytes each)
+#pragma unroll
+                for (int it = 0; it < 32 * LPR / 64; ++it) {
+                    const int row = it * (64 / LPR) + lane / LPR;
+                    const int c16 = lane % LPR;
+                    const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
+                    const uint32_t mr = m0 + static_cast<uint32_t>(wm * TM + mi * 32 + row);
+                    const int ncol = n0 + wn * TN + nc * EPI_CH + c16 * 8;
+                    if (mr < static_cast<uint32_t>(g.M) && ncol < g.NC)
+                        *reinterpret_cast<u32x4*>(Yb + static_cast<int64_t>(mr) * g.ldy + ncol) = val;
+                }
+            }
+        }
+        acc_clear();
+        ++ct;
+        if (ct < n_my) colparam_load(tile_id(ct));
+    };
+
+    // ---- prologue: column parameters of the first tile, PD slabs in flight, the first one landed ------------
+    colparam_load(tile_id(0));
+    tile_setup(tile_id(0), true);
+#pragma unroll
+    for (int s = 0; s < PD; ++s) {
+        issue_setup(s % STAGES);
+        static_for<NLOAD + 1>(issue_load);
+        issue_advance();
+    }
+    acc_clear();
+    TWN_STRACE(1);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 1) * PER_STAGE));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    TWN_STRACE(2);
+    lds_read64_n<NI, 32 * 16>(breg[0], lds_base + boff);
+    lds_read128_n<MI, 32 * 128>(afrag[0], lds_base + aoff[0]);
+    if constexpr (DEEP) {
+        lds_read128_n<MI, 32 * 128>(afrag[1], lds_base + aoff[1]);
+        lds_read128_n<MI, 32 * 128>(afrag[2], lds_base + aoff[2]);
+    }
+    lds_wait<0>();
+    lds_ready<NI>(breg[0]);
+    lds_ready<MI>(afrag[0]);
+    if constexpr (DEEP) {
+        lds_ready<MI>(afrag[1]);
+        lds_ready<MI>(afrag[2]);
+    }
+    static_for<4 * NI>([&](auto q_tag) __attribute__((always_inline)) {
+        constexpr int qq = decltype(q_tag)::value;
+        expand(std::integral_constant<int, 0>{}, std::integral_constant<int, qq / 4>{},
+               std::integral_constant<int, qq % 4>{}, breg[0], bfrag[0]);
+    });
+
+    int stage = 0;          // stage of the slab being multiplied
+    int fill = PD % STAGES; // stage that the slab PD positions ahead goes to (DEEP: the current stage)
+    int kt = 0;             // slab of the current tile
+    // one slab of the stream; CUR selects the register set holding this slab's packed codes
+    auto slab = [&](auto cur_tag) __attribute__((always_inline)) {
+        const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
+        if constexpr (DEEP) {
+            const bool last = (kt == KT - 1);
+            step_deep(std::integral_constant<int, 0>{}, cur_tag, stage, next, last);
+            // hand-over: every fragment read of this wave has completed (this slab's stage is free once all
+            // waves are here), the next slab has landed (the PD-2 younger ones may stay in flight)
+            lds_wait<0>();
+            lds_ready<MI>(afrag[1]);
+            lds_ready<MI>(afrag[2]);
+            lds_ready<MI>(afrag[3]);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 2) * PER_STAGE));
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            step_deep(std::integral_constant<int, 1>{}, cur_tag, stage, next, last);
+            step_deep(std::integral_constant<int, 2>{}, cur_tag, stage, next, last);
+            step_deep(std::integral_constant<int, 3>{}, cur_tag, stage, next, last);
+            const int done = stage;
+            stage = next;
+            if (last) {
+                kt = 0;
+                TWN_STRACE(3 + 2 * ct);
+                epilogue(done);
+                TWN_STRACE(2 + 2 * ct);      // ct was advanced by the epilogue
+                // the staging rows of every wave have been read back: the stage can take its next slab
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                issue_setup(done);
+                static_for<NLOAD + 1>(issue_load);
+                issue_advance();
+            } else {
+                ++kt;
+            }
+        } else {
+#ifdef TWN_TRACE
+            // fine-grained timeline of one slab (every step ends with lgkmcnt(0), which also covers s_memtime)
+            uint64_t ts[7];
+#define TWN_TS(i) asm volatile("s_memtime %0" : "=s"(ts[i]))
+#else
+#define TWN_TS(i) do {} while (0)
+#endif
+            TWN_TS(0);
+            step(std::integral_constant<int, 0>{}, cur_tag, stage, next, fill);
+            TWN_TS(1);
+            step(std::integral_constant<int, 1>{}, cur_tag, stage, next, fill);
+            // hand-over: the next slab of the stream has landed (the PD-2 younger slabs may stay in flight), the
+            // stage of the previous slab is free
+            TWN_TS(2);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 2) * PER_STAGE));
+            TWN_TS(3);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            TWN_TS(4);
+            step(std::integral_constant<int, 2>{}, cur_tag, stage, next, fill);
+            TWN_TS(5);
+            step(std::integral_constant<int, 3>{}, cur_tag, stage, next, fill);
+            TWN_TS(6);
+#ifdef TWN_TRACE
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (g_stream_trace && threadIdx.x == 0 && ct == 0 && kt == 5) {
+                for (int i = 0; i < 7; ++i) g_stream_trace[static_cast<size_t>(blockIdx.x) * 16 + 8 + i] = ts[i];
+            }
+#endif
+            const int done = stage;
+            stage = next;
+            fill = (fill + 1 == STAGES) ? 0 : fill + 1;
+            if (++kt == KT) {
+                kt = 0;
+                TWN_STRACE(3 + 2 * ct);
+                epilogue(done);
+                TWN_STRACE(2 + 2 * ct);      // ct was advanced by the epilogue
+            }
+        }
+    };
+    const uint32_t total = n_my * static_cast<uint32_t>(KT);
+    for (uint32_t s = 0; s < total; s += 2) {
+        slab(std::integral_constant<int, 0>{});
+        if (s + 1 < total) slab(std::integral_constant<int, 1>{});
+    }
+    // the trailing zero loads still target this workgroup's LDS: they must have landed before it ends
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+}
+
+// ---- host side ------------------------------------------------------------------------------------------
+
+bool conv_stream_applicable(const GatherGemm& g) {
+    if (g.y_f32 || g.NC % 8 != 0 || g.ldy % 8 != 0 || g.orU != 0 || g.splits > 1 || g.chunk_gather) return false;
+    if (g.M <= 0 || g.M >= (1LL << 31) - 1024) return false;
+    if (g.plain_gemm) {
+        if (g.K % 64 != 0 || g.xs % 8 != 0) return false;
+    } else {
+        if (g.divh != 1 || g.divw != 1 || g.IC % 64 != 0 || g.xs % 8 != 0) return false;
+        if (g.M % (static_cast<int64_t>(g.OH) * g.OW) != 0) return false;
+    }
+    if (!aligned(g.X, 16) || !aligned(g.Wq, 16) || !aligned(g.Y, 16) || (g.residual && !aligned(g.residual, 8))) return false;
+    const int64_t in_rows = g.plain_gemm ? g.M : (g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW;
+    const int64_t xb = ((in_rows - 1) * g.xs + (g.plain_gemm ? g.K : g.IC)) * 2;
+    const int64_t wb = static_cast<int64_t>(g.NC) * g.wpr * 4;
+    return xb > 0 && xb < (1LL << 31) && wb < (1LL << 31);
+}
+
+namespace {
+
+int num_cus(hipStream_t) {
+    static std::once_flag once;
+    static int cus = 256;
+    std::call_once(once, [] {
+        int dev = 0;
+        hipDeviceProp_t p;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess && p.multiProcessorCount > 0)
+            cus = p.multiProcessorCount;
+    });
+    return cus;
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, int OCC, bool DEEP>
+int32_t launch_stream_kernel(const StreamArgs& a, hipStream_t st) {
+    constexpr int PIPE = STAGES * (BM * 128 + BN * 16);
+    constexpr int SMEM = ((PIPE + 4 * BN * 4) * OCC > 160 * 1024) ? PIPE : PIPE + 4 * BN * 4;   // see COL_IN_STAGE
+    static_assert(SMEM <= 160 * 1024, "LDS budget");
+    auto k = conv_stream_kernel<BM, BN, WM, WN, STAGES, GEMM, OCC, DEEP>;
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel; the occupancy query sizes the grid
+    static std::once_flag once;
+    static int per_cu = 0;
+    std::call_once(once, [&] {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, SMEM) !=
+            hipSuccess)
+            return;
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k, 64 * WM * WN, SMEM) == hipSuccess && n > 0) per_cu = n;
+    });
+    if (per_cu <= 0) return TWN_ERR_HIP;
+    int occ = per_cu;
+    const int cap = env_int("TWN_STREAM_OCC", 0);
+    if (cap > 0 && cap < occ) occ = cap;
+    int64_t grid = static_cast<int64_t>(num_cus(st)) * occ;
+    if (grid > a.tiles) grid = a.tiles;
+    k<<<dim3(static_cast<unsigned>(grid)), dim3(64 * WM * WN), SMEM, st>>>(a);
+    return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int OCC, bool DEEP>
+int32_t launch_stream_tile(const GatherGemm& g, hipStream_t st) {
+    const int64_t tiles_n = (g.NC + BN - 1) / BN;
+    const int64_t tiles = ((g.M + BM - 1) / BM) * tiles_n;
+    if (tiles <= 0 || tiles >= (1LL << 31)) return TWN_ERR_SHAPE;
+    StreamArgs a;
+    a.g = g;
+    a.divOW = make_fastdiv_u(static_cast<uint32_t>(g.OW));
+    a.divOH = make_fastdiv_u(static_cast<uint32_t>(g.OH));
+    a.divTN = make_fastdiv_u(static_cast<uint32_t>(tiles_n));
+    const int64_t in_rows = g.plain_gemm ? g.M : (g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW;
+    a.x_bytes = static_cast<uint32_t>(((in_rows - 1) * g.xs + (g.plain_gemm ? g.K : g.IC)) * 2);
+    a.w_bytes = static_cast<uint32_t>(static_cast<int64_t>(g.NC) * g.wpr * 4);
+    a.tiles = static_cast<uint32_t>(tiles);
+    a.tiles_n = static_cast<uint32_t>(tiles_n);
+    a.KT = g.K / 64;
+    return g.plain_gemm ? launch_stream_kernel<BM, BN, WM, WN, STAGES, true, OCC, DEEP>(a, st)
+                        : launch_stream_kernel<BM, BN, WM, WN, STAGES, false, OCC, DEEP>(a, st);
+}
+
+}  // namespace
+
+// Tile ids as in launch_gather_gemm_dma: 12 = 128x128 2x2, 14 = 64x128 1x4, 15 = 128x128 1x4, 16 = 128x64 2x2,
+// 17 = 128x256 1x4 (4 stages).  The caller has checked conv_stream_applicable.
+int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st) {
+    const bool deep = env_int("TWN_STREAM_DEEP", 1) != 0;
+    switch (tile) {
+        case 12: return deep ? launch_stream_tile<128, 128, 2, 2, 3, 2, true>(g, st) : launch_stream_tile<128, 128, 2, 2, 3, 2, false>(g, st);
+        case 14: return deep ? launch_stream_tile<64, 128, 1, 4, 3, 4, true>(g, st) : launch_stream_tile<64, 128, 1, 4, 3, 4, false>(g, st);
+        case 15: return deep ? launch_stream_tile<128, 128, 1, 4, 3, 2, true>(g, st) : launch_stream_tile<128, 128, 1, 4, 3, 2, false>(g, st);
+        case 16: return deep ? launch_stream_tile<128, 64, 2, 2, 3, 3, true>(g, st) : launch_stream_tile<128, 64, 2, 2, 3, 3, false>(g, st);
+        case 17: return launch_stream_tile<128, 256, 1, 4, 4, 2, false>(g, st);
+        default: return TWN_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace twn

@@ -72,6 +72,12 @@ int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int 
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 
+// Persistent variant of the direct-to-LDS kernel (workgroups walk a list of tiles, loads of the next tile run
+// under the epilogue of the last); `applicable` is a pure function of the problem, `tile` one of the ids the
+// direct-to-LDS launcher takes (12, 14, 15, 16, 17).
+bool conv_stream_applicable(const GatherGemm& g);
+int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st);
+
 // Halo-tiled kernel for stride-1 filters with several taps (activations staged once per 64-channel slab and
 // reused by every tap); `applicable` is a pure function of the problem.
 bool conv_halo_applicable(const GatherGemm& g);
