@@ -1,17 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of the TWN hot path on one MI355X.
 
-A step is one pass of the whole hot path over one batch of the VGG-7 / CIFAR
-workload (batch 128, bf16 activations): ternarize all 8 weight tensors
-(Delta, alpha, 2-bit codes and the transposed copy), forward every conv / FC
-layer with the fused scale-shift-ReLU tail, then the straight-through backward
-of every layer (dX and dW on two streams, they are independent of each other).  Inputs are seeded synthetic tensors already
-resident in HBM.  Prints ONE JSON line on stdout; per-layer detail goes to stderr.
+Headline workload: ResNet-18, batch 64, bf16 (the configuration both the metric and the target are stated on).
+A step is one pass of the forward hot path over one batch: ONE multi-tensor ternarize call for all 21 weight
+tensors (Delta, alpha, 2-bit codes), then the forward of every conv / FC layer with its fused block tail
+(scale, shift, residual on the second conv of a block, ReLU).  Every layer reads its own seeded synthetic input
+of the right shape, already resident in HBM; the layers run one after the other on one stream, as the data
+dependences of the network demand.  `value` is the dense-equivalent throughput of the step (2MNK per
+contraction / step time); images per second are in `config`.
+
+Side measurements (structured, each with its own roofline object): the 8192x4096x4096 GEMM, the 2^28-element
+ternarize, and timings of the other configurations (LeNet b64 fp32, VGG-7 b128 forward + straight-through
+backward, the VGG-16-style backbone b32, ResNet-18 backward, ResNet-18 with one alpha per filter).
+
+Prints ONE JSON line on stdout; per-layer detail goes to stderr.
 """
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -21,15 +29,24 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # dense bf16 MFMA, MI355X
 PEAK_HBM_GBPS = 8000.0
-# HBM-side bytes per launch of the roofline sample (L2 fills + write-backs, rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE scaled by a 1 GiB copy), taken from profiles/vgg7_b128_step_kernels.txt; it is a property of
-# the committed kernels and tile choices at this workload, re-measured whenever those change.
-ROOFLINE_SAMPLE_TRAFFIC_BYTES = 33194744
 F = 0.7
+PROFILES = os.path.join(ROOT, "profiles")
+# consecutive forward calls of the headline step that are ONE launch each of the same kernel on the same shape:
+# the sample the `roofline` object is measured on (two events per step bracket the run)
+ROOFLINE_LAYERS = ("l1.0.conv1", "l1.0.conv2", "l1.1.conv1", "l1.1.conv2")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def profile_value(fname, key):
+    """`key=<number>` from a committed rocprofv3 summary under profiles/ (None if the file or the key is absent)."""
+    path = os.path.join(PROFILES, fname)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^%s\s*=\s*([0-9.eE+-]+)" % re.escape(key), open(path).read(), re.M)
+    return float(m.group(1)) if m else None
 
 
 def main():
@@ -38,13 +55,12 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--no-extras", action="store_true", help="skip the GEMM / ternarize-2^28 / ResNet-18 side measurements")
-    ap.add_argument("--cpu-batch", type=int, default=128)
-    ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18"], default=None,
-                    help="run one side measurement alone (used for the rocprofv3 summaries in profiles/)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the side measurements")
+    ap.add_argument("--cpu-batch", type=int, default=8)
+    ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18", "resnet18_bwd", "lenet", "vgg7", "vgg16_ssd",
+                                       "per_filter"], default=None,
+                    help="run one measurement alone (used for the rocprofv3 summaries in profiles/)")
     ap.add_argument("--variants", action="store_true", help="with --only gemm: also time the comparison weight formats")
-    ap.add_argument("--graph", action="store_true", help="also capture the step into a HIP graph and time its replay")
-    ap.add_argument("--eager-backward", action="store_true", help="launch the backward eagerly instead of replaying its HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -66,10 +82,13 @@ def main():
     def dev_bf16(a):
         return torch.from_numpy(wl.f32_to_bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16).reshape(a.shape)
 
+    def new_ev():
+        return torch.cuda.Event(enable_timing=True)
+
     def time_call(fn, reps=10, warm=2):
         for _ in range(warm):
             fn()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a, b = new_ev(), new_ev()
         a.record()
         for _ in range(reps):
             fn()
@@ -77,35 +96,109 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / reps
 
+    def geo(L):
+        return (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2
 
+    def layer_bytes(L):
+        # algorithmic bytes of one forward call: bf16 activations in and out plus the 2-bit codes
+        return 2 * L.N * L.H * L.W * L.C + 2 * L.N * L.P * L.Q * L.O + L.n_weights // 4
+
+    def roof_obj(kernel, bound, achieved, peak, unit, alg_bytes, traffic_file, launch_us, **more):
+        traffic = profile_value(traffic_file, "traffic_bytes_per_launch") if traffic_file else None
+        o = {"kernel": kernel, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+             "frac": round(achieved / peak, 4), "traffic": None if traffic is None else int(traffic),
+             "traffic_source": ("profiles/" + traffic_file) if traffic is not None else None,
+             "algorithmic_bytes_per_launch": int(alg_bytes), "avg_launch_us": round(launch_us, 2)}
+        o.update(more)
+        return o
+
+    # ------------------------------------------------------------------ network forward builders
+    def build_forward(layers, cfg, fp32=False, residual_on=("conv2",), groups_per_filter=False, transposed=False):
+        """Device tensors and prepared calls for the forward of a list of layers (each with its own input)."""
+        W, X, Y, tws, calls = [], [], [], [], []
+        for li, L in enumerate(layers):
+            w = wl.kaiming_weights(cfg, li, L)
+            W.append(torch.from_numpy(w).to(dev))
+            if fp32:
+                X.append(torch.from_numpy(wl.uniform01(cfg, wl.IDX_INPUT + li, L.x_shape)).to(dev))
+            else:
+                X.append(dev_bf16(wl.normal(cfg, wl.IDX_INPUT + li, L.x_shape)))
+            Y.append(torch.empty(L.y_shape, dtype=torch.float32 if fp32 else torch.bfloat16, device=dev))
+            groups = L.O if groups_per_filter else 1
+            tws.append(api.twn_ternarize(W[li], F, groups=groups, transposed=transposed))
+        for li, L in enumerate(layers):
+            st, pd, dl = geo(L)
+            is_fc = (L.R == 1 and L.S == 1 and L.H == 1 and L.W == 1)
+            last = (li == len(layers) - 1)
+            sc = torch.ones(L.O, dtype=torch.float32, device=dev)
+            sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
+            res = None
+            if not fp32 and any(L.name.endswith(s) for s in residual_on):
+                res = dev_bf16(wl.normal(cfg, 700 + li, L.y_shape))
+            if is_fc:
+                calls.append(api.prepare_gemm_fwd(X[li].reshape(L.N, L.C), tws[li], out=Y[li].reshape(L.N, L.O),
+                                                  scale=None if last else sc, shift=sf, relu=not last))
+            else:
+                calls.append(api.prepare_conv2d_fwd(X[li], tws[li], st, pd, dl, out=Y[li], scale=sc, shift=sf,
+                                                    residual=res, relu=True))
+        return W, X, Y, tws, calls
+
+    def per_layer_table(tag, layers, calls, reps=100, warm=20):
+        tot = 0.0
+        rows = []
+        for L, c in zip(layers, calls):
+            t = time_call(c, reps=reps, warm=warm)
+            tot += t
+            rows.append((L.name, t))
+            log("%s %-12s %26s %9.1f us %8.1f TFLOP/s-eq" % (tag, L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
+        return tot, rows
+
+    def graph_of(fn):
+        """Capture fn (library calls only launch kernels and take their workspaces from the caller) and return the
+        replayable graph, or None when capture is not available."""
+        try:
+            cap = torch.cuda.Stream()
+            cap.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(cap):
+                fn()
+            torch.cuda.synchronize()
+            g_ = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_, stream=cap):
+                fn()
+            torch.cuda.synchronize()
+            return g_
+        except RuntimeError as e:
+            log("graph capture failed (%s)" % str(e).splitlines()[0])
+            torch.cuda.synchronize()
+            return None
+
+    # ------------------------------------------------------------------ side measurements
     def side_gemm():
-        # stand-alone GEMM: X [8192 x 4096] bf16, W [4096 x 4096] N(0, 0.02^2)
         g = wl.gemm_config()
         gx = dev_bf16(wl.normal(3, wl.IDX_INPUT, (g.N, g.C)))
         gw = torch.from_numpy(wl.normal(3, 1, (g.O, g.C), std=0.02)).to(dev)
         gtw = api.twn_ternarize(gw, F)
         gy = torch.empty((g.N, g.O), dtype=torch.bfloat16, device=dev)
-        t = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=300, warm=100)
-        log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq" % (t * 1e3, g.flops / t / 1e9))
-        res = {"us": round(t * 1e3, 1), "tflops": round(g.flops / t / 1e9, 1),
-               "frac_mfma_peak": round(g.flops / t / 1e9 / PEAK_BF16_TFLOPS, 4)}
-        if args.only == "gemm" and not args.variants:
-            return res
-        # The two comparison variants live in the register-staged 128x128 kernel only; the product format is
-        # timed in that same kernel (TWN_TILE=4 selects it) so that only the weight format differs.
-        os.environ["TWN_TILE"] = "4"
-        same = {"postscale_2bit": time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=60, warm=20)}
-        del os.environ["TWN_TILE"]
-        for name, var in (("alpha_at_expansion_2bit", api.TWN_VAR_BF16_ALPHA_LDS),
-                          ("int8_stored", api.TWN_VAR_I8_STORED_POSTSCALE)):
-            same[name] = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy, variant=var), reps=60, warm=20)
-        for k, v in same.items():
-            log("gemm weight format %-24s %.1f us, %.1f TFLOP/s-eq (register-staged 128x128 kernel)" % (k, v * 1e3, g.flops / v / 1e9))
-        res["weight_formats_same_kernel_us"] = {k: round(v * 1e3, 1) for k, v in same.items()}
+        call = api.prepare_gemm_fwd(gx, gtw, out=gy)
+        t = time_call(call, reps=300, warm=100)
+        tf = g.flops / t / 1e9
+        log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq (%.3f of 2.5 PFLOP/s)" % (t * 1e3, tf, tf / PEAK_BF16_TFLOPS))
+        res = roof_obj("contraction kernel, 128x256 tile", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", layer_bytes(g),
+                       "gemm_8192x4096x4096_kernels.txt", t * 1e3, workload="gemm_8192x4096x4096_bf16", us=round(t * 1e3, 1),
+                       flops_per_launch=g.flops)
+        if args.variants:
+            os.environ["TWN_TILE"] = "4"
+            same = {"postscale_2bit": time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=60, warm=20)}
+            del os.environ["TWN_TILE"]
+            for name, var in (("alpha_at_expansion_2bit", api.TWN_VAR_BF16_ALPHA_LDS),
+                              ("int8_stored", api.TWN_VAR_I8_STORED_POSTSCALE)):
+                same[name] = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy, variant=var), reps=60, warm=20)
+            for k, v in same.items():
+                log("gemm weight format %-24s %.1f us (register-staged 128x128 kernel)" % (k, v * 1e3))
+            res["weight_formats_same_kernel_us"] = {k: round(v * 1e3, 1) for k, v in same.items()}
         return res
 
     def side_ternarize(calibrate=False):
-        # ternarize-only: 2^28 float32 N(0,1) shaped [16384][16384]
         rows = 1 << 14
         big = torch.from_numpy(wl.normal(3, 0, (rows, rows))).to(dev)
         ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
@@ -119,373 +212,281 @@ def main():
         btw = api.twn_ternarize(big, F)
         t = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=ws), reps=100, warm=20)
         nbytes = (1 << 28) * 8.25
-        log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight)" % (t * 1e3, nbytes / t / 1e6))
-        return {"us": round(t * 1e3, 1), "GBps": round(nbytes / t / 1e6, 1),
-                "frac_hbm_peak": round(nbytes / t / 1e6 / PEAK_HBM_GBPS, 4)}
+        gbps = nbytes / t / 1e6
+        res = roof_obj("abs_sum_kernel + mask_pack_flat_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s", nbytes,
+                       "ternarize_2p28_hbm.txt", t * 1e3, workload="ternarize_2p28_f32", us=round(t * 1e3, 1))
+        # HBM-side rate: bytes the memory actually served (the counters of the committed profile) over this run's
+        # time; pass 2 walks W backwards, so the end of pass 1 is re-read from the 256 MB Infinity Cache
+        if res["traffic"] is not None:
+            res["hbm_side_GBps"] = round(res["traffic"] / t / 1e6, 1)
+            res["hbm_side_frac"] = round(res["traffic"] / t / 1e6 / PEAK_HBM_GBPS, 4)
+        # the same call with pass 2 walking forwards (nothing of pass 1 left in the cache): all 8.25 B/weight from HBM
+        os.environ["TWN_TERN_REVERSE"] = "0"
+        t_fwd = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=ws), reps=50, warm=10)
+        del os.environ["TWN_TERN_REVERSE"]
+        res["forward_walk_us"] = round(t_fwd * 1e3, 1)
+        res["forward_walk_GBps"] = round(nbytes / t_fwd / 1e6, 1)
+        log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight); forward-walking pass 2: %.1f us, %.1f GB/s"
+            % (t * 1e3, gbps, t_fwd * 1e3, nbytes / t_fwd / 1e6))
+        return res
 
-    def side_resnet18():
-        # ResNet-18, batch 64: forward (per-layer synthetic inputs, fused scale/shift/ReLU tail) and STE backward
-        rl = wl.resnet18(64)
+    def side_lenet():
+        layers = wl.lenet5(64)
+        W, X, Y, tws, calls = build_forward(layers, 0, fp32=True)
+        tot, rows = per_layer_table("lenet", layers, calls)
+
+        def fwd():
+            for c in calls:
+                c()
+        g_ = graph_of(fwd)
+        t_graph = time_call(g_.replay, reps=200, warm=20) if g_ is not None else None
+        flops = sum(L.flops for L in layers)
+        best = t_graph if t_graph is not None else tot
+        log("lenet b64 fp32 forward: serial %.1f us, graph replay %s us, %.0f img/s" %
+            (tot * 1e3, "%.1f" % (t_graph * 1e3) if t_graph else "n/a", 64 / (best * 1e-3)))
+        return {"workload": "lenet5_b64_fp32_forward", "serial_us": round(tot * 1e3, 1),
+                "graph_replay_us": None if t_graph is None else round(t_graph * 1e3, 1),
+                "img_per_s": round(64 / (best * 1e-3), 1), "gflops": round(flops / best / 1e6, 1),
+                "per_layer_us": {n: round(t * 1e3, 1) for n, t in rows}, "bound": "launch latency"}
+
+    def side_vgg16():
+        layers = wl.vgg16_ssd(32)
         tot = 0.0
-        tot_b = 0.0
-        for li, L in enumerate(rl):
-            x = dev_bf16(wl.normal(2, wl.IDX_INPUT + li, L.x_shape))
-            tw = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev), F)
-            y = torch.empty(L.y_shape, dtype=torch.bfloat16, device=dev)
-            sc = torch.ones(L.O, dtype=torch.float32, device=dev)
-            sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
-            st, pd, dl = (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2
-            ws = torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tw, st, pd, dl)), dtype=torch.uint8,
-                             device=dev)
-            t = time_call(lambda: api.twn_conv2d_fwd(x, tw, st, pd, dl, scale=sc, shift=sf, relu=True, out=y,
-                                                     workspace=ws), reps=100, warm=20)
+        rows = {}
+        for li, L in enumerate(layers):
+            # one layer resident at a time (the first layers' activations are 0.7 GB each)
+            W, X, Y, tws, calls = build_forward([L], 4, residual_on=())
+            t = time_call(calls[0], reps=30, warm=5)
             tot += t
-            # straight-through backward of the same layer (serial: data gradient, then weight gradient)
-            twt = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev), F, transposed=True)
-            dy = dev_bf16(wl.normal(2, wl.IDX_DY + 10 * li, L.y_shape))
-            wsb_ = torch.empty(max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, twt, st, pd, dl)),
-                               dtype=torch.uint8, device=dev)
+            rows[L.name] = round(t * 1e3, 1)
+            log("vgg16_ssd %-8s %28s %9.1f us %8.1f TFLOP/s-eq" % (L.name, str(L.gemm_mnk), t * 1e3, L.flops / t / 1e9))
+            del W, X, Y, tws, calls
+            torch.cuda.empty_cache()
+        flops = sum(L.flops for L in layers)
+        log("vgg16-style backbone b32 forward: %.3f ms, %.0f img/s, %.1f TFLOP/s-eq" % (tot, 32 / (tot * 1e-3), flops / tot / 1e9))
+        return {"workload": "vgg16_ssd_b32_bf16_forward", "ms": round(tot, 4), "img_per_s": round(32 / (tot * 1e-3), 1),
+                "tflops": round(flops / tot / 1e9, 1), "frac_mfma_peak": round(flops / tot / 1e9 / PEAK_BF16_TFLOPS, 4),
+                "per_layer_us": rows}
+
+    def backward_table(tag, layers, cfg):
+        tot_dx = tot_dw = 0.0
+        for li, L in enumerate(layers):
+            st, pd, dl = geo(L)
+            x = dev_bf16(wl.normal(cfg, wl.IDX_INPUT + li, L.x_shape))
+            dy = dev_bf16(wl.normal(cfg, wl.IDX_DY + 10 * li, L.y_shape))
+            twt = api.twn_ternarize(torch.from_numpy(wl.kaiming_weights(cfg, li, L)).to(dev), F, transposed=True)
+            ws = torch.empty(max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, twt, st, pd, dl)), dtype=torch.uint8,
+                             device=dev)
             dxo = torch.empty(L.x_shape, dtype=torch.bfloat16, device=dev)
             dwo = torch.empty(L.w_shape, dtype=torch.float32, device=dev)
-            tb = time_call(lambda: api.twn_conv2d_bwd_ste(x, dy, twt, st, pd, dl, need_dx=(li > 0), need_dw=True, dX=dxo,
-                                                          dW=dwo, workspace=wsb_), reps=50, warm=10)
-            tot_b += tb
-            log("resnet18 %-12s %24s %9.1f us %8.1f TFLOP/s-eq | bwd %8.1f us" % (L.name, str(L.gemm_mnk), t * 1e3,
-                                                                                L.flops / t / 1e9, tb * 1e3))
-            del x, y, dy, dxo, dwo, wsb_
-        rflops = sum(L.flops for L in rl)
-        log("resnet18 b64 conv/fc layers: fwd %.3f ms, %.0f img/s; STE backward (dX + dW, serial) %.3f ms" %
-            (tot, 64 / (tot * 1e-3), tot_b))
-        return {"ms": round(tot, 4), "img_per_s": round(64 / (tot * 1e-3), 1), "tflops": round(rflops / tot / 1e9, 1),
-                "frac_mfma_peak": round(rflops / tot / 1e9 / PEAK_BF16_TFLOPS, 4), "bwd_serial_ms": round(tot_b, 4)}
+            tdx = 0.0
+            if li > 0:
+                c = api.prepare_conv2d_bwd_ste(None, dy, twt, st, pd, dl, dX=dxo, workspace=ws, x_shape=L.x_shape)
+                tdx = time_call(c, reps=50, warm=10)
+            c = api.prepare_conv2d_bwd_ste(x, dy, twt, st, pd, dl, dW=dwo, workspace=ws)
+            tdw = time_call(c, reps=50, warm=10)
+            tot_dx += tdx
+            tot_dw += tdw
+            log("%s %-12s %26s  dX %8.1f us  dW %8.1f us" % (tag, L.name, str(L.gemm_mnk), tdx * 1e3, tdw * 1e3))
+            del x, dy, dxo, dwo, ws
+        return tot_dx, tot_dw
 
-    if args.only:
-        res = {"gemm": side_gemm, "ternarize": lambda: side_ternarize(calibrate=True), "resnet18": side_resnet18}[args.only]()
-        print(json.dumps({"only": args.only, **res}), flush=True)
-        return
+    def side_resnet18_bwd():
+        layers = wl.resnet18(64)
+        tdx, tdw = backward_table("resnet18-bwd", layers, 2)
+        flops = sum(L.flops for L in layers) + sum(L.flops for L in layers[1:])
+        log("resnet18 b64 straight-through backward, serial: dX %.3f ms + dW %.3f ms" % (tdx, tdw))
+        return {"workload": "resnet18_b64_bf16_ste_backward", "dx_ms": round(tdx, 4), "dw_ms": round(tdw, 4),
+                "tflops": round(flops / (tdx + tdw) / 1e9, 1),
+                "frac_mfma_peak": round(flops / (tdx + tdw) / 1e9 / PEAK_BF16_TFLOPS, 4)}
 
-    # ---------------- workload: VGG-7, batch 128 ----------------
-    CFG = 1
-    layers = wl.vgg7(128)
-    W, X, dY, Y, dX, dW, tws, wsb, wsw, scale, shift = [], [], [], [], [], [], [], [], [], [], []
-    tern_ws = None
-    for li, L in enumerate(layers):
-        w = wl.kaiming_weights(CFG, li, L)
-        W.append(torch.from_numpy(w).to(dev))
-        X.append(dev_bf16(wl.normal(CFG, wl.IDX_INPUT + li, L.x_shape)))
-        dY.append(dev_bf16(wl.normal(CFG, wl.IDX_DY + 10 * li, L.y_shape)))
-        Y.append(torch.empty(L.y_shape, dtype=torch.bfloat16, device=dev))
-        dX.append(torch.empty(L.x_shape, dtype=torch.bfloat16, device=dev) if li > 0 else None)
-        dW.append(torch.empty(L.w_shape, dtype=torch.float32, device=dev))
-        scale.append(torch.ones(L.O, dtype=torch.float32, device=dev))
-        shift.append(torch.zeros(L.O, dtype=torch.float32, device=dev))
-        tws.append(api.twn_ternarize(W[li], F, transposed=True))
-        nws = max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, tws[li], (L.stride,) * 2, (L.pad,) * 2,
-                                                             (L.dil,) * 2))
-        wsb.append(torch.empty(nws, dtype=torch.uint8, device=dev))      # backward-data (split-K partials)
-        wsw.append(torch.empty(nws, dtype=torch.uint8, device=dev))      # backward-weight (split partials)
-    tern_ws = torch.empty(api.lib().twn_ternarize_batch_workspace_bytes(len(layers)), dtype=torch.uint8, device=dev)
-    geo = [((L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2) for L in layers]
-    wsf = [torch.empty(max(16, api.twn_conv2d_fwd_workspace_bytes(L.x_shape, tws[li], *geo[li])), dtype=torch.uint8,
-                       device=dev) for li, L in enumerate(layers)]
+    def side_vgg7():
+        layers = wl.vgg7(128)
+        W, X, Y, tws, calls = build_forward(layers, 1, residual_on=(), transposed=True)
+        tern = api.prepare_ternarize_batch(W, tws, F)
+        t_tern = time_call(tern, reps=50, warm=10)
+        t_fwd, _ = per_layer_table("vgg7", layers, calls, reps=50, warm=10)
+        del X, Y, calls
+        torch.cuda.empty_cache()
+        tdx, tdw = backward_table("vgg7-bwd", layers, 1)
+        f_fwd = sum(L.flops for L in layers)
+        f_all = 2 * f_fwd + sum(L.flops for L in layers[1:])
+        t_all = t_tern + t_fwd + tdx + tdw
+        log("vgg7 b128 step, serial: ternarize %.3f + fwd %.3f + dX %.3f + dW %.3f = %.3f ms, %.1f TFLOP/s-eq" %
+            (t_tern, t_fwd, tdx, tdw, t_all, f_all / t_all / 1e9))
+        return {"workload": "vgg7_cifar_b128_bf16_step_serial", "ternarize_ms": round(t_tern, 4), "fwd_ms": round(t_fwd, 4),
+                "dx_ms": round(tdx, 4), "dw_ms": round(tdw, 4), "ms": round(t_all, 4),
+                "tflops": round(f_all / t_all / 1e9, 1), "frac_mfma_peak": round(f_all / t_all / 1e9 / PEAK_BF16_TFLOPS, 4),
+                "img_per_s": round(128 / (t_all * 1e-3), 1)}
 
-    flops_fwd = sum(L.flops for L in layers)
-    flops_dx = sum(L.flops for L in layers[1:])
-    flops_dw = flops_fwd
-    flops_step = flops_fwd + flops_dx + flops_dw
-    tern_bytes = sum(L.n_weights for L in layers) * 8.5      # two reads + two 2-bit copies
+    def side_per_filter():
+        # Alg. 1 as printed: one (Delta, alpha) per filter; ResNet-18 has 4800 filters in 21 tensors
+        layers = wl.resnet18(64)
+        t_tern = 0.0
+        t_fwd = 0.0
+        for li, L in enumerate(layers):
+            w = torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev)
+            tw = api.twn_ternarize(w, F, groups=L.O)
+            ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
+            t_tern += time_call(lambda: api.twn_ternarize(w, F, groups=L.O, out=tw, workspace=ws), reps=30, warm=5)
+            W, X, Y, tws, calls = build_forward([L], 2, residual_on=(), groups_per_filter=True)
+            t_fwd += time_call(calls[0], reps=50, warm=10)
+            del W, X, Y, tws, calls
+        log("resnet18 per-filter (Alg. 1): ternarize of 21 tensors, one call each %.3f ms; forward %.3f ms" % (t_tern, t_fwd))
+        return {"workload": "resnet18_b64_per_filter_alpha", "ternarize_ms": round(t_tern, 4), "fwd_ms": round(t_fwd, 4)}
 
-    # One step.  Main stream: ONE multi-tensor ternarize call (three launches for the eight tensors), then the
-    # forward of every layer.  Backward: the data gradients and the weight gradients of a layer do not depend
-    # on each other (nor do the weight gradients of different layers), so they run on side streams forked from
-    # the main stream after the forward and joined at
-    # the end (the tail of one kernel is filled by the other stream's work).  `calls` lists every library
-    # call as (phase, layer index, callable(stream)); the one-tensor ternarize entry point is timed per
-    # layer in the detail pass below.
-    calls = [("ternarize", 0, lambda st_=None: api.twn_ternarize_batch(W, F, transposed=True, out=tws, workspace=tern_ws))]
-    tern_single = [lambda li=li: api.twn_ternarize(W[li], F, transposed=True, out=tws[li], workspace=tern_ws)
-                   for li in range(len(layers))]
-    for li in range(len(layers)):
-        st, pd, dl = geo[li]
-        calls.append(("fwd", li, lambda st_=None, li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_fwd(
-            X[li], tws[li], st, pd, dl, scale=scale[li], shift=shift[li], relu=True, out=Y[li], workspace=wsf[li])))
-    n_main = len(calls)
-    for li in range(len(layers) - 1, 0, -1):
-        st, pd, dl = geo[li]
-        calls.append(("bwd_data", li, lambda st_=None, li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
-            None, dY[li], tws[li], st, pd, dl, need_dx=True, need_dw=False, dX=dX[li], x_shape=layers[li].x_shape,
-            workspace=wsb[li], stream=st_)))
-    for li in range(len(layers) - 1, -1, -1):
-        st, pd, dl = geo[li]
-        calls.append(("bwd_weight", li, lambda st_=None, li=li, st=st, pd=pd, dl=dl: api.twn_conv2d_bwd_ste(
-            X[li], dY[li], tws[li], st, pd, dl, need_dx=False, need_dw=True, dW=dW[li], workspace=wsw[li], stream=st_)))
-    dx_calls = [c for c in calls if c[0] == "bwd_data"]
-    dw_calls = [c for c in calls if c[0] == "bwd_weight"]
-    # default priority; the weight gradients of different layers are independent too, so they alternate between
-    # two streams: the reduction pass of one layer overlaps the main pass of the next
-    side_a, side_b, side_c = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-    n_dw_streams = int(os.environ.get("TWN_BENCH_DW_STREAMS", "2"))
+    # ------------------------------------------------------------------ headline: ResNet-18 b64 forward
+    def headline(with_cpu):
+        CFG = 2
+        layers = wl.resnet18(64)
+        W, X, Y, tws, calls = build_forward(layers, CFG)
+        tern = api.prepare_ternarize_batch(W, tws, F)
+        names = [L.name for L in layers]
+        i0, i1 = names.index(ROOFLINE_LAYERS[0]), names.index(ROOFLINE_LAYERS[-1])
+        assert tuple(names[i0:i1 + 1]) == ROOFLINE_LAYERS
+        flops_fwd = sum(L.flops for L in layers)
+        n_w = sum(L.n_weights for L in layers)
 
-    def backward():
-        cur = torch.cuda.current_stream()
-        fork = torch.cuda.Event()
-        fork.record(cur)
-        sides = [side_a, side_b] + ([side_c] if n_dw_streams > 1 else [])
-        for st_ in sides:
-            st_.wait_event(fork)
-        # interleave the launches layer by layer so no stream runs ahead of the host
-        for i in range(len(dw_calls)):
-            if i < len(dx_calls):
-                dx_calls[i][2](side_a)
-            dw_calls[i][2](side_c if (n_dw_streams > 1 and i % 2) else side_b)
-        for st_ in sides:
-            j = torch.cuda.Event()
-            j.record(st_)
-            cur.wait_event(j)
+        def one_step(marks=None):
+            tern()
+            for li, c in enumerate(calls):
+                if marks is not None and li == i0:
+                    marks[0].record()
+                c()
+                if marks is not None and li == i1:
+                    marks[1].record()
 
-    bwd_graph = None
-
-    def one_step(marks=None):
-        for ci in range(n_main):
-            if marks is not None and ci in marks:
-                marks[ci].record()
-            calls[ci][2]()
-        if marks is not None and n_main in marks:
-            marks[n_main].record()
-        if bwd_graph is not None:
-            bwd_graph.replay()
-        else:
-            backward()
-
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-
-    # The backward (27 launches on three streams) is captured once into a HIP graph and replayed in every step:
-    # the library only launches kernels and takes its workspaces from the caller, so it captures as is.  The
-    # forward stays eager because the roofline events sit between its launches.  Replays are checked against
-    # the eager results (bit for bit) before they are used.
-    def capture_backward():
-        outs_b = [t for t in dX[1:]] + list(dW)
-        ref_b = [t.clone() for t in outs_b]
-        cap = torch.cuda.Stream()
-        cap.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(cap):
-            backward()
-        torch.cuda.synchronize()
-        g_ = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g_, stream=cap):
-            backward()
-        torch.cuda.synchronize()
-        for _ in range(2):
-            for t in outs_b:
-                t.zero_()
-            calls[1][2]()                  # eager work between two replays
-            torch.cuda.synchronize()
-            g_.replay()
-            torch.cuda.synchronize()
-            if not all(torch.equal(a, b) for a, b in zip(ref_b, outs_b)):
-                return None
-        return g_
-
-    if not args.eager_backward:
-        try:
-            bwd_graph = capture_backward()
-        except RuntimeError as e:          # capture not available: the step runs eagerly
-            log("backward graph capture failed (%s): eager backward" % str(e).splitlines()[0])
-            bwd_graph = None
-            torch.cuda.synchronize()
-        if bwd_graph is None:
-            log("backward runs eagerly (no graph)")
         for _ in range(args.warmup):
             one_step()
         torch.cuda.synchronize()
+        mev = [(new_ev(), new_ev()) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            one_step(mev[s])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / args.steps
+        span_ms = sum(a.elapsed_time(b) for a, b in mev) / args.steps
+        value = flops_fwd / (ms_per_step * 1e-3) / 1e12
 
-    # Timed region.  HIP events on the launch stream (torch's current stream) bracket each forward call that is
-    # exactly one launch of the contraction kernel (the roofline sample: forward c2-c6, which run alone on
-    # the GPU); phases and the per-layer table are taken in separate passes afterwards.
-    name_of = [L.name for L in layers]
-    single = {("fwd", n) for n in ("c2", "c3", "c4", "c5", "c6")}
-    is_single = [(c[0], name_of[c[1]]) in single for c in calls]
+        # phases (separate pass): the ternarize call, then the forward
+        NPH = max(5, min(50, args.steps))
+        pev = [[new_ev() for _ in range(3)] for _ in range(NPH)]
+        for s in range(NPH):
+            pev[s][0].record()
+            tern()
+            pev[s][1].record()
+            for c in calls:
+                c()
+            pev[s][2].record()
+        torch.cuda.synchronize()
+        t_tern = sum(pev[s][0].elapsed_time(pev[s][1]) for s in range(NPH)) / NPH
+        t_fwd = sum(pev[s][1].elapsed_time(pev[s][2]) for s in range(NPH)) / NPH
+        log("resnet18 b64 step %.3f ms (ternarize %.3f + forward %.3f), %.0f img/s, %.1f TFLOP/s-eq" %
+            (ms_per_step, t_tern, t_fwd, 64 / (ms_per_step * 1e-3), value))
 
-    def new_ev():
-        return torch.cuda.Event(enable_timing=True)
-
-    # An event between two launches costs several microseconds of idle GPU, so the timed region records only
-    # two per step: before the first and after the last call of the run of consecutive single-launch calls.
-    first_single = min(ci for ci in range(n_main) if is_single[ci])
-    last_single = max(ci for ci in range(n_main) if is_single[ci])
-    assert all(is_single[ci] for ci in range(first_single, last_single + 1))
-    marks = [first_single, last_single + 1]
-    mev = [{ci: new_ev() for ci in marks} for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        one_step(mev[s])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    span_ms = sum(mev[s][first_single].elapsed_time(mev[s][last_single + 1]) for s in range(args.steps)) / args.steps
-    single_calls = list(range(first_single, last_single + 1))
-
-    # phase times: a second pass with one event pair per phase (the two backward streams form one phase)
-    phase_names = ["ternarize", "fwd", "bwd_two_streams"]
-    NPH = max(5, min(50, args.steps))
-    pev = [[new_ev() for _ in range(4)] for _ in range(NPH)]
-    for s in range(NPH):
-        pev[s][0].record()
-        calls[0][2]()
-        pev[s][1].record()
-        for ci in range(1, n_main):
-            calls[ci][2]()
-        pev[s][2].record()
-        if bwd_graph is not None:
-            bwd_graph.replay()
-        else:
-            backward()
-        pev[s][3].record()
-    torch.cuda.synchronize()
-    phase_ms = [sum(pev[s][i].elapsed_time(pev[s][i + 1]) for s in range(NPH)) / NPH for i in range(3)]
-    value = flops_step / (ms_per_step * 1e-3) / 1e12
-    log("step %.3f ms | " % ms_per_step + " | ".join("%s %.3f ms" % (phase_names[i], phase_ms[i]) for i in range(3)))
-
-    # per-layer detail: a second, untimed pass with events around every call
-    NP = 20
-    ev = [[(new_ev(), new_ev()) for _ in calls] for _ in range(NP)]
-    for s in range(NP):
-        for ci, (_, _, fn) in enumerate(calls):
-            ev[s][ci][0].record()
-            fn()
-            ev[s][ci][1].record()
-    torch.cuda.synchronize()
-    call_ms = [sum(ev[s][ci][0].elapsed_time(ev[s][ci][1]) for s in range(NP)) / NP for ci in range(len(calls))]
-    per = {(c[0], c[1]): call_ms[ci] for ci, c in enumerate(calls)}
-    for li, fn in enumerate(tern_single):
-        per[("ternarize", li)] = time_call(fn, reps=NP, warm=2)
-    log("%-6s %22s %9s %9s %9s %9s %9s %9s" % ("layer", "(M,N,K)", "tern us", "fwd us", "fwd TF/s", "dX TF/s", "dW us", "dW TF/s"))
-    for li, L in enumerate(layers):
-        tf, tdx, tdw = per[("fwd", li)], per.get(("bwd_data", li), float("nan")), per[("bwd_weight", li)]
-        log("%-6s %22s %9.1f %9.1f %9.1f %9.1f %9.1f %9.1f" % (L.name, str(L.gemm_mnk), per[("ternarize", li)] * 1e3,
-                                                             tf * 1e3, L.flops / tf / 1e9, L.flops / tdx / 1e9,
-                                                             tdw * 1e3, L.flops / tdw / 1e9))
-
-    # Roofline of the contraction kernel named by the task (gather_gemm_dma_kernel): the forward calls that
-    # consist of exactly ONE launch of it (no split-K finish, no first-layer copy, no odd-channel fallback)
-    # and run alone on the GPU: forward c2-c6.
-    def call_bytes(ph, L):
-        # algorithmic bytes of one call: bf16 activations in and out plus the 2-bit codes
-        x_b = 2 * L.N * L.H * L.W * L.C
-        y_b = 2 * L.N * L.P * L.Q * L.O
-        return x_b + y_b + L.n_weights // 4     # the same three tensors forward (X -> Y) and backward (dY -> dX)
-    sample_bytes = {ci: call_bytes(calls[ci][0], layers[calls[ci][1]]) for ci in single_calls}
-    r_flops = sum(layers[calls[ci][1]].flops for ci in single_calls)
-    r_ms = span_ms
-    gg_tflops = r_flops / (r_ms * 1e-3) / 1e12
-    roof = {"kernel": "gather_gemm_dma_kernel", "bound": "mfma", "achieved": round(gg_tflops, 2),
-            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gg_tflops / PEAK_BF16_TFLOPS, 4),
-            "traffic": ROOFLINE_SAMPLE_TRAFFIC_BYTES,
-            "algorithmic_bytes_per_launch": round(sum(sample_bytes.values()) / len(sample_bytes)),
-            "launches_per_step": len(single_calls), "avg_launch_us": round(r_ms * 1e3 / len(single_calls), 2),
-            "flops_per_launch_avg": round(r_flops / len(single_calls) / 1e9, 2),
-            "calls": "fwd c2-c6 (one launch each)"}
-    # serial per-layer times of the detail pass give the per-phase rates of the two backward parts
-    dx_ms = sum(per[("bwd_data", li)] for li in range(1, len(layers)))
-    dw_ms = sum(per[("bwd_weight", li)] for li in range(len(layers)))
-    extras = {"phase_ms": {phase_names[i]: round(phase_ms[i], 4) for i in range(3)},
-              "fwd_tflops": round(flops_fwd / (phase_ms[1] * 1e-3) / 1e12, 2),
-              "bwd_tflops": round((flops_dx + flops_dw) / (phase_ms[2] * 1e-3) / 1e12, 2),
-              "bwd_data_serial_ms": round(dx_ms, 4), "bwd_weight_serial_ms": round(dw_ms, 4),
-              "ternarize_layers_GBps": round(tern_bytes / (phase_ms[0] * 1e-3) / 1e9, 1),
-              "backward_launch": "hip_graph_replay" if bwd_graph is not None else "eager"}
-
-    if args.graph:
-        # the same step captured once into a HIP graph and replayed (the library only launches kernels and takes
-        # its workspaces from the caller, so a step captures as is); outputs are compared with the eager step's
-        outs = (Y[1], Y[7], dX[1], dW[1], dW[5], dW[7])
-
-        def full_step():
-            for ci in range(n_main):
-                calls[ci][2]()
-            backward()
-
-        full_step()
+        # the same step replayed from a HIP graph (no host launch cost); outputs compared with the eager step's
+        graph_info = None
+        outs = [Y[0], Y[i0], Y[-1], tws[0].packed, tws[5].alpha]
+        one_step()
         torch.cuda.synchronize()
         ref = [t.clone() for t in outs]
-        cap = torch.cuda.Stream()
-        cap.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(cap):
-            full_step()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=cap):
-            full_step()
-        torch.cuda.synchronize()
-        same = True
-        for _ in range(3):
-            for t in outs:
-                t.fill_(0.0)
-            torch.cuda.synchronize()
-            graph.replay()
-            torch.cuda.synchronize()
-            same = same and all(torch.equal(a, b) for a, b in zip(ref, outs))
-        for _ in range(args.warmup):
-            graph.replay()
-        torch.cuda.synchronize()
-        g0 = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        g_ms = (time.perf_counter() - g0) * 1e3 / args.steps
-        log("graph replay: %.3f ms per step (eager %.3f), outputs identical to eager: %s" % (g_ms, ms_per_step, same))
-        extras["graph_replay"] = {"ms_per_step": round(g_ms, 4), "outputs_identical_to_eager": bool(same)}
+        g_ = graph_of(one_step)
+        if g_ is not None:
+            same = True
+            for rep in range(3):
+                for t in outs:
+                    t.zero_()
+                if rep == 1:
+                    calls[1]()                 # eager work between two replays
+                torch.cuda.synchronize()
+                g_.replay()
+                torch.cuda.synchronize()
+                same = same and all(torch.equal(a, b) for a, b in zip(ref, outs))
+            t_g = time_call(g_.replay, reps=args.steps, warm=args.warmup)
+            log("graph replay: %.3f ms per step (eager %.3f), outputs identical to eager: %s" % (t_g, ms_per_step, same))
+            graph_info = {"ms_per_step": round(t_g, 4), "outputs_identical_to_eager": bool(same),
+                          "img_per_s": round(64 / (t_g * 1e-3), 1)}
 
-    if not args.no_extras:
-        del X, dY, Y, dX, dW
+        tot, rows = per_layer_table("resnet18", layers, calls)
+        log("resnet18 b64 forward, sum of per-layer times: %.3f ms" % tot)
+
+        Ls = layers[i0]
+        n_launch = i1 - i0 + 1
+        r_tf = sum(layers[i].flops for i in range(i0, i1 + 1)) / (span_ms * 1e-3) / 1e12
+        roof = roof_obj("conv_stream_kernel (layer1 3x3 convolutions, 64 -> 64 channels, 56x56)", "mfma", r_tf,
+                        PEAK_BF16_TFLOPS, "TFLOP/s", layer_bytes(Ls), "resnet18_b64_forward_kernels.txt",
+                        span_ms * 1e3 / n_launch, launches_per_step=n_launch, flops_per_launch=Ls.flops,
+                        calls="fwd " + " ".join(ROOFLINE_LAYERS) + " (one launch each)",
+                        hbm_bound_us=round(layer_bytes(Ls) / PEAK_HBM_GBPS / 1e3, 2))
+        cpu = None
+        if with_cpu:
+            from oracle import conv as oc
+            from oracle import ternarize as ot
+            oc.build()
+            cores = oc.max_threads()
+            nb = args.cpu_batch
+            t_t = t_c = 0.0
+            for li, L in enumerate(layers):
+                w = wl.kaiming_weights(CFG, li, L)
+                a = time.perf_counter()
+                codes, delta, alpha, nnz = ot.ternarize(w, F)
+                t_t += time.perf_counter() - a
+                Lb = L.with_batch(nb)
+                x = wl.bf16_round(wl.normal(CFG, wl.IDX_INPUT + li, Lb.x_shape))
+                a = time.perf_counter()
+                oc.conv2d_fwd(x, codes, alpha, *geo(L))
+                t_c += time.perf_counter() - a
+            t_full = t_t + t_c * (64.0 / nb)
+            cpu = {"value": round(flops_fwd / t_full / 1e12, 6), "unit": "TFLOP/s-eq", "cores": cores, "kind": "oracle",
+                   "img_per_s": round(64 / t_full, 3),
+                   "sample": "ternarize of all 21 ResNet-18 tensors in full (%.2f s, numpy sort, 1 thread) + forward of every "
+                             "layer at batch %d of 64 (%.2f s, C direct loops, %d OpenMP threads), conv time scaled linearly "
+                             "to batch 64" % (t_t, nb, t_c, cores)}
+            log("cpu oracle: ternarize %.2f s, conv(b%d) %.2f s -> %.5f TFLOP/s-eq" % (t_t, nb, t_c, cpu["value"]))
+        info = {"ms_per_step": ms_per_step, "value": value, "roof": roof, "cpu": cpu, "graph": graph_info,
+                "phase_ms": {"ternarize": round(t_tern, 4), "forward": round(t_fwd, 4)},
+                "forward_only": {"ms": round(t_fwd, 4), "tflops": round(flops_fwd / t_fwd / 1e9, 1),
+                                 "frac_mfma_peak": round(flops_fwd / t_fwd / 1e9 / PEAK_BF16_TFLOPS, 4),
+                                 "img_per_s": round(64 / (t_fwd * 1e-3), 1)},
+                "per_layer_us": {n: round(t * 1e3, 1) for n, t in rows}, "per_layer_sum_ms": round(tot, 4),
+                "ternarize_layers_GBps": round(n_w * 8.25 / (t_tern * 1e-3) / 1e9, 1),
+                "gflop": flops_fwd / 1e9, "layers": len(layers)}
+        return info
+
+    sides = {"gemm": side_gemm, "ternarize": lambda: side_ternarize(calibrate=True), "lenet": side_lenet,
+             "vgg7": side_vgg7, "vgg16_ssd": side_vgg16, "resnet18_bwd": side_resnet18_bwd, "per_filter": side_per_filter}
+    if args.only and args.only != "resnet18":
+        print(json.dumps({"only": args.only, **sides[args.only]()}), flush=True)
+        return
+
+    h = headline(with_cpu=not args.no_cpu and not args.only)
+    extras = {"phase_ms": h["phase_ms"], "forward_only": h["forward_only"], "per_layer_us": h["per_layer_us"],
+              "per_layer_sum_ms": h["per_layer_sum_ms"], "graph_replay": h["graph"],
+              "ternarize_21_tensors_GBps": h["ternarize_layers_GBps"]}
+    rooflines = [h["roof"]]
+    if not args.no_extras and not args.only:
         torch.cuda.empty_cache()
-        extras["gemm_8192x4096x4096"] = side_gemm()
-        extras["ternarize_2p28"] = side_ternarize()
-        extras["resnet18_b64_fwd"] = side_resnet18()
-
-    cpu = None
-    if not args.no_cpu:
-        from oracle import conv as oc
-        from oracle import ternarize as ot
-        oc.build()
-        cores = oc.max_threads()
-        nb = args.cpu_batch
-        t_tern = 0.0
-        t_conv = 0.0
-        for li, L in enumerate(layers):
-            w = wl.kaiming_weights(CFG, li, L)
-            a = time.perf_counter()
-            codes, delta, alpha, nnz = ot.ternarize(w, F)
-            t_tern += time.perf_counter() - a
-            Ls = L.with_batch(nb)
-            x = wl.bf16_round(wl.normal(CFG, wl.IDX_INPUT + li, Ls.x_shape))
-            dy = wl.bf16_round(wl.normal(CFG, wl.IDX_DY + 10 * li, Ls.y_shape))
-            st, pd, dl = geo[li]
-            a = time.perf_counter()
-            oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
-            if li:
-                oc.conv2d_bwd_data(dy, codes, alpha, Ls.x_shape, st, pd, dl)
-            oc.conv2d_bwd_weight(x, dy, Ls.w_shape, st, pd, dl)
-            t_conv += time.perf_counter() - a
-        t_full = t_tern + t_conv * (128.0 / nb)
-        cpu = {"value": round(flops_step / t_full / 1e12, 6), "unit": "TFLOP/s-eq", "cores": cores, "kind": "oracle",
-               "sample": "ternarize of all 8 VGG-7 tensors in full (%.2f s, numpy sort, 1 thread) + fwd/dX/dW of every layer "
-                         "at batch %d of 128 (%.2f s, C direct loops, %d OpenMP threads)%s"
-                         % (t_tern, nb, t_conv, cores, "" if nb == 128 else ", conv time scaled linearly to batch 128")}
-        log("cpu oracle: ternarize %.2f s, conv(b%d) %.2f s -> %.5f TFLOP/s-eq" % (t_tern, nb, t_conv, cpu["value"]))
+        rooflines.append(side_gemm())
+        rooflines.append(side_ternarize())
+        for name in ("lenet", "vgg7", "vgg16_ssd", "resnet18_bwd", "per_filter"):
+            torch.cuda.empty_cache()
+            extras[name] = sides[name]()
 
     out = {
-        "metric": "ternary conv/GEMM throughput, dense-equivalent (2MNK per contraction; ternarize + fwd + STE bwd per step)",
-        "value": round(value, 3), "unit": "TFLOP/s-eq", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "metric": "ternary conv/GEMM throughput, dense-equivalent TFLOP/s (2MNK per contraction) and fraction of bf16 MFMA "
+                  "peak; ternarize GB/s; ResNet-18 img/s",
+        "value": round(h["value"], 1), "unit": "TFLOP/s-eq", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(h["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "vgg7_cifar_b128_twn_step", "layers": len(layers), "batch": 128, "delta_factor": F,
-                   "gflop_per_step": round(flops_step / 1e9, 1), "img_per_s": round(128 / (ms_per_step * 1e-3), 1)},
-        "roofline": roof,
-        "cpu_baseline": cpu,
+        "config": {"workload": "resnet18_b64_bf16_twn_forward", "layers": h["layers"], "batch": 64, "delta_factor": F,
+                   "step": "twn_ternarize_batch of all 21 weight tensors + forward of all 21 conv/FC layers",
+                   "gflop_per_step": round(h["gflop"], 1), "img_per_s": round(64 / (h["ms_per_step"] * 1e-3), 1),
+                   "frac_mfma_peak": round(h["value"] / PEAK_BF16_TFLOPS, 4)},
+        "roofline": h["roof"],
+        "rooflines": rooflines,
+        "cpu_baseline": h["cpu"],
         "extras": extras,
     }
     print(json.dumps(out), flush=True)

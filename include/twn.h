@@ -189,7 +189,11 @@ int32_t twn_unpack_i8(const uint32_t* packed, int32_t rows, int64_t K, int8_t* c
  * X: [M][ldx] of x_dtype; `weights`: packed twn2 [N][words_per_row(K)]
  * (for TWN_VAR_I8_STORED_POSTSCALE: int8 [N][K]); alpha: float32[alpha_groups];
  * ep may be NULL; Y: [M][ldy] of y_dtype.  bf16 variants need x_dtype = BF16,
- * X 16-byte aligned and ldx % 8 == 0; TWN_VAR_FP32 needs x_dtype = F32. */
+ * X 16-byte aligned and ldx % 8 == 0; TWN_VAR_FP32 needs x_dtype = F32.
+ * Alignment of the outputs (all entry points of section 2): when the channel
+ * count N and ldy are multiples of 8, Y (dX) and ep->residual must be 16-byte
+ * aligned (rows are written with 16-byte stores); otherwise aligned to their
+ * element size.  Violations return TWN_ERR_ALIGN before anything is launched. */
 size_t  twn_gemm_fwd_workspace_bytes(const twn_gemm_desc* d);
 int32_t twn_gemm_fwd(const twn_gemm_desc* d, const void* X, const void* weights,
                      const float* alpha, const twn_epilogue* ep, void* Y,

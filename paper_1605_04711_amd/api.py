@@ -139,8 +139,19 @@ def _dtype_code(t):
     raise TypeError("only float32 and bfloat16 tensors are accepted")
 
 
-def _workspace(nbytes, device):
-    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+def _workspace(nbytes, device, stream=None):
+    """Scratch tensor for one call.  Allocated under the stream the kernels are enqueued on, so that the
+    caching allocator cannot hand the block to later work of another stream while they still use it."""
+    if stream is None:
+        return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def _need_contiguous(**tensors):
+    for name, t in tensors.items():
+        if t is not None and not t.is_contiguous():
+            raise TypeError("%s must be contiguous (activations are read as dense NHWC)" % name)
 
 
 def twn_packed_words_per_row(k):
@@ -200,7 +211,7 @@ def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, wor
                              torch.empty(groups, dtype=torch.float32, device=dev),
                              torch.empty(groups, dtype=torch.int64, device=dev))
     if workspace is None:
-        workspace = _workspace(L.twn_ternarize_workspace_bytes(ctypes.byref(wd), groups), dev)
+        workspace = _workspace(L.twn_ternarize_workspace_bytes(ctypes.byref(wd), groups), dev, stream)
     rc = L.twn_ternarize(_ptr(W), ctypes.byref(wd), groups, ctypes.c_float(delta_factor),
                          _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha), _ptr(out.nnz),
                          _ptr(workspace), workspace.numel(), _stream(stream))
@@ -247,7 +258,7 @@ def twn_ternarize_batch(Ws, delta_factor=0.7, transposed=False, out=None, worksp
         items[i] = TernarizeItem(_ptr(W), WeightDesc(rows, c, r, s), _ptr(o.packed), _ptr(o.packed_T), _ptr(o.delta),
                                  _ptr(o.alpha), _ptr(o.nnz))
     if workspace is None:
-        workspace = _workspace(L.twn_ternarize_batch_workspace_bytes(len(Ws)), dev)
+        workspace = _workspace(L.twn_ternarize_batch_workspace_bytes(len(Ws)), dev, stream)
     rc = L.twn_ternarize_batch(items, len(Ws), ctypes.c_float(delta_factor), _ptr(workspace), workspace.numel(),
                                _stream(stream))
     _check(rc, "twn_ternarize_batch")
@@ -289,7 +300,7 @@ def twn_gemm_fwd(X, tw, y_dtype=torch.bfloat16, variant=None, scale=None, shift=
     L = lib()
     if workspace is None:
         need = L.twn_gemm_fwd_workspace_bytes(ctypes.byref(d))
-        workspace = _workspace(need, X.device) if need else None
+        workspace = _workspace(need, X.device, stream) if need else None
     rc = L.twn_gemm_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.weights_for(variant)), _ptr(tw.alpha),
                         None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
                         0 if workspace is None else workspace.numel(), _stream(stream))
@@ -324,6 +335,7 @@ def twn_conv2d_fwd_workspace_bytes(x_shape, tw, stride=(1, 1), pad=(0, 0), dil=(
 def twn_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), y_dtype=torch.bfloat16, variant=None,
                    scale=None, shift=None, residual=None, relu=False, out=None, workspace=None, stream=None):
     """X NHWC; returns Y NHWC [N][P][Q][O]."""
+    _need_contiguous(X=X, out=out, residual=residual)
     if variant is None:
         variant = TWN_VAR_FP32 if X.dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
     Y = out if out is not None else torch.empty(conv_out_shape(X.shape, tw, stride, pad, dil), dtype=y_dtype,
@@ -333,7 +345,7 @@ def twn_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), y_dtype=torch.b
     L = lib()
     if workspace is None:
         need = L.twn_conv2d_fwd_workspace_bytes(ctypes.byref(d))
-        workspace = _workspace(need, X.device) if need else None
+        workspace = _workspace(need, X.device, stream) if need else None
     rc = L.twn_conv2d_fwd(ctypes.byref(d), _ptr(X), _ptr(tw.weights_for(variant)), _ptr(tw.alpha),
                           None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
                           0 if workspace is None else workspace.numel(), _stream(stream))
@@ -352,6 +364,7 @@ def twn_conv2d_bwd_ste(X, dY, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), need_dx
     """Returns (dX or None, dW float32 [O][C][R][S] or None, dbias or None)."""
     xs = tuple(X.shape) if X is not None else tuple(x_shape)
     dev = dY.device
+    _need_contiguous(X=X, dY=dY, dX=dX, dW=dW)
     if need_dx and dX is None:
         dX = torch.empty(xs, dtype=dx_dtype, device=dev)
     if need_dw and dW is None:
@@ -360,10 +373,115 @@ def twn_conv2d_bwd_ste(X, dY, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), need_dx
     d = _conv_desc(xs, tw, stride, pad, dil, TWN_BF16, _dtype_code(dX) if need_dx else TWN_BF16, variant)
     L = lib()
     if workspace is None:
-        workspace = _workspace(L.twn_conv2d_bwd_ste_workspace_bytes(ctypes.byref(d)), dev)
+        workspace = _workspace(L.twn_conv2d_bwd_ste_workspace_bytes(ctypes.byref(d)), dev, stream)
     rc = L.twn_conv2d_bwd_ste(ctypes.byref(d), _ptr(X), _ptr(dY), _ptr(tw.packed_T), _ptr(tw.alpha),
                               _ptr(dX) if need_dx else None, _ptr(dW) if need_dw else None, _ptr(dbias),
                               ctypes.c_float(1.0 if accumulate else 0.0), _ptr(workspace), workspace.numel(),
                               _stream(stream))
     _check(rc, "twn_conv2d_bwd_ste")
     return (dX if need_dx else None), (dW if need_dw else None), dbias
+
+
+# ---- prepared calls ---------------------------------------------------------------------------------------
+# The functions above marshal their arguments on every call (descriptor structs, output shapes, workspace
+# queries): several microseconds of host time per call, which shows once a network's layers take ten
+# microseconds each.  A prepared call marshals once and returns a function that only makes the C call; the
+# tensors it was prepared with are kept alive by the closure.  `stream=None` means torch's current stream at
+# call time.
+
+def prepare_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), out=None, variant=None, scale=None, shift=None,
+                       residual=None, relu=False, workspace=None):
+    if variant is None:
+        variant = TWN_VAR_FP32 if X.dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
+    if not X.is_contiguous() or (out is not None and not out.is_contiguous()):
+        raise TypeError("X and out must be contiguous NHWC tensors")
+    Y = out if out is not None else torch.empty(conv_out_shape(X.shape, tw, stride, pad, dil), dtype=X.dtype,
+                                                device=X.device)
+    d = _conv_desc(X.shape, tw, stride, pad, dil, _dtype_code(X), _dtype_code(Y), variant)
+    ep = _epilogue(scale, shift, residual, relu)
+    L = lib()
+    if workspace is None:
+        need = L.twn_conv2d_fwd_workspace_bytes(ctypes.byref(d))
+        workspace = _workspace(need, X.device) if need else None
+    fn = L.twn_conv2d_fwd
+    args = (ctypes.byref(d), _ptr(X), _ptr(tw.weights_for(variant)), _ptr(tw.alpha),
+            None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
+            0 if workspace is None else workspace.numel())
+    keep = (d, ep, X, Y, tw, scale, shift, residual, workspace)
+
+    def call(stream=None, _keep=keep):
+        rc = fn(*args, _stream(stream))
+        if rc != 0:
+            raise TwnError(rc, "twn_conv2d_fwd")
+        return Y
+    return call
+
+
+def prepare_gemm_fwd(X, tw, out=None, y_dtype=torch.bfloat16, variant=None, scale=None, shift=None, residual=None,
+                     relu=False, workspace=None):
+    m, k = X.shape
+    if k != tw.K:
+        raise ValueError("K mismatch")
+    if variant is None:
+        variant = TWN_VAR_FP32 if X.dtype == torch.float32 else TWN_VAR_BF16_POSTSCALE
+    Y = out if out is not None else torch.empty((m, tw.rows), dtype=y_dtype, device=X.device)
+    d = GemmDesc(m, tw.rows, k, _dtype_code(X), _dtype_code(Y), variant, X.stride(0), Y.stride(0), tw.groups)
+    ep = _epilogue(scale, shift, residual, relu)
+    L = lib()
+    if workspace is None:
+        need = L.twn_gemm_fwd_workspace_bytes(ctypes.byref(d))
+        workspace = _workspace(need, X.device) if need else None
+    fn = L.twn_gemm_fwd
+    args = (ctypes.byref(d), _ptr(X), _ptr(tw.weights_for(variant)), _ptr(tw.alpha),
+            None if ep is None else ctypes.byref(ep), _ptr(Y), _ptr(workspace),
+            0 if workspace is None else workspace.numel())
+    keep = (d, ep, X, Y, tw, scale, shift, residual, workspace)
+
+    def call(stream=None, _keep=keep):
+        rc = fn(*args, _stream(stream))
+        if rc != 0:
+            raise TwnError(rc, "twn_gemm_fwd")
+        return Y
+    return call
+
+
+def prepare_conv2d_bwd_ste(X, dY, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), dX=None, dW=None, dbias=None,
+                           accumulate=False, workspace=None, x_shape=None, variant=TWN_VAR_BF16_POSTSCALE):
+    """dX / dW / dbias: the output tensors of the parts wanted (None skips a part)."""
+    xs = tuple(X.shape) if X is not None else tuple(x_shape)
+    d = _conv_desc(xs, tw, stride, pad, dil, TWN_BF16, _dtype_code(dX) if dX is not None else TWN_BF16, variant)
+    L = lib()
+    if workspace is None:
+        workspace = _workspace(L.twn_conv2d_bwd_ste_workspace_bytes(ctypes.byref(d)), dY.device)
+    fn = L.twn_conv2d_bwd_ste
+    args = (ctypes.byref(d), _ptr(X), _ptr(dY), _ptr(tw.packed_T), _ptr(tw.alpha), _ptr(dX), _ptr(dW), _ptr(dbias),
+            ctypes.c_float(1.0 if accumulate else 0.0), _ptr(workspace), workspace.numel())
+    keep = (d, X, dY, tw, dX, dW, dbias, workspace)
+
+    def call(stream=None, _keep=keep):
+        rc = fn(*args, _stream(stream))
+        if rc != 0:
+            raise TwnError(rc, "twn_conv2d_bwd_ste")
+    return call
+
+
+def prepare_ternarize_batch(Ws, out, delta_factor=0.7, workspace=None):
+    L = lib()
+    items = (TernarizeItem * len(Ws))()
+    for i, (W, o) in enumerate(zip(Ws, out)):
+        if not W.is_contiguous() or W.dtype != torch.float32 or not W.is_cuda:
+            raise TypeError("every W must be a contiguous float32 CUDA tensor")
+        items[i] = TernarizeItem(_ptr(W), WeightDesc(o.rows, o.C, o.R, o.S), _ptr(o.packed), _ptr(o.packed_T),
+                                 _ptr(o.delta), _ptr(o.alpha), _ptr(o.nnz))
+    if workspace is None:
+        workspace = _workspace(L.twn_ternarize_batch_workspace_bytes(len(Ws)), Ws[0].device)
+    fn = L.twn_ternarize_batch
+    args = (items, len(Ws), ctypes.c_float(delta_factor), _ptr(workspace), workspace.numel())
+    keep = (items, list(Ws), list(out), workspace)
+
+    def call(stream=None, _keep=keep):
+        rc = fn(*args, _stream(stream))
+        if rc != 0:
+            raise TwnError(rc, "twn_ternarize_batch")
+        return out
+    return call

@@ -44,6 +44,16 @@ int32_t check_variant(int32_t variant, int32_t x_dtype) {
     }
 }
 
+// Output / residual alignment: rows whose channel count and leading dimension are multiples of 8 are written
+// with 16-byte stores (and the residual read with 8-byte loads); other shapes are accessed element by element.
+int32_t check_out_align(int32_t y_dtype, int64_t NC, int64_t ldy, const void* Y, const void* residual) {
+    const size_t elem = (y_dtype == TWN_F32) ? 4 : 2;
+    const bool vec = (NC % 8 == 0) && (ldy % 8 == 0);
+    if (!aligned(Y, vec ? 16 : elem)) return TWN_ERR_ALIGN;
+    if (residual && !aligned(residual, vec ? 16 : elem)) return TWN_ERR_ALIGN;
+    return TWN_OK;
+}
+
 void set_epilogue(GatherGemm& g, const twn_epilogue* ep) {
     g.scale = ep ? ep->scale : nullptr;
     g.shift = ep ? ep->shift : nullptr;
@@ -299,6 +309,8 @@ extern "C" int32_t twn_gemm_fwd(const twn_gemm_desc* d, const void* X, const voi
     if (d->x_dtype == TWN_BF16 && !aligned(X, 2)) return TWN_ERR_ALIGN;
     if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
     if (d->x_dtype == TWN_BF16 && d->K % 8 == 0 && ldx % 8 == 0 && !aligned(X, 16)) return TWN_ERR_ALIGN;
+    rc = check_out_align(d->y_dtype, d->N, ldy, Y, ep ? ep->residual : nullptr);
+    if (rc != TWN_OK) return rc;
 
     GatherGemm g{};
     g.X = X;
@@ -337,6 +349,8 @@ extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const v
     if (!aligned(weights, 16)) return TWN_ERR_ALIGN;
     if (d->x_dtype == TWN_BF16 && !aligned(X, (d->C % 8 == 0) ? 16 : 2)) return TWN_ERR_ALIGN;
     if (d->x_dtype == TWN_F32 && !aligned(X, 4)) return TWN_ERR_ALIGN;
+    rc = check_out_align(d->y_dtype, d->O, d->O, Y, ep ? ep->residual : nullptr);
+    if (rc != TWN_OK) return rc;
 
     GatherGemm g{};
     g.X = X;
@@ -398,6 +412,10 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
     if (X && !aligned(X, (d->C % 8 == 0) ? 16 : 2)) return TWN_ERR_ALIGN;
     if (packed_T && !aligned(packed_T, 16)) return TWN_ERR_ALIGN;
     if (dW && !aligned(dW, 4)) return TWN_ERR_ALIGN;
+    if (dX) {
+        rc = check_out_align(d->y_dtype, d->C, d->C, dX, nullptr);
+        if (rc != TWN_OK) return rc;
+    }
     if (dW || dbias) {
         const size_t need = weight_grad_bytes(d, P, Q);
         if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return TWN_ERR_WORKSPACE;

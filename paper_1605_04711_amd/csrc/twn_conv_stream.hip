@@ -56,35 +56,43 @@ struct StreamArgs {
     int32_t KT;                 // K / 64
 };
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, int OCC, bool DEEP>
-__global__ __launch_bounds__(64 * WM * WN, OCC)
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, int OCC, int KS>
+__global__ __launch_bounds__(64 * WM * WN * KS, OCC)
 void conv_stream_kernel(const StreamArgs a) {
-    constexpr int NW = WM * WN;                    // waves per workgroup
+    // KS > 1: the workgroup holds KS groups of WM*WN waves.  All groups work on the SAME output tile; group kg
+    // takes the K slabs kg, kg+KS, kg+2KS, ... (it stages and multiplies them on its own, in its own part of
+    // every stage), and the partial tiles are summed through LDS in a fixed order before the epilogue.  This
+    // multiplies the waves per CU for layers with too few tiles to fill the chip (few pixels, deep K).
+    constexpr int NWG = WM * WN;                   // waves per K group
+    constexpr int NW = NWG * KS;                   // waves per workgroup
     constexpr int NT = 64 * NW;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
-    constexpr int NLOAD = BM / (8 * NW);           // 1 KB (8 rows) per wave-level load
+    constexpr int NLOAD = BM / (8 * NWG);          // 1 KB (8 rows) per wave-level load
     constexpr int A_BYTES = BM * 128;
     constexpr int B_BYTES = BN * 16;
-    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    // slabs in flight ahead of the one being multiplied.  DEEP: activation fragments are read from LDS three MFMA
-    // steps ahead, so a stage is read for the last time in step 0 of its slab and can be refilled for the
-    // rest of that slab: all STAGES stages carry loads, and a load has two slab times to land
-    constexpr int PD = DEEP ? STAGES : STAGES - 1;
+    constexpr int SUB_BYTES = A_BYTES + B_BYTES;   // one slab of one K group
+    constexpr int STAGE_BYTES = KS * SUB_BYTES;
+    constexpr int PD = STAGES - 1;                 // slabs in flight ahead of the one being multiplied
     constexpr int PER_STAGE = NLOAD + 1;           // vector-memory loads per wave per slab
     constexpr int EPI_CH = TN < 64 ? TN : 64;      // channels staged at a time
     constexpr int EPI_ROW = EPI_CH * 2 + 16;       // bytes per staged pixel row (pad keeps 16-byte reads conflict-free)
     constexpr int EPI_NI = EPI_CH / 32;
     constexpr int EPI_WAVE = 32 * EPI_ROW;         // one block of 32 pixel rows per wave
-    static_assert(BM % (8 * NW) == 0 && BN % 64 == 0 && BN <= 64 * NW && TN % 32 == 0 && TM % 32 == 0, "tile shape");
-    static_assert(NW % 2 == 0, "the swizzle of the staged rows assumes an even number of waves");
+    static_assert(BM % (8 * NWG) == 0 && BN % 64 == 0 && BN <= 64 * NWG && TN % 32 == 0 && TM % 32 == 0, "tile shape");
+    static_assert(NWG % 2 == 0, "the swizzle of the staged rows assumes an even number of waves");
     static_assert(STAGES >= 3, "the mid-slab hand-over needs two slabs in flight");
-    static_assert(NW * EPI_WAVE <= STAGE_BYTES, "epilogue staging must fit in one pipeline stage");
+    static_assert(NWG * EPI_WAVE <= STAGE_BYTES, "epilogue staging must fit in one pipeline stage");
+    static_assert(KS == 1 || KS == 2 || KS == 4, "K groups");
+    // partial tiles of a K group pass through the free stage RED_MI row blocks (of 32 pixels) at a time
+    constexpr int RED_MI_FIT = STAGE_BYTES / (NWG * NI * 4096);
+    constexpr int RED_MI = RED_MI_FIT < MI ? RED_MI_FIT : MI;
+    static_assert(KS == 1 || (RED_MI >= 1 && MI % RED_MI == 0), "the reduction must fit in the free stage");
     // Column parameters of a tile: a region of their own behind the stages (double-buffered, no extra barrier),
     // unless that region would cost a resident workgroup; then they share the free stage with the staging
     // rows, at the price of a second barrier per tile.
     constexpr bool COL_IN_STAGE = (STAGES * STAGE_BYTES + 4 * BN * 4) * OCC > 160 * 1024;
-    static_assert(!COL_IN_STAGE || NW * EPI_WAVE + 2 * BN * 4 <= STAGE_BYTES, "column parameters must fit in the free stage");
+    static_assert(!COL_IN_STAGE || NWG * EPI_WAVE + 2 * BN * 4 <= STAGE_BYTES, "column parameters must fit in the free stage");
     static_assert(BN <= NT, "one thread per column loads the column parameters");
     static_assert(MI <= 8 && NI <= 4, "fragment reads use immediate offsets");
 
@@ -99,7 +107,8 @@ void conv_stream_kernel(const StreamArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
+    const int kg = wave / NWG, wv = wave % NWG;    // K group, wave inside the group
+    const int wm = wv / WN, wn = wv % WN;
     const int lrow = lane & 31, lh = lane >> 5;
 
     // ---- this workgroup's tiles ------------------------------------------------------------------
@@ -116,15 +125,16 @@ void conv_stream_kernel(const StreamArgs a) {
     const uint32_t n_my = (count_x - j + gx - 1) / gx;
     auto tile_id = [&](uint32_t i) __attribute__((always_inline)) -> uint32_t { return start_x + j + i * gx; };
 
-    const int KT = a.KT;
+    const int KT = a.KT;                           // 64-wide slabs of K
+    const int KTS = (KT + KS - 1) / KS;            // slabs per K group (the last one of a group may be empty)
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(g.X, a.x_bytes), rw = make_rsrc(g.Wq, a.w_bytes);
 
     // ---- per-lane load state of the tile the load stream is in ----------------------------------------
-    // wave-level load i covers rows (i*NW + wave)*8 .. +7 of the tile; LDS row r keeps logical 16-byte chunk
+    // wave-level load i covers rows (i*NWG + wv)*8 .. +7 of the tile; LDS row r keeps logical 16-byte chunk
     // c at position c ^ ((r >> 1) & 7) (conflict-free ds_read_b128 with 64 banks); the swizzle is applied by
     // choosing which chunk of the row this lane fetches.
-    const int kc = (lane & 7) ^ ((wave & 1) * 4 + ((lane >> 4) & 3));
-    const int brow = (wave * 64) % BN + lane;               // column whose codes this lane stages
+    const int kc = (lane & 7) ^ ((wv & 1) * 4 + ((lane >> 4) & 3));
+    const int brow = (wv * 64) % BN + lane;                 // column whose codes this lane stages
     uint32_t voffA[NLOAD];      // GEMM: byte offset of the row; convolution: byte offset of tap (0,0) (any sign, wraps)
     int ih0[NLOAD], iw0[NLOAD];
     uint32_t voffB;
@@ -136,7 +146,7 @@ void conv_stream_kernel(const StreamArgs a) {
         voffB = (valid && ncol < static_cast<uint32_t>(g.NC)) ? ncol * static_cast<uint32_t>(g.wpr) * 4u : kBufOutside;
 #pragma unroll
         for (int i = 0; i < NLOAD; ++i) {
-            const uint32_t m = m0 + static_cast<uint32_t>((i * NW + wave) * 8 + (lane >> 3));
+            const uint32_t m = m0 + static_cast<uint32_t>((i * NWG + wv) * 8 + (lane >> 3));
             // computed unconditionally and selected afterwards (no memory is touched here)
             const bool rv = valid && m < static_cast<uint32_t>(g.M);
             uint32_t vo;
@@ -164,18 +174,35 @@ void conv_stream_kernel(const StreamArgs a) {
 
     // ---- the load stream: (tile lt, slab lk), wave-uniform ----------------------------------------------
     uint32_t lt = 0;
-    int lk = 0;
+    int lk = 0;                         // slab of this K group inside the tile: K slab lk*KS + kg
     int nc0 = 0, nss = 0, nrr = 0;      // convolution: channel base and tap of the slab to issue next
+    // carries of the (channel base, tap column, tap row) counter; at most KS of them per advance
+    auto tap_normalize = [&]() __attribute__((always_inline)) {
+        while (nc0 >= g.IC) {
+            nc0 -= g.IC;
+            if (++nss == g.S) {
+                nss = 0;
+                ++nrr;
+            }
+        }
+    };
+    auto tap_reset = [&]() __attribute__((always_inline)) {
+        nc0 = 64 * kg;
+        nss = nrr = 0;
+        if (KS > 1) tap_normalize();
+    };
     const int32_t strR = g.dh * g.IW * static_cast<int>(g.xs) * 2, strS = g.dw * static_cast<int>(g.xs) * 2;
     struct {
         unsigned char* sbase;
+        bool in_k;                      // KS > 1: false for the empty last slab of a group (every lane reads zeros)
         uint32_t soff;                  // slab index inside the tile
         int32_t delta_b;                // convolution: byte offset of this slab's tap and channel base
         int dth, dtw;
     } si;
     auto issue_setup = [&](int stage) __attribute__((always_inline)) {
-        si.sbase = smem + stage * STAGE_BYTES;
-        si.soff = static_cast<uint32_t>(lk);
+        si.sbase = smem + stage * STAGE_BYTES + kg * SUB_BYTES;
+        si.soff = static_cast<uint32_t>(lk * KS + kg);
+        si.in_k = (KS == 1) || (lk * KS + kg < KT);
         if (!GEMM) {
             si.delta_b = nrr * strR + nss * strS + nc0 * 2;
             si.dth = nrr * g.dh;
@@ -185,14 +212,14 @@ void conv_stream_kernel(const StreamArgs a) {
     auto issue_load = [&](auto i_tag) __attribute__((always_inline)) {
         constexpr int i = decltype(i_tag)::value;
         if constexpr (i == NLOAD) {
-            buf_dma16(rw, voffB, si.soff * 16u, si.sbase + A_BYTES + ((wave * 64) % BN) * 16);
+            buf_dma16(rw, si.in_k ? voffB : kBufOutside, si.soff * 16u, si.sbase + A_BYTES + ((wv * 64) % BN) * 16);
         } else if (GEMM) {
-            buf_dma16(rx, voffA[i], si.soff * 128u, si.sbase + (i * NW + wave) * 1024);
+            buf_dma16(rx, si.in_k ? voffA[i] : kBufOutside, si.soff * 128u, si.sbase + (i * NWG + wv) * 1024);
         } else {
             const bool ok = (static_cast<unsigned>(ih0[i] + si.dth) < static_cast<unsigned>(g.IH)) &
-                            (static_cast<unsigned>(iw0[i] + si.dtw) < static_cast<unsigned>(g.IW));
+                            (static_cast<unsigned>(iw0[i] + si.dtw) < static_cast<unsigned>(g.IW)) & si.in_k;
             buf_dma16(rx, ok ? voffA[i] + static_cast<uint32_t>(si.delta_b) : kBufOutside, 0u,
-                      si.sbase + (i * NW + wave) * 1024);
+                      si.sbase + (i * NWG + wv) * 1024);
         }
     };
     // after the last load of a slab: next slab, or the first slab of the next tile (past the last tile every
@@ -200,18 +227,12 @@ void conv_stream_kernel(const StreamArgs a) {
     auto issue_advance = [&]() __attribute__((always_inline)) {
         ++lk;
         if (!GEMM) {
-            nc0 += 64;
-            if (nc0 == g.IC) {
-                nc0 = 0;
-                if (++nss == g.S) {
-                    nss = 0;
-                    ++nrr;
-                }
-            }
+            nc0 += 64 * KS;
+            tap_normalize();
         }
-        if (lk == KT) {
+        if (lk == KTS) {
             lk = 0;
-            nc0 = nss = nrr = 0;
+            if (!GEMM) tap_reset();
             ++lt;
             tile_setup(tile_id(lt), lt < n_my);
         }
@@ -249,11 +270,11 @@ void conv_stream_kernel(const StreamArgs a) {
     uint32_t aoff[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-        aoff[kk] = (wm * TM + lrow) * 128 + (((lh * 4 + kk) ^ ((lrow >> 1) & 7)) * 16);
-    const uint32_t boff = A_BYTES + (wn * TN + lrow) * 16 + lh * 8;
+        aoff[kk] = kg * SUB_BYTES + (wm * TM + lrow) * 128 + (((lh * 4 + kk) ^ ((lrow >> 1) & 7)) * 16);
+    const uint32_t boff = kg * SUB_BYTES + A_BYTES + (wn * TN + lrow) * 16 + lh * 8;
 
     u32x2 breg[2][NI];      // packed codes of the slab being multiplied / of the next slab
-    u32x4 afrag[DEEP ? 4 : 2][MI];   // activation fragments of step kk in set kk & 1 (DEEP: in set kk)
+    u32x4 afrag[2][MI];     // activation fragments of step kk in set kk & 1
     u32x4 bfrag[2][NI];     // expanded codes of step kk in set kk & 1
 
     uint32_t kmask[8];
@@ -322,78 +343,6 @@ void conv_stream_kernel(const StreamArgs a) {
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // DEEP variant of a step.  With few MFMAs per step (MI*NI of 2 or 4) the one-step-ahead fragment reads above
-    // leave every step waiting for LDS latency (measured: 1300 cycles per slab for 256 cycles of MFMA work).  Here
-    // step kk reads the fragments of step kk+3 into the set that step kk-1 has just consumed, and waits only for
-    // reads issued two steps earlier:
-    //   step 0: fragments (this slab, step 3);  then the hand-over: all reads done (this stage is then free
-    //           in every wave), next slab landed, barrier;
-    //   step 1: codes of the next slab, fragments (next slab, step 0), first half of the global loads, which
-    //           refill THIS slab's stage with the slab STAGES positions ahead;
-    //   step 2: fragments (next, 1), the other global loads;   step 3: fragments (next, 2).
-    // `hold` (last slab of a tile) skips the global loads: the stage is used by the epilogue first.
-    auto step_deep = [&](auto kk_tag, auto cur_tag, int stage, int next, bool hold) __attribute__((always_inline)) {
-        constexpr int KK = decltype(kk_tag)::value;
-        constexpr int CUR = decltype(cur_tag)::value;
-        constexpr int NM = MI * NI;
-        constexpr int SET = KK & 1, NSET = SET ^ 1;              // expanded codes: one step ahead, as above
-        constexpr int KN = (KK + 1) & 3;
-        constexpr int BSRC = (KK == 3) ? (CUR ^ 1) : CUR;
-        constexpr int RS = (KK + 3) & 3;                         // the step whose fragments are read now
-        constexpr int HALF = (NLOAD + 2) / 2;
-        constexpr int G0 = (KK == 1) ? 0 : HALF;
-        constexpr int P_RB = (KK == 1) ? 1 : 0;
-        constexpr int P_RA = MI;
-        constexpr int P_D = 4 * NI;
-        constexpr int P_G = (KK == 1) ? HALF : (KK == 2) ? NLOAD + 1 - HALF : 0;
-        constexpr int P = P_RB + P_RA + P_D + P_G;
-        const uint32_t a_addr = lds_base + ((KK == 0) ? stage : next) * STAGE_BYTES + aoff[RS];
-        auto piece = [&](auto p_tag) __attribute__((always_inline)) {
-            constexpr int p = decltype(p_tag)::value;
-            if constexpr (p < P_RB) {
-                lds_read64_n<NI, 32 * 16>(breg[CUR ^ 1], lds_base + next * STAGE_BYTES + boff);
-            } else if constexpr (p < P_RB + P_RA) {
-                constexpr int idx = p - P_RB;
-                lds_read128<idx * 32 * 128>(afrag[RS][idx], a_addr);
-            } else if constexpr (p < P_RB + P_RA + P_D) {
-                constexpr int qq = p - P_RB - P_RA;
-                expand(std::integral_constant<int, KN>{}, std::integral_constant<int, qq / 4>{},
-                       std::integral_constant<int, qq % 4>{}, breg[BSRC], bfrag[NSET]);
-            } else {
-                constexpr int gi = G0 + p - (P_RB + P_RA + P_D);
-                if (!hold) {
-                    if constexpr (gi == 0) issue_setup(stage);
-                    issue_load(std::integral_constant<int, gi>{});
-                    if constexpr (gi == NLOAD) issue_advance();
-                }
-            }
-        };
-        static_for<NM>([&](auto j_tag) __attribute__((always_inline)) {
-            constexpr int jj = decltype(j_tag)::value;
-            constexpr int mi = jj / NI, ni = jj % NI;
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag[SET][ni]),
-                                                                  __builtin_bit_cast(bf16x8, afrag[DEEP ? KK : 0][mi]),
-                                                                  acc[mi][ni], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            static_for<P>([&](auto p_tag) __attribute__((always_inline)) {
-                constexpr int p = decltype(p_tag)::value;
-                if constexpr (p * NM / P == jj) piece(p_tag);
-            });
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        // LDS operations complete in issue order: "at most 2*MI outstanding" leaves the fragment reads of the
-        // last two steps in flight and guarantees everything older
-        if constexpr (KK == 2) {
-            lds_wait<2 * MI>();
-            lds_ready<NI>(breg[CUR ^ 1]);           // issued first in step 1
-        }
-        if constexpr (KK == 3) {
-            lds_wait<2 * MI>();
-            lds_ready<MI>(afrag[0]);                // issued in step 1
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
     // ---- epilogue of the tile the compute stream has just finished -------------------------------------
     uint32_t ct = 0;        // tiles finished so far
     auto epilogue = [&](int free_stage) __attribute__((always_inline)) {
@@ -403,7 +352,7 @@ void conv_stream_kernel(const StreamArgs a) {
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            cmul = reinterpret_cast<float*>(smem + free_stage * STAGE_BYTES + NW * EPI_WAVE);
+            cmul = reinterpret_cast<float*>(smem + free_stage * STAGE_BYTES + NWG * EPI_WAVE);
         }
         float* cadd = cmul + BN;
         if (tid < BN) {
@@ -415,15 +364,59 @@ void conv_stream_kernel(const StreamArgs a) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+        if constexpr (KS > 1) {
+            // Sum of the K groups' partial tiles, in a fixed order (group 1, then 2, ...), through the free
+            // stage: a lane of group kg writes the accumulator quads of RED_MI row blocks, the same lane of
+            // group 0 adds them.  Every wave takes part in every barrier.
+            f32x4* red = reinterpret_cast<f32x4*>(smem + free_stage * STAGE_BYTES);
+#pragma unroll
+            for (int src = 1; src < KS; ++src) {
+#pragma unroll
+                for (int c0 = 0; c0 < MI; c0 += RED_MI) {
+                    if (kg == src) {
+#pragma unroll
+                        for (int mi = 0; mi < RED_MI; ++mi)
+#pragma unroll
+                            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                                for (int q4 = 0; q4 < 4; ++q4) {
+                                    const f32x16& t = acc[c0 + mi][ni];
+                                    red[(((wv * RED_MI + mi) * NI + ni) * 4 + q4) * 64 + lane] =
+                                        f32x4{t[q4 * 4], t[q4 * 4 + 1], t[q4 * 4 + 2], t[q4 * 4 + 3]};
+                                }
+                    }
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    if (kg == 0) {
+#pragma unroll
+                        for (int mi = 0; mi < RED_MI; ++mi)
+#pragma unroll
+                            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                                for (int q4 = 0; q4 < 4; ++q4) {
+                                    const f32x4 v = red[(((wv * RED_MI + mi) * NI + ni) * 4 + q4) * 64 + lane];
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) acc[c0 + mi][ni][q4 * 4 + e] += v[e];
+                                }
+                    }
+                    // the sums are in registers (their LDS reads have returned) before the region is reused
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+            }
+        }
         const uint32_t t = tile_id(ct);
         const uint32_t tm = fdiv_u(t, a.divTN);
         const uint32_t m0 = tm * BM;
         const int n0 = static_cast<int>((t - tm * a.tiles_n) * BN);
-        unsigned char* stg = smem + free_stage * STAGE_BYTES + wave * EPI_WAVE;
+        unsigned char* stg = smem + free_stage * STAGE_BYTES + wv * EPI_WAVE;
         const uint16_t* res = static_cast<const uint16_t*>(g.residual);
         uint16_t* Yb = static_cast<uint16_t*>(g.Y);
         // accumulator element e of tile (mi, ni) in this lane: pixel wm*TM + mi*32 + lrow,
         // channel wn*TN + ni*32 + (e>>2)*8 + lh*4 + (e&3)
+        if (KS == 1 || kg == 0) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
             const uint32_t m = m0 + static_cast<uint32_t>(wm * TM + mi * 32 + lrow);
@@ -471,6 +464,7 @@ void conv_stream_kernel(const StreamArgs a) {
                 }
             }
         }
+        }
         acc_clear();
         ++ct;
         if (ct < n_my) colparam_load(tile_id(ct));
@@ -478,6 +472,7 @@ void conv_stream_kernel(const StreamArgs a) {
 
     // ---- prologue: column parameters of the first tile, PD slabs in flight, the first one landed ------------
     colparam_load(tile_id(0));
+    if (!GEMM) tap_reset();
     tile_setup(tile_id(0), true);
 #pragma unroll
     for (int s = 0; s < PD; ++s) {
@@ -493,17 +488,9 @@ void conv_stream_kernel(const StreamArgs a) {
     TWN_STRACE(2);
     lds_read64_n<NI, 32 * 16>(breg[0], lds_base + boff);
     lds_read128_n<MI, 32 * 128>(afrag[0], lds_base + aoff[0]);
-    if constexpr (DEEP) {
-        lds_read128_n<MI, 32 * 128>(afrag[1], lds_base + aoff[1]);
-        lds_read128_n<MI, 32 * 128>(afrag[2], lds_base + aoff[2]);
-    }
     lds_wait<0>();
     lds_ready<NI>(breg[0]);
     lds_ready<MI>(afrag[0]);
-    if constexpr (DEEP) {
-        lds_ready<MI>(afrag[1]);
-        lds_ready<MI>(afrag[2]);
-    }
     static_for<4 * NI>([&](auto q_tag) __attribute__((always_inline)) {
         constexpr int qq = decltype(q_tag)::value;
         expand(std::integral_constant<int, 0>{}, std::integral_constant<int, qq / 4>{},
@@ -511,45 +498,12 @@ void conv_stream_kernel(const StreamArgs a) {
     });
 
     int stage = 0;          // stage of the slab being multiplied
-    int fill = PD % STAGES; // stage that the slab PD positions ahead goes to (DEEP: the current stage)
+    int fill = PD % STAGES; // stage that the slab PD positions ahead goes to
     int kt = 0;             // slab of the current tile
     // one slab of the stream; CUR selects the register set holding this slab's packed codes
     auto slab = [&](auto cur_tag) __attribute__((always_inline)) {
         const int next = (stage + 1 == STAGES) ? 0 : stage + 1;
-        if constexpr (DEEP) {
-            const bool last = (kt == KT - 1);
-            step_deep(std::integral_constant<int, 0>{}, cur_tag, stage, next, last);
-            // hand-over: every fragment read of this wave has completed (this slab's stage is free once all
-            // waves are here), the next slab has landed (the PD-2 younger ones may stay in flight)
-            lds_wait<0>();
-            lds_ready<MI>(afrag[1]);
-            lds_ready<MI>(afrag[2]);
-            lds_ready<MI>(afrag[3]);
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm((PD - 2) * PER_STAGE));
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            step_deep(std::integral_constant<int, 1>{}, cur_tag, stage, next, last);
-            step_deep(std::integral_constant<int, 2>{}, cur_tag, stage, next, last);
-            step_deep(std::integral_constant<int, 3>{}, cur_tag, stage, next, last);
-            const int done = stage;
-            stage = next;
-            if (last) {
-                kt = 0;
-                TWN_STRACE(3 + 2 * ct);
-                epilogue(done);
-                TWN_STRACE(2 + 2 * ct);      // ct was advanced by the epilogue
-                // the staging rows of every wave have been read back: the stage can take its next slab
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                asm volatile("" ::: "memory");
-                issue_setup(done);
-                static_for<NLOAD + 1>(issue_load);
-                issue_advance();
-            } else {
-                ++kt;
-            }
-        } else {
+        {
 #ifdef TWN_TRACE
             // fine-grained timeline of one slab (every step ends with lgkmcnt(0), which also covers s_memtime)
             uint64_t ts[7];
@@ -583,7 +537,7 @@ void conv_stream_kernel(const StreamArgs a) {
             const int done = stage;
             stage = next;
             fill = (fill + 1 == STAGES) ? 0 : fill + 1;
-            if (++kt == KT) {
+            if (++kt == KTS) {
                 kt = 0;
                 TWN_STRACE(3 + 2 * ct);
                 epilogue(done);
@@ -591,7 +545,7 @@ void conv_stream_kernel(const StreamArgs a) {
             }
         }
     };
-    const uint32_t total = n_my * static_cast<uint32_t>(KT);
+    const uint32_t total = n_my * static_cast<uint32_t>(KTS);
     for (uint32_t s = 0; s < total; s += 2) {
         slab(std::integral_constant<int, 0>{});
         if (s + 1 < total) slab(std::integral_constant<int, 1>{});
@@ -632,12 +586,12 @@ int num_cus(hipStream_t) {
     return cus;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, int OCC, bool DEEP>
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, int OCC, int KS>
 int32_t launch_stream_kernel(const StreamArgs& a, hipStream_t st) {
-    constexpr int PIPE = STAGES * (BM * 128 + BN * 16);
+    constexpr int PIPE = STAGES * KS * (BM * 128 + BN * 16);
     constexpr int SMEM = ((PIPE + 4 * BN * 4) * OCC > 160 * 1024) ? PIPE : PIPE + 4 * BN * 4;   // see COL_IN_STAGE
     static_assert(SMEM <= 160 * 1024, "LDS budget");
-    auto k = conv_stream_kernel<BM, BN, WM, WN, STAGES, GEMM, OCC, DEEP>;
+    auto k = conv_stream_kernel<BM, BN, WM, WN, STAGES, GEMM, OCC, KS>;
     // more than 64 KB of dynamic LDS has to be allowed once per kernel; the occupancy query sizes the grid
     static std::once_flag once;
     static int per_cu = 0;
@@ -646,7 +600,7 @@ int32_t launch_stream_kernel(const StreamArgs& a, hipStream_t st) {
             hipSuccess)
             return;
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k, 64 * WM * WN, SMEM) == hipSuccess && n > 0) per_cu = n;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k, 64 * WM * WN * KS, SMEM) == hipSuccess && n > 0) per_cu = n;
     });
     if (per_cu <= 0) return TWN_ERR_HIP;
     int occ = per_cu;
@@ -654,11 +608,11 @@ int32_t launch_stream_kernel(const StreamArgs& a, hipStream_t st) {
     if (cap > 0 && cap < occ) occ = cap;
     int64_t grid = static_cast<int64_t>(num_cus(st)) * occ;
     if (grid > a.tiles) grid = a.tiles;
-    k<<<dim3(static_cast<unsigned>(grid)), dim3(64 * WM * WN), SMEM, st>>>(a);
+    k<<<dim3(static_cast<unsigned>(grid)), dim3(64 * WM * WN * KS), SMEM, st>>>(a);
     return launch_status();
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int OCC, bool DEEP>
+template <int BM, int BN, int WM, int WN, int STAGES, int OCC, int KS>
 int32_t launch_stream_tile(const GatherGemm& g, hipStream_t st) {
     const int64_t tiles_n = (g.NC + BN - 1) / BN;
     const int64_t tiles = ((g.M + BM - 1) / BM) * tiles_n;
@@ -674,8 +628,8 @@ int32_t launch_stream_tile(const GatherGemm& g, hipStream_t st) {
     a.tiles = static_cast<uint32_t>(tiles);
     a.tiles_n = static_cast<uint32_t>(tiles_n);
     a.KT = g.K / 64;
-    return g.plain_gemm ? launch_stream_kernel<BM, BN, WM, WN, STAGES, true, OCC, DEEP>(a, st)
-                        : launch_stream_kernel<BM, BN, WM, WN, STAGES, false, OCC, DEEP>(a, st);
+    return g.plain_gemm ? launch_stream_kernel<BM, BN, WM, WN, STAGES, true, OCC, KS>(a, st)
+                        : launch_stream_kernel<BM, BN, WM, WN, STAGES, false, OCC, KS>(a, st);
 }
 
 }  // namespace
@@ -683,13 +637,26 @@ int32_t launch_stream_tile(const GatherGemm& g, hipStream_t st) {
 // Tile ids as in launch_gather_gemm_dma: 12 = 128x128 2x2, 14 = 64x128 1x4, 15 = 128x128 1x4, 16 = 128x64 2x2,
 // 17 = 128x256 1x4 (4 stages).  The caller has checked conv_stream_applicable.
 int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st) {
-    const bool deep = env_int("TWN_STREAM_DEEP", 1) != 0;
+    // K groups: layers whose 64x128 tiles do not even give every CU one workgroup (few pixels, deep K) run two
+    // groups of four waves per tile (ResNet-18 stage 4: 31 -> 24 us); TWN_STREAM_KS overrides for experiments
+    int ks = env_int("TWN_STREAM_KS", 0);
+    if (ks == 0) {
+        const int64_t tiles64 = ((g.M + 63) / 64) * ((g.NC + 127) / 128);
+        ks = (tile == 14 && tiles64 <= 320 && g.K >= 1024) ? 2 : 1;
+    }
     switch (tile) {
-        case 12: return deep ? launch_stream_tile<128, 128, 2, 2, 3, 2, true>(g, st) : launch_stream_tile<128, 128, 2, 2, 3, 2, false>(g, st);
-        case 14: return deep ? launch_stream_tile<64, 128, 1, 4, 3, 4, true>(g, st) : launch_stream_tile<64, 128, 1, 4, 3, 4, false>(g, st);
-        case 15: return deep ? launch_stream_tile<128, 128, 1, 4, 3, 2, true>(g, st) : launch_stream_tile<128, 128, 1, 4, 3, 2, false>(g, st);
-        case 16: return deep ? launch_stream_tile<128, 64, 2, 2, 3, 3, true>(g, st) : launch_stream_tile<128, 64, 2, 2, 3, 3, false>(g, st);
-        case 17: return launch_stream_tile<128, 256, 1, 4, 4, 2, false>(g, st);
+        case 12: return launch_stream_tile<128, 128, 2, 2, 3, 2, 1>(g, st);
+        case 14:
+            if (ks == 2) return launch_stream_tile<64, 128, 1, 4, 3, 2, 2>(g, st);
+            if (ks == 4) return launch_stream_tile<64, 128, 1, 4, 3, 1, 4>(g, st);
+            return launch_stream_tile<64, 128, 1, 4, 3, 4, 1>(g, st);
+        case 15:
+            if (ks == 2) return launch_stream_tile<128, 128, 1, 4, 3, 1, 2>(g, st);
+            return launch_stream_tile<128, 128, 1, 4, 3, 2, 1>(g, st);
+        case 16:
+            if (ks == 2) return launch_stream_tile<128, 64, 2, 2, 3, 1, 2>(g, st);
+            return launch_stream_tile<128, 64, 2, 2, 3, 3, 1>(g, st);
+        case 17: return launch_stream_tile<128, 256, 1, 4, 4, 2, 1>(g, st);
         default: return TWN_ERR_UNSUPPORTED;
     }
 }

@@ -123,3 +123,22 @@ def test_missing_library_is_loud(monkeypatch):
     monkeypatch.setattr(api, "_LIB_PATH", "/nonexistent/libtwn.so")
     with pytest.raises(FileNotFoundError):
         api.lib()
+
+
+def test_output_and_residual_alignment_is_validated():
+    # rows with channel counts in multiples of 8 are written with 16-byte stores: Y and the residual must be 16-byte aligned
+    L = api.lib()
+    d = api.GemmDesc(64, 32, 128, api.TWN_BF16, api.TWN_BF16, api.TWN_VAR_BF16_POSTSCALE, 0, 0, 1)
+    Y2 = ctypes.c_void_p(0x10002)
+    assert L.twn_gemm_fwd(ctypes.byref(d), FAKE, FAKE, FAKE, None, Y2, None, 0, None) == -3
+    ep = api.Epilogue(None, None, 0x10008, 0)
+    assert L.twn_gemm_fwd(ctypes.byref(d), FAKE, FAKE, FAKE, ctypes.byref(ep), FAKE, None, 0, None) == -3
+    c = api.ConvDesc(1, 8, 8, 16, 32, 3, 3, 1, 1, 1, 1, 1, 1, api.TWN_BF16, api.TWN_BF16, api.TWN_VAR_BF16_POSTSCALE, 1)
+    assert L.twn_conv2d_fwd(ctypes.byref(c), FAKE, FAKE, FAKE, None, Y2, None, 0, None) == -3
+    assert L.twn_conv2d_bwd_ste(ctypes.byref(c), None, FAKE, FAKE, FAKE, Y2, None, None, ctypes.c_float(0.0),
+                                None, 0, None) == -3
+    # odd channel counts are stored element by element: 2-byte alignment is enough (the call then fails later,
+    # on the missing workspace or not at all; it must not fail on alignment)
+    c2 = api.ConvDesc(1, 8, 8, 16, 30, 3, 3, 1, 1, 1, 1, 1, 1, api.TWN_BF16, api.TWN_BF16, api.TWN_VAR_BF16_POSTSCALE, 1)
+    assert L.twn_conv2d_bwd_ste(ctypes.byref(c2), None, FAKE, FAKE, FAKE, None, None, None, ctypes.c_float(0.0),
+                                None, 0, None) != -3
