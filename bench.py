@@ -4,9 +4,11 @@
 Headline workload: ResNet-18, batch 64, bf16 (the configuration both the metric and the target are stated on).
 A step is one pass of the forward hot path over one batch: ONE multi-tensor ternarize call for all 21 weight
 tensors (Delta, alpha, 2-bit codes), then the forward of every conv / FC layer with its fused block tail
-(scale, shift, residual on the second conv of a block, ReLU).  Every layer reads its own seeded synthetic input
-of the right shape, already resident in HBM; the layers run one after the other on one stream, as the data
-dependences of the network demand.  `value` is the dense-equivalent throughput of the step (2MNK per
+(scale, shift, residual on the second conv of a block, ReLU).  Inside a basic block the tensors flow as in the
+network (conv2 reads conv1's output and adds the block input or its down-sampled copy, the next block reads
+conv2's output); the stem, the first block and the classifier start from seeded synthetic tensors because the
+pooling between them is glue outside the hot path.  All inputs are resident in HBM and the layers run one after
+the other on one stream, as the data dependences of the network demand.  `value` is the dense-equivalent throughput of the step (2MNK per
 contraction / step time); images per second are in `config`.
 
 Side measurements (structured, each with its own roofline object): the 8192x4096x4096 GEMM, the 2^28-element
@@ -113,34 +115,61 @@ def main():
         return o
 
     # ------------------------------------------------------------------ network forward builders
-    def build_forward(layers, cfg, fp32=False, residual_on=("conv2",), groups_per_filter=False, transposed=False):
-        """Device tensors and prepared calls for the forward of a list of layers (each with its own input)."""
+    def build_forward(layers, cfg, fp32=False, residual_on=("conv2",), groups_per_filter=False, transposed=False,
+                      chain_blocks=False):
+        """Device tensors and prepared calls for the forward of a list of layers.  Every layer reads its own
+        synthetic input, except with chain_blocks (residual networks): inside a basic block the data flows as in
+        the network (conv1 and the down-sample read the block input, conv2 reads conv1's output and adds the
+        block input or the down-sampled one, the next block reads conv2's output); only where the network has
+        glue that is outside the hot path (pooling before the first block and before the classifier) does a
+        layer start from a synthetic tensor."""
         W, X, Y, tws, calls = [], [], [], [], []
         for li, L in enumerate(layers):
             w = wl.kaiming_weights(cfg, li, L)
             W.append(torch.from_numpy(w).to(dev))
-            if fp32:
-                X.append(torch.from_numpy(wl.uniform01(cfg, wl.IDX_INPUT + li, L.x_shape)).to(dev))
-            else:
-                X.append(dev_bf16(wl.normal(cfg, wl.IDX_INPUT + li, L.x_shape)))
             Y.append(torch.empty(L.y_shape, dtype=torch.float32 if fp32 else torch.bfloat16, device=dev))
             groups = L.O if groups_per_filter else 1
             tws.append(api.twn_ternarize(W[li], F, groups=groups, transposed=transposed))
+
+        def synthetic(li, L):
+            if fp32:
+                return torch.from_numpy(wl.uniform01(cfg, wl.IDX_INPUT + li, L.x_shape)).to(dev)
+            return dev_bf16(wl.normal(cfg, wl.IDX_INPUT + li, L.x_shape))
+
+        RES = [None] * len(layers)
+        block_in = conv1_out = down_out = None
+        for li, L in enumerate(layers):
+            x = None
+            part = L.name.rsplit(".", 1)[-1]
+            if chain_blocks and part in ("conv1", "down", "conv2"):
+                if part == "conv1":
+                    if block_in is None or tuple(block_in.shape) != tuple(L.x_shape):
+                        block_in = synthetic(li, L)
+                    x, conv1_out, down_out = block_in, Y[li], None
+                elif part == "down":
+                    x, down_out = block_in, Y[li]
+                else:
+                    x = conv1_out
+                    RES[li] = down_out if down_out is not None else block_in
+                    block_in = Y[li]
+                assert tuple(x.shape) == tuple(L.x_shape)
+            else:
+                x = synthetic(li, L)
+                if not fp32 and any(L.name.endswith(s) for s in residual_on):
+                    RES[li] = dev_bf16(wl.normal(cfg, 700 + li, L.y_shape))
+            X.append(x)
         for li, L in enumerate(layers):
             st, pd, dl = geo(L)
             is_fc = (L.R == 1 and L.S == 1 and L.H == 1 and L.W == 1)
             last = (li == len(layers) - 1)
             sc = torch.ones(L.O, dtype=torch.float32, device=dev)
             sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
-            res = None
-            if not fp32 and any(L.name.endswith(s) for s in residual_on):
-                res = dev_bf16(wl.normal(cfg, 700 + li, L.y_shape))
             if is_fc:
                 calls.append(api.prepare_gemm_fwd(X[li].reshape(L.N, L.C), tws[li], out=Y[li].reshape(L.N, L.O),
                                                   scale=None if last else sc, shift=sf, relu=not last))
             else:
                 calls.append(api.prepare_conv2d_fwd(X[li], tws[li], st, pd, dl, out=Y[li], scale=sc, shift=sf,
-                                                    residual=res, relu=True))
+                                                    residual=RES[li], relu=True))
         return W, X, Y, tws, calls
 
     def per_layer_table(tag, layers, calls, reps=100, warm=20):
@@ -339,7 +368,7 @@ def main():
     def headline(with_cpu):
         CFG = 2
         layers = wl.resnet18(64)
-        W, X, Y, tws, calls = build_forward(layers, CFG)
+        W, X, Y, tws, calls = build_forward(layers, CFG, chain_blocks=True)
         tern = api.prepare_ternarize_batch(W, tws, F)
         names = [L.name for L in layers]
         i0, i1 = names.index(ROOFLINE_LAYERS[0]), names.index(ROOFLINE_LAYERS[-1])

@@ -358,6 +358,24 @@ extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const v
     g.alpha = alpha;
     set_epilogue(g, ep);
     g.Y = Y;
+    if (d->variant == TWN_VAR_BF16_POSTSCALE && d->x_dtype == TWN_BF16 && d->y_dtype == TWN_BF16 && d->C == 3 &&
+        d->dil_h == 1 && d->dil_w == 1 && env_int("TWN_FIRST", 1) != 0) {
+        // three-channel first layer: persistent kernel with the input patch widened to four channels in LDS and
+        // the expanded weights resident in registers (no workspace, no preparation launch)
+        FirstLayer f{};
+        f.X = static_cast<const uint16_t*>(X);
+        f.Wq = static_cast<const uint32_t*>(weights);
+        f.alpha = alpha;
+        f.scale = g.scale;
+        f.shift = g.shift;
+        f.residual = static_cast<const uint16_t*>(g.residual);
+        f.Y = static_cast<uint16_t*>(Y);
+        f.N = d->N; f.H = d->H; f.W = d->W; f.C = d->C; f.O = d->O; f.R = d->R; f.S = d->S;
+        f.sh = d->stride_h; f.sw = d->stride_w; f.ph = d->pad_h; f.pw = d->pad_w; f.P = P; f.Q = Q;
+        f.rows_per_group = d->O / d->alpha_groups;
+        f.relu = g.relu;
+        if (conv_first_applicable(f)) return launch_conv_first(f, as_stream(stream));
+    }
     SmallC sc;
     if (small_c(d, &sc)) {
         // first-layer path: padded 4-channel copy of X and re-ordered codes live in the workspace

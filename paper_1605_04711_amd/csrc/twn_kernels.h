@@ -78,6 +78,22 @@ int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 bool conv_stream_applicable(const GatherGemm& g);
 int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st);
 
+// First layers with three input channels, bf16 in and out, dilation 1 (forward): one persistent kernel, no
+// workspace and no preparation launch; `applicable` is a pure function of the problem (shapes and alignment).
+struct FirstLayer {
+    const uint16_t* X;
+    const uint32_t* Wq;
+    const float* alpha;
+    const float* scale;
+    const float* shift;
+    const uint16_t* residual;
+    uint16_t* Y;
+    int32_t N, H, W, C, O, R, S, sh, sw, ph, pw, P, Q;
+    int32_t rows_per_group, relu;
+};
+bool conv_first_applicable(const FirstLayer& f);
+int32_t launch_conv_first(const FirstLayer& f, hipStream_t st);
+
 // Halo-tiled kernel for stride-1 filters with several taps (activations staged once per 64-channel slab and
 // reused by every tap); `applicable` is a pure function of the problem.
 bool conv_halo_applicable(const GatherGemm& g);

@@ -616,3 +616,46 @@ def test_full_size_resnet18_backward_sampled(name):
         i1 = np.unique(np.concatenate([_sample(int(np.prod(layer.x_shape)), 20000, li), np.array(corners)]))
         ref_dx = oc.conv2d_bwd_data_at(dy, codes, alpha, layer.x_shape, i1, st, pd, dl)
         assert rel_err(to_host_f64(dx).ravel()[i1], ref_dx) <= BF16_TOL
+
+
+FIRST_LAYER_CASES = [
+    # N  H   W   O   R  S  stride  pad      (C = 3, even W: the persistent first-layer kernel)
+    (2, 30, 28, 64, 7, 7, (2, 2), (3, 3)),
+    (3, 18, 20, 72, 3, 3, (1, 1), (1, 1)),
+    (2, 17, 22, 40, 5, 5, (2, 2), (2, 2)),       # even padding: the patch starts at the first tap
+    (1, 9, 10, 8, 3, 3, (1, 1), (0, 0)),
+    (2, 21, 26, 136, 3, 3, (1, 2), (1, 1)),      # three channel tiles, mixed strides
+    (2, 40, 36, 64, 7, 5, (2, 1), (3, 2)),
+    (5, 33, 34, 64, 1, 1, (1, 1), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("ci", range(len(FIRST_LAYER_CASES)))
+def test_first_layer_kernel(ci):
+    n, h, w_, o, r, s, st, pd = FIRST_LAYER_CASES[ci]
+    dl = (1, 1)
+    groups = o if ci % 2 else 1
+    x, w, tw, codes, alpha = make_layer(800 + ci, (n, h, w_, 3), (o, 3, r, s), groups=groups)
+    g = np.random.default_rng(ci)
+    scale = g.uniform(0.5, 1.5, o).astype(np.float32)
+    shift = g.standard_normal(o).astype(np.float32)
+    ref0 = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl)
+    assert tuple(y.shape) == ref0.shape
+    assert rel_err(to_host_f64(y), ref0) <= BF16_TOL
+    res = wl.bf16_round(g.standard_normal(ref0.shape).astype(np.float32))
+    y2 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, scale=to_dev_f32(scale), shift=to_dev_f32(shift),
+                            residual=to_dev_bf16(res), relu=True)
+    assert rel_err(to_host_f64(y2), oc.epilogue(ref0, scale, shift, res, relu=True)) <= BF16_TOL
+
+
+def test_first_layer_kernel_matches_generic_path(monkeypatch):
+    # the same call through the generic small-C path (padded copy + re-ordered codes): both round once from fp32
+    n, h, w_, o, r, s, st, pd = FIRST_LAYER_CASES[0]
+    x, w, tw, codes, alpha = make_layer(850, (n, h, w_, 3), (o, 3, r, s))
+    y1 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, (1, 1))
+    monkeypatch.setenv("TWN_FIRST", "0")
+    y0 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, (1, 1))
+    ref = oc.conv2d_fwd(x, codes, alpha, st, pd, (1, 1))
+    assert rel_err(to_host_f64(y0), ref) <= BF16_TOL and rel_err(to_host_f64(y1), ref) <= BF16_TOL
+    assert rel_err(to_host_f64(y1), to_host_f64(y0)) <= BF16_TOL
