@@ -28,6 +28,7 @@
 #include "twn_kernels.h"
 #include "twn_lds_asm.h"
 #include "twn_mfma.h"
+#include "twn_stream_epilogue.h"
 
 namespace twn {
 
@@ -51,13 +52,14 @@ struct StreamArgs {
     GatherGemm g;
     FastDivU divOW, divOH;      // GEMM row -> (image, oh, ow)
     FastDivU divTN;             // tile -> (row block, column block)
-    uint32_t x_bytes, w_bytes;  // sizes for the buffer descriptors
+    uint32_t x_bytes, w_bytes, y_bytes;  // sizes for the buffer descriptors
     uint32_t tiles, tiles_n;
     int32_t KT;                 // K / 64
 };
 
 template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, int OCC, int KS>
-__global__ __launch_bounds__(64 * WM * WN * KS, OCC)
+// (the second launch bound is in waves per SIMD)
+__global__ __launch_bounds__(64 * WM * WN * KS, (OCC * WM * WN * KS + 3) / 4)
 void conv_stream_kernel(const StreamArgs a) {
     // KS > 1: the workgroup holds KS groups of WM*WN waves.  All groups work on the SAME output tile; group kg
     // takes the K slabs kg, kg+KS, kg+2KS, ... (it stages and multiplies them on its own, in its own part of
@@ -77,7 +79,6 @@ void conv_stream_kernel(const StreamArgs a) {
     constexpr int PER_STAGE = NLOAD + 1;           // vector-memory loads per wave per slab
     constexpr int EPI_CH = TN < 64 ? TN : 64;      // channels staged at a time
     constexpr int EPI_ROW = EPI_CH * 2 + 16;       // bytes per staged pixel row (pad keeps 16-byte reads conflict-free)
-    constexpr int EPI_NI = EPI_CH / 32;
     constexpr int EPI_WAVE = 32 * EPI_ROW;         // one block of 32 pixel rows per wave
     static_assert(BM % (8 * NWG) == 0 && BN % 64 == 0 && BN <= 64 * NWG && TN % 32 == 0 && TM % 32 == 0, "tile shape");
     static_assert(NWG % 2 == 0, "the swizzle of the staged rows assumes an even number of waves");
@@ -344,6 +345,9 @@ void conv_stream_kernel(const StreamArgs a) {
     };
 
     // ---- epilogue of the tile the compute stream has just finished -------------------------------------
+    const uint32_t ldyB = static_cast<uint32_t>(g.ldy) * 2u;
+    TileStoreLane<EPI_CH> store_lane;
+    store_lane.init(lane, ldyB);
     uint32_t ct = 0;        // tiles finished so far
     auto epilogue = [&](int free_stage) __attribute__((always_inline)) {
         float* cmul = colbuf + (ct & 1u) * (2 * BN);
@@ -411,60 +415,16 @@ void conv_stream_kernel(const StreamArgs a) {
         const uint32_t tm = fdiv_u(t, a.divTN);
         const uint32_t m0 = tm * BM;
         const int n0 = static_cast<int>((t - tm * a.tiles_n) * BN);
-        unsigned char* stg = smem + free_stage * STAGE_BYTES + wv * EPI_WAVE;
-        const uint16_t* res = static_cast<const uint16_t*>(g.residual);
-        uint16_t* Yb = static_cast<uint16_t*>(g.Y);
-        // accumulator element e of tile (mi, ni) in this lane: pixel wm*TM + mi*32 + lrow,
-        // channel wn*TN + ni*32 + (e>>2)*8 + lh*4 + (e&3)
-        if (KS == 1 || kg == 0) {
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) {
-            const uint32_t m = m0 + static_cast<uint32_t>(wm * TM + mi * 32 + lrow);
-#pragma unroll
-            for (int nc = 0; nc < NI / EPI_NI; ++nc) {
-#pragma unroll
-                for (int nh = 0; nh < EPI_NI; ++nh) {
-                    const int ni = nc * EPI_NI + nh;
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const int nl = wn * TN + ni * 32 + q4 * 8 + lh * 4;     // column within the block tile
-                        const f32x4 mul = *reinterpret_cast<const f32x4*>(cmul + nl);
-                        const f32x4 add = *reinterpret_cast<const f32x4*>(cadd + nl);
-                        float v[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][q4 * 4 + e] * mul[e] + add[e];
-                        if (res && m < static_cast<uint32_t>(g.M) && n0 + nl < g.NC) {
-                            const u32x2 rr = *reinterpret_cast<const u32x2*>(res + static_cast<int64_t>(m) * g.ldy + n0 + nl);
-                            v[0] += __uint_as_float(rr[0] << 16);
-                            v[1] += __uint_as_float(rr[0] & 0xFFFF0000u);
-                            v[2] += __uint_as_float(rr[1] << 16);
-                            v[3] += __uint_as_float(rr[1] & 0xFFFF0000u);
-                        }
-                        if (g.relu) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
-                        }
-                        u32x2 pk;
-                        pk[0] = pack_bf16x2(v[0], v[1]);
-                        pk[1] = pack_bf16x2(v[2], v[3]);
-                        *reinterpret_cast<u32x2*>(stg + lrow * EPI_ROW + (nh * 32 + q4 * 8 + lh * 4) * 2) = pk;
-                    }
-                }
-                // same wave wrote and reads: LDS executes a wave's operations in order
-                constexpr int LPR = EPI_CH / 8;          // lanes per staged row (16 bytes each)
-#pragma unroll
-                for (int it = 0; it < 32 * LPR / 64; ++it) {
-                    const int row = it * (64 / LPR) + lane / LPR;
-                    const int c16 = lane % LPR;
-                    const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
-                    const uint32_t mr = m0 + static_cast<uint32_t>(wm * TM + mi * 32 + row);
-                    const int ncol = n0 + wn * TN + nc * EPI_CH + c16 * 8;
-                    if (mr < static_cast<uint32_t>(g.M) && ncol < g.NC)
-                        *reinterpret_cast<u32x4*>(Yb + static_cast<int64_t>(mr) * g.ldy + ncol) = val;
-                }
-            }
-        }
-        }
+        // the output descriptors are built here, per tile: scalar registers are scarce in the main loop
+        uint32_t yb = a.y_bytes;
+        asm volatile("" : "+s"(yb));
+        const __amdgpu_buffer_rsrc_t ry = make_rsrc(g.Y, yb);
+        const __amdgpu_buffer_rsrc_t rr = make_rsrc(g.residual ? g.residual : g.Y, yb);
+        const uint32_t relu_floor = g.relu ? 0u : 0x80008000u;
+        if (KS == 1 || kg == 0)
+            store_tile_bf16<MI, NI, EPI_CH>(acc, cmul + wn * TN, cadd + wn * TN, smem + free_stage * STAGE_BYTES + wv * EPI_WAVE,
+                                            store_lane, ry, rr, g.residual != nullptr, m0 + static_cast<uint32_t>(wm * TM),
+                                            n0 + wn * TN, static_cast<uint32_t>(g.M), g.NC, ldyB, relu_floor, lane);
         acc_clear();
         ++ct;
         if (ct < n_my) colparam_load(tile_id(ct));
@@ -569,7 +529,8 @@ bool conv_stream_applicable(const GatherGemm& g) {
     const int64_t in_rows = g.plain_gemm ? g.M : (g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW;
     const int64_t xb = ((in_rows - 1) * g.xs + (g.plain_gemm ? g.K : g.IC)) * 2;
     const int64_t wb = static_cast<int64_t>(g.NC) * g.wpr * 4;
-    return xb > 0 && xb < (1LL << 31) && wb < (1LL << 31);
+    const int64_t yb = ((g.M - 1) * g.ldy + g.NC) * 2;       // the output path addresses Y and the residual by 32-bit offsets
+    return xb > 0 && xb < (1LL << 31) && wb < (1LL << 31) && yb < (1LL << 31);
 }
 
 namespace {
@@ -625,6 +586,7 @@ int32_t launch_stream_tile(const GatherGemm& g, hipStream_t st) {
     const int64_t in_rows = g.plain_gemm ? g.M : (g.M / (static_cast<int64_t>(g.OH) * g.OW)) * g.IH * g.IW;
     a.x_bytes = static_cast<uint32_t>(((in_rows - 1) * g.xs + (g.plain_gemm ? g.K : g.IC)) * 2);
     a.w_bytes = static_cast<uint32_t>(static_cast<int64_t>(g.NC) * g.wpr * 4);
+    a.y_bytes = static_cast<uint32_t>(((g.M - 1) * g.ldy + g.NC) * 2);
     a.tiles = static_cast<uint32_t>(tiles);
     a.tiles_n = static_cast<uint32_t>(tiles_n);
     a.KT = g.K / 64;
@@ -640,6 +602,16 @@ int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st) {
     // K groups: layers whose 64x128 tiles do not even give every CU one workgroup (few pixels, deep K) run two
     // groups of four waves per tile (ResNet-18 stage 4: 31 -> 24 us); TWN_STREAM_KS overrides for experiments
     int ks = env_int("TWN_STREAM_KS", 0);
+    // Load waves (conv_stream_pc_kernel): four of them next to the four compute waves.  They pay off where a
+    // workgroup has few tiles and a deep K (ResNet-18 stages 3 and 4: 22 -> 19.5 us and 24 -> 20.7 us per 3x3
+    // layer), and replace the K groups there; 128x64 tiles (64 output channels) gain nothing.
+    // TWN_STREAM_PC: 0 = never, 2 / 4 = that many load waves wherever a build exists, unset = this rule.
+    int np = env_int("TWN_STREAM_PC", -1);
+    if (np < 0) np = (tile == 14 || tile == 15) ? 4 : 0;
+    if (np > 0) {
+        const int32_t rc = launch_conv_stream_pc(g, tile, ks == 0 ? 1 : ks, np, env_int("TWN_STREAM_PC_STAGES", 4), st);
+        if (rc != TWN_ERR_UNSUPPORTED) return rc;
+    }
     if (ks == 0) {
         const int64_t tiles64 = ((g.M + 63) / 64) * ((g.NC + 127) / 128);
         ks = (tile == 14 && tiles64 <= 320 && g.K >= 1024) ? 2 : 1;

@@ -77,6 +77,7 @@ int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 // direct-to-LDS launcher takes (12, 14, 15, 16, 17).
 bool conv_stream_applicable(const GatherGemm& g);
 int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st);
+int32_t launch_conv_stream_pc(const GatherGemm& g, int tile, int ks, int np, int stages, hipStream_t st);
 
 // First layers with three input channels, bf16 in and out, dilation 1 (forward): one persistent kernel, no
 // workspace and no preparation launch; `applicable` is a pure function of the problem (shapes and alignment).
