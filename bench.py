@@ -59,10 +59,13 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the side measurements")
     ap.add_argument("--cpu-batch", type=int, default=8)
-    ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18", "resnet18_bwd", "lenet", "vgg7", "vgg16_ssd",
+    ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18", "resnet18_bwd", "lenet", "vgg7", "vgg16_ssd", "sgd",
                                        "per_filter"], default=None,
                     help="run one measurement alone (used for the rocprofv3 summaries in profiles/)")
     ap.add_argument("--variants", action="store_true", help="with --only gemm: also time the comparison weight formats")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="first run three plain 1 GiB device copies: a kernel of known traffic for the HBM byte counters "
+                         "of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -257,6 +260,27 @@ def main():
         res["forward_walk_GBps"] = round(nbytes / t_fwd / 1e6, 1)
         log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight); forward-walking pass 2: %.1f us, %.1f GB/s"
             % (t * 1e3, gbps, t_fwd * 1e3, nbytes / t_fwd / 1e6))
+        return res
+
+    def side_sgd():
+        """Parameter update of 2^28 float32 weights (Alg. 1 step 10) fused with pass 1 of the next ternarization, and
+        the ternarization that follows with and without the sums it leaves behind."""
+        n = 1 << 28
+        Wt = torch.from_numpy(wl.normal(3, 0, (1 << 14, 1 << 14), std=0.05)).to(dev)
+        Vt = torch.zeros_like(Wt)
+        dWt = torch.from_numpy(wl.normal(3, 1, (1 << 14, 1 << 14), std=0.02)).to(dev)
+        ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
+        tw = api.twn_ternarize(Wt, F)
+        t_u = time_call(lambda: api.twn_sgd_update(Wt, Vt, dWt, 1e-3, 0.9, 1e-4, tern_workspace=ws), reps=50, warm=10)
+        t_p = time_call(lambda: api.twn_ternarize_presummed(Wt, tw, ws, F), reps=50, warm=10)
+        t_t = time_call(lambda: api.twn_ternarize(Wt, F, out=tw, workspace=ws), reps=50, warm=10)
+        nbytes = n * 20.0
+        gbps = nbytes / t_u / 1e6
+        res = roof_obj("sgd_update_kernel", "hbm", gbps, PEAK_HBM_GBPS, "GB/s", nbytes, None, t_u * 1e3,
+                       workload="sgd_momentum_wd_2p28_f32 (+ |W| sums of the next ternarization)", us=round(t_u * 1e3, 1),
+                       ternarize_after_update_us={"reusing_the_sums": round(t_p * 1e3, 1), "from_scratch": round(t_t * 1e3, 1)})
+        log("sgd update 2^28: %.1f us, %.1f GB/s (20 B/weight); ternarize after it: %.1f us reusing the sums, %.1f us from "
+            "scratch" % (t_u * 1e3, gbps, t_p * 1e3, t_t * 1e3))
         return res
 
     def side_lenet():
@@ -484,8 +508,17 @@ def main():
                 "gflop": flops_fwd / 1e9, "layers": len(layers)}
         return info
 
+    if args.calibrate:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     sides = {"gemm": side_gemm, "ternarize": lambda: side_ternarize(calibrate=True), "lenet": side_lenet,
-             "vgg7": side_vgg7, "vgg16_ssd": side_vgg16, "resnet18_bwd": side_resnet18_bwd, "per_filter": side_per_filter}
+             "vgg7": side_vgg7, "vgg16_ssd": side_vgg16, "resnet18_bwd": side_resnet18_bwd, "per_filter": side_per_filter,
+             "sgd": side_sgd}
     if args.only and args.only != "resnet18":
         print(json.dumps({"only": args.only, **sides[args.only]()}), flush=True)
         return
@@ -499,6 +532,8 @@ def main():
         torch.cuda.empty_cache()
         rooflines.append(side_gemm())
         rooflines.append(side_ternarize())
+        torch.cuda.empty_cache()
+        rooflines.append(side_sgd())
         for name in ("lenet", "vgg7", "vgg16_ssd", "resnet18_bwd", "per_filter"):
             torch.cuda.empty_cache()
             extras[name] = sides[name]()

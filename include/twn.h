@@ -233,6 +233,32 @@ int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY
                            void* dX, float* dW, float* dbias, float dW_beta,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- 3. parameter update (Alg. 1 step 10; Sec. 2.4; Table 1) -----------------
+ * SGD with momentum and L2 weight decay on the float32 weights that are kept
+ * across iterations, with the gradient of twn_conv2d_bwd_ste (taken with respect
+ * to the ternary weights) applied to them unchanged:
+ *     g = dW[i] + weight_decay * W[i];  V[i] = momentum * V[i] + g;  W[i] -= lr * V[i]
+ * in float32, each line one fused multiply-add.  W, V (velocity, zero before the
+ * first step) and dW are device arrays of n floats, 16-byte aligned; W and V
+ * are updated in place, dW is only read.
+ * Fused with it is pass 1 of the next ternarization of this tensor as one
+ * group: the per-block float64 sums of |W[i]| after the update are left in
+ * `tern_workspace` (device memory, 8-byte aligned, at least
+ * twn_ternarize_workspace_bytes bytes: the workspace of the twn_ternarize call
+ * that follows), in the block partition and order twn_ternarize itself uses.
+ * twn_ternarize_presummed is twn_ternarize with groups = 1 that trusts those
+ * sums instead of reading W once more; its results are bit-identical to
+ * twn_ternarize's on the updated tensor.  It must be given the workspace of
+ * the twn_sgd_update call for the same W (n = rows*C*R*S), with no other use
+ * of that workspace in between.  tern_workspace may be NULL (no sums). */
+int32_t twn_sgd_update(float* W, float* V, const float* dW, int64_t n,
+                       float lr, float momentum, float weight_decay,
+                       void* tern_workspace, size_t workspace_bytes, void* stream);
+int32_t twn_ternarize_presummed(const float* W, const twn_weight_desc* wd, float delta_factor,
+                                uint32_t* packed, uint32_t* packed_T,
+                                float* delta, float* alpha, uint64_t* nnz,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

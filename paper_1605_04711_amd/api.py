@@ -27,6 +27,7 @@ EXPORTS = [
     "twn_gemm_fwd_workspace_bytes", "twn_gemm_fwd",
     "twn_conv2d_fwd_workspace_bytes", "twn_conv2d_fwd",
     "twn_conv2d_bwd_ste_workspace_bytes", "twn_conv2d_bwd_ste",
+    "twn_sgd_update", "twn_ternarize_presummed",
 ]
 
 
@@ -96,6 +97,10 @@ def lib():
         L.twn_ternarize_batch.argtypes = [ctypes.POINTER(TernarizeItem), i32, f32, vp, sz, vp]
         L.twn_unpack_i8.restype = i32
         L.twn_unpack_i8.argtypes = [vp, i32, i64, vp, vp]
+        L.twn_sgd_update.restype = i32
+        L.twn_sgd_update.argtypes = [vp, vp, vp, i64, f32, f32, f32, vp, sz, vp]
+        L.twn_ternarize_presummed.restype = i32
+        L.twn_ternarize_presummed.argtypes = [vp, ctypes.POINTER(WeightDesc), f32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.twn_gemm_fwd_workspace_bytes.restype = sz
         L.twn_gemm_fwd_workspace_bytes.argtypes = [ctypes.POINTER(GemmDesc)]
         L.twn_gemm_fwd.restype = i32
@@ -216,6 +221,32 @@ def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, wor
                          _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha), _ptr(out.nnz),
                          _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "twn_ternarize")
+    return out
+
+
+def twn_sgd_update(W, V, dW, lr, momentum=0.9, weight_decay=1e-4, tern_workspace=None, stream=None):
+    """In-place SGD step on the float32 weights W with velocity V and gradient dW (all contiguous float32 CUDA
+    tensors of one shape).  With `tern_workspace` (a uint8 tensor of twn_ternarize's workspace size) the pass-1 sums
+    of the next ternarization are left there for twn_ternarize(..., presummed=True)."""
+    for name, t in (("W", W), ("V", V), ("dW", dW)):
+        if not t.is_contiguous() or t.dtype != torch.float32 or not t.is_cuda or t.shape != W.shape:
+            raise TypeError("%s must be a contiguous float32 CUDA tensor of the shape of W" % name)
+    rc = lib().twn_sgd_update(_ptr(W), _ptr(V), _ptr(dW), W.numel(), ctypes.c_float(lr), ctypes.c_float(momentum),
+                              ctypes.c_float(weight_decay), _ptr(tern_workspace),
+                              tern_workspace.numel() if tern_workspace is not None else 0, _stream(stream))
+    _check(rc, "twn_sgd_update")
+
+
+def twn_ternarize_presummed(W, out, workspace, delta_factor=0.7, stream=None):
+    """twn_ternarize (one group) on the weights twn_sgd_update has just updated, using the sums it left in
+    `workspace`; `out` is a TernaryWeights with groups == 1."""
+    if not W.is_contiguous() or W.dtype != torch.float32 or not W.is_cuda:
+        raise TypeError("W must be a contiguous float32 CUDA tensor")
+    wd = WeightDesc(out.rows, out.C, out.R, out.S)
+    rc = lib().twn_ternarize_presummed(_ptr(W), ctypes.byref(wd), ctypes.c_float(delta_factor),
+                                       _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha),
+                                       _ptr(out.nnz), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "twn_ternarize_presummed")
     return out
 
 

@@ -582,14 +582,25 @@ static int32_t ternarize_check(const float* W, const twn_weight_desc* wd, int32_
     return TWN_OK;
 }
 
+// Blocks of pass 1 for a tensor of n weights (two persistent blocks per CU measured best with the prefetch);
+// the parameter update that leaves pass-1 sums behind uses the same partition.
+static int pass1_blocks(int64_t n) {
+    const int64_t nchunks = (n + kChunk - 1) / kChunk;
+    int want = env_int("TWN_TERN_BLOCKS", 512);
+    if (want < 1) want = 1;
+    if (want > kMaxBlocks) want = kMaxBlocks;
+    return static_cast<int>(nchunks < want ? nchunks : want);
+}
+
 // Launches of one ternarization; `workspace` is device memory of at least sizeof(TernWorkspace) bytes, either
 // the caller's (twn_ternarize) or the library's own per-device array (twn_ternarize_static).
 static int32_t ternarize_impl(const float* W, const twn_weight_desc* wd, int32_t groups,
                               float delta_factor, uint32_t* packed, uint32_t* packed_T,
                               float* delta, float* alpha, uint64_t* nnz,
-                              void* workspace, size_t workspace_bytes, void* stream) {
+                              void* workspace, size_t workspace_bytes, void* stream, bool presummed = false) {
     const int32_t rc = ternarize_check(W, wd, groups, delta_factor, packed, packed_T, delta, alpha, nnz);
     if (rc != TWN_OK) return rc;
+    if (presummed && groups != 1) return TWN_ERR_UNSUPPORTED;
     const int64_t RS = static_cast<int64_t>(wd->R) * wd->S;
     const int64_t K = RS * wd->C;
     const int64_t KT = RS * wd->rows;
@@ -603,12 +614,8 @@ static int32_t ternarize_impl(const float* W, const twn_weight_desc* wd, int32_t
 
     if (groups == 1) {
         TernWorkspace* ws = static_cast<TernWorkspace*>(workspace);
-        const int64_t nchunks = (n + kChunk - 1) / kChunk;
-        int want = env_int("TWN_TERN_BLOCKS", 512);   // two persistent blocks per CU measured best with the prefetch
-        if (want < 1) want = 1;
-        if (want > kMaxBlocks) want = kMaxBlocks;
-        const int nb = static_cast<int>(nchunks < want ? nchunks : want);
-        abs_sum_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1);
+        const int nb = pass1_blocks(n);
+        if (!presummed) abs_sum_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1);
         // matrices stream through the flat kernel; when the transposed copy is wanted too, the tile kernel
         // writes both from one read of W instead of a second, gathering pass
         const bool flat = (RS == 1) && (K % 128 == 0) && !(packed_T && tile_ok(wd->rows, wd->C, 1));
@@ -656,6 +663,107 @@ extern "C" int32_t twn_ternarize(const float* W, const twn_weight_desc* wd, int3
                                  void* workspace, size_t workspace_bytes, void* stream) {
     return ternarize_impl(W, wd, groups, delta_factor, packed, packed_T, delta, alpha, nnz, workspace, workspace_bytes,
                           stream);
+}
+
+// ---- parameter update fused with pass 1 of the next ternarization (Alg. 1 step 10; Sec. 2.4; Table 1) --------
+// One read of W, V, dW and one write of W, V per weight (20 bytes); the float64 sum of |W| after the update is
+// accumulated chunk by chunk and element by element exactly as abs_sum_body does it, so that the partial sums
+// (and with them Delta of the ternarization that follows) are bit-identical to a separate pass over the updated
+// tensor, which would cost 4 more bytes per weight.
+__global__ __launch_bounds__(kTernThreads) void sgd_update_kernel(float* __restrict__ W, float* __restrict__ V,
+                                                                  const float* __restrict__ dW, int64_t n, float lr,
+                                                                  float momentum, float wd, double* __restrict__ partial) {
+    __shared__ double scratch[16];
+    const int tid = threadIdx.x;
+    const int bid = blockIdx.x, nblk = gridDim.x;
+    const int64_t nfull = n / kChunk;
+    double acc = 0.0;
+    auto load4 = [&](const float* p, int64_t c, float4* v) {
+        const float4* src = reinterpret_cast<const float4*>(p + c * kChunk);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = src[j * kTernThreads + tid];
+    };
+    auto update = [&](float& w, float& v, float g) {
+        g = fmaf(wd, w, g);
+        v = fmaf(momentum, v, g);
+        w = fmaf(-lr, v, w);
+        acc += static_cast<double>(fabsf(w));
+    };
+    int64_t c = bid;
+    float4 w4[4], v4[4], g4[4];
+    if (c < nfull) {
+        load4(W, c, w4);
+        load4(V, c, v4);
+        load4(dW, c, g4);
+    }
+    while (c < nfull) {
+        const int64_t nx = c + nblk;
+        float4 wn[4], vn[4], gn[4];
+        if (nx < nfull) {
+            load4(W, nx, wn);
+            load4(V, nx, vn);
+            load4(dW, nx, gn);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            update(w4[j].x, v4[j].x, g4[j].x);
+            update(w4[j].y, v4[j].y, g4[j].y);
+            update(w4[j].z, v4[j].z, g4[j].z);
+            update(w4[j].w, v4[j].w, g4[j].w);
+        }
+        float4* wdst = reinterpret_cast<float4*>(W + c * kChunk);
+        float4* vdst = reinterpret_cast<float4*>(V + c * kChunk);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            wdst[j * kTernThreads + tid] = w4[j];
+            vdst[j * kTernThreads + tid] = v4[j];
+        }
+        if (nx < nfull) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                w4[j] = wn[j];
+                v4[j] = vn[j];
+                g4[j] = gn[j];
+            }
+        }
+        c = nx;
+    }
+    // ragged tail (at most one chunk), taken by the block abs_sum_body gives it to, in its element order
+    if (nfull * kChunk < n && static_cast<int64_t>(bid) == nfull % nblk) {
+        const int64_t base = nfull * kChunk;
+        for (int j = 0; j < 4; ++j)
+            for (int e = 0; e < 4; ++e) {
+                const int64_t idx = base + static_cast<int64_t>(j * kTernThreads + tid) * 4 + e;
+                if (idx < n) {
+                    float w = W[idx], v = V[idx];
+                    update(w, v, dW[idx]);
+                    W[idx] = w;
+                    V[idx] = v;
+                }
+            }
+    }
+    const double total = block_sum(acc, scratch);
+    if (partial && tid == 0) partial[bid] = total;
+}
+
+extern "C" int32_t twn_sgd_update(float* W, float* V, const float* dW, int64_t n, float lr, float momentum,
+                                  float weight_decay, void* tern_workspace, size_t workspace_bytes, void* stream) {
+    if (!W || !V || !dW) return TWN_ERR_NULL;
+    if (n <= 0 || n >= (1LL << 40)) return TWN_ERR_SHAPE;
+    if (!(lr == lr) || !(momentum == momentum) || !(weight_decay == weight_decay)) return TWN_ERR_SHAPE;
+    if (!aligned(W, 16) || !aligned(V, 16) || !aligned(dW, 16)) return TWN_ERR_ALIGN;
+    if (tern_workspace && (workspace_bytes < sizeof(TernWorkspace) || !aligned(tern_workspace, 8))) return TWN_ERR_WORKSPACE;
+    TernWorkspace* ws = static_cast<TernWorkspace*>(tern_workspace);
+    sgd_update_kernel<<<pass1_blocks(n), kTernThreads, 0, as_stream(stream)>>>(W, V, dW, n, lr, momentum, weight_decay,
+                                                                              ws ? ws->p1 : nullptr);
+    return launch_status();
+}
+
+extern "C" int32_t twn_ternarize_presummed(const float* W, const twn_weight_desc* wd, float delta_factor,
+                                           uint32_t* packed, uint32_t* packed_T, float* delta, float* alpha,
+                                           uint64_t* nnz, void* workspace, size_t workspace_bytes, void* stream) {
+    return ternarize_impl(W, wd, 1, delta_factor, packed, packed_T, delta, alpha, nnz, workspace, workspace_bytes, stream,
+                          true);
 }
 
 // ---- the entry point that allocates nothing -------------------------------------------------------------
