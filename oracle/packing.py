@@ -16,6 +16,13 @@ here from the format's definition, independently of the GPU code:
   00 -> 0, 01 -> +1, 11 -> -1; 10 is never written.
 * The transposed copy used by the backward-data pass has one row per input
   channel c and K_T = R*S*rows with k_T = (r*S + s)*rows + o.
+
+1-bit format of the sign codes of the binary-weight comparison (this library's own as well):
+
+* Same matrix view and row padding (a multiple of 128 weights: 4*ceil(K/128) words per row).
+* Word j of a row holds the 32 codes k = 32j .. 32j+31: the code of k = 32j + 2i sits in bit i, the code of
+  k = 32j + 2i + 1 in bit 16+i (i = 0..15): even-k codes in the low half-word, odd-k codes in the high one.
+* A bit is 1 for -1 and 0 for +1; padding bits are 0.
 """
 
 import numpy as np
@@ -97,3 +104,40 @@ def unpack_weights(packed, rows, c, r, s):
 def unpack_weights_t(packed_t, rows, c, r, s):
     m, bad, clean = unpack_matrix(packed_t, c, r * s * rows)
     return m.reshape(c, r, s, rows).transpose(3, 0, 1, 2).copy(), bad, clean
+
+
+def words_per_row1(k):
+    return 4 * ((int(k) + 127) // 128)
+
+
+def pack_matrix1(codes2d):
+    """Pack an int8 matrix [rows][K] of sign codes (-1 / +1) into uint32 [rows][words_per_row1]."""
+    codes2d = np.asarray(codes2d, dtype=np.int8)
+    rows, k = codes2d.shape
+    assert np.all((codes2d == 1) | (codes2d == -1))
+    wpr = words_per_row1(k)
+    neg = np.zeros((rows, wpr * 32), dtype=np.uint32)
+    neg[:, :k] = (codes2d < 0)
+    neg = neg.reshape(rows, wpr, 16, 2)                # [..., i, parity]
+    out = np.zeros((rows, wpr), dtype=np.uint32)
+    for i in range(16):
+        out |= neg[:, :, i, 0] << np.uint32(i)
+        out |= neg[:, :, i, 1] << np.uint32(16 + i)
+    return out
+
+
+def unpack_matrix1(packed, rows, k):
+    """Inverse of pack_matrix1; also reports whether every padding bit is zero."""
+    wpr = words_per_row1(k)
+    p = np.asarray(packed, dtype=np.uint32).reshape(rows, wpr)
+    bits = np.zeros((rows, wpr, 16, 2), dtype=np.uint32)
+    for i in range(16):
+        bits[:, :, i, 0] = (p >> np.uint32(i)) & np.uint32(1)
+        bits[:, :, i, 1] = (p >> np.uint32(16 + i)) & np.uint32(1)
+    bits = bits.reshape(rows, wpr * 32)
+    pad_clean = bool(np.all(bits[:, k:] == 0))
+    return np.where(bits[:, :k] == 1, np.int8(-1), np.int8(1)).astype(np.int8), pad_clean
+
+
+def pack_weights1(codes_oihw):
+    return pack_matrix1(to_matrix(codes_oihw))
