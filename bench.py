@@ -225,6 +225,13 @@ def main():
             for name, var in (("alpha_at_expansion_2bit", api.TWN_VAR_BF16_ALPHA_LDS),
                               ("int8_stored", api.TWN_VAR_I8_STORED_POSTSCALE)):
                 same[name] = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy, variant=var), reps=60, warm=20)
+            # the binary-weight comparison of Sec. 3: sign codes, one bit per weight, alpha = mean|W|
+            gbw = api.twn_binarize(gw)
+            same["sign_1bit (binary-weight comparison)"] = time_call(
+                lambda: api.twn_gemm_fwd(gx, gbw, out=gy, variant=api.TWN_VAR_BF16_SIGN1_POSTSCALE), reps=60, warm=20)
+            t_b = time_call(lambda: api.twn_binarize(gw), reps=30, warm=5)
+            log("twn_binarize of the 4096x4096 weights: %.1f us" % (t_b * 1e3))
+            res["binarize_4096x4096_us"] = round(t_b * 1e3, 1)
             for k, v in same.items():
                 log("gemm weight format %-24s %.1f us (register-staged 128x128 kernel)" % (k, v * 1e3))
             res["weight_formats_same_kernel_us"] = {k: round(v * 1e3, 1) for k, v in same.items()}
@@ -530,6 +537,7 @@ def main():
     rooflines = [h["roof"]]
     if not args.no_extras and not args.only:
         torch.cuda.empty_cache()
+        args.variants = True
         rooflines.append(side_gemm())
         rooflines.append(side_ternarize())
         torch.cuda.empty_cache()

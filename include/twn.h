@@ -72,7 +72,9 @@ typedef enum {
     TWN_VAR_I8_STORED_POSTSCALE = 2,/* comparison: weights stored as int8 {-1,0,1} [rows][K] (8 bits per weight, from
                                        twn_unpack_i8), bf16 MFMA, alpha afterwards.  Forward only; K % 8 == 0 and the
                                        weights 8-byte aligned, else TWN_ERR_UNSUPPORTED. */
-    TWN_VAR_FP32 = 3                /* float32 activations and outputs, vector-ALU FMAs with float64 running sums */
+    TWN_VAR_FP32 = 3,               /* float32 activations and outputs, vector-ALU FMAs with float64 running sums */
+    TWN_VAR_BF16_SIGN1_POSTSCALE = 4/* the binary-weight comparison of Sec. 3: 1-bit sign codes from twn_binarize
+                                       (twn1 format) -> exact bf16 +-1, bf16 MFMA, alpha afterwards.  Forward only. */
 } twn_variant;
 
 /* Filter bank [rows][C][R][S], float32, contiguous (fully-connected: R=S=1). */
@@ -232,6 +234,25 @@ int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY
                            const uint32_t* packed_T, const float* alpha,
                            void* dX, float* dW, float* dbias, float dW_beta,
                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- 1c. sign binarization of the binary-weight comparison (Sec. 3) ----------
+ * The counterpart the paper measures ternary weights against: codes are the
+ * sign of the weight (+1 for W >= 0, the zero included; -1 for W < 0) and the
+ * scale is alpha_g = (float)(sum|W_i| / n) per group, i.e. Eq. 5 with no weight
+ * set to zero.  Groups as in twn_ternarize.
+ * twn1 format: the matrix view of the twn2 format ([rows][K], k = (r*S+s)*C + c,
+ * rows padded to a multiple of 128 weights), one bit per weight, 1 = negative:
+ * word j of a row holds k = 32j .. 32j+31, the code of k = 32j+2i in bit i and
+ * that of k = 32j+2i+1 in bit 16+i (i = 0..15); padding bits are 0 (the
+ * contraction never multiplies them: activations beyond K read as zero).
+ * packed1: [rows][twn_packed1_words_per_row(R*S*C)], 16-byte aligned; alpha:
+ * float32[groups].  Workspace: device memory, 8-byte aligned, at least
+ * twn_binarize_workspace_bytes bytes. */
+int64_t twn_packed1_words_per_row(int64_t K);          /* host: 4 * ceil(K / 128) */
+size_t  twn_binarize_workspace_bytes(const twn_weight_desc* wd, int32_t groups);
+int32_t twn_binarize(const float* W, const twn_weight_desc* wd, int32_t groups,
+                     uint32_t* packed1, float* alpha,
+                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- 3. parameter update (Alg. 1 step 10; Sec. 2.4; Table 1) -----------------
  * SGD with momentum and L2 weight decay on the float32 weights that are kept

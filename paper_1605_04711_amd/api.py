@@ -15,6 +15,7 @@ import torch
 
 TWN_F32, TWN_BF16 = 0, 1
 TWN_VAR_BF16_POSTSCALE, TWN_VAR_BF16_ALPHA_LDS, TWN_VAR_I8_STORED_POSTSCALE, TWN_VAR_FP32 = 0, 1, 2, 3
+TWN_VAR_BF16_SIGN1_POSTSCALE = 4
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtwn.so")
 _lib = None
@@ -28,6 +29,7 @@ EXPORTS = [
     "twn_conv2d_fwd_workspace_bytes", "twn_conv2d_fwd",
     "twn_conv2d_bwd_ste_workspace_bytes", "twn_conv2d_bwd_ste",
     "twn_sgd_update", "twn_ternarize_presummed",
+    "twn_packed1_words_per_row", "twn_binarize_workspace_bytes", "twn_binarize",
 ]
 
 
@@ -97,6 +99,12 @@ def lib():
         L.twn_ternarize_batch.argtypes = [ctypes.POINTER(TernarizeItem), i32, f32, vp, sz, vp]
         L.twn_unpack_i8.restype = i32
         L.twn_unpack_i8.argtypes = [vp, i32, i64, vp, vp]
+        L.twn_packed1_words_per_row.restype = i64
+        L.twn_packed1_words_per_row.argtypes = [i64]
+        L.twn_binarize_workspace_bytes.restype = sz
+        L.twn_binarize_workspace_bytes.argtypes = [ctypes.POINTER(WeightDesc), i32]
+        L.twn_binarize.restype = i32
+        L.twn_binarize.argtypes = [vp, ctypes.POINTER(WeightDesc), i32, vp, vp, vp, sz, vp]
         L.twn_sgd_update.restype = i32
         L.twn_sgd_update.argtypes = [vp, vp, vp, i64, f32, f32, f32, vp, sz, vp]
         L.twn_ternarize_presummed.restype = i32
@@ -188,6 +196,8 @@ class TernaryWeights:
 
     def weights_for(self, variant):
         """Device tensor a forward call reads as its `weights` argument."""
+        if variant == TWN_VAR_BF16_SIGN1_POSTSCALE:
+            raise ValueError("TWN_VAR_BF16_SIGN1_POSTSCALE reads the 1-bit codes of twn_binarize")
         if variant != TWN_VAR_I8_STORED_POSTSCALE:
             return self.packed
         if self.codes_i8 is None:
@@ -221,6 +231,50 @@ def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, wor
                          _ptr(out.packed), _ptr(out.packed_T), _ptr(out.delta), _ptr(out.alpha), _ptr(out.nnz),
                          _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "twn_ternarize")
+    return out
+
+
+@dataclass
+class BinaryWeights:
+    """Device-resident result of twn_binarize: 1-bit sign codes and the scale(s) of the binary-weight comparison.
+    Passed to the forward calls with variant=TWN_VAR_BF16_SIGN1_POSTSCALE."""
+    rows: int
+    C: int
+    R: int
+    S: int
+    groups: int
+    packed: torch.Tensor                 # uint32 viewed as int32 [rows][packed1_words_per_row(R*S*C)]
+    alpha: torch.Tensor                  # float32 [groups]
+
+    @property
+    def K(self):
+        return self.R * self.S * self.C
+
+    def weights_for(self, variant):
+        if variant != TWN_VAR_BF16_SIGN1_POSTSCALE:
+            raise ValueError("sign codes are read by TWN_VAR_BF16_SIGN1_POSTSCALE only")
+        return self.packed
+
+
+def twn_binarize(W, groups=1, workspace=None, stream=None):
+    """Sign codes and alpha = mean|W| per group of a float32 CUDA tensor [rows][C][R][S] (or [rows][K])."""
+    if W.dim() == 2:
+        rows, c = W.shape
+        r = s = 1
+    else:
+        rows, c, r, s = W.shape
+    if not W.is_contiguous() or W.dtype != torch.float32 or not W.is_cuda:
+        raise TypeError("W must be a contiguous float32 CUDA tensor")
+    L = lib()
+    wd = WeightDesc(rows, c, r, s)
+    out = BinaryWeights(rows, c, r, s, groups,
+                        torch.empty((rows, int(L.twn_packed1_words_per_row(r * s * c))), dtype=torch.int32, device=W.device),
+                        torch.empty(groups, dtype=torch.float32, device=W.device))
+    if workspace is None:
+        workspace = _workspace(L.twn_binarize_workspace_bytes(ctypes.byref(wd), groups), W.device, stream)
+    rc = L.twn_binarize(_ptr(W), ctypes.byref(wd), groups, _ptr(out.packed), _ptr(out.alpha), _ptr(workspace),
+                        workspace.numel(), _stream(stream))
+    _check(rc, "twn_binarize")
     return out
 
 

@@ -33,6 +33,11 @@ extern "C" int64_t twn_packed_words_per_row(int64_t K) {
     return 8 * ((K + 127) / 128);
 }
 
+extern "C" int64_t twn_packed1_words_per_row(int64_t K) {
+    if (K <= 0) return 0;
+    return 4 * ((K + 127) / 128);
+}
+
 extern "C" size_t twn_packed_bytes(int32_t rows, int64_t K) {
     if (rows <= 0 || K <= 0) return 0;
     return static_cast<size_t>(rows) * static_cast<size_t>(twn_packed_words_per_row(K)) * 4u;

@@ -39,7 +39,8 @@ int32_t check_variant(int32_t variant, int32_t x_dtype) {
         case TWN_VAR_BF16_POSTSCALE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         case TWN_VAR_FP32: return x_dtype == TWN_F32 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         case TWN_VAR_BF16_ALPHA_LDS:
-        case TWN_VAR_I8_STORED_POSTSCALE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
+        case TWN_VAR_I8_STORED_POSTSCALE:
+        case TWN_VAR_BF16_SIGN1_POSTSCALE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         default: return TWN_ERR_UNSUPPORTED;
     }
 }
@@ -72,6 +73,10 @@ int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_b
     if (variant == TWN_VAR_FP32) return launch_gather_gemm_fp32(g, st);
     if (variant != TWN_VAR_BF16_POSTSCALE) {
         if (variant == TWN_VAR_I8_STORED_POSTSCALE && (g.K % 8 != 0 || !aligned(g.Wq, 8))) return TWN_ERR_UNSUPPORTED;
+        if (variant == TWN_VAR_BF16_SIGN1_POSTSCALE) {
+            if (!aligned(g.Wq, 16)) return TWN_ERR_ALIGN;
+            g.wpr = static_cast<int32_t>(twn_packed1_words_per_row(g.K));    // 1-bit rows
+        }
         g.splits = 1;
         g.partial = nullptr;
         return launch_gather_gemm_mfma(g, variant, st);

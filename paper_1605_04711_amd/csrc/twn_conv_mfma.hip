@@ -30,8 +30,9 @@ enum { kModeGemm = 0, kModeVec8 = 1, kModeScalar = 2 };
 
 // Weight operand formats.  kFmtPacked is the product path; the other two exist to be measured against it:
 // kFmtAlpha builds the paper's operand alpha*W~ itself (bf16 {-alpha, 0, +alpha}, alpha rounded to bf16)
-// at expansion time instead of scaling the fp32 sum, kFmtInt8 reads weights stored one int8 per weight.
-enum { kFmtPacked = 0, kFmtAlpha = 1, kFmtInt8 = 2 };
+// at expansion time instead of scaling the fp32 sum, kFmtInt8 reads weights stored one int8 per weight,
+// kFmtSign1 reads the 1-bit sign codes of the binary-weight comparison (Sec. 3) and expands them to +-1.
+enum { kFmtPacked = 0, kFmtAlpha = 1, kFmtInt8 = 2, kFmtSign1 = 3 };
 
 template <int BM, int BN, int WM, int WN, int MODE, int BFMT>
 __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const GatherGemm g) {
@@ -185,6 +186,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
                     const int k = kt * 64 + lh * 32 + kk * 8;   // the k range of this lane's A fragment at step kk
                     dst[ni][kk] = (ncol < g.NC && k < g.K) ? *reinterpret_cast<const u32x2*>(wrow + k) : u32x2{0, 0};
                 }
+            } else if (BFMT == kFmtSign1) {
+                // two words per row and slab; this lane's half of the slab (k = lh*32 .. +31) is one of them
+                dst[ni][0] = u32x2{(ncol < g.NC) ? Wq[static_cast<int64_t>(ncol) * g.wpr + kt * 2 + lh] : 0u, 0u};
             } else {
                 dst[ni][0] = (ncol < g.NC)
                                  ? *reinterpret_cast<const u32x2*>(Wq + static_cast<int64_t>(ncol) * g.wpr + kt * 4 + 2 * lh)
@@ -214,6 +218,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
                 b[2 * h] = __builtin_amdgcn_perm(0u, y, 0x010C000Cu);       // [0, y.b0, 0, y.b1]
                 b[2 * h + 1] = __builtin_amdgcn_perm(0u, y, 0x030C020Cu);   // [0, y.b2, 0, y.b3]
             }
+        } else if (BFMT == kFmtSign1) {
+            // weights k = 8*kk + 2r (bit 4*kk + r) and 8*kk + 2r + 1 (bit 16 + 4*kk + r): sign bits onto bf16 1.0
+            const uint32_t word = breg[ni][0][0];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) b[r] = ((word << (15 - (kk * 4 + r))) & 0x80008000u) | 0x3F803F80u;
         } else {
             const uint32_t word = breg[ni][0][kk >> 1];
 #pragma unroll
@@ -292,7 +301,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gather_gemm_mfma_kernel(const Ga
         const int ncol = n0 + wn * TN + ni * 32 + lrow;
         if (ncol >= g.NC) continue;
         // codes were expanded to +-2 (or, for kFmtAlpha, to +-alpha already)
-        const float al = (BFMT == kFmtAlpha) ? 1.0f : 0.5f * g.alpha[ncol / g.rows_per_group];
+        const float al = (BFMT == kFmtAlpha) ? 1.0f : (BFMT == kFmtSign1 ? 1.0f : 0.5f) * g.alpha[ncol / g.rows_per_group];
         const float sc = g.scale ? g.scale[ncol] : 1.0f;
         const float sf = g.shift ? g.shift[ncol] : 0.0f;
 #pragma unroll
@@ -515,6 +524,7 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
         if (g.K % 8 != 0) return TWN_ERR_UNSUPPORTED;
         return launch_tile<128, 128, 2, 2, kFmtInt8>(g, mode, st);
     }
+    if (variant == TWN_VAR_BF16_SIGN1_POSTSCALE) return launch_tile<128, 128, 2, 2, kFmtSign1>(g, mode, st);
     if (variant != TWN_VAR_BF16_POSTSCALE) return TWN_ERR_UNSUPPORTED;
 
     // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.

@@ -502,6 +502,49 @@ __global__ __launch_bounds__(kTernThreads) void group_stats_kernel(
     }
 }
 
+// ---- sign binarization of the binary-weight comparison (Sec. 3) ------------------------------------------
+// alpha of one group per block (float64 sum in a fixed order); used for several groups, where a group is small.
+__global__ __launch_bounds__(kTernThreads) void group_abs_mean_kernel(const float* __restrict__ W, int64_t n_per_group,
+                                                                      float* __restrict__ alpha) {
+    __shared__ double scratch[16];
+    const float* seg = W + static_cast<int64_t>(blockIdx.x) * n_per_group;
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < n_per_group; i += blockDim.x) acc += static_cast<double>(fabsf(seg[i]));
+    const double s1 = block_sum(acc, scratch);
+    if (threadIdx.x == 0) alpha[blockIdx.x] = static_cast<float>(s1 / static_cast<double>(n_per_group));
+}
+
+// alpha of a whole tensor from the pass-1 partial sums of abs_sum_kernel (one block).
+__global__ __launch_bounds__(kTernThreads) void abs_mean_finalize_kernel(const double* __restrict__ p1, int nb1, int64_t n,
+                                                                         float* __restrict__ alpha) {
+    __shared__ double scratch[16];
+    double acc = 0.0;
+    for (int i = threadIdx.x; i < nb1; i += blockDim.x) acc += p1[i];
+    const double s1 = block_sum(acc, scratch);
+    if (threadIdx.x == 0) alpha[0] = static_cast<float>(s1 / static_cast<double>(n));
+}
+
+// 1-bit sign codes, one thread per output word (32 weights): k = (r*S+s)*C + c of filter `row`.
+__global__ __launch_bounds__(256) void sign_pack_kernel(const float* __restrict__ W, int rows, int C, int RS,
+                                                        uint32_t* __restrict__ out, int wpr) {
+    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (id >= static_cast<int64_t>(rows) * wpr) return;
+    const int row = static_cast<int>(id / wpr), j = static_cast<int>(id % wpr);
+    const int64_t K = static_cast<int64_t>(RS) * C;
+    uint32_t word = 0;
+#pragma unroll 8
+    for (int t = 0; t < 32; ++t) {
+        const int64_t k = static_cast<int64_t>(j) * 32 + t;
+        if (k < K) {
+            const int rs = static_cast<int>(k / C);
+            const int c = static_cast<int>(k - static_cast<int64_t>(rs) * C);
+            const float w = W[(static_cast<int64_t>(row) * C + c) * RS + rs];
+            word |= (w < 0.0f ? 1u : 0u) << ((t & 1) * 16 + (t >> 1));
+        }
+    }
+    out[id] = word;
+}
+
 // Codes for any layout.  One thread per output word.
 //   normal:     out row = filter o,        k   = (r*S+s)*C + c
 //   transposed: out row = input channel c, k_T = (r*S+s)*rows + o
@@ -764,6 +807,39 @@ extern "C" int32_t twn_ternarize_presummed(const float* W, const twn_weight_desc
                                            uint64_t* nnz, void* workspace, size_t workspace_bytes, void* stream) {
     return ternarize_impl(W, wd, 1, delta_factor, packed, packed_T, delta, alpha, nnz, workspace, workspace_bytes, stream,
                           true);
+}
+
+extern "C" size_t twn_binarize_workspace_bytes(const twn_weight_desc* wd, int32_t groups) {
+    (void)groups;
+    if (!wd) return 0;
+    return sizeof(TernWorkspace);
+}
+
+extern "C" int32_t twn_binarize(const float* W, const twn_weight_desc* wd, int32_t groups, uint32_t* packed1,
+                                float* alpha, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!W || !wd || !packed1 || !alpha) return TWN_ERR_NULL;
+    if (wd->rows <= 0 || wd->C <= 0 || wd->R <= 0 || wd->S <= 0) return TWN_ERR_SHAPE;
+    if (groups < 1 || wd->rows % groups != 0) return TWN_ERR_SHAPE;
+    const int64_t RS = static_cast<int64_t>(wd->R) * wd->S;
+    const int64_t K = RS * wd->C;
+    const int64_t n = K * wd->rows;
+    if (RS > (1 << 15) || K >= (1LL << 31) || n >= (1LL << 40)) return TWN_ERR_SHAPE;
+    if (!aligned(W, 16) || !aligned(packed1, 16)) return TWN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < sizeof(TernWorkspace) || !aligned(workspace, 8)) return TWN_ERR_WORKSPACE;
+    hipStream_t st = as_stream(stream);
+    if (groups == 1) {
+        TernWorkspace* ws = static_cast<TernWorkspace*>(workspace);
+        const int nb = pass1_blocks(n);
+        abs_sum_kernel<<<nb, kTernThreads, 0, st>>>(W, n, ws->p1);
+        abs_mean_finalize_kernel<<<1, kTernThreads, 0, st>>>(ws->p1, nb, n, alpha);
+    } else {
+        group_abs_mean_kernel<<<groups, kTernThreads, 0, st>>>(W, n / groups, alpha);
+    }
+    const int wpr = static_cast<int>(twn_packed1_words_per_row(K));
+    const int64_t words = static_cast<int64_t>(wd->rows) * wpr;
+    sign_pack_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(W, wd->rows, wd->C, static_cast<int>(RS),
+                                                                                  packed1, wpr);
+    return launch_status();
 }
 
 // ---- the entry point that allocates nothing -------------------------------------------------------------
