@@ -524,6 +524,22 @@ __global__ __launch_bounds__(kTernThreads) void abs_mean_finalize_kernel(const d
     if (threadIdx.x == 0) alpha[0] = static_cast<float>(s1 / static_cast<double>(n));
 }
 
+// 1-bit sign codes of a matrix whose rows need no padding (K % 128 == 0): a wave takes 64 consecutive weights
+// per step, lane l reading the weight whose code lands in bit l of the two output words (even k first, then
+// odd k, per word), so that the wave's ballot is the pair of words.
+__global__ __launch_bounds__(256) void sign_pack_flat_kernel(const float* __restrict__ W, int64_t npairs,
+                                                             uint64_t* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
+    const int64_t nwaves = (static_cast<int64_t>(gridDim.x) * blockDim.x) >> 6;
+    const int l = lane & 31;
+    const int koff = (lane >> 5) * 32 + (l < 16 ? 2 * l : 2 * (l - 16) + 1);
+    for (int64_t p = wave; p < npairs; p += nwaves) {
+        const unsigned long long m = __ballot(W[p * 64 + koff] < 0.0f);
+        if (lane == 0) out[p] = m;
+    }
+}
+
 // 1-bit sign codes, one thread per output word (32 weights): k = (r*S+s)*C + c of filter `row`.
 __global__ __launch_bounds__(256) void sign_pack_kernel(const float* __restrict__ W, int rows, int C, int RS,
                                                         uint32_t* __restrict__ out, int wpr) {
@@ -837,8 +853,14 @@ extern "C" int32_t twn_binarize(const float* W, const twn_weight_desc* wd, int32
     }
     const int wpr = static_cast<int>(twn_packed1_words_per_row(K));
     const int64_t words = static_cast<int64_t>(wd->rows) * wpr;
-    sign_pack_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(W, wd->rows, wd->C, static_cast<int>(RS),
-                                                                                  packed1, wpr);
+    if (RS == 1 && K % 128 == 0) {
+        const int64_t npairs = n / 64;
+        const int64_t blocks = (npairs + 3) / 4 < 4096 ? (npairs + 3) / 4 : 4096;
+        sign_pack_flat_kernel<<<static_cast<unsigned>(blocks), 256, 0, st>>>(W, npairs, reinterpret_cast<uint64_t*>(packed1));
+    } else {
+        sign_pack_kernel<<<static_cast<unsigned>((words + 255) / 256), 256, 0, st>>>(W, wd->rows, wd->C,
+                                                                                      static_cast<int>(RS), packed1, wpr);
+    }
     return launch_status();
 }
 
