@@ -220,8 +220,10 @@ def main():
                        flops_per_launch=g.flops)
         if args.variants:
             os.environ["TWN_TILE"] = "4"
+            api.reload_env()
             same = {"postscale_2bit": time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy), reps=60, warm=20)}
             del os.environ["TWN_TILE"]
+            api.reload_env()
             for name, var in (("alpha_at_expansion_2bit", api.TWN_VAR_BF16_ALPHA_LDS),
                               ("int8_stored", api.TWN_VAR_I8_STORED_POSTSCALE)):
                 same[name] = time_call(lambda: api.twn_gemm_fwd(gx, gtw, out=gy, variant=var), reps=60, warm=20)
@@ -261,8 +263,10 @@ def main():
             res["hbm_side_frac"] = round(res["traffic"] / t / 1e6 / PEAK_HBM_GBPS, 4)
         # the same call with pass 2 walking forwards (nothing of pass 1 left in the cache): all 8.25 B/weight from HBM
         os.environ["TWN_TERN_REVERSE"] = "0"
+        api.reload_env()
         t_fwd = time_call(lambda: api.twn_ternarize(big, F, out=btw, workspace=ws), reps=50, warm=10)
         del os.environ["TWN_TERN_REVERSE"]
+        api.reload_env()
         res["forward_walk_us"] = round(t_fwd * 1e3, 1)
         res["forward_walk_GBps"] = round(nbytes / t_fwd / 1e6, 1)
         log("ternarize 2^28: %.1f us, %.1f GB/s algorithmic (8.25 B/weight); forward-walking pass 2: %.1f us, %.1f GB/s"

@@ -116,6 +116,11 @@ typedef struct {
 } twn_epilogue;
 
 const char* twn_status_str(int32_t status);   /* host; static string */
+/* The library's tuning overrides (environment variables TWN_*: tile and kernel
+ * choices for sweeps, none needed for normal use) are read once each, at their
+ * first use.  A process that changes one afterwards calls twn_reload_env to
+ * have it read again (host; thread-safe against launches on other threads). */
+void twn_reload_env(void);
 int32_t twn_abi_version(void);                 /* host */
 
 /* ---- packed format helpers (host, pure) --------------------------------- */

@@ -21,7 +21,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtwn.so"
 _lib = None
 
 EXPORTS = [
-    "twn_status_str", "twn_abi_version", "twn_packed_words_per_row", "twn_packed_bytes",
+    "twn_status_str", "twn_reload_env", "twn_abi_version", "twn_packed_words_per_row", "twn_packed_bytes",
     "twn_ternarize_workspace_bytes", "twn_ternarize", "twn_ternarize_static_scratch_bytes", "twn_ternarize_static",
     "twn_ternarize_batch_workspace_bytes", "twn_ternarize_batch",
     "twn_unpack_i8",
@@ -99,6 +99,8 @@ def lib():
         L.twn_ternarize_batch.argtypes = [ctypes.POINTER(TernarizeItem), i32, f32, vp, sz, vp]
         L.twn_unpack_i8.restype = i32
         L.twn_unpack_i8.argtypes = [vp, i32, i64, vp, vp]
+        L.twn_reload_env.restype = None
+        L.twn_reload_env.argtypes = []
         L.twn_packed1_words_per_row.restype = i64
         L.twn_packed1_words_per_row.argtypes = [i64]
         L.twn_binarize_workspace_bytes.restype = sz
@@ -232,6 +234,11 @@ def twn_ternarize(W, delta_factor=0.7, groups=1, transposed=False, out=None, wor
                          _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "twn_ternarize")
     return out
+
+
+def reload_env():
+    """Have the library read its TWN_* tuning overrides again (they are read once and remembered)."""
+    lib().twn_reload_env()
 
 
 @dataclass

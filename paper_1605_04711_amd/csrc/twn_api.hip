@@ -1,17 +1,43 @@
 // Host-only helpers of the C ABI: status strings, packed-format sizes, env overrides.
 #include <cstdlib>
+#include <cstring>
+#include <mutex>
 
 #include "twn_common.h"
 
 namespace twn {
 
+// The TWN_* tuning knobs are read from the environment once each and remembered: launches do not call getenv
+// (which is neither free nor safe against a concurrent setenv).  twn_reload_env forgets what was read.
+namespace {
+struct EnvEntry {
+    const char* name;     // the caller's string literal
+    bool set;
+    int value;
+};
+constexpr int kEnvMax = 64;
+std::mutex g_env_mutex;
+EnvEntry g_env[kEnvMax];
+int g_env_count = 0;
+}  // namespace
+
 int env_int(const char* name, int fallback) {
+    std::lock_guard<std::mutex> lock(g_env_mutex);
+    for (int i = 0; i < g_env_count; ++i)
+        if (g_env[i].name == name || std::strcmp(g_env[i].name, name) == 0) return g_env[i].set ? g_env[i].value : fallback;
     const char* v = std::getenv(name);
-    if (!v || !*v) return fallback;
-    return std::atoi(v);
+    const bool set = v && *v;
+    const int value = set ? std::atoi(v) : 0;
+    if (g_env_count < kEnvMax) g_env[g_env_count++] = EnvEntry{name, set, value};
+    return set ? value : fallback;
 }
 
 }  // namespace twn
+
+extern "C" void twn_reload_env(void) {
+    std::lock_guard<std::mutex> lock(twn::g_env_mutex);
+    twn::g_env_count = 0;
+}
 
 extern "C" const char* twn_status_str(int32_t status) {
     switch (status) {

@@ -471,6 +471,7 @@ int32_t launch_zero_fill(void* p, int64_t bytes, hipStream_t st) {
 int32_t launch_pad_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp,
                       uint16_t* Xp, hipStream_t st) {
     const int64_t total = static_cast<int64_t>(N) * Hp * Wp;
+    if (total <= 0 || (total + 255) / 256 >= (1LL << 31)) return TWN_ERR_SHAPE;
     pad_c4_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(X, N, H, W, C, ph, pw, Hp, Wp, Xp);
     return launch_status();
 }
@@ -529,7 +530,6 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
 
     // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.
     int tile = env_int("TWN_TILE", 0);
-    if (mode != kModeScalar && tile == 0 && conv_halo_applicable(g)) return launch_conv_halo(g, st);
     if (mode != kModeScalar && (tile == 0 || tile > 10)) {
         // multi-stage direct-to-LDS kernel
         if (tile == 0) {

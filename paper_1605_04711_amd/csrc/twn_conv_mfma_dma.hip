@@ -16,6 +16,8 @@
 //     block instead, so padding costs no branches and slabs past the end of K
 //     are harmless zero loads that keep the outstanding-load count constant.
 #include "twn_agpr_tiles.h"
+#include <mutex>
+
 #include "twn_kernels.h"
 #include "twn_lds_asm.h"
 #include "twn_mfma.h"
@@ -638,13 +640,14 @@ static int32_t launch_dma_kernel_b(const DmaArgs& a, int64_t blocks, hipStream_t
     constexpr int SMEM = STAGES * (BM * 128 + BN * 16);
     static_assert(SMEM <= 160 * 1024, "LDS budget");
     // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    static bool allowed = false;
     auto k = gather_gemm_dma_kernel<BM, BN, WM, WN, STAGES, GEMM, SPLITK, BUF, OCC>;
-    if (!allowed) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                SMEM) != hipSuccess) return TWN_ERR_HIP;
-        allowed = true;
-    }
+    static std::once_flag once;
+    static bool allowed = false;
+    std::call_once(once, [&] {
+        allowed = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      SMEM) == hipSuccess;
+    });
+    if (!allowed) return TWN_ERR_HIP;
     k<<<dim3(static_cast<unsigned>(blocks), SPLITK ? a.g.splits : 1), dim3(64 * WM * WN), SMEM, st>>>(a);
     return launch_status();
 }

@@ -95,10 +95,6 @@ struct FirstLayer {
 bool conv_first_applicable(const FirstLayer& f);
 int32_t launch_conv_first(const FirstLayer& f, hipStream_t st);
 
-// Halo-tiled kernel for stride-1 filters with several taps (activations staged once per 64-channel slab and
-// reused by every tap); `applicable` is a pure function of the problem.
-bool conv_halo_applicable(const GatherGemm& g);
-int32_t launch_conv_halo(const GatherGemm& g, hipStream_t st);
 
 // dW[o][c][r][s] = beta*dW + sum_{n,p,q} X[n,ih,iw,c] * dY[n,p,q,o]; dbias[o] = sum dY.
 struct WeightGrad {

@@ -17,3 +17,18 @@ def oracle_lib():
     from oracle import conv
     conv.build()
     return conv
+
+
+@pytest.fixture
+def knob(monkeypatch):
+    """Set one of the library's TWN_* tuning overrides for the rest of the test: the library reads them once, so
+    it is told to read them again after the change and after the change is undone."""
+    from paper_1605_04711_amd import api
+
+    def set_knob(name, value):
+        monkeypatch.setenv(name, str(value))
+        api.reload_env()
+
+    yield set_knob
+    monkeypatch.undo()
+    api.reload_env()

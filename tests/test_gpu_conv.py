@@ -48,8 +48,8 @@ def test_gemm_fwd_bf16(m, n, k):
 
 
 @pytest.mark.parametrize("tile", [1, 2, 3, 4, 5, 6])
-def test_gemm_fwd_every_tile_shape(tile, monkeypatch):
-    monkeypatch.setenv("TWN_TILE", str(tile))
+def test_gemm_fwd_every_tile_shape(tile, knob):
+    knob("TWN_TILE", str(tile))
     m, n, k = 520, 300, 448
     x, w, tw, codes, alpha = make_layer(tile, (m, k), (n, k))
     y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
@@ -61,9 +61,9 @@ DMA_TILES = [12, 14, 15, 16, 17, 24, 30]
 
 
 @pytest.mark.parametrize("tile", DMA_TILES)
-def test_every_direct_to_lds_tile_shape(tile, monkeypatch):
+def test_every_direct_to_lds_tile_shape(tile, knob):
     # every instantiated tile of the direct-to-LDS kernel: a ragged GEMM and a padded, strided convolution
-    monkeypatch.setenv("TWN_TILE", str(tile))
+    knob("TWN_TILE", str(tile))
     m, n, k = 520, 300, 448
     x, w, tw, codes, alpha = make_layer(tile, (m, k), (n, k))
     y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
@@ -75,10 +75,10 @@ def test_every_direct_to_lds_tile_shape(tile, monkeypatch):
 
 
 @pytest.mark.parametrize("tile", [30])
-def test_pinned_accumulator_tiles(tile, monkeypatch):
+def test_pinned_accumulator_tiles(tile, knob):
     # the 256x256 tiles keep their 16 accumulator tiles per wave in hand-assigned registers: both load paths
     # (K and channel counts that are / are not multiples of 64), both epilogues, and backward-data
-    monkeypatch.setenv("TWN_TILE", str(tile))
+    knob("TWN_TILE", str(tile))
     for seed, (m, n, k) in enumerate([(520, 600, 448), (300, 257, 440), (1100, 512, 1024)]):
         x, w, tw, codes, alpha = make_layer(300 + seed, (m, k), (n, k))
         ref = oc.gemm_fwd(x, codes.reshape(n, k), alpha)
@@ -111,8 +111,8 @@ def test_pinned_accumulator_tiles(tile, monkeypatch):
         assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, (nb, h, w_, c), st, pd, dl)) <= 1e-4
 
 
-HALO_CASES = [
-    # N  H   W   C    O    R  S  pad     dil      (stride 1: the halo-tiled kernel's domain)
+STRIDE1_CASES = [
+    # N  H   W   C    O    R  S  pad     dil      (stride 1, several taps, channels in whole 64-wide slabs)
     (3, 17, 17, 64, 128, 3, 3, (1, 1), (1, 1)),
     (5, 8, 8, 128, 72, 3, 3, (1, 1), (1, 1)),
     (2, 20, 33, 64, 64, 3, 3, (0, 2), (1, 1)),
@@ -122,12 +122,9 @@ HALO_CASES = [
 ]
 
 
-@pytest.mark.parametrize("shape", ["0", "1"])
-@pytest.mark.parametrize("ci", range(len(HALO_CASES)))
-def test_halo_tiled_kernel_forward_and_backward_data(ci, shape, monkeypatch):
-    monkeypatch.setenv("TWN_HALO", "1")
-    monkeypatch.setenv("TWN_HALO_SHAPE", shape)      # 1: 256-pixel patches with 32-channel slabs
-    n, h, w_, c, o, r, s, pd, dl = HALO_CASES[ci]
+@pytest.mark.parametrize("ci", range(len(STRIDE1_CASES)))
+def test_stride1_multi_tap_layers_forward_and_backward_data(ci):
+    n, h, w_, c, o, r, s, pd, dl = STRIDE1_CASES[ci]
     st = (1, 1)
     x, w, tw, codes, alpha = make_layer(600 + ci, (n, h, w_, c), (o, c, r, s), transposed=True)
     g = np.random.default_rng(ci)
@@ -490,10 +487,10 @@ def test_library_calls_capture_into_a_graph_and_replay():
             assert torch.equal(a, b)
 
 
-def test_per_lane_pointer_load_path(monkeypatch):
+def test_per_lane_pointer_load_path(knob):
     # tensors of 2 GiB and more cannot use buffer descriptors and fall back to per-lane pointers; the switch
     # that forces that path keeps it covered at test sizes: GEMM, convolution, both gradients
-    monkeypatch.setenv("TWN_BUFLOAD", "0")
+    knob("TWN_BUFLOAD", "0")
     m, n, k = 520, 300, 448
     x, w, tw, codes, alpha = make_layer(41, (m, k), (n, k))
     y = api.twn_gemm_fwd(to_dev_bf16(x), tw, y_dtype=torch.float32)
@@ -548,7 +545,7 @@ STRIDED_DX_CASES = [
 
 
 @pytest.mark.parametrize("ci", range(len(STRIDED_DX_CASES)))
-def test_strided_backward_data_by_residue_classes(ci, monkeypatch):
+def test_strided_backward_data_by_residue_classes(ci, knob):
     # strided layers run one stride-1 contraction per residue class of the output pixels (forced here for
     # small shapes); both output types, and the generic divided gather as a cross-check
     n, h, w_, c, o, r, s, st, pd = STRIDED_DX_CASES[ci]
@@ -557,13 +554,13 @@ def test_strided_backward_data_by_residue_classes(ci, monkeypatch):
     p, q = oc.out_size(h, r, st[0], pd[0], 1), oc.out_size(w_, s, st[1], pd[1], 1)
     dy = wl.bf16_round(np.random.default_rng(710 + ci).standard_normal((n, p, q, o)).astype(np.float32))
     ref = oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)
-    monkeypatch.setenv("TWN_DX_CLASS_MIN_PIXELS", "0")
+    knob("TWN_DX_CLASS_MIN_PIXELS", "0")
     dx32, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape,
                                         dx_dtype=torch.float32)
     assert rel_err(to_host_f64(dx32), ref) <= 1e-4
     dxb, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape)
     assert rel_err(to_host_f64(dxb), ref) <= BF16_TOL
-    monkeypatch.setenv("TWN_DX_CLASSES", "0")
+    knob("TWN_DX_CLASSES", "0")
     dxg, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape,
                                        dx_dtype=torch.float32)
     assert rel_err(to_host_f64(dxg), ref) <= 1e-4
@@ -649,12 +646,12 @@ def test_first_layer_kernel(ci):
     assert rel_err(to_host_f64(y2), oc.epilogue(ref0, scale, shift, res, relu=True)) <= BF16_TOL
 
 
-def test_first_layer_kernel_matches_generic_path(monkeypatch):
+def test_first_layer_kernel_matches_generic_path(knob):
     # the same call through the generic small-C path (padded copy + re-ordered codes): both round once from fp32
     n, h, w_, o, r, s, st, pd = FIRST_LAYER_CASES[0]
     x, w, tw, codes, alpha = make_layer(850, (n, h, w_, 3), (o, 3, r, s))
     y1 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, (1, 1))
-    monkeypatch.setenv("TWN_FIRST", "0")
+    knob("TWN_FIRST", "0")
     y0 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, (1, 1))
     ref = oc.conv2d_fwd(x, codes, alpha, st, pd, (1, 1))
     assert rel_err(to_host_f64(y0), ref) <= BF16_TOL and rel_err(to_host_f64(y1), ref) <= BF16_TOL
