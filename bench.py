@@ -388,16 +388,29 @@ def main():
         layers = wl.resnet18(64)
         t_tern = 0.0
         t_fwd = 0.0
+        t_dx = 0.0
         for li, L in enumerate(layers):
+            st, pd, dl = geo(L)
             w = torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev)
-            tw = api.twn_ternarize(w, F, groups=L.O)
+            tw = api.twn_ternarize(w, F, groups=L.O, transposed=True)
             ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
             t_tern += time_call(lambda: api.twn_ternarize(w, F, groups=L.O, out=tw, workspace=ws), reps=30, warm=5)
             W, X, Y, tws, calls = build_forward([L], 2, residual_on=(), groups_per_filter=True)
             t_fwd += time_call(calls[0], reps=50, warm=10)
             del W, X, Y, tws, calls
-        log("resnet18 per-filter (Alg. 1): ternarize of 21 tensors, one call each %.3f ms; forward %.3f ms" % (t_tern, t_fwd))
-        return {"workload": "resnet18_b64_per_filter_alpha", "ternarize_ms": round(t_tern, 4), "fwd_ms": round(t_fwd, 4)}
+            if li > 0:
+                # backward-data with one alpha per filter: alpha*dY carried as two bf16 terms, two contraction passes
+                dy = dev_bf16(wl.normal(2, wl.IDX_DY + 10 * li, L.y_shape))
+                wsb = torch.empty(max(16, api.twn_conv2d_bwd_ste_workspace_bytes(L.x_shape, tw, st, pd, dl)),
+                                  dtype=torch.uint8, device=dev)
+                dxo = torch.empty(L.x_shape, dtype=torch.bfloat16, device=dev)
+                c = api.prepare_conv2d_bwd_ste(None, dy, tw, st, pd, dl, dX=dxo, workspace=wsb, x_shape=L.x_shape)
+                t_dx += time_call(c, reps=30, warm=5)
+                del dy, wsb, dxo
+        log("resnet18 per-filter (Alg. 1): ternarize of 21 tensors, one call each %.3f ms; forward %.3f ms; backward-data "
+            "%.3f ms" % (t_tern, t_fwd, t_dx))
+        return {"workload": "resnet18_b64_per_filter_alpha", "ternarize_ms": round(t_tern, 4), "fwd_ms": round(t_fwd, 4),
+                "dx_ms": round(t_dx, 4)}
 
     # ------------------------------------------------------------------ headline: ResNet-18 b64 forward
     def headline(with_cpu):

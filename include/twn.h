@@ -232,8 +232,11 @@ int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weight
  * twn_conv2d_bwd_ste_workspace_bytes is passed (otherwise, and for other
  * shapes, by the generic gather: same result, slower).
  * With alpha_groups > 1 (one alpha per filter group, Alg. 1) alpha_o is a
- * factor inside the sum over o: dX then needs a workspace, where dY is first
- * scaled per channel (rounded once more to bf16) before the contraction. */
+ * factor inside the sum over o: dX then needs a workspace, where alpha_o*dY is
+ * formed in float32 and kept as two bf16 terms (high part and remainder, about
+ * 17 significant bits together); the contraction runs over each term, the
+ * second pass adding onto the first, so no rounding of the inputs is added
+ * (twice the contraction time on this path only). */
 size_t  twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d);
 int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, const void* dY,
                            const uint32_t* packed_T, const float* alpha,

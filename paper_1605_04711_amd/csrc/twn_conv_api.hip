@@ -269,10 +269,14 @@ size_t strided_dx_bytes(const twn_conv_desc* d, int P, int Q) {
     return round_up(static_cast<size_t>(cl.code_words) * sizeof(uint32_t), 256) + split;
 }
 
-// Backward-data with one alpha per group of filters: scaled copy of dY + one float (the unit alpha).
+// Backward-data with one alpha per group of filters: two scaled copies of dY (high and low bf16 term) + one float
+// (the unit alpha).
+size_t scaled_dy_term_bytes(const twn_conv_desc* d, int P, int Q) {
+    return round_up(static_cast<size_t>(d->N) * P * Q * d->O * sizeof(uint16_t), 256);
+}
 size_t scaled_dy_bytes(const twn_conv_desc* d, int P, int Q) {
     if (d->alpha_groups == 1) return 0;
-    return round_up(static_cast<size_t>(d->N) * P * Q * d->O * sizeof(uint16_t), 256) + 256;
+    return 2 * scaled_dy_term_bytes(d, P, Q) + 256;
 }
 
 // Weight-gradient workspace: [padded copy of X in first-layer mode] + split partials + bias partials.
@@ -485,15 +489,22 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
             // scaled first (into the workspace) and the contraction runs with alpha = 1
             if (!workspace || workspace_bytes < head + splitk_bytes(g, d->variant) || !aligned(workspace, 256))
                 return TWN_ERR_WORKSPACE;
-            uint16_t* scaled = static_cast<uint16_t*>(workspace);
+            uint16_t* hi = static_cast<uint16_t*>(workspace);
+            uint16_t* lo = reinterpret_cast<uint16_t*>(ws + scaled_dy_term_bytes(d, P, Q));
             float* one = reinterpret_cast<float*>(ws + head - 256);
             rc = launch_scale_channels(static_cast<const uint16_t*>(dY), alpha, d->O / d->alpha_groups, d->O,
-                                       static_cast<int64_t>(d->N) * P * Q, scaled, one, st);
+                                       static_cast<int64_t>(d->N) * P * Q, hi, lo, one, st);
             if (rc != TWN_OK) return rc;
-            g.X = scaled;
+            g.X = hi;
             g.alpha = one;
             ws += head;
             ws_bytes -= head;
+            rc = dispatch(g, d->variant, ws, ws_bytes, st);
+            if (rc != TWN_OK) return rc;
+            // second term, added onto the first: every output element is read (as the residual) and written by the
+            // same thread of the second pass
+            g.X = lo;
+            g.residual = dX;
         }
         rc = dispatch(g, d->variant, ws, ws_bytes, st);
         if (rc != TWN_OK) return rc;

@@ -401,26 +401,31 @@ int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int 
     return launch_status();
 }
 
-// Per-filter alpha in backward-data (Alg. 1 with one alpha per filter): alpha multiplies per forward output
-// channel o, which is a reduction index of dX, so it cannot be applied after the sum.  dY is scaled instead,
-// out[p][o] = bf16(dY[p][o] * alpha[o / rows_per_group]) (one extra rounding to bf16), and the contraction then
-// runs with alpha = 1, which thread 0 writes to `one`.
+// Backward-data with one alpha per group of filters (Alg. 1 steps 3-7 feeding step 9): alpha multiplies per forward
+// output channel o, which is a reduction index of dX, so it cannot be applied after the sum.  dY is scaled instead.
+// The product v = dY[p][o] * alpha[o / rows_per_group] (float32) is carried as two bf16 terms, hi = bf16(v) and
+// lo = bf16(v - hi), which together hold v to about 2^-17: the contraction runs once over each (alpha = 1, which
+// thread 0 writes to `one`), the second pass adding onto the first, and no rounding of the inputs is added.
 __global__ __launch_bounds__(256) void scale_channels_kernel(const uint16_t* __restrict__ dY, const float* __restrict__ alpha,
                                                              int rows_per_group, int O, int64_t total,
-                                                             uint16_t* __restrict__ out, float* __restrict__ one) {
+                                                             uint16_t* __restrict__ hi, uint16_t* __restrict__ lo,
+                                                             float* __restrict__ one) {
     const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (id == 0) *one = 1.0f;
     if (id >= total) return;
     const int o = static_cast<int>(id % O);
-    out[id] = f32_to_bf16(bf16_to_f32(dY[id]) * alpha[o / rows_per_group]);
+    const float v = bf16_to_f32(dY[id]) * alpha[o / rows_per_group];
+    const uint16_t h = f32_to_bf16(v);
+    hi[id] = h;
+    lo[id] = f32_to_bf16(v - bf16_to_f32(h));
 }
 
 int32_t launch_scale_channels(const uint16_t* dY, const float* alpha, int rows_per_group, int O, int64_t pixels,
-                              uint16_t* out, float* one, hipStream_t st) {
+                              uint16_t* hi, uint16_t* lo, float* one, hipStream_t st) {
     const int64_t total = pixels * O;
     if (total <= 0 || (total + 255) / 256 >= (1LL << 31)) return TWN_ERR_SHAPE;
     scale_channels_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(dY, alpha, rows_per_group, O, total,
-                                                                                   out, one);
+                                                                                   hi, lo, one);
     return launch_status();
 }
 

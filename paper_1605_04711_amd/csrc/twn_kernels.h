@@ -66,7 +66,7 @@ int32_t launch_gather_class_codes(const uint32_t* packed_T, int C, int wprT, int
                                   const DxClassTable& tb, int64_t total_words, uint32_t* out, hipStream_t st);
 int32_t launch_zero_fill(void* p, int64_t bytes, hipStream_t st);
 int32_t launch_scale_channels(const uint16_t* dY, const float* alpha, int rows_per_group, int O, int64_t pixels,
-                              uint16_t* out, float* one, hipStream_t st);
+                              uint16_t* hi, uint16_t* lo, float* one, hipStream_t st);
 int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp, uint16_t* Xp,
                              const uint32_t* packed, int rows, int R, int S, int Sp, uint32_t* out, hipStream_t st);
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);

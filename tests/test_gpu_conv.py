@@ -510,23 +510,21 @@ def test_per_lane_pointer_load_path(knob):
 @pytest.mark.parametrize("groups", ["filters", 4])
 def test_conv2d_bwd_data_per_filter_alpha(groups):
     # Alg. 1 with one alpha per filter (or per group of filters): alpha_o sits inside the sum over o, so the
-    # library scales dY per channel first (one more rounding to bf16)
+    # library scales dY per channel first and carries the product as two bf16 terms (16 significant bits, 2^-17
+    # relative per input).  Under the metric of every other test (error against max(|ref|, 1% of the RMS)) that is
+    # 2^-17 / 1e-2 = 8e-4 at the smallest outputs with float32 output (bar here 2e-3; the per-layer path, whose
+    # inputs are exact, has 1e-4), and the bf16-MFMA bar of 2e-2 with bf16 output as for every other layer.
     for ci in (1, 2, 9):
         n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
         gcount = o if groups == "filters" else groups
         x, w, tw, codes, alpha = make_layer(500 + ci, (n, h, w_, c), (o, c, r, s), groups=gcount, transposed=True)
         p, q = oc.out_size(h, r, st[0], pd[0], dl[0]), oc.out_size(w_, s, st[1], pd[1], dl[1])
         dy = wl.bf16_round(np.random.default_rng(510 + ci).standard_normal((n, p, q, o)).astype(np.float32))
-        dx, dw, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, dx_dtype=torch.float32)
-        got = to_host_f64(dx)
-        # (1) the kernel computes what the header says: the oracle on the scaled, re-rounded dY with alpha = 1
-        a_vec = np.repeat(np.asarray(alpha, dtype=np.float32), o // gcount)
-        dy_scaled = wl.bf16_round((dy * a_vec[None, None, None, :]).astype(np.float32))
-        assert rel_err(got, oc.conv2d_bwd_data(dy_scaled, codes, np.float32(1.0), x.shape, st, pd, dl)) <= 1e-4
-        # (2) and that differs from the exact per-filter result only by the extra rounding of the inputs
-        # (2^-9 per term, accumulating like the terms themselves): bf16 tolerance against the result's RMS
         ref = oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)
-        assert np.max(np.abs(got - ref)) <= BF16_TOL * np.sqrt(np.mean(ref * ref))
+        dx, dw, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, dx_dtype=torch.float32)
+        assert rel_err(to_host_f64(dx), ref) <= 2e-3
+        dxb, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape)
+        assert rel_err(to_host_f64(dxb), ref) <= BF16_TOL
         assert rel_err(to_host_f64(dw), oc.conv2d_bwd_weight(x, dy, codes.shape, st, pd, dl)) <= 1e-4
 
 
