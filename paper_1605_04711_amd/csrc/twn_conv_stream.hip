@@ -604,10 +604,11 @@ int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st) {
     int ks = env_int("TWN_STREAM_KS", 0);
     // Load waves (conv_stream_pc_kernel): four of them next to the four compute waves.  They pay off where a
     // workgroup has few tiles and a deep K (ResNet-18 stages 3 and 4: 22 -> 19.5 us and 24 -> 20.7 us per 3x3
-    // layer), and replace the K groups there; 128x64 tiles (64 output channels) gain nothing.
+    // layer), and replace the K groups there; with 128x256 tiles one workgroup of 4 + 4 waves per CU does what two
+    // workgroups of four waves did (VGG-16 conv5-7: 5-8 % faster); 128x64 tiles (64 output channels) gain nothing.
     // TWN_STREAM_PC: 0 = never, 2 / 4 = that many load waves wherever a build exists, unset = this rule.
     int np = env_int("TWN_STREAM_PC", -1);
-    if (np < 0) np = (tile == 14 || tile == 15) ? 4 : 0;
+    if (np < 0) np = (tile == 14 || tile == 15 || tile == 17) ? 4 : 0;
     if (np > 0) {
         const int32_t rc = launch_conv_stream_pc(g, tile, ks == 0 ? 1 : ks, np, env_int("TWN_STREAM_PC_STAGES", 4), st);
         if (rc != TWN_ERR_UNSUPPORTED) return rc;

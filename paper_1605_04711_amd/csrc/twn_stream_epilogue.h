@@ -74,7 +74,10 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[MI][NI], con
             }
     }
 
-    u32x2 rres[2][NI][4];
+    // residual values: requested one row block ahead into a second buffer, or (large accumulator tiles, where
+    // registers are short) into the same buffer as soon as the current block's values are consumed
+    constexpr int RES_BUF = (MI * NI >= 8) ? 1 : 2;
+    u32x2 rres[RES_BUF][NI][4];
     auto res_load = [&](int mi, u32x2 (&dst)[NI][4]) __attribute__((always_inline)) {
         const uint32_t so = tile_off + static_cast<uint32_t>(mi * 32) * ldyB;
         const bool row_ok = FULL || (mi * 32 + lrow < rows_in);
@@ -92,7 +95,7 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[MI][NI], con
     if (has_res) res_load(0, rres[0]);
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        if (has_res && mi + 1 < MI) res_load(mi + 1, rres[(mi + 1) & 1]);
+        if (RES_BUF == 2 && has_res && mi + 1 < MI) res_load(mi + 1, rres[(mi + 1) % RES_BUF]);
 #pragma unroll
         for (int nc = 0; nc < NI / EPI_NI; ++nc) {
 #pragma unroll
@@ -112,7 +115,7 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[MI][NI], con
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = acc[mi][ni][q4 * 4 + e] * mul[e] + add[e];
                     if (has_res) {
-                        const u32x2 r2 = rres[mi & 1][ni][q4];
+                        const u32x2 r2 = rres[mi % RES_BUF][ni][q4];
                         v[0] += __uint_as_float(r2[0] << 16);
                         v[1] += __uint_as_float(r2[0] & 0xFFFF0000u);
                         v[2] += __uint_as_float(r2[1] << 16);
@@ -126,6 +129,7 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[MI][NI], con
                     *reinterpret_cast<u32x2*>(stg + lrow * EPI_ROW + (nh * 32 + q4 * 8 + lh * 4) * 2) = pk;
                 }
             }
+            if (RES_BUF == 1 && nc + 1 == NI / EPI_NI && has_res && mi + 1 < MI) res_load(mi + 1, rres[0]);
             // the same wave wrote and reads: LDS executes a wave's operations in order
             const uint32_t so = tile_off + static_cast<uint32_t>(mi * 32) * ldyB + static_cast<uint32_t>(nc * EPI_CH * 2);
 #pragma unroll
