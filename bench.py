@@ -31,6 +31,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # dense bf16 MFMA, MI355X
 PEAK_HBM_GBPS = 8000.0
+PEAK_ADDS_T = 256 * 64 * 2.4e9 / 1e12   # float32 additions per second (non-packed), in units of 1e12
 F = 0.7
 PROFILES = os.path.join(ROOT, "profiles")
 # consecutive forward calls of the headline step that are ONE launch each of the same kernel on the same shape:
@@ -60,7 +61,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the side measurements")
     ap.add_argument("--cpu-batch", type=int, default=8)
     ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18", "resnet18_bwd", "lenet", "vgg7", "vgg16_ssd", "sgd",
-                                       "per_filter"], default=None,
+                                       "per_filter", "addsub", "resnet18b"], default=None,
                     help="run one measurement alone (used for the rocprofv3 summaries in profiles/)")
     ap.add_argument("--variants", action="store_true", help="with --only gemm: also time the comparison weight formats")
     ap.add_argument("--calibrate", action="store_true",
@@ -119,7 +120,7 @@ def main():
 
     # ------------------------------------------------------------------ network forward builders
     def build_forward(layers, cfg, fp32=False, residual_on=("conv2",), groups_per_filter=False, transposed=False,
-                      chain_blocks=False):
+                      chain_blocks=False, variant=None):
         """Device tensors and prepared calls for the forward of a list of layers.  Every layer reads its own
         synthetic input, except with chain_blocks (residual networks): inside a basic block the data flows as in
         the network (conv1 and the down-sample read the block input, conv2 reads conv1's output and adds the
@@ -169,10 +170,10 @@ def main():
             sf = torch.zeros(L.O, dtype=torch.float32, device=dev)
             if is_fc:
                 calls.append(api.prepare_gemm_fwd(X[li].reshape(L.N, L.C), tws[li], out=Y[li].reshape(L.N, L.O),
-                                                  scale=None if last else sc, shift=sf, relu=not last))
+                                                  scale=None if last else sc, shift=sf, relu=not last, variant=variant))
             else:
                 calls.append(api.prepare_conv2d_fwd(X[li], tws[li], st, pd, dl, out=Y[li], scale=sc, shift=sf,
-                                                    residual=RES[li], relu=True))
+                                                    residual=RES[li], relu=True, variant=variant))
         return W, X, Y, tws, calls
 
     def per_layer_table(tag, layers, calls, reps=100, warm=20):
@@ -412,6 +413,54 @@ def main():
         return {"workload": "resnet18_b64_per_filter_alpha", "ternarize_ms": round(t_tern, 4), "fwd_ms": round(t_fwd, 4),
                 "dx_ms": round(t_dx, 4)}
 
+    def side_addsub():
+        """Eq. 2's multiplication-free form on the vector ALUs (zero codes skipped) against the matrix-core kernels, on
+        every ResNet-18 b64 layer whose channel count it accepts (all but the three-channel stem)."""
+        layers = wl.resnet18(64)[1:]
+        rows = {}
+        t_as = t_mfma = 0.0
+        adds = 0
+        for li, L in enumerate(layers, start=1):
+            W, X, Y, tws, calls = build_forward([L], 2, variant=api.TWN_VAR_ADDSUB_SPARSE)
+            ta = time_call(calls[0], reps=10, warm=2)
+            nnz = int(tws[0].nnz.sum().item())
+            del W, X, Y, tws, calls
+            W, X, Y, tws, calls = build_forward([L], 2)
+            tm = time_call(calls[0], reps=50, warm=10)
+            del W, X, Y, tws, calls
+            m = L.gemm_mnk[0]
+            adds += m * nnz
+            t_as += ta
+            t_mfma += tm
+            rows[L.name] = {"addsub_us": round(ta * 1e3, 1), "mfma_us": round(tm * 1e3, 1),
+                            "nonzero_fraction": round(nnz / L.n_weights, 4)}
+            log("addsub %-12s %26s  add/sub %9.1f us (%6.1f TFLOP/s-eq, %5.2f Tadd/s)   matrix cores %8.1f us" %
+                (L.name, str(L.gemm_mnk), ta * 1e3, L.flops / ta / 1e9, m * nnz / ta / 1e9, tm * 1e3))
+        flops = sum(L.flops for L in layers)
+        tadds = adds / t_as / 1e9
+        log("addsub resnet18 b64 (20 layers): %.3f ms = %.1f TFLOP/s-eq, %.2f T additions/s; matrix-core path %.3f ms (%.1fx)"
+            % (t_as, flops / t_as / 1e9, tadds, t_mfma, t_as / t_mfma))
+        # peak: one float32 addition per lane and clock, 64 lanes per CU and clock (4 SIMDs x 16 lanes), 256 CUs, 2.4 GHz;
+        # the library is built without packed-float32 instructions
+        return roof_obj("conv_addsub_kernel", "alu", tadds, PEAK_ADDS_T, "Tadd/s", sum(layer_bytes(L) for L in layers),
+                        None, t_as * 1e3 / len(layers), workload="resnet18_b64_bf16_forward_without_stem, TWN_VAR_ADDSUB_SPARSE",
+                        ms=round(t_as, 4), tflops_eq=round(flops / t_as / 1e9, 1), additions=adds,
+                        matrix_core_path_ms=round(t_mfma, 4), slowdown_vs_matrix_cores=round(t_as / t_mfma, 2),
+                        per_layer=rows)
+
+    def side_resnet18b():
+        # ResNet-18B of Sec. 3.1: the same blocks with 1.5x the filters (96 / 192 / 384 / 768)
+        layers = wl.resnet18(64, width_mult=1.5)
+        W, X, Y, tws, calls = build_forward(layers, 5, chain_blocks=True)
+        tot, rows = per_layer_table("resnet18b", layers, calls, reps=50, warm=10)
+        flops = sum(L.flops for L in layers)
+        log("resnet18b b64 forward, sum of per-layer times: %.3f ms, %.0f img/s, %.1f TFLOP/s-eq" %
+            (tot, 64 / (tot * 1e-3), flops / tot / 1e9))
+        return {"workload": "resnet18b_b64_bf16_forward (1.5x filters)", "ms": round(tot, 4),
+                "img_per_s": round(64 / (tot * 1e-3), 1), "gflop": round(flops / 1e9, 1),
+                "tflops": round(flops / tot / 1e9, 1), "frac_mfma_peak": round(flops / tot / 1e9 / PEAK_BF16_TFLOPS, 4),
+                "per_layer_us": {n: round(t * 1e3, 1) for n, t in rows}}
+
     # ------------------------------------------------------------------ headline: ResNet-18 b64 forward
     def headline(with_cpu):
         CFG = 2
@@ -542,7 +591,7 @@ def main():
         torch.cuda.empty_cache()
     sides = {"gemm": side_gemm, "ternarize": lambda: side_ternarize(calibrate=True), "lenet": side_lenet,
              "vgg7": side_vgg7, "vgg16_ssd": side_vgg16, "resnet18_bwd": side_resnet18_bwd, "per_filter": side_per_filter,
-             "sgd": side_sgd}
+             "sgd": side_sgd, "addsub": side_addsub, "resnet18b": side_resnet18b}
     if args.only and args.only != "resnet18":
         print(json.dumps({"only": args.only, **sides[args.only]()}), flush=True)
         return
@@ -559,7 +608,9 @@ def main():
         rooflines.append(side_ternarize())
         torch.cuda.empty_cache()
         rooflines.append(side_sgd())
-        for name in ("lenet", "vgg7", "vgg16_ssd", "resnet18_bwd", "per_filter"):
+        torch.cuda.empty_cache()
+        rooflines.append(side_addsub())
+        for name in ("lenet", "vgg7", "vgg16_ssd", "resnet18_bwd", "per_filter", "resnet18b"):
             torch.cuda.empty_cache()
             extras[name] = sides[name]()
 

@@ -73,8 +73,14 @@ typedef enum {
                                        twn_unpack_i8), bf16 MFMA, alpha afterwards.  Forward only; K % 8 == 0 and the
                                        weights 8-byte aligned, else TWN_ERR_UNSUPPORTED. */
     TWN_VAR_FP32 = 3,               /* float32 activations and outputs, vector-ALU FMAs with float64 running sums */
-    TWN_VAR_BF16_SIGN1_POSTSCALE = 4/* the binary-weight comparison of Sec. 3: 1-bit sign codes from twn_binarize
+    TWN_VAR_BF16_SIGN1_POSTSCALE = 4,/* the binary-weight comparison of Sec. 3: 1-bit sign codes from twn_binarize
                                        (twn1 format) -> exact bf16 +-1, bf16 MFMA, alpha afterwards.  Forward only. */
+    TWN_VAR_ADDSUB_SPARSE = 5       /* comparison: Eq. 2's multiplication-free form (Sec. 2.1 "Computational requirement").
+                                       bf16 activations, the ordinary 2-bit codes; float32 additions and subtractions on
+                                       the vector ALUs, one per non-zero code and pixel, none for a zero code; alpha and
+                                       the block tail once per output.  Forward only; channel count, K and the pixel
+                                       stride of X multiples of 8 and X, weights 16-byte aligned, else
+                                       TWN_ERR_UNSUPPORTED. */
 } twn_variant;
 
 /* Filter bank [rows][C][R][S], float32, contiguous (fully-connected: R=S=1). */

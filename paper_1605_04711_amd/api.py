@@ -16,6 +16,7 @@ import torch
 TWN_F32, TWN_BF16 = 0, 1
 TWN_VAR_BF16_POSTSCALE, TWN_VAR_BF16_ALPHA_LDS, TWN_VAR_I8_STORED_POSTSCALE, TWN_VAR_FP32 = 0, 1, 2, 3
 TWN_VAR_BF16_SIGN1_POSTSCALE = 4
+TWN_VAR_ADDSUB_SPARSE = 5
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtwn.so")
 _lib = None

@@ -40,7 +40,8 @@ int32_t check_variant(int32_t variant, int32_t x_dtype) {
         case TWN_VAR_FP32: return x_dtype == TWN_F32 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         case TWN_VAR_BF16_ALPHA_LDS:
         case TWN_VAR_I8_STORED_POSTSCALE:
-        case TWN_VAR_BF16_SIGN1_POSTSCALE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
+        case TWN_VAR_BF16_SIGN1_POSTSCALE:
+        case TWN_VAR_ADDSUB_SPARSE: return x_dtype == TWN_BF16 ? TWN_OK : TWN_ERR_UNSUPPORTED;
         default: return TWN_ERR_UNSUPPORTED;
     }
 }
@@ -71,6 +72,11 @@ size_t splitk_bytes(const GatherGemm& g, int variant) {
 // Attaches the split-K workspace (if the problem uses one) and launches.
 int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_bytes, hipStream_t st) {
     if (variant == TWN_VAR_FP32) return launch_gather_gemm_fp32(g, st);
+    if (variant == TWN_VAR_ADDSUB_SPARSE) {
+        g.splits = 1;
+        g.partial = nullptr;
+        return launch_conv_addsub(g, st);
+    }
     if (variant != TWN_VAR_BF16_POSTSCALE) {
         if (variant == TWN_VAR_I8_STORED_POSTSCALE && (g.K % 8 != 0 || !aligned(g.Wq, 8))) return TWN_ERR_UNSUPPORTED;
         if (variant == TWN_VAR_BF16_SIGN1_POSTSCALE) {

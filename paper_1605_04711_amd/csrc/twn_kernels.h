@@ -71,6 +71,9 @@ int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int 
                              const uint32_t* packed, int rows, int R, int S, int Sp, uint32_t* out, hipStream_t st);
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
+// Multiplication-free comparison kernel (vector ALUs, zero codes skipped); `applicable` is a pure function of the problem.
+bool conv_addsub_applicable(const GatherGemm& g);
+int32_t launch_conv_addsub(const GatherGemm& g, hipStream_t st);
 
 // Persistent variant of the direct-to-LDS kernel (workgroups walk a list of tiles, loads of the next tile run
 // under the epilogue of the last); `applicable` is a pure function of the problem, `tile` one of the ids the
