@@ -220,7 +220,7 @@ bool strided_dx_classes(const twn_conv_desc* d, int P, int Q, DxClasses* out) {
         d->variant != TWN_VAR_BF16_POSTSCALE || d->x_dtype != TWN_BF16 || d->alpha_groups != 1)
         return false;
     // several small launches only pay when each class still has enough pixels to fill the chip
-    if (static_cast<int64_t>(d->N) * ((d->H + sh - 1) / sh) * ((d->W + sw - 1) / sw) < env_int("TWN_DX_CLASS_MIN_PIXELS", 8192))
+    if (static_cast<int64_t>(d->N) * ((d->H + sh - 1) / sh) * ((d->W + sw - 1) / sw) < env_int("TWN_DX_CLASS_MIN_PIXELS", 2048))
         return false;
     out->count = 0;
     out->any_empty = false;
