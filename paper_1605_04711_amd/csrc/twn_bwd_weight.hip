@@ -24,6 +24,8 @@
 // tiles go to a workspace and are summed in a fixed order (deterministic).
 #include <type_traits>
 
+#include <mutex>
+
 #include "twn_kernels.h"
 #include "twn_mfma.h"
 
@@ -296,23 +298,31 @@ __device__ __forceinline__ bf16x8 wg_join(const u32x2& lo, const u32x2& hi) {
 // is wave-uniform (scalar arithmetic), and a lane whose pixel, tap or channel is outside gets an offset beyond
 // the descriptor's size and reads zeros: no 64-bit address arithmetic and no branches are left in the loop.
 // EXACT (buffer path only): every patch lies inside the output image, so no lane tests its output pixel.
-template <int STAGES, bool BUF, bool EXACT>
-__global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs a) {
+// KS = 2: the workgroup holds two groups of four waves that work on the SAME tile; group kg takes the slabs
+// kg, kg+2, ... of the workgroup's pixel range in its own pipeline stages, and the two accumulator tiles are
+// summed through LDS (group 1 first, a fixed order) before group 0 writes.  One such workgroup per CU keeps the
+// eight waves per CU of two four-wave workgroups but dumps half as many partial tiles.
+template <int STAGES, bool BUF, bool EXACT, int KS>
+__global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WGArgs a) {
     constexpr int A_BYTES = 32 * 256;               // 32 pixels x 128 channels bf16
     constexpr int B_BYTES = 2 * A_BYTES;            // two 128-column halves
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int PD = STAGES - 1;
     constexpr int PER_STAGE = 6;                    // direct LDS loads per wave per slab
-    extern __shared__ __attribute__((aligned(1024))) unsigned char wsm[];
-    // LDS byte address of the dynamic array (low 32 bits of its generic address are the LDS offset)
-    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
-        (__attribute__((address_space(3))) unsigned char*)wsm));
+    static_assert(KS == 1 || KS == 2, "pixel groups per workgroup");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char wsm_all[];
 
     const WeightGrad& w = a.w;
     const WgPlan& pl = a.plan;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = (KS == 1) ? 0 : (wave_all >> 2);     // pixel group
+    const int wave = wave_all & 3;                      // wave inside the group
+    unsigned char* wsm = wsm_all + kg * (STAGES * STAGE_BYTES);
+    // LDS byte address of the group's stages (low 32 bits of the generic address are the LDS offset)
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+        (__attribute__((address_space(3))) unsigned char*)wsm));
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lh = lane >> 5;
 
@@ -334,6 +344,10 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
     int64_t slab_end = slab_begin + a.slabs_per_split;
     if (slab_end > pl.slabs) slab_end = pl.slabs;
     const int nslab = static_cast<int>(slab_end - slab_begin);
+    // group kg multiplies the slabs slab_begin + kg + KS*i; every group runs the same number of loop rounds
+    // (the barriers are workgroup-wide), a round past the group's last slab loads zeros
+    const int nround = (nslab + KS - 1) / KS;
+    auto round_live = [&](int i) __attribute__((always_inline)) -> bool { return i * KS + kg < nslab; };
     const void* zero = kWgZeroBlock;
 
     // ---- loader: a wave-level load covers 4 pixel rows x 256 bytes; this wave loads row groups wave and wave+4 ----
@@ -394,7 +408,7 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
     // as running scalar counters and every uniform offset is three multiplications by a per-launch stride
     uint32_t cx, cy, cn;
     {
-        const uint32_t su = static_cast<uint32_t>(slab_begin);
+        const uint32_t su = static_cast<uint32_t>(slab_begin) + static_cast<uint32_t>(kg);
         const uint32_t t1 = fdiv(su, a.divSX);
         cx = su - t1 * pl.sx;
         cn = fdiv(t1, a.divSY);
@@ -417,14 +431,17 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
             const int hb = static_cast<int>(cy) * strH, wb = static_cast<int>(cx) * strW;
             const int remN = w.N - static_cast<int>(cn) * pl.pn, remP = w.P - static_cast<int>(cy) * pl.ph,
                       remQ = w.Q - static_cast<int>(cx) * pl.pw;      // unused when EXACT
-            // advance to the next slab's patch
-            ++cx;
-            if (cx == static_cast<uint32_t>(pl.sx)) {
-                cx = 0;
-                ++cy;
-                if (cy == static_cast<uint32_t>(pl.sy)) {
-                    cy = 0;
-                    ++cn;
+            // advance to the patch of this group's next slab
+#pragma unroll
+            for (int adv = 0; adv < KS; ++adv) {
+                ++cx;
+                if (cx == static_cast<uint32_t>(pl.sx)) {
+                    cx = 0;
+                    ++cy;
+                    if (cy == static_cast<uint32_t>(pl.sy)) {
+                        cy = 0;
+                        ++cn;
+                    }
                 }
             }
 #pragma unroll
@@ -531,7 +548,7 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
     };
 
 #pragma unroll
-    for (int s = 0; s < PD; ++s) issue(slab_begin + s, s, s < nslab);
+    for (int s = 0; s < PD; ++s) issue(slab_begin + s * KS + kg, s, round_live(s));
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 1) * PER_STAGE));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -569,14 +586,14 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
         __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm((PD - 2) * PER_STAGE));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue(slab_begin + it + PD, FILL, it + PD < nslab);
+        issue(slab_begin + (it + PD) * KS + kg, FILL, round_live(it + PD));
         __builtin_amdgcn_sched_barrier(0);
         step(std::integral_constant<int, 1>{});
     };
-    for (int it = 0; it < nslab; it += 3) {
+    for (int it = 0; it < nround; it += 3) {
         slab(it, std::integral_constant<int, 0>{});
-        if (it + 1 < nslab) slab(it + 1, std::integral_constant<int, 1>{});
-        if (it + 2 < nslab) slab(it + 2, std::integral_constant<int, 2>{});
+        if (it + 1 < nround) slab(it + 1, std::integral_constant<int, 1>{});
+        if (it + 2 < nround) slab(it + 2, std::integral_constant<int, 2>{});
     }
     // the fragments fetched ahead for the slab after the last one are never used: let them land, and drain
     // the trailing zero loads, before registers and LDS are reused
@@ -586,6 +603,37 @@ __global__ __launch_bounds__(256, 2) void weight_grad_patch_kernel(const WGArgs 
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) wg_ready_b(fb[ni]);
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm(0));
+
+    if constexpr (KS == 2) {
+        // group 1 hands its accumulator tile to group 0 through LDS, one 32-row block (64 KB) at a time; every
+        // wave of the workgroup passes all four barriers
+        f32x4* red = reinterpret_cast<f32x4*>(wsm_all);
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            __syncthreads();        // the stages are free (first round: all loads landed, all fragments read)
+            if (kg == 1) {
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x16& t = acc[mi][ni];
+                        red[((wave * 4 + ni) * 4 + q4) * 64 + lane] = f32x4{t[q4 * 4], t[q4 * 4 + 1], t[q4 * 4 + 2], t[q4 * 4 + 3]};
+                    }
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x4 v = red[((wave * 4 + ni) * 4 + q4) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[mi][ni][q4 * 4 + e] += v[e];
+                    }
+            }
+        }
+        if (kg != 0) return;        // after the last barrier
+    }
 
     if (pl.splits == 1 && !w.pad_sp) {
         // the only range: write the gradient itself, [O][C][R][S], without a reduction pass
@@ -745,10 +793,10 @@ __global__ __launch_bounds__(256) void bias_grad_final_kernel(const float* __res
     dbias[ch] = s;
 }
 
-static int32_t choose_splits(int64_t tiles, int64_t slabs) {
-    int64_t want = env_int("TWN_WG_BLOCKS", 512);
-    // tiles x splits must not exceed the workgroups that are resident at once (two per CU), or the launch
-    // grows a second, nearly empty round
+static int32_t choose_splits(int64_t tiles, int64_t slabs, int ks = 1) {
+    int64_t want = env_int("TWN_WG_BLOCKS", 512) / ks;
+    // tiles x splits must not exceed the workgroups that are resident at once (two of four waves or one of eight
+    // per CU), or the launch grows a second, nearly empty round
     int64_t splits = (tiles >= 256) ? 1 : want / tiles;
     if (splits > slabs) splits = slabs;
     if (splits > 256) splits = 256;
@@ -767,6 +815,7 @@ WgPlan plan_weight_grad(int32_t N, int32_t P, int32_t Q, int32_t C, int32_t O, i
         pl.tiles = static_cast<int32_t>(((O + kWgTile - 1) / kWgTile) * ((J + kWgTile - 1) / kWgTile));
         pl.slabs = (pixels + 63) / 64;
         pl.splits = choose_splits(pl.tiles, pl.slabs);
+        pl.ks = 1;
         return pl;
     }
     // 32-pixel patch pn x ph x pw (powers of two) that wastes the fewest padded pixels; ties go to wide rows
@@ -784,7 +833,11 @@ WgPlan plan_weight_grad(int32_t N, int32_t P, int32_t Q, int32_t C, int32_t O, i
         }
     pl.slabs = best;
     pl.tiles = static_cast<int32_t>(((O + 127) / 128) * ((J + 255) / 256));
-    pl.splits = choose_splits(pl.tiles, pl.slabs);
+    // Layers with fewer tiles than CUs split the pixels over workgroups, and every workgroup dumps a partial tile
+    // (128 KB) that the reduction pass reads back: two groups of waves per workgroup halve that traffic at the
+    // same number of waves per CU.  TWN_WG_KS=1 keeps four-wave workgroups.
+    pl.ks = (pl.tiles < 256 && env_int("TWN_WG_KS", 2) == 2 && pl.slabs >= 4) ? 2 : 1;
+    pl.splits = choose_splits(pl.tiles, pl.slabs, pl.ks);
     return pl;
 }
 
@@ -811,28 +864,41 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
         if (a.plan.patch) {
             constexpr int kStages = 3;
             constexpr int kSmem = kStages * 3 * 32 * 256;
-            static bool allowed = false;
             const int64_t dyb = a.pixels * w.O * 2;
             const int64_t xb = ((static_cast<int64_t>(w.N) * w.H * w.W - 1) * w.xc + w.C) * 2;
             const bool buf = env_int("TWN_BUFLOAD", 1) != 0 && dyb < (1LL << 31) && xb < (1LL << 31);
             a.dy_bytes = static_cast<uint32_t>(buf ? dyb : 0);
             a.x_bytes = static_cast<uint32_t>(buf ? xb : 0);
             a.exact = (w.N % a.plan.pn == 0 && w.P % a.plan.ph == 0 && w.Q % a.plan.pw == 0) ? 1 : 0;
-            if (!allowed) {
-                const void* ks[3] = {reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, true>),
-                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, false>),
-                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false, false>)};
-                for (const void* kp : ks)
-                    if (hipFuncSetAttribute(kp, hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) != hipSuccess)
-                        return TWN_ERR_HIP;
-                allowed = true;
-            }
-            if (buf && a.exact)
-                weight_grad_patch_kernel<kStages, true, true><<<grid, 256, kSmem, st>>>(a);
+            static std::once_flag once;
+            static bool allowed = false;
+            std::call_once(once, [] {
+                const void* ks[6] = {reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, true, 1>),
+                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, false, 1>),
+                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false, false, 1>),
+                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, true, 2>),
+                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, false, 2>),
+                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false, false, 2>)};
+                bool ok = true;
+                for (int i = 0; i < 6; ++i)
+                    ok = ok && hipFuncSetAttribute(ks[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   (i < 3 ? 1 : 2) * kSmem) == hipSuccess;
+                allowed = ok;
+            });
+            if (!allowed) return TWN_ERR_HIP;
+            if (a.plan.ks == 2) {
+                if (buf && a.exact)
+                    weight_grad_patch_kernel<kStages, true, true, 2><<<grid, 512, 2 * kSmem, st>>>(a);
+                else if (buf)
+                    weight_grad_patch_kernel<kStages, true, false, 2><<<grid, 512, 2 * kSmem, st>>>(a);
+                else
+                    weight_grad_patch_kernel<kStages, false, false, 2><<<grid, 512, 2 * kSmem, st>>>(a);
+            } else if (buf && a.exact)
+                weight_grad_patch_kernel<kStages, true, true, 1><<<grid, 256, kSmem, st>>>(a);
             else if (buf)
-                weight_grad_patch_kernel<kStages, true, false><<<grid, 256, kSmem, st>>>(a);
+                weight_grad_patch_kernel<kStages, true, false, 1><<<grid, 256, kSmem, st>>>(a);
             else
-                weight_grad_patch_kernel<kStages, false, false><<<grid, 256, kSmem, st>>>(a);
+                weight_grad_patch_kernel<kStages, false, false, 1><<<grid, 256, kSmem, st>>>(a);
         } else {
             weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
         }

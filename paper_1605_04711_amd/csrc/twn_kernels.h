@@ -126,6 +126,7 @@ struct WgPlan {
     int64_t slabs;          // reduction slabs in total
     int32_t splits;         // blockIdx.y ranges of slabs
     int32_t tiles;          // output tiles (blockIdx.x)
+    int32_t ks;             // patch kernel: groups of four waves per workgroup that share a range (1 or 2)
 };
 WgPlan plan_weight_grad(int32_t N, int32_t P, int32_t Q, int32_t C, int32_t O, int32_t R, int32_t S);
 int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st);
