@@ -138,7 +138,7 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[MI][NI], con
                 const int c16 = lane % LPR;
                 const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
                 const bool ok = FULL || (mi * 32 + row < rows_in && nc * EPI_CH + c16 * 8 < cols_in);
-                __builtin_amdgcn_raw_buffer_store_b128(val, ry, ok ? L.st_off[it] : kBufOutside, so, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(val, ry, ok ? L.st_off[it] : kBufOutside, so, kStoreThrough);
             }
         }
     }
