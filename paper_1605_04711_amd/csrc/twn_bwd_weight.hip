@@ -72,6 +72,9 @@ struct WGArgs {
     int32_t exact;
 };
 
+#ifndef TWN_WG_STORE_AUX
+#define TWN_WG_STORE_AUX kStoreThrough
+#endif
 constexpr int kWgTile = 128;
 
 __device__ __forceinline__ int wg_swz(int row, int chunk) { return chunk ^ (row & 7) ^ ((row >> 3) & 7); }
@@ -657,7 +660,11 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
         }
         return;
     }
+    // The partial tile is written through (see kStoreThrough): the reduction pass reads it right after this kernel,
+    // and left dirty in L2 it would all be written back in one burst when the kernel ends.  One split's tile set is
+    // far below 2 GiB (checked by the launcher), so offsets are 32-bit.
     float* out = w.partial + static_cast<int64_t>(by) * w.O * a.J;
+    const __amdgpu_buffer_rsrc_t rout = make_rsrc(out, 0x7FFFFFFFu);
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -667,7 +674,9 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int o = o0 + wm * 64 + mi * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-                if (o < w.O) out[static_cast<int64_t>(o) * a.J + j] = acc[mi][ni][e];
+                if (o < w.O)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[mi][ni][e]), rout,
+                                                          static_cast<uint32_t>(o * a.J + j) * 4u, 0, TWN_WG_STORE_AUX);
             }
         }
 }
@@ -851,6 +860,7 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
     a.divC = make_fastdiv(w.C);
     a.divS = make_fastdiv(w.S);
     if (a.pixels >= (1LL << 31)) return TWN_ERR_SHAPE;
+    if (static_cast<int64_t>(w.O) * a.J >= (1LL << 28)) return TWN_ERR_SHAPE;   // 32-bit byte offsets inside one partial tile set
     a.plan = plan_weight_grad(w.N, w.P, w.Q, w.C, w.O, w.R, w.S);
     a.divSX = make_fastdiv(a.plan.patch ? a.plan.sx : 1);
     a.divSY = make_fastdiv(a.plan.patch ? a.plan.sy : 1);

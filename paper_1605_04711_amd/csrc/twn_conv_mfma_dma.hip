@@ -553,7 +553,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
                 const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
                 const int64_t m = m0 + wm * TM + row;
                 const int ncol = n0 + wn * TN + nc * EPI_CH + c16 * 8;
-                if (m < g.M && ncol < g.NC) *reinterpret_cast<u32x4*>(Yb + out_row(g, a.divUV, a.divV, m) * g.ldy + ncol) = val;
+                if (m < g.M && ncol < g.NC) store16_through(Yb + out_row(g, a.divUV, a.divV, m) * g.ldy + ncol, val);
             }
         }
     } else {

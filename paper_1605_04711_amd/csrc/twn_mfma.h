@@ -59,5 +59,9 @@ constexpr uint32_t kBufOutside = 0x80000000u;   // voffset of a lane that must r
 // b64 forward: 0.452 -> 0.440 ms).  The data still stays in the cache for the next layer (the non-temporal hint
 // instead makes single layers faster and the chain slower, because the consumer then reads from memory).
 constexpr int kStoreThrough = 16;
+// The same policy for a 16-byte store through a plain pointer (outputs addressed with 64-bit offsets).
+__device__ __forceinline__ void store16_through(void* p, const u32x4& v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
 
 }  // namespace twn
