@@ -305,8 +305,11 @@ __device__ __forceinline__ bf16x8 wg_join(const u32x2& lo, const u32x2& hi) {
 // kg, kg+2, ... of the workgroup's pixel range in its own pipeline stages, and the two accumulator tiles are
 // summed through LDS (group 1 first, a fixed order) before group 0 writes.  One such workgroup per CU keeps the
 // eight waves per CU of two four-wave workgroups but dumps half as many partial tiles.
-template <int STAGES, bool BUF, bool EXACT, int KS>
+// O64 (layers with at most 64 filters): the four waves of a group sit side by side along j (wave tile 64 x 64) and
+// multiply only the lower 64 rows of the dY tile, instead of spending half of every MFMA on rows that do not exist.
+template <int STAGES, bool BUF, bool EXACT, int KS, bool O64>
 __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WGArgs a) {
+    constexpr int NI = O64 ? 2 : 4;                 // 32-column blocks of a wave's tile
     constexpr int A_BYTES = 32 * 256;               // 32 pixels x 128 channels bf16
     constexpr int B_BYTES = 2 * A_BYTES;            // two 128-column halves
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -326,7 +329,10 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
     // LDS byte address of the group's stages (low 32 bits of the generic address are the LDS offset)
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) unsigned char*)wsm));
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = O64 ? 0 : (wave >> 1);           // 64-row block of the tile
+    const int wh = O64 ? (wave >> 1) : (wave & 1);  // 128-column half of the B tile the wave reads
+    const int wc = O64 ? (wave & 1) * 64 : 0;       // first column inside that half
+    const int wcol = wh * 128 + wc;                 // first column of the wave's tile inside the 256-column tile
     const int lrow = lane & 31, lh = lane >> 5;
 
     // Workgroups are dealt round-robin to the 8 XCDs in dispatch order (x fastest).  The tiles of one pixel
@@ -499,20 +505,20 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
         const int chunk = (ch >> 3) ^ (2 * (pixel & 3));
         return pixel * 256 + chunk * 16 + (ch & 7) * 2;
     };
-    int offA[2][2], offB[4][2];
+    int offA[2][2], offB[NI][2];
 #pragma unroll
     for (int hv = 0; hv < 2; ++hv) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi) offA[mi][hv] = frag_off(wm * 64 + mi * 32, fpix + 4 * hv);
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) offB[ni][hv] = wn * A_BYTES + frag_off(ni * 32, fpix + 4 * hv);
+        for (int ni = 0; ni < NI; ++ni) offB[ni][hv] = wh * A_BYTES + frag_off(wc + ni * 32, fpix + 4 * hv);
     }
 
-    f32x16 acc[2][4];
+    f32x16 acc[2][NI];
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
+        for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
 
@@ -521,21 +527,22 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
     // fragments of the NEXT step are fetched while this one multiplies: the four dY fragments into the
     // other register set right after the first pair, the two halves of X fragment ni as soon as pair ni
     // has consumed the old ones.  LDS reads complete in issue order, so s_waitcnt lgkmcnt(n) with the
-    // number of younger reads is exact: 6 before the first pair of a step, 10 before the others.
+    // number of younger reads is exact: before the first pair of a step the 2*(NI-1) reads of the later X
+    // fragments, before pair ni > 0 those plus what this step has issued so far, 2*NI + 2 in all.
     // Hand-over between the steps of slab `it`: slab it+1 has landed (its step 0 is prefetched during step
     // 1), and the stage of slab it-1, whose reads were all issued during step 0 of that slab, is refilled.
-    u32x2 fa[2][2][2], fb[4][2];
+    u32x2 fa[2][2][2], fb[NI][2];
     // LDS byte addresses of this lane's fragments in stage 0; the stage and the half of the slab go into the
     // instruction's immediate offset (the loop is unrolled over the three stages), so a read costs no vector
     // arithmetic
     static_assert(STAGES == 3 && 2 * STAGE_BYTES + A_BYTES + 4096 < 65536, "immediate offsets of the fragment reads");
-    uint32_t adrA[2][2], adrB[4][2];
+    uint32_t adrA[2][2], adrB[NI][2];
 #pragma unroll
     for (int hv = 0; hv < 2; ++hv) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi) adrA[mi][hv] = lds_base + offA[mi][hv];
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) adrB[ni][hv] = lds_base + offB[ni][hv];
+        for (int ni = 0; ni < NI; ++ni) adrB[ni][hv] = lds_base + offB[ni][hv];
     }
     auto read_fa = [&](auto off_tag, u32x2 (*dst)[2]) __attribute__((always_inline)) {
         constexpr int OFF = decltype(off_tag)::value;
@@ -557,7 +564,7 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
     asm volatile("" ::: "memory");
     read_fa(std::integral_constant<int, 0>{}, fa[0]);
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) read_fb(std::integral_constant<int, 0>{}, ni);
+    for (int ni = 0; ni < NI; ++ni) read_fb(std::integral_constant<int, 0>{}, ni);
 
     // one slab that lives in stage STG (compile-time: the loop below walks the stages in order)
     auto slab = [&](int it, auto stg_tag) __attribute__((always_inline)) {
@@ -568,8 +575,8 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
             // where the next step's fragments live: second half of this slab, or first half of the next one
             using NOff = std::integral_constant<int, (KK == 0) ? STG * STAGE_BYTES + 4096 : NEXT * STAGE_BYTES>;
 #pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-                if (ni == 0) wg_wait<6>(); else wg_wait<10>();
+            for (int ni = 0; ni < NI; ++ni) {
+                if (ni == 0) wg_wait<2 * (NI - 1)>(); else wg_wait<2 * NI + 2>();
                 if (ni == 0) wg_ready(fa[KK]);
                 wg_ready_b(fb[ni]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -604,7 +611,7 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
     wg_ready(fa[0]);
     wg_ready(fa[1]);
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) wg_ready_b(fb[ni]);
+    for (int ni = 0; ni < NI; ++ni) wg_ready_b(fb[ni]);
     __builtin_amdgcn_s_waitcnt(wg_vmcnt_imm(0));
 
     if constexpr (KS == 2) {
@@ -616,7 +623,7 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
             __syncthreads();        // the stages are free (first round: all loads landed, all fragments read)
             if (kg == 1) {
 #pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4) {
                         const f32x16& t = acc[mi][ni];
@@ -626,7 +633,7 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
             __syncthreads();
             if (kg == 0) {
 #pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
+                for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4) {
                         const f32x4 v = red[((wave * 4 + ni) * 4 + q4) * 64 + lane];
@@ -642,8 +649,8 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
         // the only range: write the gradient itself, [O][C][R][S], without a reduction pass
         const int RS = w.R * w.S;
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const int j = j0 + wn * 128 + ni * 32 + lrow;
+        for (int ni = 0; ni < NI; ++ni) {
+            const int j = j0 + wcol + ni * 32 + lrow;
             if (j >= a.J) continue;
             const uint32_t rs = fdiv(j, a.divC);
             const int c = j - static_cast<int>(rs) * w.C;
@@ -668,8 +675,8 @@ __global__ __launch_bounds__(256 * KS, 2) void weight_grad_patch_kernel(const WG
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-            const int j = j0 + wn * 128 + ni * 32 + lrow;
+        for (int ni = 0; ni < NI; ++ni) {
+            const int j = j0 + wcol + ni * 32 + lrow;
             if (j >= a.J) continue;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
@@ -850,6 +857,23 @@ WgPlan plan_weight_grad(int32_t N, int32_t P, int32_t Q, int32_t C, int32_t O, i
     return pl;
 }
 
+// One build of the patch kernel: the dynamic-LDS limit is raised once per build.
+template <bool BUF, bool EXACT, int KS, bool O64>
+static int32_t launch_patch(const WGArgs& a, dim3 grid, hipStream_t st) {
+    constexpr int kStages = 3;
+    constexpr int kSmem = KS * kStages * 3 * 32 * 256;
+    auto k = weight_grad_patch_kernel<kStages, BUF, EXACT, KS, O64>;
+    static std::once_flag once;
+    static bool allowed = false;
+    std::call_once(once, [&] {
+        allowed = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem) ==
+                  hipSuccess;
+    });
+    if (!allowed) return TWN_ERR_HIP;
+    k<<<grid, 256 * KS, kSmem, st>>>(a);
+    return TWN_OK;
+}
+
 int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
     WGArgs a;
     a.w = w;
@@ -872,43 +896,27 @@ int32_t launch_weight_grad(const WeightGrad& w, hipStream_t st) {
     if (w.dW) {
         const dim3 grid(a.plan.tiles, splits);
         if (a.plan.patch) {
-            constexpr int kStages = 3;
-            constexpr int kSmem = kStages * 3 * 32 * 256;
             const int64_t dyb = a.pixels * w.O * 2;
             const int64_t xb = ((static_cast<int64_t>(w.N) * w.H * w.W - 1) * w.xc + w.C) * 2;
             const bool buf = env_int("TWN_BUFLOAD", 1) != 0 && dyb < (1LL << 31) && xb < (1LL << 31);
             a.dy_bytes = static_cast<uint32_t>(buf ? dyb : 0);
             a.x_bytes = static_cast<uint32_t>(buf ? xb : 0);
             a.exact = (w.N % a.plan.pn == 0 && w.P % a.plan.ph == 0 && w.Q % a.plan.pw == 0) ? 1 : 0;
-            static std::once_flag once;
-            static bool allowed = false;
-            std::call_once(once, [] {
-                const void* ks[6] = {reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, true, 1>),
-                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, false, 1>),
-                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false, false, 1>),
-                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, true, 2>),
-                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, true, false, 2>),
-                                     reinterpret_cast<const void*>(weight_grad_patch_kernel<kStages, false, false, 2>)};
-                bool ok = true;
-                for (int i = 0; i < 6; ++i)
-                    ok = ok && hipFuncSetAttribute(ks[i], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                   (i < 3 ? 1 : 2) * kSmem) == hipSuccess;
-                allowed = ok;
-            });
-            if (!allowed) return TWN_ERR_HIP;
-            if (a.plan.ks == 2) {
-                if (buf && a.exact)
-                    weight_grad_patch_kernel<kStages, true, true, 2><<<grid, 512, 2 * kSmem, st>>>(a);
-                else if (buf)
-                    weight_grad_patch_kernel<kStages, true, false, 2><<<grid, 512, 2 * kSmem, st>>>(a);
-                else
-                    weight_grad_patch_kernel<kStages, false, false, 2><<<grid, 512, 2 * kSmem, st>>>(a);
-            } else if (buf && a.exact)
-                weight_grad_patch_kernel<kStages, true, true, 1><<<grid, 256, kSmem, st>>>(a);
+            const bool o64 = w.O <= 64;
+            int32_t rc;
+            auto pick = [&](auto buf_tag, auto exact_tag) {
+                constexpr bool B = decltype(buf_tag)::value, E = decltype(exact_tag)::value;
+                if (a.plan.ks == 2)
+                    return o64 ? launch_patch<B, E, 2, true>(a, grid, st) : launch_patch<B, E, 2, false>(a, grid, st);
+                return o64 ? launch_patch<B, E, 1, true>(a, grid, st) : launch_patch<B, E, 1, false>(a, grid, st);
+            };
+            if (buf && a.exact)
+                rc = pick(std::true_type{}, std::true_type{});
             else if (buf)
-                weight_grad_patch_kernel<kStages, true, false, 1><<<grid, 256, kSmem, st>>>(a);
+                rc = pick(std::true_type{}, std::false_type{});
             else
-                weight_grad_patch_kernel<kStages, false, false, 1><<<grid, 256, kSmem, st>>>(a);
+                rc = pick(std::false_type{}, std::false_type{});
+            if (rc != TWN_OK) return rc;
         } else {
             weight_grad_kernel<false><<<grid, 256, 0, st>>>(a);
         }
