@@ -59,7 +59,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the side measurements")
-    ap.add_argument("--cpu-batch", type=int, default=8)
+    ap.add_argument("--cpu-batch", type=int, default=64,
+                    help="batch the CPU oracle runs every layer at (64 = the whole workload, no extrapolation)")
     ap.add_argument("--only", choices=["gemm", "ternarize", "resnet18", "resnet18_bwd", "lenet", "vgg7", "vgg16_ssd", "sgd",
                                        "per_filter", "addsub", "resnet18b"], default=None,
                     help="run one measurement alone (used for the rocprofv3 summaries in profiles/)")
@@ -312,7 +313,8 @@ def main():
         return {"workload": "lenet5_b64_fp32_forward", "serial_us": round(tot * 1e3, 1),
                 "graph_replay_us": None if t_graph is None else round(t_graph * 1e3, 1),
                 "img_per_s": round(64 / (best * 1e-3), 1), "gflops": round(flops / best / 1e6, 1),
-                "per_layer_us": {n: round(t * 1e3, 1) for n, t in rows}, "bound": "launch latency"}
+                "per_layer_us": {n: round(t * 1e3, 1) for n, t in rows},
+                "bound": "latency: 0.55 GFLOP in four dependent launches of 2 to 576 workgroups"}
 
     def side_vgg16():
         layers = wl.vgg16_ssd(32)
@@ -546,6 +548,27 @@ def main():
                         span_ms * 1e3 / n_launch, launches_per_step=n_launch, flops_per_launch=Ls.flops,
                         calls="fwd " + " ".join(ROOFLINE_LAYERS) + " (one launch each)",
                         hbm_bound_us=round(layer_bytes(Ls) / PEAK_HBM_GBPS / 1e3, 2))
+        # the other kernel templates of the forward, from the per-layer pass (each layer looped alone, 100 launches)
+        tmap = dict(rows)
+        layer_roofs = []
+        for kern, bound, names_ in (
+                ("conv_first_kernel (stem, 7x7 / 2, 3 -> 64 channels)", "hbm", ["stem"]),
+                ("conv_stream_pc_kernel 128x128 (layer2 3x3 convolutions, 128 channels, 28x28)", "mfma",
+                 ["l2.0.conv2", "l2.1.conv1", "l2.1.conv2"]),
+                ("conv_stream_pc_kernel 64x128 (layer3 3x3 convolutions, 256 channels, 14x14)", "mfma",
+                 ["l3.0.conv2", "l3.1.conv1", "l3.1.conv2"]),
+                ("conv_stream_pc_kernel 64x128 (layer4 3x3 convolutions, 512 channels, 7x7)", "mfma",
+                 ["l4.0.conv2", "l4.1.conv1", "l4.1.conv2"])):
+            Lg = [layers[names.index(n)] for n in names_]
+            t_ms = sum(tmap[n] for n in names_)
+            if bound == "mfma":
+                ach, peak, unit = sum(L.flops for L in Lg) / t_ms / 1e9, PEAK_BF16_TFLOPS, "TFLOP/s"
+            else:
+                ach, peak, unit = sum(layer_bytes(L) for L in Lg) / t_ms / 1e6, PEAK_HBM_GBPS, "GB/s"
+            layer_roofs.append(roof_obj(kern, bound, ach, peak, unit, layer_bytes(Lg[0]), None, t_ms * 1e3 / len(Lg),
+                                        launches_per_step=len(Lg), flops_per_launch=Lg[0].flops,
+                                        calls="fwd " + " ".join(names_) + " (each looped alone)",
+                                        workload="resnet18_b64_bf16_twn_forward"))
         cpu = None
         if with_cpu:
             from oracle import conv as oc
@@ -571,7 +594,7 @@ def main():
                              "layer at batch %d of 64 (%.2f s, C direct loops, %d OpenMP threads), conv time scaled linearly "
                              "to batch 64" % (t_t, nb, t_c, cores)}
             log("cpu oracle: ternarize %.2f s, conv(b%d) %.2f s -> %.5f TFLOP/s-eq" % (t_t, nb, t_c, cpu["value"]))
-        info = {"ms_per_step": ms_per_step, "value": value, "roof": roof, "cpu": cpu, "graph": graph_info,
+        info = {"ms_per_step": ms_per_step, "value": value, "roof": roof, "layer_roofs": layer_roofs, "cpu": cpu, "graph": graph_info,
                 "phase_ms": {"ternarize": round(t_tern, 4), "forward": round(t_fwd, 4)},
                 "forward_only": {"ms": round(t_fwd, 4), "tflops": round(flops_fwd / t_fwd / 1e9, 1),
                                  "frac_mfma_peak": round(flops_fwd / t_fwd / 1e9 / PEAK_BF16_TFLOPS, 4),
@@ -600,7 +623,7 @@ def main():
     extras = {"phase_ms": h["phase_ms"], "forward_only": h["forward_only"], "per_layer_us": h["per_layer_us"],
               "per_layer_sum_ms": h["per_layer_sum_ms"], "graph_replay": h["graph"],
               "ternarize_21_tensors_GBps": h["ternarize_layers_GBps"]}
-    rooflines = [h["roof"]]
+    rooflines = [h["roof"]] + h["layer_roofs"]
     if not args.no_extras and not args.only:
         torch.cuda.empty_cache()
         args.variants = True
