@@ -367,8 +367,6 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
 #pragma unroll
             for (int it = 0; it < 4; ++it) val[it] = *reinterpret_cast<const u32x4*>(stg + (it * 16 + (lane >> 2)) * 80 + (lane & 3) * 16);
             uint16_t* ytile = a.Y + ((static_cast<int64_t>(cur.img) * a.P + cur.p0) * a.Q + cur.q0) * a.O + n0;   // wave-uniform
-            // descriptor on the tile's first element (offsets inside a tile are small; lanes outside are predicated)
-            const __amdgpu_buffer_rsrc_t ry = make_rsrc(ytile, 0x7FFFFFFFu);
             const bool full = cur.p0 + kFirstTH <= a.P && cur.q0 + kFirstTW <= a.Q && n0 + 64 <= a.O;           // wave-uniform
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
@@ -377,7 +375,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
                     const int row = it * 16 + (lane >> 2);
                     ok = cur.p0 + wm * 4 + (row >> 4) < a.P && cur.q0 + (row & 15) < a.Q && n0 + wn * 32 + (lane & 3) * 8 < a.O;
                 }
-                if (ok) __builtin_amdgcn_raw_buffer_store_b128(val[it], ry, yoff[it] * 2u, 0, kStoreThrough);
+                if (ok) *reinterpret_cast<u32x4*>(ytile + yoff[it]) = val[it];
             }
         }
         // The next patch is complete (this wave's LDS writes have landed) and every wave is done with the current

@@ -53,7 +53,7 @@ __device__ __forceinline__ void buf_dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t 
                                              static_cast<int>(voffset), static_cast<int>(soffset), 0, 0);
 }
 constexpr uint32_t kBufOutside = 0x80000000u;   // voffset of a lane that must read zeros (tensors stay below 2 GiB)
-// Cache policy of the output stores of the contraction kernels (buffer-store auxiliary bit 4 = sc1): the line is
+// Cache policy of the output stores of the persistent contraction kernels (buffer-store auxiliary bit 4 = sc1): the line is
 // written through to memory when it is stored instead of staying dirty in the XCD's L2 until the release at the end
 // of the kernel, which would write a layer's whole output back in one burst while the next kernel waits (ResNet-18
 // b64 forward: 0.452 -> 0.440 ms).  The data still stays in the cache for the next layer (the non-temporal hint
