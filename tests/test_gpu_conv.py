@@ -278,6 +278,22 @@ def test_lenet_layers_fp32(batch):
 BWD_CASES = list(range(len(CONV_CASES)))      # includes the 7x7 / stride-2 / C = 3 stem shape (index 5)
 
 
+@pytest.mark.parametrize("ks", [1, 2])
+@pytest.mark.parametrize("ci", [1, 2, 4, 7])
+def test_weight_grad_wave_groups(ci, ks, knob):
+    # the weight-gradient kernel with one and with two groups of waves per workgroup (the second sums the groups
+    # through LDS), on tiles of 128 filters (cases 1, 2, 7) and on the 64-filter arrangement (case 4), several
+    # pixel ranges per tile in each
+    knob("TWN_WG_KS", ks)
+    n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
+    n = 4 * n                                     # more pixels: more than one range per tile
+    x, w, tw, codes, alpha = make_layer(260 + ci, (n, h, w_, c), (o, c, r, s), transposed=True)
+    p, q = oc.out_size(h, r, st[0], pd[0], dl[0]), oc.out_size(w_, s, st[1], pd[1], dl[1])
+    dy = wl.bf16_round(np.random.default_rng(360 + ci).standard_normal((n, p, q, o)).astype(np.float32))
+    _, dw, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl, need_dx=False)
+    assert rel_err(to_host_f64(dw), oc.conv2d_bwd_weight(x, dy, codes.shape, st, pd, dl)) <= 1e-4
+
+
 @pytest.mark.parametrize("ci", BWD_CASES)
 def test_conv2d_bwd_ste(ci):
     n, h, w_, c, o, r, s, st, pd, dl = CONV_CASES[ci]
