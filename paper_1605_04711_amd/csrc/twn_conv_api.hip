@@ -217,7 +217,7 @@ struct DxClasses {
 bool strided_dx_classes(const twn_conv_desc* d, int P, int Q, DxClasses* out) {
     const int sh = d->stride_h, sw = d->stride_w;
     if (sh * sw <= 1 || sh * sw > 4 || d->dil_h != 1 || d->dil_w != 1 || d->O % 64 != 0 || d->C % 8 != 0 ||
-        d->variant != TWN_VAR_BF16_POSTSCALE || d->x_dtype != TWN_BF16 || d->alpha_groups != 1)
+        d->variant != TWN_VAR_BF16_POSTSCALE || d->x_dtype != TWN_BF16)
         return false;
     // several small launches only pay when each class still has enough pixels to fill the chip
     if (static_cast<int64_t>(d->N) * ((d->H + sh - 1) / sh) * ((d->W + sw - 1) / sw) < env_int("TWN_DX_CLASS_MIN_PIXELS", 2048))
@@ -263,7 +263,11 @@ bool strided_dx_classes(const twn_conv_desc* d, int P, int Q, DxClasses* out) {
     return out->count > 0;
 }
 
-// Workspace of the class path: gathered codes (256-byte multiple) + the largest split-K need of a class.
+size_t scaled_dy_bytes(const twn_conv_desc* d, int P, int Q);
+size_t scaled_dy_term_bytes(const twn_conv_desc* d, int P, int Q);
+
+// Workspace of the class path: gathered codes (256-byte multiple) + the two scaled copies of dY (several alphas
+// only) + the largest split-K need of a class.
 size_t strided_dx_bytes(const twn_conv_desc* d, int P, int Q) {
     DxClasses cl;
     if (!strided_dx_classes(d, P, Q, &cl)) return 0;
@@ -272,7 +276,7 @@ size_t strided_dx_bytes(const twn_conv_desc* d, int P, int Q) {
         const size_t b = splitk_bytes(cl.g[k], d->variant);
         if (b > split) split = b;
     }
-    return round_up(static_cast<size_t>(cl.code_words) * sizeof(uint32_t), 256) + split;
+    return round_up(static_cast<size_t>(cl.code_words) * sizeof(uint32_t), 256) + scaled_dy_bytes(d, P, Q) + split;
 }
 
 // Backward-data with one alpha per group of filters: two scaled copies of dY (high and low bf16 term) + one float
@@ -470,15 +474,35 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
             rc = launch_zero_fill(dX, bytes, st);
             if (rc != TWN_OK) return rc;
         }
+        // several alphas: the two bf16 terms of alpha_o * dY, as in the undivided path below
+        const size_t head = scaled_dy_bytes(d, P, Q);
+        unsigned char* wsb = static_cast<unsigned char*>(workspace) + code_bytes;
+        const uint16_t* hi = nullptr;
+        const uint16_t* lo = nullptr;
+        const float* one = nullptr;
+        if (head) {
+            uint16_t* h = reinterpret_cast<uint16_t*>(wsb);
+            uint16_t* l = reinterpret_cast<uint16_t*>(wsb + scaled_dy_term_bytes(d, P, Q));
+            float* o1 = reinterpret_cast<float*>(wsb + head - 256);
+            rc = launch_scale_channels(static_cast<const uint16_t*>(dY), alpha, d->O / d->alpha_groups, d->O,
+                                       static_cast<int64_t>(d->N) * P * Q, h, l, o1, st);
+            if (rc != TWN_OK) return rc;
+            hi = h; lo = l; one = o1;
+        }
         for (int k = 0; k < cl.count; ++k) {
             GatherGemm& g = cl.g[k];
-            g.X = dY;
+            g.X = head ? static_cast<const void*>(hi) : dY;
             g.Wq = codes + cl.tb.first_word[k];
-            g.alpha = alpha;
+            g.alpha = head ? one : alpha;
             g.Y = dX;
-            rc = dispatch(g, d->variant, static_cast<unsigned char*>(workspace) + code_bytes,
-                          workspace_bytes - code_bytes, st);
+            rc = dispatch(g, d->variant, wsb + head, workspace_bytes - code_bytes - head, st);
             if (rc != TWN_OK) return rc;
+            if (head) {
+                g.X = lo;
+                g.residual = dX;
+                rc = dispatch(g, d->variant, wsb + head, workspace_bytes - code_bytes - head, st);
+                if (rc != TWN_OK) return rc;
+            }
         }
     } else if (dX) {
         GatherGemm g{};

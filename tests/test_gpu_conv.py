@@ -580,6 +580,24 @@ def test_strided_backward_data_by_residue_classes(ci, knob):
     assert rel_err(to_host_f64(dxg), ref) <= 1e-4
 
 
+@pytest.mark.parametrize("ci", range(len(STRIDED_DX_CASES)))
+def test_strided_backward_data_by_residue_classes_per_filter_alpha(ci, knob):
+    # the residue-class path with one alpha per filter: alpha_o * dY as two bf16 terms, two contraction passes per
+    # class, the second adding onto the first through the output-row remap (bars as in the per-filter test above)
+    n, h, w_, c, o, r, s, st, pd = STRIDED_DX_CASES[ci]
+    dl = (1, 1)
+    x, w, tw, codes, alpha = make_layer(720 + ci, (n, h, w_, c), (o, c, r, s), groups=o, transposed=True)
+    p, q = oc.out_size(h, r, st[0], pd[0], 1), oc.out_size(w_, s, st[1], pd[1], 1)
+    dy = wl.bf16_round(np.random.default_rng(730 + ci).standard_normal((n, p, q, o)).astype(np.float32))
+    ref = oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)
+    knob("TWN_DX_CLASS_MIN_PIXELS", "0")
+    dx32, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape,
+                                        dx_dtype=torch.float32)
+    assert rel_err(to_host_f64(dx32), ref) <= 2e-3
+    dxb, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape)
+    assert rel_err(to_host_f64(dxb), ref) <= BF16_TOL
+
+
 def test_full_size_resnet18_strided_backward_data_sampled():
     layers = {l.name: (i, l) for i, l in enumerate(wl.resnet18(64))}
     for name in ("l2.0.conv1", "l2.0.down"):
