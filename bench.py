@@ -219,7 +219,11 @@ def main():
         log("gemm 8192x4096x4096: %.1f us, %.1f TFLOP/s-eq (%.3f of 2.5 PFLOP/s)" % (t * 1e3, tf, tf / PEAK_BF16_TFLOPS))
         res = roof_obj("contraction kernel, 128x256 tile", "mfma", tf, PEAK_BF16_TFLOPS, "TFLOP/s", layer_bytes(g),
                        "gemm_8192x4096x4096_kernels.txt", t * 1e3, workload="gemm_8192x4096x4096_bf16", us=round(t * 1e3, 1),
-                       flops_per_launch=g.flops)
+                       flops_per_launch=g.flops,
+                       # the same launch with everything but the MFMAs removed ran 128.9 us on this chip (ablation build,
+                       # clock 2.49 GHz): the rate the matrix pipes sustain when nothing else draws power
+                       mfma_only_rate_tflops=round(g.flops / 128.9e-6 / 1e12, 1),
+                       frac_of_mfma_only_rate=round(tf / (g.flops / 128.9e-6 / 1e12), 4))
         if args.variants:
             os.environ["TWN_TILE"] = "4"
             api.reload_env()
