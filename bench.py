@@ -393,15 +393,15 @@ def main():
     def side_per_filter():
         # Alg. 1 as printed: one (Delta, alpha) per filter; ResNet-18 has 4800 filters in 21 tensors
         layers = wl.resnet18(64)
-        t_tern = 0.0
         t_fwd = 0.0
         t_dx = 0.0
+        Wall = [torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev) for li, L in enumerate(layers)]
+        tws_all = api.twn_ternarize_batch(Wall, F, transposed=True, per_filter=True)
+        t_tern = time_call(api.prepare_ternarize_batch(Wall, tws_all, F), reps=50, warm=10)
         for li, L in enumerate(layers):
             st, pd, dl = geo(L)
-            w = torch.from_numpy(wl.kaiming_weights(2, li, L)).to(dev)
-            tw = api.twn_ternarize(w, F, groups=L.O, transposed=True)
-            ws = torch.empty(1 << 17, dtype=torch.uint8, device=dev)
-            t_tern += time_call(lambda: api.twn_ternarize(w, F, groups=L.O, out=tw, workspace=ws), reps=30, warm=5)
+            w = Wall[li]
+            tw = tws_all[li]
             W, X, Y, tws, calls = build_forward([L], 2, residual_on=(), groups_per_filter=True)
             t_fwd += time_call(calls[0], reps=50, warm=10)
             del W, X, Y, tws, calls
@@ -414,7 +414,7 @@ def main():
                 c = api.prepare_conv2d_bwd_ste(None, dy, tw, st, pd, dl, dX=dxo, workspace=wsb, x_shape=L.x_shape)
                 t_dx += time_call(c, reps=30, warm=5)
                 del dy, wsb, dxo
-        log("resnet18 per-filter (Alg. 1): ternarize of 21 tensors, one call each %.3f ms; forward %.3f ms; backward-data "
+        log("resnet18 per-filter (Alg. 1): ternarize of 21 tensors with both packed copies, one multi-tensor call %.3f ms; forward %.3f ms; backward-data "
             "%.3f ms" % (t_tern, t_fwd, t_dx))
         return {"workload": "resnet18_b64_per_filter_alpha", "ternarize_ms": round(t_tern, 4), "fwd_ms": round(t_fwd, 4),
                 "dx_ms": round(t_dx, 4)}

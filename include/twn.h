@@ -173,9 +173,10 @@ int32_t twn_ternarize_static(const float* W, const twn_weight_desc* wd, int32_t 
                              float* delta, float* alpha, uint64_t* nnz, void* stream);
 
 /* ---- 1b. several tensors per call (same passages as above) ------------------
- * The per-layer form of twn_ternarize (groups = 1) for `count` <= 32 weight
- * tensors at once, in three launches in total: meant for the weight tensors of
- * a network, which are too small to fill the chip one at a time.  `items` is a
+ * twn_ternarize for `count` <= 32 weight tensors at once, in three launches in
+ * total for the tensors with one group and two more for those with several
+ * (per-filter) groups: meant for the weight tensors of a network, which are too
+ * small to fill the chip one at a time.  `items` is a
  * host array (read during the call, not retained); the pointers inside are
  * device pointers with the meaning and alignment of twn_ternarize's arguments
  * (packed_T may be NULL).  Results equal those of `count` separate calls up to
@@ -189,6 +190,9 @@ typedef struct {
     float* delta;
     float* alpha;
     uint64_t* nnz;
+    int32_t groups;     /* 1: one Delta, alpha for the tensor; rows: one per filter (Alg. 1 as printed); must divide rows;
+                           delta, alpha, nnz then hold `groups` values each */
+    int32_t reserved;   /* 0 */
 } twn_ternarize_item;
 size_t  twn_ternarize_batch_workspace_bytes(int32_t count);
 int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t count, float delta_factor,

@@ -46,7 +46,8 @@ class WeightDesc(ctypes.Structure):
 
 class TernarizeItem(ctypes.Structure):
     _fields_ = [("W", ctypes.c_void_p), ("wd", WeightDesc), ("packed", ctypes.c_void_p), ("packed_T", ctypes.c_void_p),
-                ("delta", ctypes.c_void_p), ("alpha", ctypes.c_void_p), ("nnz", ctypes.c_void_p)]
+                ("delta", ctypes.c_void_p), ("alpha", ctypes.c_void_p), ("nnz", ctypes.c_void_p),
+                ("groups", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class GemmDesc(ctypes.Structure):
@@ -335,8 +336,9 @@ def _new_ternary_weights(rows, c, r, s, groups, transposed, dev):
                           torch.empty(groups, dtype=torch.int64, device=dev))
 
 
-def twn_ternarize_batch(Ws, delta_factor=0.7, transposed=False, out=None, workspace=None, stream=None):
-    """Per-layer ternarization of up to 32 weight tensors in one call; returns a list of TernaryWeights."""
+def twn_ternarize_batch(Ws, delta_factor=0.7, transposed=False, out=None, workspace=None, stream=None, per_filter=False):
+    """Ternarization of up to 32 weight tensors in one call (per layer, or one Delta and alpha per filter with
+    per_filter=True; with `out` given, each tensor's own `groups` decides); returns a list of TernaryWeights."""
     L = lib()
     shapes = []
     for W in Ws:
@@ -345,11 +347,11 @@ def twn_ternarize_batch(Ws, delta_factor=0.7, transposed=False, out=None, worksp
         shapes.append(tuple(W.shape) + (1, 1) if W.dim() == 2 else tuple(W.shape))
     dev = Ws[0].device
     if out is None:
-        out = [_new_ternary_weights(r_, c, r, s, 1, transposed, dev) for (r_, c, r, s) in shapes]
+        out = [_new_ternary_weights(r_, c, r, s, r_ if per_filter else 1, transposed, dev) for (r_, c, r, s) in shapes]
     items = (TernarizeItem * len(Ws))()
     for i, (W, o, (rows, c, r, s)) in enumerate(zip(Ws, out, shapes)):
         items[i] = TernarizeItem(_ptr(W), WeightDesc(rows, c, r, s), _ptr(o.packed), _ptr(o.packed_T), _ptr(o.delta),
-                                 _ptr(o.alpha), _ptr(o.nnz))
+                                 _ptr(o.alpha), _ptr(o.nnz), o.groups, 0)
     if workspace is None:
         workspace = _workspace(L.twn_ternarize_batch_workspace_bytes(len(Ws)), dev, stream)
     rc = L.twn_ternarize_batch(items, len(Ws), ctypes.c_float(delta_factor), _ptr(workspace), workspace.numel(),
@@ -565,7 +567,7 @@ def prepare_ternarize_batch(Ws, out, delta_factor=0.7, workspace=None):
         if not W.is_contiguous() or W.dtype != torch.float32 or not W.is_cuda:
             raise TypeError("every W must be a contiguous float32 CUDA tensor")
         items[i] = TernarizeItem(_ptr(W), WeightDesc(o.rows, o.C, o.R, o.S), _ptr(o.packed), _ptr(o.packed_T),
-                                 _ptr(o.delta), _ptr(o.alpha), _ptr(o.nnz))
+                                 _ptr(o.delta), _ptr(o.alpha), _ptr(o.nnz), o.groups, 0)
     if workspace is None:
         workspace = _workspace(L.twn_ternarize_batch_workspace_bytes(len(Ws)), Ws[0].device)
     fn = L.twn_ternarize_batch

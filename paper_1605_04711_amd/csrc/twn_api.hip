@@ -52,7 +52,7 @@ extern "C" const char* twn_status_str(int32_t status) {
     }
 }
 
-extern "C" int32_t twn_abi_version(void) { return 1; }
+extern "C" int32_t twn_abi_version(void) { return 2; }
 
 extern "C" int64_t twn_packed_words_per_row(int64_t K) {
     if (K <= 0) return 0;

@@ -429,6 +429,11 @@ struct BatchItem {
     int32_t tiled;              // pass 2 through the LDS-staged tile body
     int32_t flat_blocks;        // > 0: flat layout, the first flat_blocks pass-2 blocks stream W, the rest gather the transposed copy
     int32_t first1, first2;     // index of its first block in the pass-1 / pass-2 launch
+    // several groups (one Delta, alpha per `rows / groups` filters): the tensor takes no part in the three per-layer
+    // launches (nb1 = nb2 = 0) but in the two per-group ones
+    int32_t groups;
+    int32_t firstg, firstp;     // index of its first block in the group-statistics / the code-packing launch
+    int32_t npb;                // its blocks in the code-packing launch
 };
 struct BatchTable {
     BatchItem item[kBatchMax];
@@ -439,6 +444,13 @@ struct BatchTable {
 __device__ __forceinline__ int batch_find(const BatchTable& tb, int block, bool pass2) {
     int i = 0;
     while (i + 1 < tb.count && block >= (pass2 ? tb.item[i + 1].first2 : tb.item[i + 1].first1)) ++i;
+    return i;
+}
+// the same for the two per-group launches (a tensor without blocks in a launch shares its first index with its
+// successor and is passed over)
+__device__ __forceinline__ int batch_find_group(const BatchTable& tb, int block, bool pack) {
+    int i = 0;
+    while (i + 1 < tb.count && block >= (pack ? tb.item[i + 1].firstp : tb.item[i + 1].firstg)) ++i;
     return i;
 }
 
@@ -469,17 +481,18 @@ __global__ __launch_bounds__(kTernThreads) void batch_mask_pack_kernel(const Bat
 
 __global__ __launch_bounds__(kTernThreads) void batch_finalize_kernel(const BatchTable tb, const TernWorkspace* __restrict__ ws) {
     const BatchItem& it = tb.item[blockIdx.x];
+    if (it.groups > 1) return;      // per-group tensors were finished by batch_group_stats_kernel
     finalize_body(ws + blockIdx.x, it.nb1, it.nb2, tb.f, static_cast<int64_t>(it.rows) * it.C * it.RS, it.delta, it.alpha,
                   it.nnz);
 }
 
 // One block per group: both passes over the group's contiguous weights.
-__global__ __launch_bounds__(kTernThreads) void group_stats_kernel(
-    const float* __restrict__ W, int64_t n_per_group, float f,
-    float* __restrict__ delta, float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
+__device__ __forceinline__ void group_stats_body(const float* __restrict__ W, int64_t n_per_group, float f,
+                                                 float* __restrict__ delta, float* __restrict__ alpha,
+                                                 uint64_t* __restrict__ nnz, int group) {
     __shared__ double scratch[16];
     __shared__ unsigned long long scratch_u[16];
-    const float* seg = W + static_cast<int64_t>(blockIdx.x) * n_per_group;
+    const float* seg = W + static_cast<int64_t>(group) * n_per_group;
     double acc = 0.0;
     for (int64_t i = threadIdx.x; i < n_per_group; i += blockDim.x) acc += static_cast<double>(fabsf(seg[i]));
     const double s1 = block_sum(acc, scratch);
@@ -496,10 +509,23 @@ __global__ __launch_bounds__(kTernThreads) void group_stats_kernel(
     const double s = block_sum(acc, scratch);
     const unsigned long long total = block_sum(static_cast<unsigned long long>(count), scratch_u);
     if (threadIdx.x == 0) {
-        delta[blockIdx.x] = d;
-        nnz[blockIdx.x] = total;
-        alpha[blockIdx.x] = total ? static_cast<float>(s / static_cast<double>(total)) : 0.0f;
+        delta[group] = d;
+        nnz[group] = total;
+        alpha[group] = total ? static_cast<float>(s / static_cast<double>(total)) : 0.0f;
     }
+}
+
+__global__ __launch_bounds__(kTernThreads) void group_stats_kernel(
+    const float* __restrict__ W, int64_t n_per_group, float f,
+    float* __restrict__ delta, float* __restrict__ alpha, uint64_t* __restrict__ nnz) {
+    group_stats_body(W, n_per_group, f, delta, alpha, nnz, blockIdx.x);
+}
+
+__global__ __launch_bounds__(kTernThreads) void batch_group_stats_kernel(const BatchTable tb) {
+    const int i = batch_find_group(tb, blockIdx.x, false);
+    const BatchItem& it = tb.item[i];
+    group_stats_body(it.W, static_cast<int64_t>(it.rows) * it.C * it.RS / it.groups, tb.f, it.delta, it.alpha, it.nnz,
+                     blockIdx.x - it.firstg);
 }
 
 // ---- sign binarization of the binary-weight comparison (Sec. 3) ------------------------------------------
@@ -566,10 +592,9 @@ __global__ __launch_bounds__(256) void sign_pack_kernel(const float* __restrict_
 //   transposed: out row = input channel c, k_T = (r*S+s)*rows + o
 // Threads are ordered so that neighbouring threads read neighbouring source
 // weights where the layout allows it.
-__global__ __launch_bounds__(256) void pack_gather_kernel(
+__device__ __forceinline__ void pack_gather_body(
     const float* __restrict__ W, int rows, int C, int RS, const float* __restrict__ delta,
-    int rows_per_group, uint32_t* __restrict__ out, int wpr, int transposed) {
-    const int64_t id = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    int rows_per_group, uint32_t* __restrict__ out, int wpr, int transposed, int64_t id) {
     int64_t out_rows = transposed ? C : rows;
     if (id >= out_rows * wpr) return;
     int row, j;
@@ -602,6 +627,26 @@ __global__ __launch_bounds__(256) void pack_gather_kernel(
         }
     }
     out[static_cast<int64_t>(row) * wpr + j] = word;
+}
+
+__global__ __launch_bounds__(256) void pack_gather_kernel(
+    const float* __restrict__ W, int rows, int C, int RS, const float* __restrict__ delta,
+    int rows_per_group, uint32_t* __restrict__ out, int wpr, int transposed) {
+    pack_gather_body(W, rows, C, RS, delta, rows_per_group, out, wpr, transposed,
+                     static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x);
+}
+
+// Per-group tensors of a multi-tensor call: the words of the normal copy, then those of the transposed copy.
+__global__ __launch_bounds__(256) void batch_pack_gather_kernel(const BatchTable tb) {
+    const int i = batch_find_group(tb, blockIdx.x, true);
+    const BatchItem& it = tb.item[i];
+    const int64_t id = static_cast<int64_t>(blockIdx.x - it.firstp) * blockDim.x + threadIdx.x;
+    const int64_t words_n = static_cast<int64_t>(it.rows) * it.wpr;
+    const int rpg = it.rows / it.groups;
+    if (id < words_n)
+        pack_gather_body(it.W, it.rows, it.C, it.RS, it.delta, rpg, it.packed, it.wpr, 0, id);
+    else if (it.packed_T)
+        pack_gather_body(it.W, it.rows, it.C, it.RS, it.delta, rpg, it.packed_T, it.wprT, 1, id - words_n);
 }
 
 __global__ __launch_bounds__(256) void unpack_i8_kernel(const uint32_t* __restrict__ packed, int rows,
@@ -928,10 +973,13 @@ extern "C" int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t 
         const int64_t K = RS * wd.C, KT = RS * wd.rows, n = K * wd.rows;
         if (RS > (1 << 15) || K >= (1LL << 31) || KT >= (1LL << 31) || n >= (1LL << 40)) return TWN_ERR_SHAPE;
         if (!aligned(in.W, 16) || !aligned(in.packed, 16) || (in.packed_T && !aligned(in.packed_T, 16))) return TWN_ERR_ALIGN;
-        total_n += n;
+        if (in.groups < 1 || wd.rows % in.groups != 0) return TWN_ERR_SHAPE;
+        if (in.groups == 1) total_n += n;
     }
+    if (total_n == 0) total_n = 1;      // only per-group tensors
     // blocks are shared out in proportion to the tensor sizes: about 1024 per pass in total
     int first1 = 0, first2 = 0;
+    int64_t firstg = 0, firstp = 0;
     for (int i = 0; i < count; ++i) {
         const twn_ternarize_item& in = items[i];
         const twn_weight_desc& wd = in.wd;
@@ -943,6 +991,23 @@ extern "C" int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t 
         it.rows = wd.rows; it.C = wd.C; it.RS = static_cast<int32_t>(RS);
         it.wpr = static_cast<int32_t>(twn_packed_words_per_row(K));
         it.wprT = static_cast<int32_t>(twn_packed_words_per_row(KT));
+        it.groups = in.groups;
+        it.firstg = static_cast<int32_t>(firstg);
+        it.firstp = static_cast<int32_t>(firstp);
+        it.npb = 0;
+        if (in.groups > 1) {
+            // one block per group for the statistics, one thread per output word for the codes
+            const int64_t words = static_cast<int64_t>(wd.rows) * it.wpr + (in.packed_T ? static_cast<int64_t>(wd.C) * it.wprT : 0);
+            it.npb = static_cast<int32_t>((words + 255) / 256);
+            firstg += in.groups;
+            firstp += it.npb;
+            if (firstg >= (1LL << 30) || firstp >= (1LL << 30)) return TWN_ERR_SHAPE;
+            it.nb1 = it.nb2 = 0;
+            it.tiled = it.flat_blocks = 0;
+            it.first1 = first1;
+            it.first2 = first2;
+            continue;
+        }
         int64_t share = (1024 * n + total_n - 1) / total_n;
         if (share < 1) share = 1;
         const int64_t nchunks = (n + kChunk - 1) / kChunk;
@@ -972,9 +1037,15 @@ extern "C" int32_t twn_ternarize_batch(const twn_ternarize_item* items, int32_t 
     }
     hipStream_t st = as_stream(stream);
     TernWorkspace* ws = static_cast<TernWorkspace*>(workspace);
-    batch_abs_sum_kernel<<<first1, kTernThreads, 0, st>>>(tb, ws);
-    batch_mask_pack_kernel<<<first2, kTernThreads, 0, st>>>(tb, ws);
-    batch_finalize_kernel<<<count, kTernThreads, 0, st>>>(tb, ws);
+    if (first1 > 0) {
+        batch_abs_sum_kernel<<<first1, kTernThreads, 0, st>>>(tb, ws);
+        batch_mask_pack_kernel<<<first2, kTernThreads, 0, st>>>(tb, ws);
+        batch_finalize_kernel<<<count, kTernThreads, 0, st>>>(tb, ws);
+    }
+    if (firstg > 0) {
+        batch_group_stats_kernel<<<static_cast<unsigned>(firstg), kTernThreads, 0, st>>>(tb);
+        batch_pack_gather_kernel<<<static_cast<unsigned>(firstp), 256, 0, st>>>(tb);
+    }
     return launch_status();
 }
 

@@ -26,7 +26,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(api.EXPORTS) == names
-    assert L.twn_abi_version() == 1
+    assert L.twn_abi_version() == 2
     assert api.status_str(0) == "ok" and api.status_str(-3).startswith("misaligned")
 
 

@@ -80,6 +80,38 @@ def check_batch(shapes, f, transposed):
 
 
 @pytest.mark.parametrize("transposed", [False, True])
+def test_batch_per_filter_and_mixed(transposed):
+    # Alg. 1 as printed (one Delta, alpha per filter) for several tensors in one call, alone and next to per-layer
+    # tensors in the same call; bit-identical to the one-tensor entry point and exact against the oracle
+    shapes = [(64, 16, 3, 3), (128, 256), (8, 3, 7, 7), (40, 24, 1, 1), (256, 64, 3, 3)]
+    ws = [wl.normal(11, 10 * i + len(sh), sh, std=0.03 * (i + 1)) for i, sh in enumerate(shapes)]
+    dws = [to_dev_f32(w) for w in ws]
+    tws = api.twn_ternarize_batch(dws, 0.75, transposed=transposed, per_filter=True)
+    # mixed: tensors 0, 2, 4 per filter, 1 and 3 per layer
+    mixed = [api.twn_ternarize(dw, 0.75, groups=(w.shape[0] if i % 2 == 0 else 1), transposed=transposed)
+             for i, (w, dw) in enumerate(zip(ws, dws))]
+    for t in mixed:
+        t.packed.zero_(); t.delta.zero_(); t.alpha.zero_(); t.nnz.zero_()
+        if transposed:
+            t.packed_T.zero_()
+    api.twn_ternarize_batch(dws, 0.75, transposed=transposed, out=mixed)
+    torch.cuda.synchronize()
+    for i, w in enumerate(ws):
+        w4 = w if w.ndim == 4 else w.reshape(w.shape[0], w.shape[1], 1, 1)
+        for tw, g in ((tws[i], w.shape[0]), (mixed[i], w.shape[0] if i % 2 == 0 else 1)):
+            codes, delta, alpha, nnz = ot.ternarize(w4, 0.75, groups=g)
+            assert tw.groups == g and np.array_equal(tw.nnz.cpu().numpy(), nnz)
+            assert np.all(np.abs(tw.delta.cpu().numpy() - delta) <= REL * np.abs(delta))
+            assert np.all(np.abs(tw.alpha.cpu().numpy() - alpha) <= REL * np.abs(alpha))
+            assert np.array_equal(packed_to_host(tw.packed), op.pack_weights(codes))
+            if transposed:
+                assert np.array_equal(packed_to_host(tw.packed_T), op.pack_weights_t(codes))
+            one = api.twn_ternarize(dws[i], 0.75, groups=g, transposed=transposed)
+            assert torch.equal(one.packed, tw.packed) and torch.equal(one.nnz, tw.nnz)
+            assert torch.equal(one.delta, tw.delta) and torch.equal(one.alpha, tw.alpha)
+
+
+@pytest.mark.parametrize("transposed", [False, True])
 def test_batch_of_mixed_tensors(transposed):
     check_batch([(5, 3, 3, 3), (64, 32, 5, 5), (1000, 128 * 33), (17, 24), (1, 1), (128, 128, 3, 3), (64, 3, 7, 7),
                  (10, 1024)], 0.7, transposed)
