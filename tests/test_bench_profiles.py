@@ -29,3 +29,11 @@ def test_traffic_figures_against_algorithmic_bytes():
         v, text = _value(fname)
         assert 0.9 * alg <= v <= 3.0 * alg, (fname, v, alg)
         assert "rocprofv3" in text and "bench.py" in text      # the summary states the command that made it
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # this build runs on one GPU; asking for more ends with a message that says so (no GPU is touched before that)
+    import subprocess
+    import sys
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0 and "ONE GPU" in (p.stderr + p.stdout)
