@@ -111,6 +111,22 @@ def test_batch_per_filter_and_mixed(transposed):
             assert torch.equal(one.delta, tw.delta) and torch.equal(one.alpha, tw.alpha)
 
 
+def test_batch_per_filter_resnet18_full_size():
+    # the call the benchmark times: all 21 ResNet-18 tensors, one Delta and alpha per filter (4800 filters), both copies
+    layers = wl.resnet18(64)
+    ws = [wl.kaiming_weights(2, li, L) for li, L in enumerate(layers)]
+    tws = api.twn_ternarize_batch([to_dev_f32(w) for w in ws], 0.7, transposed=True, per_filter=True)
+    torch.cuda.synchronize()
+    for w, tw in zip(ws, tws):
+        w4 = w if w.ndim == 4 else w.reshape(w.shape[0], w.shape[1], 1, 1)
+        codes, delta, alpha, nnz = ot.ternarize(w4, 0.7, groups=w.shape[0])
+        assert np.array_equal(tw.nnz.cpu().numpy(), nnz)
+        assert np.all(np.abs(tw.delta.cpu().numpy() - delta) <= REL * np.abs(delta))
+        assert np.all(np.abs(tw.alpha.cpu().numpy() - alpha) <= REL * np.abs(alpha))
+        assert np.array_equal(packed_to_host(tw.packed), op.pack_weights(codes))
+        assert np.array_equal(packed_to_host(tw.packed_T), op.pack_weights_t(codes))
+
+
 @pytest.mark.parametrize("transposed", [False, True])
 def test_batch_of_mixed_tensors(transposed):
     check_batch([(5, 3, 3, 3), (64, 32, 5, 5), (1000, 128 * 33), (17, 24), (1, 1), (128, 128, 3, 3), (64, 3, 7, 7),
