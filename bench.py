@@ -596,8 +596,8 @@ def main():
             cpu = {"value": round(flops_fwd / t_full / 1e12, 6), "unit": "TFLOP/s-eq", "cores": cores, "kind": "oracle",
                    "img_per_s": round(64 / t_full, 3),
                    "sample": "ternarize of all 21 ResNet-18 tensors in full (%.2f s, numpy sort, 1 thread) + forward of every "
-                             "layer at batch %d of 64 (%.2f s, C direct loops, %d OpenMP threads), conv time scaled linearly "
-                             "to batch 64" % (t_t, nb, t_c, cores)}
+                             "layer at batch %d of 64 (%.2f s, C direct loops, %d OpenMP threads)%s"
+                             % (t_t, nb, t_c, cores, "" if nb == 64 else ", conv time scaled linearly to batch 64")}
             log("cpu oracle: ternarize %.2f s, conv(b%d) %.2f s -> %.5f TFLOP/s-eq" % (t_t, nb, t_c, cpu["value"]))
         info = {"ms_per_step": ms_per_step, "value": value, "roof": roof, "layer_roofs": layer_roofs, "cpu": cpu, "graph": graph_info,
                 "phase_ms": {"ternarize": round(t_tern, 4), "forward": round(t_fwd, 4)},
