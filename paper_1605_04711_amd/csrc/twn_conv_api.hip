@@ -70,7 +70,8 @@ size_t splitk_bytes(const GatherGemm& g, int variant) {
 }
 
 // Attaches the split-K workspace (if the problem uses one) and launches.
-int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_bytes, hipStream_t st) {
+int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_bytes, hipStream_t st,
+                 bool allow_split = true) {
     if (variant == TWN_VAR_FP32) return launch_gather_gemm_fp32(g, st);
     if (variant == TWN_VAR_ADDSUB_SPARSE) {
         g.splits = 1;
@@ -87,7 +88,7 @@ int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_b
         g.partial = nullptr;
         return launch_gather_gemm_mfma(g, variant, st);
     }
-    g.splits = gather_gemm_splits(g);
+    g.splits = allow_split ? gather_gemm_splits(g) : 1;
     g.partial = nullptr;
     if (g.splits > 1) {
         const size_t need = static_cast<size_t>(g.splits) * static_cast<size_t>(g.M) * g.NC * sizeof(float);
@@ -495,12 +496,14 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
             g.Wq = codes + cl.tb.first_word[k];
             g.alpha = head ? one : alpha;
             g.Y = dX;
-            rc = dispatch(g, d->variant, wsb + head, workspace_bytes - code_bytes - head, st);
+            // no split-K here: a class is one of several launches of a layer whose own launch would not be split either,
+            // and partial tiles plus a finishing launch per class cost more than the idle CUs (ResNet-18 stage 4: 70 -> 48 us)
+            rc = dispatch(g, d->variant, wsb + head, workspace_bytes - code_bytes - head, st, false);
             if (rc != TWN_OK) return rc;
             if (head) {
                 g.X = lo;
                 g.residual = dX;
-                rc = dispatch(g, d->variant, wsb + head, workspace_bytes - code_bytes - head, st);
+                rc = dispatch(g, d->variant, wsb + head, workspace_bytes - code_bytes - head, st, false);
                 if (rc != TWN_OK) return rc;
             }
         }
