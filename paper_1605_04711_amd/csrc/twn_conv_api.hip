@@ -496,6 +496,36 @@ extern "C" int32_t twn_conv2d_bwd_ste(const twn_conv_desc* d, const void* X, con
             g.Wq = codes + cl.tb.first_word[k];
             g.alpha = head ? one : alpha;
             g.Y = dX;
+            g.splits = 1;
+            g.partial = nullptr;
+        }
+        // all classes in ONE launch when the dispatcher would give each of them the same tile of the
+        // one-tile-per-workgroup kernel (they are too small to be worth a launch each: ResNet-18 b64, the three
+        // strided 3x3 layers 33 / 34 / 48 us as four launches)
+        int batch_tile = env_int("TWN_DX_CLASS_BATCH", 1) != 0 ? gather_gemm_dma_tile(cl.g[0]) : 0;
+        for (int k = 1; k < cl.count && batch_tile; ++k)
+            if (gather_gemm_dma_tile(cl.g[k]) != batch_tile) batch_tile = 0;
+        if (batch_tile && cl.count > 1 && d->variant == TWN_VAR_BF16_POSTSCALE) {
+            rc = launch_gather_gemm_dma_batch(cl.g, cl.count, batch_tile, st);
+            if (rc == TWN_OK && head) {
+                for (int k = 0; k < cl.count; ++k) {
+                    cl.g[k].X = lo;
+                    cl.g[k].residual = dX;
+                }
+                rc = launch_gather_gemm_dma_batch(cl.g, cl.count, batch_tile, st);
+            }
+            if (rc != TWN_ERR_UNSUPPORTED) {
+                if (rc != TWN_OK) return rc;
+                cl.count = 0;       // done
+            } else {
+                for (int k = 0; k < cl.count; ++k) {
+                    cl.g[k].X = head ? static_cast<const void*>(hi) : dY;
+                    cl.g[k].residual = nullptr;
+                }
+            }
+        }
+        for (int k = 0; k < cl.count; ++k) {
+            GatherGemm& g = cl.g[k];
             // no split-K here: a class is one of several launches of a layer whose own launch would not be split either,
             // and partial tiles plus a finishing launch per class cost more than the idle CUs (ResNet-18 stage 4: 70 -> 48 us)
             rc = dispatch(g, d->variant, wsb + head, workspace_bytes - code_bytes - head, st, false);

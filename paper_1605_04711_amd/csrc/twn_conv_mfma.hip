@@ -522,6 +522,21 @@ int32_t gather_gemm_splits(const GatherGemm& g) {
     return static_cast<int32_t>((KT + kps - 1) / kps);
 }
 
+// Tile id launch_gather_gemm_mfma would give an unsplit problem in the one-tile-per-workgroup direct-to-LDS kernel,
+// or 0 when the problem would not run there (scalar gathers, forced tiles, persistent kernels).
+int32_t gather_gemm_dma_tile(const GatherGemm& g) {
+    if (gather_mode(g) == kModeScalar || env_int("TWN_TILE", 0) != 0 || g.splits > 1) return 0;
+    if (env_int("TWN_STREAM", 1) != 0 && conv_stream_applicable(g)) return 0;
+    auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
+    int tile;
+    if (g.NC <= 64) tile = 16;
+    else if (g.NC <= 128) tile = 12;
+    else tile = (blocks(128, 256) >= 512) ? 17 : 12;
+    if (tile == 12 && blocks(128, 128) <= 256) tile = 14;
+    if (tile == 12) tile = 15;
+    return tile;
+}
+
 int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st) {
     const int mode = gather_mode(g);
     // the comparison variants run in the register-staged 128x128 kernel only

@@ -66,9 +66,9 @@ constexpr int dma_min_blocks(int nw, int smem) {
     return b < 1 ? 1 : b;
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF, int OCC = 0>
-__global__ __launch_bounds__(64 * WM * WN, OCC ? OCC : dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
-void gather_gemm_dma_kernel(const DmaArgs a) {
+// The kernel proper: workgroup `b` of `nb` of problem `a` (`by`: the K range of a split-K launch).
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF>
+__device__ __forceinline__ void gather_gemm_dma_body(const DmaArgs& a, const uint32_t nb, const uint32_t b, const uint32_t by) {
     constexpr int NW = WM * WN;                    // waves per workgroup
     constexpr int NT = 64 * NW;
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -110,7 +110,6 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     const int lrow = lane & 31, lh = lane >> 5;
 
     // workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles
-    const uint32_t nb = gridDim.x, b = blockIdx.x;
     const uint32_t q = nb >> 3, r = nb & 7, xcd = b & 7, idx = b >> 3;
     const uint32_t t = (xcd < r) ? xcd * (q + 1) + idx : r * (q + 1) + (xcd - r) * q + idx;
     const uint32_t tiles_n = (g.NC + BN - 1) / BN;
@@ -174,7 +173,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
     // K slabs handled by this workgroup: all of them, or one range of a split-K launch (blockIdx.y)
     const int KT_all = (g.K + 63) / 64;
     const int kps = SPLITK ? (KT_all + g.splits - 1) / g.splits : KT_all;
-    const int kt_begin = SPLITK ? static_cast<int>(blockIdx.y) * kps : 0;
+    const int kt_begin = SPLITK ? static_cast<int>(by) * kps : 0;
     const int KT = (kt_begin + kps < KT_all) ? kt_begin + kps : KT_all;      // end of this range
 
     auto tap_coord = [&](int base, int tap, int step, int div, int limit, int& out) __attribute__((always_inline)) -> bool {
@@ -457,7 +456,7 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 
     if (SPLITK) {
         // raw fp32 partial sums; alpha, scale, shift, residual and ReLU are applied by the reduction kernel
-        float* part = g.partial + static_cast<int64_t>(blockIdx.y) * g.M * g.NC;
+        float* part = g.partial + static_cast<int64_t>(by) * g.M * g.NC;
         const bool v4 = (g.NC % 4 == 0);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -590,6 +589,29 @@ void gather_gemm_dma_kernel(const DmaArgs a) {
 
 // Sums the split-K partials in a fixed order and applies the block tail:
 // y = relu?((0.5*alpha*sum)*scale + shift + residual).  One thread per VEC consecutive output elements.
+template <int BM, int BN, int WM, int WN, int STAGES, bool GEMM, bool SPLITK, bool BUF, int OCC = 0>
+__global__ __launch_bounds__(64 * WM * WN, OCC ? OCC : dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
+void gather_gemm_dma_kernel(const DmaArgs a) {
+    gather_gemm_dma_body<BM, BN, WM, WN, STAGES, GEMM, SPLITK, BUF>(a, gridDim.x, blockIdx.x, blockIdx.y);
+}
+
+// Up to four problems of the same tile shape in one launch (blockIdx.y = problem): the residue classes of a strided
+// backward-data pass, which are too small to be worth a launch each.  The grid is as wide as the largest problem;
+// the surplus workgroups of the others leave at once.
+constexpr int kDmaBatchMax = 4;
+struct DmaBatchArgs {
+    DmaArgs p[kDmaBatchMax];
+    uint32_t blocks[kDmaBatchMax];
+};
+template <int BM, int BN, int WM, int WN, int STAGES, bool BUF>
+__global__ __launch_bounds__(64 * WM * WN, dma_min_blocks(WM * WN, STAGES * (BM * 128 + BN * 16)))
+void gather_gemm_dma_batch_kernel(const DmaBatchArgs ba) {
+    const uint32_t c = blockIdx.y;
+    const uint32_t nb = ba.blocks[c];
+    if (blockIdx.x >= nb) return;           // whole workgroup, before any barrier
+    gather_gemm_dma_body<BM, BN, WM, WN, STAGES, false, false, BUF>(ba.p[c], nb, blockIdx.x, 0u);
+}
+
 template <int VEC>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const GatherGemm g) {
     const int64_t id0 = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) * VEC;
@@ -658,10 +680,7 @@ static int32_t launch_dma_kernel(const DmaArgs& a, int64_t blocks, hipStream_t s
                      : launch_dma_kernel_b<BM, BN, WM, WN, STAGES, GEMM, SPLITK, false, OCC>(a, blocks, st);
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int OCC = 0>
-static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
-    const int64_t blocks = ((g.M + BM - 1) / BM) * ((g.NC + BN - 1) / BN);
-    if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
+static DmaArgs make_dma_args(const GatherGemm& g) {
     DmaArgs a;
     a.g = g;
     a.divIC = make_fastdiv_u(static_cast<uint32_t>(g.IC));
@@ -682,6 +701,14 @@ static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
         a.x_bytes = static_cast<uint32_t>(xb < (1LL << 31) ? xb : 0);
         a.w_bytes = static_cast<uint32_t>(wb < (1LL << 31) ? wb : 0);
     }
+    return a;
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int OCC = 0>
+static int32_t launch_dma_tile(const GatherGemm& g, hipStream_t st) {
+    const int64_t blocks = ((g.M + BM - 1) / BM) * ((g.NC + BN - 1) / BN);
+    if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
+    const DmaArgs a = make_dma_args(g);
     if (g.splits > 1) {
         // the dispatcher splits K only for grids of few 128x128 tiles: no other tile has a split-K build
         if constexpr (BM == 128 && BN == 128 && WM == 2 && WN == 2) {
@@ -713,6 +740,53 @@ extern "C" int32_t twn_debug_set_trace(void* buf) {
     return hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &p, sizeof(p)) == hipSuccess ? 0 : -6;
 }
 #endif
+
+template <int BM, int BN, int WM, int WN, int STAGES, bool BUF>
+static int32_t launch_dma_batch_kernel(const DmaBatchArgs& ba, unsigned width, int count, hipStream_t st) {
+    constexpr int SMEM = STAGES * (BM * 128 + BN * 16);
+    auto k = gather_gemm_dma_batch_kernel<BM, BN, WM, WN, STAGES, BUF>;
+    static std::once_flag once;
+    static bool allowed = false;
+    std::call_once(once, [&] {
+        allowed = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      SMEM) == hipSuccess;
+    });
+    if (!allowed) return TWN_ERR_HIP;
+    k<<<dim3(width, static_cast<unsigned>(count)), dim3(64 * WM * WN), SMEM, st>>>(ba);
+    return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES>
+static int32_t launch_dma_batch_tile(const GatherGemm* gs, int count, hipStream_t st) {
+    DmaBatchArgs ba{};
+    int64_t width = 0;
+    bool buf = true;
+    for (int c = 0; c < count; ++c) {
+        const GatherGemm& g = gs[c];
+        if (g.splits > 1 || g.plain_gemm) return TWN_ERR_UNSUPPORTED;
+        const int64_t blocks = ((g.M + BM - 1) / BM) * ((g.NC + BN - 1) / BN);
+        if (blocks <= 0 || blocks >= (1LL << 31)) return TWN_ERR_SHAPE;
+        ba.p[c] = make_dma_args(g);
+        ba.blocks[c] = static_cast<uint32_t>(blocks);
+        if (blocks > width) width = blocks;
+        buf = buf && ba.p[c].use_buf;
+    }
+    // one build serves all problems of the launch: buffer-descriptor loads only if every problem qualifies
+    return buf ? launch_dma_batch_kernel<BM, BN, WM, WN, STAGES, true>(ba, static_cast<unsigned>(width), count, st)
+               : launch_dma_batch_kernel<BM, BN, WM, WN, STAGES, false>(ba, static_cast<unsigned>(width), count, st);
+}
+
+// `count` <= 4 unsplit convolution problems with the same tile id in one launch.
+int32_t launch_gather_gemm_dma_batch(const GatherGemm* gs, int count, int tile, hipStream_t st) {
+    if (count < 1 || count > kDmaBatchMax) return TWN_ERR_UNSUPPORTED;
+    switch (tile) {
+        case 12: return launch_dma_batch_tile<128, 128, 2, 2, 3>(gs, count, st);
+        case 14: return launch_dma_batch_tile<64, 128, 1, 4, 3>(gs, count, st);
+        case 15: return launch_dma_batch_tile<128, 128, 1, 4, 3>(gs, count, st);
+        case 16: return launch_dma_batch_tile<128, 64, 2, 2, 3>(gs, count, st);
+        default: return TWN_ERR_UNSUPPORTED;
+    }
+}
 
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st) {
     switch (tile) {

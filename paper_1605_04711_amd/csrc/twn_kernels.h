@@ -70,6 +70,10 @@ int32_t launch_scale_channels(const uint16_t* dY, const float* alpha, int rows_p
 int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int ph, int pw, int Hp, int Wp, uint16_t* Xp,
                              const uint32_t* packed, int rows, int R, int S, int Sp, uint32_t* out, hipStream_t st);
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
+// Several small unsplit convolution problems of one tile id in one launch of the one-tile-per-workgroup kernel
+// (count <= 4); gather_gemm_dma_tile names the tile the dispatcher would use for a problem there (0: none).
+int32_t gather_gemm_dma_tile(const GatherGemm& g);
+int32_t launch_gather_gemm_dma_batch(const GatherGemm* gs, int count, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 // Multiplication-free comparison kernel (vector ALUs, zero codes skipped); `applicable` is a pure function of the problem.
 bool conv_addsub_applicable(const GatherGemm& g);

@@ -574,6 +574,11 @@ def test_strided_backward_data_by_residue_classes(ci, knob):
     assert rel_err(to_host_f64(dx32), ref) <= 1e-4
     dxb, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape)
     assert rel_err(to_host_f64(dxb), ref) <= BF16_TOL
+    # one launch per class instead of all classes in one launch: the same bits
+    knob("TWN_DX_CLASS_BATCH", "0")
+    dxs, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape,
+                                       dx_dtype=torch.float32)
+    assert torch.equal(dxs, dx32)
     knob("TWN_DX_CLASSES", "0")
     dxg, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dw=False, x_shape=x.shape,
                                        dx_dtype=torch.float32)
