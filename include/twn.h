@@ -224,6 +224,18 @@ int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weight
                        const float* alpha, const twn_epilogue* ep, void* Y,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* Two convolutions over the SAME input X in one call: the first convolution of a
+ * residual block and its projection shortcut (the ResNet-18 of Sec. 3.1 has three
+ * such block heads).  Results are those of two twn_conv2d_fwd calls (each problem
+ * has its own filters, alpha, geometry, epilogue and output); when both problems
+ * get the same tile shape they run in ONE launch, else one after the other.
+ * Product variant, bf16 in and out, C % 8 == 0 (else TWN_ERR_UNSUPPORTED); d0 and
+ * d1 must agree in N, H, W, C (else TWN_ERR_SHAPE); no workspace is used. */
+int32_t twn_conv2d_fwd_pair(const twn_conv_desc* d0, const twn_conv_desc* d1, const void* X,
+                            const void* weights0, const float* alpha0, const twn_epilogue* ep0, void* Y0,
+                            const void* weights1, const float* alpha1, const twn_epilogue* ep1, void* Y1,
+                            void* stream);
+
 /* ---- 2c. straight-through backward (Alg. 1 steps 9-10) --------------------
  * Ordinary back-propagation with T = alpha W~ in place of W:
  *   dX[n,h,w,c]   = sum_{o,r,s} alpha_o * dY[n,p,q,o] * W~[o,c,r,s]   over the (p,q) that read (h,w)

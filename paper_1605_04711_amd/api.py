@@ -27,7 +27,7 @@ EXPORTS = [
     "twn_ternarize_batch_workspace_bytes", "twn_ternarize_batch",
     "twn_unpack_i8",
     "twn_gemm_fwd_workspace_bytes", "twn_gemm_fwd",
-    "twn_conv2d_fwd_workspace_bytes", "twn_conv2d_fwd",
+    "twn_conv2d_fwd_workspace_bytes", "twn_conv2d_fwd", "twn_conv2d_fwd_pair",
     "twn_conv2d_bwd_ste_workspace_bytes", "twn_conv2d_bwd_ste",
     "twn_sgd_update", "twn_ternarize_presummed",
     "twn_packed1_words_per_row", "twn_binarize_workspace_bytes", "twn_binarize",
@@ -121,6 +121,9 @@ def lib():
         L.twn_conv2d_fwd_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
         L.twn_conv2d_fwd.restype = i32
         L.twn_conv2d_fwd.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, ctypes.POINTER(Epilogue), vp, vp, sz, vp]
+        L.twn_conv2d_fwd_pair.restype = i32
+        L.twn_conv2d_fwd_pair.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(ConvDesc), vp,
+                                          vp, vp, ctypes.POINTER(Epilogue), vp, vp, vp, ctypes.POINTER(Epilogue), vp, vp]
         L.twn_conv2d_bwd_ste_workspace_bytes.restype = sz
         L.twn_conv2d_bwd_ste_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
         L.twn_conv2d_bwd_ste.restype = i32
@@ -510,6 +513,38 @@ def prepare_conv2d_fwd(X, tw, stride=(1, 1), pad=(0, 0), dil=(1, 1), out=None, v
             raise TwnError(rc, "twn_conv2d_fwd")
         return Y
     return call
+
+
+def prepare_conv2d_fwd_pair(X, tws, geos, outs, scales=(None, None), shifts=(None, None), residuals=(None, None),
+                            relus=(False, False)):
+    """Two convolutions over the same bf16 NHWC input in one call (a residual block's first convolution and its
+    projection shortcut): tws, geos = ((stride, pad, dil), ...), outs and the epilogue tuples have two entries."""
+    if not X.is_contiguous() or any(not o.is_contiguous() for o in outs):
+        raise TypeError("X and the outputs must be contiguous NHWC tensors")
+    ds, eps = [], []
+    for tw, (st, pd, dl), Y, sc, sf, rs, rl in zip(tws, geos, outs, scales, shifts, residuals, relus):
+        ds.append(_conv_desc(X.shape, tw, st, pd, dl, _dtype_code(X), _dtype_code(Y), TWN_VAR_BF16_POSTSCALE))
+        eps.append(_epilogue(sc, sf, rs, rl))
+    fn = lib().twn_conv2d_fwd_pair
+    args = (ctypes.byref(ds[0]), ctypes.byref(ds[1]), _ptr(X),
+            _ptr(tws[0].packed), _ptr(tws[0].alpha), None if eps[0] is None else ctypes.byref(eps[0]), _ptr(outs[0]),
+            _ptr(tws[1].packed), _ptr(tws[1].alpha), None if eps[1] is None else ctypes.byref(eps[1]), _ptr(outs[1]))
+    keep = (ds, eps, X, tws, outs, scales, shifts, residuals)
+
+    def call(stream=None, _keep=keep):
+        rc = fn(*args, _stream(stream))
+        if rc != 0:
+            raise TwnError(rc, "twn_conv2d_fwd_pair")
+        return outs
+    return call
+
+
+def twn_conv2d_fwd_pair(X, tws, geos, scales=(None, None), shifts=(None, None), residuals=(None, None),
+                        relus=(False, False), outs=None, stream=None):
+    if outs is None:
+        outs = tuple(torch.empty(conv_out_shape(X.shape, tw, *g), dtype=torch.bfloat16, device=X.device)
+                     for tw, g in zip(tws, geos))
+    return prepare_conv2d_fwd_pair(X, tws, geos, outs, scales, shifts, residuals, relus)(stream)
 
 
 def prepare_gemm_fwd(X, tw, out=None, y_dtype=torch.bfloat16, variant=None, scale=None, shift=None, residual=None,

@@ -417,6 +417,58 @@ extern "C" int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const v
     return dispatch(g, d->variant, workspace, workspace_bytes, as_stream(stream));
 }
 
+// One problem of twn_conv2d_fwd_pair: the checks of twn_conv2d_fwd for the product variant on bf16 tensors whose
+// channel count is a multiple of 8 (no first-layer paths), then the problem descriptor.
+static int32_t build_pair_problem(const twn_conv_desc* d, const void* X, const void* weights, const float* alpha,
+                                  const twn_epilogue* ep, void* Y, GatherGemm* g) {
+    int P, Q;
+    int32_t rc = check_conv_desc(d, &P, &Q);
+    if (rc != TWN_OK) return rc;
+    if (!X || !weights || !alpha || !Y) return TWN_ERR_NULL;
+    if (d->variant != TWN_VAR_BF16_POSTSCALE || d->x_dtype != TWN_BF16 || d->y_dtype != TWN_BF16 || d->C % 8 != 0)
+        return TWN_ERR_UNSUPPORTED;
+    if (!aligned(weights, 16) || !aligned(X, 16)) return TWN_ERR_ALIGN;
+    rc = check_out_align(d->y_dtype, d->O, d->O, Y, ep ? ep->residual : nullptr);
+    if (rc != TWN_OK) return rc;
+    *g = GatherGemm{};
+    g->X = X;
+    g->Wq = weights;
+    g->alpha = alpha;
+    set_epilogue(*g, ep);
+    g->Y = Y;
+    fill_conv_fwd(*g, d, P, Q);
+    g->splits = 1;
+    g->partial = nullptr;
+    return TWN_OK;
+}
+
+extern "C" int32_t twn_conv2d_fwd_pair(const twn_conv_desc* d0, const twn_conv_desc* d1, const void* X,
+                                       const void* weights0, const float* alpha0, const twn_epilogue* ep0, void* Y0,
+                                       const void* weights1, const float* alpha1, const twn_epilogue* ep1, void* Y1,
+                                       void* stream) {
+    if (!d0 || !d1) return TWN_ERR_NULL;
+    if (d0->N != d1->N || d0->H != d1->H || d0->W != d1->W || d0->C != d1->C) return TWN_ERR_SHAPE;
+    GatherGemm g[2];
+    int32_t rc = build_pair_problem(d0, X, weights0, alpha0, ep0, Y0, &g[0]);
+    if (rc == TWN_OK) rc = build_pair_problem(d1, X, weights1, alpha1, ep1, Y1, &g[1]);
+    if (rc != TWN_OK) return rc;
+    hipStream_t st = as_stream(stream);
+    const int t0 = gather_gemm_dma_tile(g[0], true), t1 = gather_gemm_dma_tile(g[1], true);
+    // One launch pays while the reduction is short: with more than 24 slabs per tile the persistent kernels with load
+    // waves win back more than the saved launch (ResNet-18 b64 block heads, two launches -> one: 128 filters, K = 576:
+    // 23.4 -> 19.1 us; 256 filters, K = 1152: 17.9 -> 15.9 us; 512 filters, K = 2304: 18.2 -> 19.3 us).
+    const int64_t kmax = g[0].K > g[1].K ? g[0].K : g[1].K;
+    const int pair_knob = env_int("TWN_FWD_PAIR", 1);          // 0: never one launch, 2: whenever the tiles agree
+    if (t0 != 0 && t0 == t1 && (pair_knob == 2 || (pair_knob == 1 && kmax <= 1536))) {
+        rc = launch_gather_gemm_dma_batch(g, 2, t0, st);
+        if (rc != TWN_ERR_UNSUPPORTED) return rc;
+    }
+    // different tile shapes (or no build for the pair): one after the other, as two twn_conv2d_fwd calls without a workspace
+    rc = dispatch(g[0], d0->variant, nullptr, 0, st, false);
+    if (rc != TWN_OK) return rc;
+    return dispatch(g[1], d1->variant, nullptr, 0, st, false);
+}
+
 extern "C" size_t twn_conv2d_bwd_ste_workspace_bytes(const twn_conv_desc* d) {
     int P, Q;
     if (check_conv_desc(d, &P, &Q) != TWN_OK) return 0;

@@ -523,10 +523,11 @@ int32_t gather_gemm_splits(const GatherGemm& g) {
 }
 
 // Tile id launch_gather_gemm_mfma would give an unsplit problem in the one-tile-per-workgroup direct-to-LDS kernel,
-// or 0 when the problem would not run there (scalar gathers, forced tiles, persistent kernels).
-int32_t gather_gemm_dma_tile(const GatherGemm& g) {
+// or 0 when the problem would not run there (scalar gathers, forced tiles; persistent kernels unless
+// `instead_of_persistent` asks for the tile the problem would get if they did not exist).
+int32_t gather_gemm_dma_tile(const GatherGemm& g, bool instead_of_persistent) {
     if (gather_mode(g) == kModeScalar || env_int("TWN_TILE", 0) != 0 || g.splits > 1) return 0;
-    if (env_int("TWN_STREAM", 1) != 0 && conv_stream_applicable(g)) return 0;
+    if (!instead_of_persistent && env_int("TWN_STREAM", 1) != 0 && conv_stream_applicable(g)) return 0;
     auto blocks = [&](int bm, int bn) { return ((g.M + bm - 1) / bm) * ((g.NC + bn - 1) / bn); };
     int tile;
     if (g.NC <= 64) tile = 16;

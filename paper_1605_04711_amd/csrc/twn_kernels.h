@@ -72,7 +72,7 @@ int32_t launch_pad_repack_c4(const uint16_t* X, int N, int H, int W, int C, int 
 int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
 // Several small unsplit convolution problems of one tile id in one launch of the one-tile-per-workgroup kernel
 // (count <= 4); gather_gemm_dma_tile names the tile the dispatcher would use for a problem there (0: none).
-int32_t gather_gemm_dma_tile(const GatherGemm& g);
+int32_t gather_gemm_dma_tile(const GatherGemm& g, bool instead_of_persistent = false);
 int32_t launch_gather_gemm_dma_batch(const GatherGemm* gs, int count, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
 // Multiplication-free comparison kernel (vector ALUs, zero codes skipped); `applicable` is a pure function of the problem.

@@ -108,6 +108,21 @@ def test_gemm_and_conv_argument_errors():
     assert L.twn_conv2d_fwd(ctypes.byref(bad), FAKE, FAKE, FAKE, None, FAKE, None, 0, None) == -2
     assert L.twn_conv2d_fwd(ctypes.byref(c), FAKE, ODD, FAKE, None, FAKE, None, 0, None) == -3
 
+    # two convolutions over one input: both descriptors are checked before any launch
+    c3 = api.ConvDesc(2, 8, 8, 16, 32, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1, 0, 1)
+    c1 = api.ConvDesc(2, 8, 8, 16, 32, 1, 1, 2, 2, 0, 0, 1, 1, 1, 1, 0, 1)
+    pair = lambda a, b, x=FAKE, w0=FAKE, y1=FAKE: L.twn_conv2d_fwd_pair(
+        ctypes.byref(a), ctypes.byref(b), x, w0, FAKE, None, FAKE, FAKE, FAKE, None, y1, None)
+    assert pair(c3, c1, x=None) == -1
+    assert pair(c3, c1, y1=None) == -1
+    other = api.ConvDesc(2, 8, 8, 32, 32, 1, 1, 2, 2, 0, 0, 1, 1, 1, 1, 0, 1)            # another channel count
+    assert pair(c3, other) == -2
+    c12 = api.ConvDesc(2, 8, 8, 12, 32, 1, 1, 2, 2, 0, 0, 1, 1, 1, 1, 0, 1)             # C % 8 != 0
+    assert pair(c12, c12) == -4
+    f32 = api.ConvDesc(2, 8, 8, 16, 32, 1, 1, 2, 2, 0, 0, 1, 1, api.TWN_F32, api.TWN_F32, api.TWN_VAR_FP32, 1)
+    assert pair(c3, f32) == -4
+    assert pair(c3, c1, w0=ODD) == -3
+
     ws = L.twn_conv2d_bwd_ste_workspace_bytes(ctypes.byref(c))
     assert ws > 0
     f0 = ctypes.c_float(0.0)

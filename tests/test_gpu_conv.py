@@ -253,6 +253,42 @@ def test_conv2d_fwd_fused_block_tail():
     assert rel_err(to_host_f64(y), oc.epilogue(ref0, scale, shift, res, relu=True)) <= BF16_TOL
 
 
+PAIR_CASES = [   # x shape, O of the 3x3 / stride-2 convolution, O of the 1x1 / stride-2 shortcut
+    ((4, 28, 28, 64), 128, 128),       # same tile shape: one launch; 784 pixels leave a ragged last tile
+    ((3, 14, 14, 128), 256, 256),
+    ((2, 13, 9, 72), 136, 136),        # odd image, C % 64 != 0 (per-lane pointer loads), ragged channel tile
+    ((2, 16, 16, 64), 64, 128),        # different tile shapes: one launch after the other
+]
+
+
+@pytest.mark.parametrize("one_launch", [2, 0])
+@pytest.mark.parametrize("ci", range(len(PAIR_CASES)))
+def test_conv2d_fwd_pair(ci, one_launch, knob):
+    """A residual block's first convolution and its projection shortcut over the same input (Sec. 3.1's ResNet-18
+    has three such block heads), each against the oracle and against its own twn_conv2d_fwd call."""
+    knob("TWN_FWD_PAIR", str(one_launch))
+    xs, o0, o1 = PAIR_CASES[ci]
+    c = xs[3]
+    x, _, tw0, codes0, alpha0 = make_layer(700 + ci, xs, (o0, c, 3, 3), groups=o0 if ci == 1 else 1)
+    _, _, tw1, codes1, alpha1 = make_layer(720 + ci, xs, (o1, c, 1, 1))
+    g = np.random.default_rng(40 + ci)
+    sc0, sf0 = g.uniform(0.5, 1.5, o0).astype(np.float32), g.standard_normal(o0).astype(np.float32)
+    sc1, sf1 = g.uniform(0.5, 1.5, o1).astype(np.float32), g.standard_normal(o1).astype(np.float32)
+    geos = (((2, 2), (1, 1), (1, 1)), ((2, 2), (0, 0), (1, 1)))
+    xd = to_dev_bf16(x)
+    y0, y1 = api.twn_conv2d_fwd_pair(xd, (tw0, tw1), geos, scales=(to_dev_f32(sc0), to_dev_f32(sc1)),
+                                     shifts=(to_dev_f32(sf0), to_dev_f32(sf1)), relus=(True, False))
+    ref0 = oc.epilogue(oc.conv2d_fwd(x, codes0, alpha0, *geos[0]), sc0, sf0, None, relu=True)
+    ref1 = oc.epilogue(oc.conv2d_fwd(x, codes1, alpha1, *geos[1]), sc1, sf1, None, relu=False)
+    assert tuple(y0.shape) == ref0.shape and tuple(y1.shape) == ref1.shape
+    assert rel_err(to_host_f64(y0), ref0) <= BF16_TOL
+    assert rel_err(to_host_f64(y1), ref1) <= BF16_TOL
+    s0 = api.twn_conv2d_fwd(xd, tw0, *geos[0], scale=to_dev_f32(sc0), shift=to_dev_f32(sf0), relu=True)
+    s1 = api.twn_conv2d_fwd(xd, tw1, *geos[1], scale=to_dev_f32(sc1), shift=to_dev_f32(sf1), relu=False)
+    assert rel_err(to_host_f64(y0), to_host_f64(s0)) <= 1e-2      # a bf16 ulp: the K order may differ between kernels
+    assert rel_err(to_host_f64(y1), to_host_f64(s1)) <= 1e-2
+
+
 @pytest.mark.parametrize("batch", [8, 64])
 def test_lenet_layers_fp32(batch):
     for li, layer in enumerate(wl.lenet5(batch)):
