@@ -551,6 +551,8 @@ int32_t launch_gather_gemm_mfma(const GatherGemm& g, int variant, hipStream_t st
 
     // Tile choice: the largest tile that still gives every CU work; narrow N tiles for narrow layers.
     int tile = env_int("TWN_TILE", 0);
+    // 3x3 stride-1 layers over 64 channels: weights resident in registers, input patches with halo in LDS
+    if (tile == 0 && env_int("TWN_C64", 1) != 0 && conv_c64_applicable(g)) return launch_conv_c64(g, st);
     if (mode != kModeScalar && (tile == 0 || tile > 10)) {
         // multi-stage direct-to-LDS kernel
         if (tile == 0) {

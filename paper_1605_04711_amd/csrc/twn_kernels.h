@@ -86,6 +86,12 @@ bool conv_stream_applicable(const GatherGemm& g);
 int32_t launch_conv_stream(const GatherGemm& g, int tile, hipStream_t st);
 int32_t launch_conv_stream_pc(const GatherGemm& g, int tile, int ks, int np, int stages, hipStream_t st);
 
+// 3x3 stride-1 convolutions over 64 input channels (forward, or backward-data with mirrored taps), bf16 in and out,
+// output channels a multiple of 64: persistent kernel with the expanded weights resident in registers and the input
+// patch of an 8x8 pixel tile (with halo) in LDS; `applicable` is a pure function of the problem.
+bool conv_c64_applicable(const GatherGemm& g);
+int32_t launch_conv_c64(const GatherGemm& g, hipStream_t st);
+
 // First layers with three input channels, bf16 in and out, dilation 1 (forward): one persistent kernel, no
 // workspace and no preparation launch; `applicable` is a pure function of the problem (shapes and alignment).
 struct FirstLayer {

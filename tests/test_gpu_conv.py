@@ -729,3 +729,65 @@ def test_first_layer_kernel_matches_generic_path(knob):
     ref = oc.conv2d_fwd(x, codes, alpha, st, pd, (1, 1))
     assert rel_err(to_host_f64(y0), ref) <= BF16_TOL and rel_err(to_host_f64(y1), ref) <= BF16_TOL
     assert rel_err(to_host_f64(y1), to_host_f64(y0)) <= BF16_TOL
+
+
+C64_CASES = [
+    # N  H   W   O    pad     (C = 64, 3x3, stride 1: weights resident in registers, 8x8 pixel tiles with halo in LDS)
+    (3, 17, 19, 64, (1, 1)),        # ragged tiles in both directions
+    (2, 16, 24, 128, (1, 1)),       # two channel tiles, whole pixel tiles
+    (5, 8, 8, 64, (1, 1)),          # one tile per image
+    (2, 20, 33, 64, (0, 2)),        # output smaller / larger than the input
+    (1, 7, 5, 192, (2, 0)),
+    (24, 40, 36, 64, (1, 1)),       # 600 tiles: more than the resident workgroups, so some walk two tiles
+]
+
+
+@pytest.mark.parametrize("ci", range(len(C64_CASES)))
+def test_resident_weight_3x3_kernel_forward(ci):
+    n, h, w_, o, pd = C64_CASES[ci]
+    st = dl = (1, 1)
+    groups = o if ci % 2 else 1
+    x, w, tw, codes, alpha = make_layer(900 + ci, (n, h, w_, 64), (o, 64, 3, 3), groups=groups)
+    g = np.random.default_rng(ci)
+    scale = g.uniform(0.5, 1.5, o).astype(np.float32)
+    shift = g.standard_normal(o).astype(np.float32)
+    ref0 = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl)
+    assert tuple(y.shape) == ref0.shape
+    assert rel_err(to_host_f64(y), ref0) <= BF16_TOL
+    res = wl.bf16_round(g.standard_normal(ref0.shape).astype(np.float32))
+    y2 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, scale=to_dev_f32(scale), shift=to_dev_f32(shift),
+                            residual=to_dev_bf16(res), relu=True)
+    assert rel_err(to_host_f64(y2), oc.epilogue(ref0, scale, shift, res, relu=True)) <= BF16_TOL
+
+
+@pytest.mark.parametrize("ci", range(len(C64_CASES)))
+def test_resident_weight_3x3_kernel_backward_data(ci):
+    # the data gradient of a layer with 64 FILTERS is the same kind of problem over dY (mirrored taps, transposed codes)
+    n, h, w_, c, pd = C64_CASES[ci]
+    st = dl = (1, 1)
+    x, w, tw, codes, alpha = make_layer(930 + ci, (n, h, w_, c), (64, c, 3, 3), transposed=True)
+    p, q = h + 2 * pd[0] - 2, w_ + 2 * pd[1] - 2
+    dy = wl.bf16_round(np.random.default_rng(ci).standard_normal((n, p, q, 64)).astype(np.float32))
+    dx, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dx=True, need_dw=False,
+                                      x_shape=(n, h, w_, c))
+    assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, (n, h, w_, c), st, pd, dl)) <= BF16_TOL
+
+
+def test_resident_weight_3x3_kernel_long_tile_walks(knob):
+    knob("TWN_C64_OCC", "1")          # half the workgroups: two to three tiles each
+    n, h, w_, o, pd = C64_CASES[5]
+    x, w, tw, codes, alpha = make_layer(950, (n, h, w_, 64), (o, 64, 3, 3))
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, (1, 1), pd, (1, 1))
+    assert rel_err(to_host_f64(y), oc.conv2d_fwd(x, codes, alpha, (1, 1), pd, (1, 1))) <= BF16_TOL
+
+
+def test_resident_weight_3x3_kernel_matches_generic_path(knob):
+    n, h, w_, o, pd = C64_CASES[0]
+    x, w, tw, codes, alpha = make_layer(960, (n, h, w_, 64), (o, 64, 3, 3))
+    y1 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, (1, 1), pd, (1, 1), relu=True)
+    knob("TWN_C64", "0")
+    y0 = api.twn_conv2d_fwd(to_dev_bf16(x), tw, (1, 1), pd, (1, 1), relu=True)
+    ref = oc.epilogue(oc.conv2d_fwd(x, codes, alpha, (1, 1), pd, (1, 1)), relu=True)
+    assert rel_err(to_host_f64(y0), ref) <= BF16_TOL and rel_err(to_host_f64(y1), ref) <= BF16_TOL
+    assert rel_err(to_host_f64(y1), to_host_f64(y0)) <= BF16_TOL
