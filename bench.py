@@ -568,7 +568,7 @@ def main():
         Ls = layers[i0]
         n_launch = i1 - i0 + 1
         r_tf = sum(layers[i].flops for i in range(i0, i1 + 1)) / (span_ms * 1e-3) / 1e12
-        roof = roof_obj("conv_stream_kernel (layer1 3x3 convolutions, 64 -> 64 channels, 56x56)", "mfma", r_tf,
+        roof = roof_obj("conv_c64_kernel (layer1 3x3 convolutions, 64 -> 64 channels, 56x56)", "mfma", r_tf,
                         PEAK_BF16_TFLOPS, "TFLOP/s", layer_bytes(Ls), "resnet18_b64_forward_kernels.txt",
                         span_ms * 1e3 / n_launch, launches_per_step=n_launch, flops_per_launch=Ls.flops,
                         calls="fwd " + " ".join(ROOFLINE_LAYERS) + " (one launch each)",

@@ -51,7 +51,6 @@ struct C64Args {
     uint32_t tiles, tiles_x, tiles_y;
     FastDivU divTX, divTY;
     uint32_t x_bytes, y_bytes;      // sizes of X and of the output / residual tensor
-    int32_t through;                // 1: output stores are written through (sc1)
 };
 
 // FLIP: the taps run against the pixel order (backward-data: input row = output row + pad - r)
@@ -88,6 +87,7 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
     const uint32_t n_my = (count_x - j + gx - 1) / gx;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.X, a.x_bytes);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.Y, a.y_bytes);
     const __amdgpu_buffer_rsrc_t rr_desc = make_rsrc(RES ? a.residual : a.X, RES ? a.y_bytes : 0u);
     struct Tile {
         int img, p0, q0;
@@ -120,14 +120,14 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
         loff[it] = static_cast<uint32_t>(y * kC64RowB + x * kC64PixB + c * 16);
     }
     u32x4 pr[kC64Nit];
-    auto load_patch = [&](const Tile& t) __attribute__((always_inline)) {
+    auto load_patch = [&](const Tile& t, bool live) __attribute__((always_inline)) {
         const int y0 = t.p0 + a.y0off, x0 = t.q0 + a.x0off;
         // 32-bit wrapping arithmetic: the offset of every chunk that lies inside the image is in [0, x_bytes);
         // a chunk outside the image (the zero border) gets an offset past the descriptor and reads zeros
         const uint32_t base = ((static_cast<uint32_t>(t.img) * a.H + static_cast<uint32_t>(y0)) * a.W + static_cast<uint32_t>(x0)) * 128u;
 #pragma unroll
         for (int it = 0; it < kC64Nit; ++it) {
-            const bool ok = (static_cast<unsigned>(y0 + py[it]) < static_cast<unsigned>(a.H)) &
+            const bool ok = live & (static_cast<unsigned>(y0 + py[it]) < static_cast<unsigned>(a.H)) &
                             (static_cast<unsigned>(x0 + px[it]) < static_cast<unsigned>(a.W));
             pr[it] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? base + goff[it] : kBufOutside, 0, 0));
         }
@@ -146,17 +146,31 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
     f32x16 acc;
     unsigned char* stg = stg_base + wave * (32 * 80);
     // read-back lane (it): staged row it*16 + lane/4 = tile pixel (wm*4 + row/8, row%8), 16-byte chunk lane&3;
-    // its element offset in Y relative to the tile's first pixel and channel n0
+    // its byte offset in Y relative to the tile's first pixel and channel n0
     uint32_t yoff[2];
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int row = it * 16 + (lane >> 2);
-        yoff[it] = (static_cast<uint32_t>(wm * 4 + (row >> 3)) * a.Q + static_cast<uint32_t>(row & 7)) * a.ldy +
-                   static_cast<uint32_t>(wn * 32 + (lane & 3) * 8);
+        yoff[it] = ((static_cast<uint32_t>(wm * 4 + (row >> 3)) * a.Q + static_cast<uint32_t>(row & 7)) * a.ldy +
+                    static_cast<uint32_t>(wn * 32 + (lane & 3) * 8)) * 2u;
     }
 
+    // Order of the vector-memory operations per tile i: MFMA loop; wait for everything in flight; patch i+1
+    // registers -> LDS; request patch i+2; epilogue arithmetic; request the residual values of tile i+1; output
+    // stores of tile i; barrier.  The one wait of an iteration sits behind a whole MFMA loop, so the stores it
+    // covers (tile i-1) have had a tile's time to complete.
+    auto load_residual = [&](const Tile& t, u32x2* dst, bool live) __attribute__((always_inline)) {
+        // accumulator layout: lane (pixel, k half lh) adds to channels q4*8 + lh*4 .. + 3
+        const int p = t.p0 + wm * 4 + (lrow >> 3), q = t.q0 + (lrow & 7);
+        const bool pix_ok = live & (p < a.P) & (q < a.Q);
+        const uint32_t ro = ((static_cast<uint32_t>(t.img) * a.P + static_cast<uint32_t>(p)) * a.Q + static_cast<uint32_t>(q)) *
+                                static_cast<uint32_t>(a.ldy) * 2u + static_cast<uint32_t>(n0 + wn * 32 + lh * 4) * 2u;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+            dst[q4] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rr_desc, pix_ok ? ro + q4 * 16u : kBufOutside, 0, 0));
+    };
     Tile cur = tile_of(0);
-    load_patch(cur);            // in flight while the weight fragments are built
+    load_patch(cur, true);      // in flight while the weight fragments are built
 
     // ---- once per workgroup: the weight fragments of this wave's 32 channels, all 36 steps -------------------
     // Step ks covers k = 16 ks .. 16 ks + 15, i.e. packed word ks of the channel's row; lane (channel lrow, half lh)
@@ -178,28 +192,21 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
         }
     }
 
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     store_patch(smem);
-    __syncthreads();
+    // Every request of the loop is issued unconditionally (a tile past the end of the walk gets offsets outside the
+    // descriptor: no memory traffic, zeros back): straight-line code without divergent paths around the requests.
+    Tile nxt = tile_of(1);
+    load_patch(nxt, n_my > 1);
+    u32x2 rres[4];
+    if constexpr (RES) load_residual(cur, rres, true);
+    // the first patch and the column parameters are in LDS (a bare barrier: the requests just issued stay in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     int buf = 0;
     for (uint32_t i = 0; i < n_my; ++i) {
-        const bool more = (i + 1 < n_my);
-        Tile nxt = cur;
-        if (more) {
-            nxt = tile_of(i + 1);
-            load_patch(nxt);
-        }
-        // residual values of the current tile in accumulator layout: lane (pixel, k half lh) adds to channels
-        // q4*8 + lh*4 .. + 3; requested here, consumed after the MFMA loop
-        u32x2 rres[4];
-        if constexpr (RES) {
-            const int p = cur.p0 + wm * 4 + (lrow >> 3), q = cur.q0 + (lrow & 7);
-            const bool pix_ok = (p < a.P) & (q < a.Q);
-            const uint32_t ro = ((static_cast<uint32_t>(cur.img) * a.P + static_cast<uint32_t>(p)) * a.Q + static_cast<uint32_t>(q)) *
-                                    static_cast<uint32_t>(a.ldy) * 2u + static_cast<uint32_t>(n0 + wn * 32 + lh * 4) * 2u;
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                rres[q4] = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rr_desc, pix_ok ? ro + q4 * 16u : kBufOutside, 0, 0));
-        }
+        const bool more = (i + 1 < n_my), more2 = (i + 2 < n_my);
         const uint32_t pb = lds_base + static_cast<uint32_t>(buf * kC64Patch + pbase);
         {
             // Step ks = tap * 4 + cq reads the 16 channels 16 cq .. 16 cq + 15 of the pixel one tap away: the whole
@@ -228,9 +235,14 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
                                                               __builtin_bit_cast(bf16x8, af[ks % RING]), c_in, 0, 0, 0);
             });
         }
-        // the next patch goes to the other buffer BEFORE the epilogue's stores are issued: waiting for its loads
-        // must not mean waiting for those stores
-        if (more) store_patch(smem + (buf ^ 1) * kC64Patch);
+        // Everything this wave has requested so far (patch i+1, the residual values of tile i, the stores of tile
+        // i-1) is complete before the registers are used: a full wait instead of counted ones, because a request
+        // whose lanes all lie outside the tensor touches no memory and may be answered ahead of older requests,
+        // which would let a counted wait for those pass early.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        store_patch(smem + (buf ^ 1) * kC64Patch);
+        const Tile nn = tile_of(i + 2);
+        load_patch(nn, more2);
         // ---- epilogue: accumulator element e in this lane: tile pixel (wm*4 + (lrow>>3), lrow & 7),
         // channel wn*32 + (e>>2)*8 + lh*4 + (e&3) ----
         {
@@ -259,24 +271,19 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
                 *reinterpret_cast<u32x2*>(stg + lrow * 80 + (q4 * 8 + lh * 4) * 2) = pk;
             }
         }
+        if constexpr (RES) load_residual(nxt, rres, more);
         // same wave wrote and reads: LDS executes a wave's operations in order
         {
             u32x4 val[2];
 #pragma unroll
             for (int it = 0; it < 2; ++it) val[it] = *reinterpret_cast<const u32x4*>(stg + (it * 16 + (lane >> 2)) * 80 + (lane & 3) * 16);
-            uint16_t* ytile = a.Y + ((static_cast<int64_t>(cur.img) * a.P + cur.p0) * a.Q + cur.q0) * a.ldy + n0;   // wave-uniform
-            const bool full = cur.p0 + kC64Tile <= a.P && cur.q0 + kC64Tile <= a.Q;                                  // wave-uniform
+            const uint32_t ytile = (((static_cast<uint32_t>(cur.img) * a.P + static_cast<uint32_t>(cur.p0)) * a.Q +
+                                     static_cast<uint32_t>(cur.q0)) * static_cast<uint32_t>(a.ldy) + static_cast<uint32_t>(n0)) * 2u;   // wave-uniform
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
-                bool ok = true;
-                if (!full) {
-                    const int row = it * 16 + (lane >> 2);
-                    ok = cur.p0 + wm * 4 + (row >> 3) < a.P && cur.q0 + (row & 7) < a.Q;
-                }
-                if (ok) {
-                    if (a.through) store16_through(ytile + yoff[it], val[it]);
-                    else *reinterpret_cast<u32x4*>(ytile + yoff[it]) = val[it];
-                }
+                const int row = it * 16 + (lane >> 2);
+                const bool ok = (cur.p0 + wm * 4 + (row >> 3) < a.P) & (cur.q0 + (row & 7) < a.Q);
+                __builtin_amdgcn_raw_buffer_store_b128(val[it], ry, ok ? yoff[it] : kBufOutside, ytile, kStoreThrough);
             }
         }
         // The next patch is complete (this wave's LDS writes have landed) and every wave is done with the current
@@ -287,6 +294,7 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
         asm volatile("" ::: "memory");
         buf ^= 1;
         cur = nxt;
+        nxt = nn;
     }
 }
 
@@ -325,9 +333,8 @@ static bool c64_plan(const GatherGemm& g, C64Args* a) {
     a->divTY = make_fastdiv_u(a->tiles_y);
     a->x_bytes = static_cast<uint32_t>(xb);
     const int64_t yb = g.M * g.ldy * 2;
-    if (g.residual && yb >= (1LL << 31)) return false;
-    a->y_bytes = static_cast<uint32_t>(yb < (1LL << 31) ? yb : 0);
-    a->through = env_int("TWN_C64_THROUGH", 1) != 0 ? 1 : 0;
+    if (yb >= (1LL << 31)) return false;
+    a->y_bytes = static_cast<uint32_t>(yb);
     return true;
 }
 
