@@ -567,12 +567,15 @@ def main():
 
         Ls = layers[i0]
         n_launch = i1 - i0 + 1
+        # the second convolution of a block also reads the residual tensor (as large as its output): averaged over the launches
+        res_bytes = sum(2 * layers[i].N * layers[i].P * layers[i].Q * layers[i].O
+                        for i in range(i0, i1 + 1) if layers[i].name.endswith("conv2")) // n_launch
         r_tf = sum(layers[i].flops for i in range(i0, i1 + 1)) / (span_ms * 1e-3) / 1e12
         roof = roof_obj("conv_c64_kernel (layer1 3x3 convolutions, 64 -> 64 channels, 56x56)", "mfma", r_tf,
-                        PEAK_BF16_TFLOPS, "TFLOP/s", layer_bytes(Ls), "resnet18_b64_forward_kernels.txt",
+                        PEAK_BF16_TFLOPS, "TFLOP/s", layer_bytes(Ls) + res_bytes, "resnet18_b64_forward_kernels.txt",
                         span_ms * 1e3 / n_launch, launches_per_step=n_launch, flops_per_launch=Ls.flops,
                         calls="fwd " + " ".join(ROOFLINE_LAYERS) + " (one launch each)",
-                        hbm_bound_us=round(layer_bytes(Ls) / PEAK_HBM_GBPS / 1e3, 2))
+                        hbm_bound_us=round((layer_bytes(Ls) + res_bytes) / PEAK_HBM_GBPS / 1e3, 2))
         # the other kernel templates of the forward, from the per-layer pass (each layer looped alone, 100 launches)
         tmap = dict(rows)
         layer_roofs = []

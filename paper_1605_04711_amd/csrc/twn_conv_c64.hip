@@ -236,9 +236,10 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
             });
         }
         // Everything this wave has requested so far (patch i+1, the residual values of tile i, the stores of tile
-        // i-1) is complete before the registers are used: a full wait instead of counted ones, because a request
-        // whose lanes all lie outside the tensor touches no memory and may be answered ahead of older requests,
-        // which would let a counted wait for those pass early.
+        // i-1) is complete before the registers are used: one full wait instead of counted ones.  Counted waits
+        // would rest on requests being answered in issue order also when all lanes of a request fall outside the
+        // tensor and no memory is touched; the full wait needs no such assumption and sits behind a whole MFMA
+        // loop, so it costs nothing measurable with two workgroups per CU.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         store_patch(smem + (buf ^ 1) * kC64Patch);
         const Tile nn = tile_of(i + 2);
@@ -283,7 +284,9 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
             for (int it = 0; it < 2; ++it) {
                 const int row = it * 16 + (lane >> 2);
                 const bool ok = (cur.p0 + wm * 4 + (row >> 3) < a.P) & (cur.q0 + (row & 7) < a.Q);
-                __builtin_amdgcn_raw_buffer_store_b128(val[it], ry, ok ? yoff[it] : kBufOutside, ytile, kStoreThrough);
+                // no scalar-offset field (the compiler adds no wait state after that form of a 16-byte store, and an
+                // overwrite of the data registers in the next instruction then reaches memory)
+                __builtin_amdgcn_raw_buffer_store_b128(val[it], ry, ok ? yoff[it] + ytile : kBufOutside, 0, kStoreThrough);
             }
         }
         // The next patch is complete (this wave's LDS writes have landed) and every wave is done with the current

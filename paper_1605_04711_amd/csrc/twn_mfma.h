@@ -61,7 +61,9 @@ constexpr uint32_t kBufOutside = 0x80000000u;   // voffset of a lane that must r
 constexpr int kStoreThrough = 16;
 // The same policy for a 16-byte store through a plain pointer (outputs addressed with 64-bit offsets).
 __device__ __forceinline__ void store16_through(void* p, const u32x4& v) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    // the wait states ride in the same statement: the compiler cannot see that this is a store of more than 8 bytes, so
+    // it would not keep the next instruction from overwriting the data registers while they are still being read
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 
 }  // namespace twn

@@ -138,7 +138,11 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[MI][NI], con
                 const int c16 = lane % LPR;
                 const u32x4 val = *reinterpret_cast<const u32x4*>(stg + row * EPI_ROW + c16 * 16);
                 const bool ok = FULL || (mi * 32 + row < rows_in && nc * EPI_CH + c16 * 8 < cols_in);
-                __builtin_amdgcn_raw_buffer_store_b128(val, ry, ok ? L.st_off[it] : kBufOutside, so, kStoreThrough);
+                // The tile offset is added to the lane offset instead of travelling in the scalar-offset field: for a
+                // store of more than 8 bytes with a scalar offset the compiler adds no wait state before an
+                // instruction that overwrites the data registers, and on this part such an overwrite in the very
+                // next instruction was seen to reach memory in place of the first data dword.
+                __builtin_amdgcn_raw_buffer_store_b128(val, ry, ok ? L.st_off[it] + so : kBufOutside, 0, kStoreThrough);
             }
         }
     }

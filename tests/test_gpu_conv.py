@@ -791,3 +791,27 @@ def test_resident_weight_3x3_kernel_matches_generic_path(knob):
     ref = oc.epilogue(oc.conv2d_fwd(x, codes, alpha, (1, 1), pd, (1, 1)), relu=True)
     assert rel_err(to_host_f64(y0), ref) <= BF16_TOL and rel_err(to_host_f64(y1), ref) <= BF16_TOL
     assert rel_err(to_host_f64(y1), to_host_f64(y0)) <= BF16_TOL
+
+
+@pytest.mark.parametrize("name", ["l1.0.conv1", "l1.0.conv2", "l2.0.conv2", "l3.0.conv2", "l4.1.conv2", "stem"])
+def test_full_size_layers_are_identical_run_to_run(name):
+    """Every output element is written, with the same bits, on every run (a 16-byte store whose data registers were
+    overwritten one instruction later once left a few pixels per launch with an address in place of data)."""
+    layers = {L.name: (li, L) for li, L in enumerate(wl.resnet18(64))}
+    li, L = layers[name]
+    g = torch.Generator(device="cuda").manual_seed(li)
+    x = torch.randn(L.x_shape, device="cuda", generator=g).to(torch.bfloat16)
+    tw = api.twn_ternarize(to_dev_f32(wl.kaiming_weights(2, li, L)), F)
+    res = torch.randn(L.y_shape, device="cuda", generator=g).to(torch.bfloat16) if name.endswith("conv2") else None
+    y = torch.empty(L.y_shape, dtype=torch.bfloat16, device="cuda")
+    call = api.prepare_conv2d_fwd(x, tw, (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2, out=y, residual=res, relu=True)
+    y.fill_(-7.0)
+    call()
+    torch.cuda.synchronize()
+    ref = y.clone()
+    for fill in (0.0, -7.0, 3.0, 0.0, -7.0, 3.0, 0.0, -7.0):
+        y.fill_(fill)
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref)
+    assert float(ref.min()) >= 0.0          # ReLU everywhere: no fill value left
