@@ -815,3 +815,25 @@ def test_full_size_layers_are_identical_run_to_run(name):
         torch.cuda.synchronize()
         assert torch.equal(y, ref)
     assert float(ref.min()) >= 0.0          # ReLU everywhere: no fill value left
+
+
+@pytest.mark.parametrize("name", ["l1.0.conv1", "l2.0.conv1", "l3.1.conv2", "l4.0.down"])
+def test_full_size_backward_is_identical_run_to_run(name):
+    layers = {L.name: (li, L) for li, L in enumerate(wl.resnet18(64))}
+    li, L = layers[name]
+    g = torch.Generator(device="cuda").manual_seed(100 + li)
+    x = torch.randn(L.x_shape, device="cuda", generator=g).to(torch.bfloat16)
+    dy = torch.randn(L.y_shape, device="cuda", generator=g).to(torch.bfloat16)
+    tw = api.twn_ternarize(to_dev_f32(wl.kaiming_weights(2, li, L)), F, transposed=True)
+    geo = ((L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2)
+    dx = torch.empty(L.x_shape, dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((L.O, L.C, L.R, L.S), dtype=torch.float32, device="cuda")
+    ref = None
+    for fill in (0.0, -7.0, 3.0, 0.0, -7.0, 3.0):
+        dx.fill_(fill)
+        dw.fill_(fill)
+        api.twn_conv2d_bwd_ste(x, dy, tw, *geo, dX=dx, dW=dw)
+        torch.cuda.synchronize()
+        if ref is None:
+            ref = (dx.clone(), dw.clone())
+        assert torch.equal(dx, ref[0]) and torch.equal(dw, ref[1])
