@@ -6,8 +6,8 @@
 //   * persistent workgroups walk 8x16 tiles of output pixels; for each tile the input patch with its halo
 //     ((8-1)*stride+R rows) is read ONCE from global memory, two pixels (12 bytes, dword aligned because
 //     patches start at even columns) per lane, widened to 4 channels on the way into LDS (8 bytes per pixel:
-//     every tap pair is then one aligned 16-byte fragment), and the next tile's patch is in flight in
-//     registers while the current one is multiplied;
+//     every tap pair is then one aligned 16-byte fragment), and the patch of tile i+2 is requested
+//     during tile i (in flight in registers while tile i+1 is multiplied);
 //   * K is re-ordered to (filter row, tap, 4 channels) with the taps of a row padded to a multiple of four
 //     (7 -> 8 for the stem, 3 -> 4 for 3x3): one MFMA step covers four taps of one filter row.  The codes of
 //     the phantom tap / channel are zero.  The whole expanded weight tile of a wave (32 channels x all K:
@@ -268,20 +268,27 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
         for (int d = 0; d < slot * a.stagger; ++d) __builtin_amdgcn_s_sleep(8);
     }
     TWN_FTRACE(1);
+    // Order per tile i: MFMA loop; wait for everything in flight; patch i+1 registers -> LDS; request patch i+2;
+    // epilogue and output stores of tile i; barrier.  A patch request so has a whole tile's time to be answered
+    // (the input comes from memory: with the request at the top of the tile that consumes it, a third of the
+    // kernel's time was spent waiting for it), and it is older than the stores it would otherwise queue behind.
     Tile cur = tile_of(0);
     load_patch(cur);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     store_patch(smem);
-    __syncthreads();
+    Tile nxt = cur;
+    if (n_my > 1) {
+        nxt = tile_of(1);
+        load_patch(nxt);
+    }
+    // the first patch is in LDS (a bare barrier: the request just issued stays in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     TWN_FTRACE(2);
     int buf = 0;
     for (uint32_t i = 0; i < n_my; ++i) {
-        const bool more = (i + 1 < n_my);
-        Tile nxt = cur;
-        if (more) {
-            nxt = tile_of(i + 1);
-            load_patch(nxt);
-        }
+        const bool more = (i + 1 < n_my), more2 = (i + 2 < n_my);
         const unsigned char* pb = smem + buf * a.patch_bytes;
         if (i == 1) TWN_FTRACE(3);
         {
@@ -324,14 +331,16 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
                     }
             }
         }
-        // the next patch goes to the other buffer BEFORE the epilogue's stores are issued: waiting for its loads
-        // must not mean waiting for those stores
         if (i == 1) TWN_FTRACE(4);
         // a full wait, not a counted one: it does not rest on requests being answered in issue order when all lanes
-        // of one fall outside the image (the stores of the previous tile are older than the patch requests, so a
-        // counted wait would cover them as well: nothing is lost)
+        // of one fall outside the image; it covers the stores of tile i-1 too, which have had a tile's time
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (more) store_patch(smem + (buf ^ 1) * a.patch_bytes);
+        Tile nn = nxt;
+        if (more2) {
+            nn = tile_of(i + 2);
+            load_patch(nn);
+        }
         if (i == 1) TWN_FTRACE(5);
         // ---- epilogue: accumulator element e of block mi in this lane: pixel row wm*4 + mi*2 + (lrow>>4),
         // column lrow & 15, channel wn*32 + (e>>2)*8 + lh*4 + (e&3) ----
@@ -393,6 +402,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
         if (i == 1) TWN_FTRACE(7);
         buf ^= 1;
         cur = nxt;
+        nxt = nn;
     }
     TWN_FTRACE(8);
 }
