@@ -143,6 +143,8 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
 
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
         (__attribute__((address_space(3))) unsigned char*)smem));
+    typedef short s16x2 __attribute__((ext_vector_type(2)));
+    const s16x2 floor2 = __builtin_bit_cast(s16x2, a.relu ? 0u : 0x80008000u);
     f32x16 acc;
     unsigned char* stg = stg_base + wave * (32 * 80);
     // read-back lane (it): staged row it*16 + lane/4 = tile pixel (wm*4 + row/8, row%8), 16-byte chunk lane&3;
@@ -262,13 +264,11 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
                     v[2] += __uint_as_float(rr[1] << 16);
                     v[3] += __uint_as_float(rr[1] & 0xFFFF0000u);
                 }
-                if (a.relu) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.0f);
-                }
+                // ReLU on the rounded pair: a packed signed 16-bit maximum against 0 (negative bf16 values are negative
+                // as integers), or against the int16 minimum when there is no ReLU
                 u32x2 pk;
-                pk[0] = pack_bf16x2(v[0], v[1]);
-                pk[1] = pack_bf16x2(v[2], v[3]);
+                pk[0] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pack_bf16x2(v[0], v[1])), floor2));
+                pk[1] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2, pack_bf16x2(v[2], v[3])), floor2));
                 *reinterpret_cast<u32x2*>(stg + lrow * 80 + (q4 * 8 + lh * 4) * 2) = pk;
             }
         }
