@@ -17,6 +17,7 @@
 //     stores) is that of the other contraction kernels.
 // Nothing is prepared in a separate launch and no workspace is used.
 #include <mutex>
+#include <type_traits>
 
 #include "twn_kernels.h"
 #include "twn_mfma.h"
@@ -44,7 +45,8 @@ struct FirstArgs {
     int32_t stagger;            // start delay per residency slot, in units of 512 cycles
     uint32_t tiles, tiles_x, tiles_y;
     FastDivU divTX, divTY, divPairs, divKq;
-    uint32_t x_bytes;
+    uint32_t x_bytes, y_bytes;
+    int32_t through;            // 1: output stores are written through (sc1)
 };
 
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
@@ -171,6 +173,7 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
     const uint32_t n_my = (count_x - j + gx - 1) / gx;
 
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(a.X, a.x_bytes);
+    const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.Y, a.y_bytes);
     struct Tile {
         int img, p0, q0;
     };
@@ -186,42 +189,40 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
 
     // patch of a tile -> registers: lane handles pixel pairs tid, tid + 256, ... (12 bytes each).  Which patch
     // pixel a lane handles never changes: its coordinates and offsets are computed once.
-    int py[NITMAX], px[NITMAX];             // patch row and column of the pair (py = -1: the lane has no pair)
+    int py[NITMAX], px[NITMAX];             // patch row and column of the pair (far negative: the lane has no pair)
     uint32_t goff[NITMAX];                  // byte offset of the pair relative to the patch origin in X
     uint32_t loff[NITMAX];                  // byte offset in the LDS patch
+    bool has[NITMAX];
 #pragma unroll
     for (int it = 0; it < NITMAX; ++it) {
         const uint32_t pi = static_cast<uint32_t>(it * 256 + tid);
         const uint32_t y = fdiv_u(pi, a.divPairs);
         const int xp = static_cast<int>(pi - y * a.pairs);
-        const bool has = it < a.nit && y < static_cast<uint32_t>(a.PH);
-        py[it] = has ? static_cast<int>(y) : -1;
+        has[it] = y < static_cast<uint32_t>(a.PH);
+        py[it] = has[it] ? static_cast<int>(y) : -(1 << 24);
         px[it] = 2 * xp;
         goff[it] = (y * static_cast<uint32_t>(a.W) + static_cast<uint32_t>(2 * xp)) * 6u;
         loff[it] = (y * static_cast<uint32_t>(a.PW) + static_cast<uint32_t>(2 * xp)) * 8u;
     }
     u32x3 pr[NITMAX];
+    // branch-free: a pair outside the image (the zero border) or a lane without a pair gets an offset past the
+    // descriptor and reads zeros
     auto load_patch = [&](const Tile& t) __attribute__((always_inline)) {
         const int y0 = t.p0 * a.sh - a.ph, x0 = t.q0 * a.sw - a.pw - a.xoff;
         // 32-bit wrapping arithmetic: the offset of every pair that lies inside the image is in [0, x_bytes)
         const uint32_t base = ((static_cast<uint32_t>(t.img) * a.H + static_cast<uint32_t>(y0)) * a.W + static_cast<uint32_t>(x0)) * 6u;
-        const bool inside = y0 >= 0 && x0 >= 0 && y0 + a.PH <= a.H && x0 + a.PW <= a.W;      // wave-uniform
 #pragma unroll
         for (int it = 0; it < NITMAX; ++it) {
-            if (it < a.nit) {
-                bool ok = py[it] >= 0;
-                if (!inside)
-                    ok = ok && static_cast<unsigned>(y0 + py[it]) < static_cast<unsigned>(a.H) &&
-                         static_cast<unsigned>(x0 + px[it]) < static_cast<unsigned>(a.W);
-                pr[it] = __builtin_bit_cast(u32x3, __builtin_amdgcn_raw_buffer_load_b96(rx, ok ? base + goff[it] : kBufOutside, 0, 0));
-            }
+            const bool ok = (static_cast<unsigned>(y0 + py[it]) < static_cast<unsigned>(a.H)) &
+                            (static_cast<unsigned>(x0 + px[it]) < static_cast<unsigned>(a.W));
+            pr[it] = __builtin_bit_cast(u32x3, __builtin_amdgcn_raw_buffer_load_b96(rx, ok ? base + goff[it] : kBufOutside, 0, 0));
         }
     };
     // registers -> LDS, widened to four channels: [c0 c1 | c2 c0' | c1' c2'] -> [c0 c1 | c2 0 | c0' c1' | c2' 0]
     auto store_patch = [&](unsigned char* buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int it = 0; it < NITMAX; ++it) {
-            if (it < a.nit && py[it] >= 0) {
+            if (has[it]) {
                 const u32x3 d = pr[it];
                 const u32x4 w = {d[0], d[1] & 0xFFFFu, (d[1] >> 16) | (d[2] << 16), d[2] >> 16};
                 *reinterpret_cast<u32x4*>(buf + loff[it]) = w;
@@ -254,13 +255,13 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
     f32x16 acc[2];
     unsigned char* stg = stg_base + wave * (64 * 80);
     // read-back lane (it): staged row it*16 + lane/4 = pixel row wm*4 + it (+ lane/64...), 16-byte chunk lane&3;
-    // its element offset in Y relative to the tile's first pixel and channel n0
+    // its byte offset in Y relative to the tile's first pixel and channel n0
     uint32_t yoff[4];
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const int row = it * 16 + (lane >> 2);
-        yoff[it] = (static_cast<uint32_t>(wm * 4 + (row >> 4)) * a.Q + static_cast<uint32_t>(row & 15)) * a.O +
-                   static_cast<uint32_t>(wn * 32 + (lane & 3) * 8);
+        yoff[it] = ((static_cast<uint32_t>(wm * 4 + (row >> 4)) * a.Q + static_cast<uint32_t>(row & 15)) * a.O +
+                    static_cast<uint32_t>(wn * 32 + (lane & 3) * 8)) * 2u;
     }
 
     // Optional one-time start stagger by residency slot (TWN_FIRST_STAGGER, in units of 512 cycles; off by
@@ -380,16 +381,17 @@ __global__ __launch_bounds__(256, 3) void conv_first_kernel(const FirstArgs a) {
             u32x4 val[4];
 #pragma unroll
             for (int it = 0; it < 4; ++it) val[it] = *reinterpret_cast<const u32x4*>(stg + (it * 16 + (lane >> 2)) * 80 + (lane & 3) * 16);
-            uint16_t* ytile = a.Y + ((static_cast<int64_t>(cur.img) * a.P + cur.p0) * a.Q + cur.q0) * a.O + n0;   // wave-uniform
-            const bool full = cur.p0 + kFirstTH <= a.P && cur.q0 + kFirstTW <= a.Q && n0 + 64 <= a.O;           // wave-uniform
+            // byte offset of the tile's first pixel and channel n0 (wave-uniform); a lane outside the tensor gets an offset
+            // past the descriptor and its store is dropped
+            const uint32_t ytile = (((static_cast<uint32_t>(cur.img) * a.P + static_cast<uint32_t>(cur.p0)) * a.Q +
+                                     static_cast<uint32_t>(cur.q0)) * static_cast<uint32_t>(a.O) + static_cast<uint32_t>(n0)) * 2u;
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
-                bool ok = true;
-                if (!full) {
-                    const int row = it * 16 + (lane >> 2);
-                    ok = cur.p0 + wm * 4 + (row >> 4) < a.P && cur.q0 + (row & 15) < a.Q && n0 + wn * 32 + (lane & 3) * 8 < a.O;
-                }
-                if (ok) *reinterpret_cast<u32x4*>(ytile + yoff[it]) = val[it];
+                const int row = it * 16 + (lane >> 2);
+                const bool ok = (cur.p0 + wm * 4 + (row >> 4) < a.P) & (cur.q0 + (row & 15) < a.Q) & (n0 + wn * 32 + (lane & 3) * 8 < a.O);
+                const uint32_t vo = ok ? yoff[it] + ytile : kBufOutside;
+                if (a.through) __builtin_amdgcn_raw_buffer_store_b128(val[it], ry, vo, 0, kStoreThrough);
+                else __builtin_amdgcn_raw_buffer_store_b128(val[it], ry, vo, 0, 0);
             }
         }
         // The next patch is complete (this wave's LDS writes have landed) and every wave is done with the current
@@ -447,7 +449,13 @@ static bool first_plan(const FirstLayer& f, FirstArgs* a) {
     // the expanded weight table (64 channels x ktot*32 bytes) is built where the patches and staging rows go
     if (64 * ktot * 32 > 2 * a->patch_bytes + kFirstStg) return false;
     a->x_bytes = static_cast<uint32_t>(xb);
+    const int64_t yb = static_cast<int64_t>(f.N) * f.P * f.Q * f.O * 2;
+    if (yb >= (1LL << 31)) return false;
+    a->y_bytes = static_cast<uint32_t>(yb);
     a->stagger = env_int("TWN_FIRST_STAGGER", 0);
+    // Ordinary stores by default: written through, this kernel alone is faster (ResNet-18 stem 35.6 -> 33.7 us) but the
+    // step it is part of slower (0.442 -> 0.450 ms, A/B on one box): its 103 MB of output then drain into the next launch.
+    a->through = env_int("TWN_FIRST_THROUGH", 0) != 0 ? 1 : 0;
     return true;
 }
 
@@ -458,7 +466,13 @@ bool conv_first_applicable(const FirstLayer& f) {
 
 template <int KMAX>
 static int32_t launch_first(const FirstArgs& a, hipStream_t st) {
-    auto k = (a.sw % 2 == 0) ? conv_first_kernel<KMAX, 4, true> : conv_first_kernel<KMAX, 4, false>;
+    // patch pairs per lane: 1, 2 or 4 (a plan with 3 runs the build for 4: the fourth request of a lane reads zeros)
+    auto pick = [&](auto nit_tag) {
+        constexpr int NIT = decltype(nit_tag)::value;
+        return (a.sw % 2 == 0) ? conv_first_kernel<KMAX, NIT, true> : conv_first_kernel<KMAX, NIT, false>;
+    };
+    auto k = a.nit <= 1 ? pick(std::integral_constant<int, 1>{})
+             : a.nit == 2 ? pick(std::integral_constant<int, 2>{}) : pick(std::integral_constant<int, 4>{});
     const int smem = 2 * a.patch_bytes + kFirstStg + 2 * 64 * 4 + 64 * a.wpr * 4;
     static std::once_flag once;
     static int cus = 256;
