@@ -837,3 +837,28 @@ def test_full_size_backward_is_identical_run_to_run(name):
         if ref is None:
             ref = (dx.clone(), dw.clone())
         assert torch.equal(dx, ref[0]) and torch.equal(dw, ref[1])
+
+
+def test_full_size_gemm_and_wide_tiles_are_identical_run_to_run():
+    g = torch.Generator(device="cuda").manual_seed(5)
+    cases = []
+    x = torch.randn((8192, 4096), device="cuda", generator=g).to(torch.bfloat16)
+    tw = api.twn_ternarize(torch.randn((4096, 4096), device="cuda", generator=g) * 0.02, F)
+    y = torch.empty((8192, 4096), dtype=torch.bfloat16, device="cuda")
+    cases.append((api.prepare_gemm_fwd(x, tw, out=y, relu=True), y))
+    L = {l.name: l for l in wl.vgg16_ssd(32)}["conv8"]
+    x2 = torch.randn(L.x_shape, device="cuda", generator=g).to(torch.bfloat16)
+    tw2 = api.twn_ternarize(to_dev_f32(wl.kaiming_weights(5, 7, L)), F)
+    y2 = torch.empty(L.y_shape, dtype=torch.bfloat16, device="cuda")
+    cases.append((api.prepare_conv2d_fwd(x2, tw2, (L.stride,) * 2, (L.pad,) * 2, (L.dil,) * 2, out=y2, relu=True), y2))
+    for call, out in cases:
+        out.fill_(-7.0)
+        call()
+        torch.cuda.synchronize()
+        ref = out.clone()
+        for fill in (0.0, -7.0, 3.0, 0.0):
+            out.fill_(fill)
+            call()
+            torch.cuda.synchronize()
+            assert torch.equal(out, ref)
+        assert float(ref.min()) >= 0.0
