@@ -64,6 +64,10 @@ void set_epilogue(GatherGemm& g, const twn_epilogue* ep) {
 }
 
 size_t splitk_bytes(const GatherGemm& g, int variant) {
+    if (variant == TWN_VAR_FP32) {
+        const int32_t splits = gather_gemm_fp32_splits(g);
+        return splits > 1 ? static_cast<size_t>(splits) * static_cast<size_t>(g.M) * g.NC * sizeof(double) : 0;
+    }
     if (variant != TWN_VAR_BF16_POSTSCALE) return 0;   // the other variants never split K
     const int32_t splits = gather_gemm_splits(g);
     return splits > 1 ? static_cast<size_t>(splits) * static_cast<size_t>(g.M) * g.NC * sizeof(float) : 0;
@@ -72,7 +76,16 @@ size_t splitk_bytes(const GatherGemm& g, int variant) {
 // Attaches the split-K workspace (if the problem uses one) and launches.
 int32_t dispatch(GatherGemm& g, int variant, void* workspace, size_t workspace_bytes, hipStream_t st,
                  bool allow_split = true) {
-    if (variant == TWN_VAR_FP32) return launch_gather_gemm_fp32(g, st);
+    if (variant == TWN_VAR_FP32) {
+        g.splits = allow_split ? gather_gemm_fp32_splits(g) : 1;
+        g.partial = nullptr;
+        if (g.splits > 1) {
+            const size_t need = static_cast<size_t>(g.splits) * static_cast<size_t>(g.M) * g.NC * sizeof(double);
+            if (!workspace || workspace_bytes < need || !aligned(workspace, 16)) return TWN_ERR_WORKSPACE;
+            g.partial = static_cast<float*>(workspace);
+        }
+        return launch_gather_gemm_fp32(g, st);
+    }
     if (variant == TWN_VAR_ADDSUB_SPARSE) {
         g.splits = 1;
         g.partial = nullptr;

@@ -8,13 +8,16 @@
 // The layers that use it (LeNet-sized) are small, so the kernel is kept simple, but two things matter even
 // there: the gathers of the next K slab are in flight (in registers) while the current slab is multiplied, and
 // problems with few 64x64 tiles (the fully-connected layers at batch 64) run 32x32 tiles, four times as many
-// workgroups.  A thread owns (TS/16)^2 outputs.
+// workgroups.  A thread owns (TS/16)^2 outputs.  Problems that still have few tiles and a long reduction (the
+// fully-connected layers of LeNet at batch 64: 32 tiles, 13 slabs each) are split along K over blockIdx.y: every
+// range writes its float64 sums to the workspace and a second launch adds them in a fixed order and applies the tail.
 #include "twn_kernels.h"
 
 namespace twn {
 
-template <int TS>
-__global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm g) {
+// SPLIT: blockIdx.y owns `kps` slabs of K and writes raw float64 sums to g.partial ([split][M][NC] doubles)
+template <int TS, bool SPLIT>
+__global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm g, int kps) {
     // K slab: 32 for 64x64 tiles, 64 for 32x32 tiles.  Both operands are widened to float64 once, when they are
     // staged (every staged value is read by 16 threads), so the inner loop is LDS reads and float64 FMAs only.
     constexpr int kF32K = (TS == 32) ? 64 : 32;
@@ -101,11 +104,13 @@ __global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm 
     const int ty = tid >> 4, tx = tid & 15;
     double acc[TT][TT] = {};
 
-    fetch(0);
-    for (int k0 = 0; k0 < g.K; k0 += kF32K) {
+    const int kbeg = SPLIT ? static_cast<int>(blockIdx.y) * kps * kF32K : 0;
+    const int kend = SPLIT ? min(g.K, kbeg + kps * kF32K) : g.K;
+    fetch(kbeg);
+    for (int k0 = kbeg; k0 < kend; k0 += kF32K) {
         stage(k0);
         __syncthreads();
-        if (k0 + kF32K < g.K) fetch(k0 + kF32K);        // in flight while this slab is multiplied
+        if (k0 + kF32K < kend) fetch(k0 + kF32K);        // in flight while this slab is multiplied
 #pragma unroll 8
         for (int k = 0; k < kF32K; ++k) {
             double a[TT], b[TT];
@@ -121,6 +126,19 @@ __global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm 
         __syncthreads();
     }
 
+    if constexpr (SPLIT) {
+        double* __restrict__ part = reinterpret_cast<double*>(g.partial) + static_cast<int64_t>(blockIdx.y) * g.M * g.NC;
+#pragma unroll
+        for (int i = 0; i < TT; ++i) {
+            const int64_t m = m0 + ty * TT + i;
+#pragma unroll
+            for (int j = 0; j < TT; ++j) {
+                const int ncol = n0 + tx * TT + j;
+                if (m < g.M && ncol < g.NC) part[m * g.NC + ncol] = acc[i][j];
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
         const int ncol = n0 + tx * TT + j;
@@ -147,15 +165,91 @@ __global__ __launch_bounds__(256) void gather_gemm_fp32_kernel(const GatherGemm 
     }
 }
 
-int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st) {
+// Sum of the K ranges in a fixed order (float64), then the same tail as the unsplit kernel.
+__global__ __launch_bounds__(256) void fp32_splitk_finish_kernel(const GatherGemm g) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t total = g.M * g.NC;
+    if (i >= total) return;
+    const double* __restrict__ part = reinterpret_cast<const double*>(g.partial);
+    double sum = 0.0;
+    for (int s = 0; s < g.splits; ++s) sum += part[static_cast<int64_t>(s) * total + i];
+    const int64_t m = i / g.NC;
+    const int ncol = static_cast<int>(i - m * g.NC);
+    const float al = g.alpha[ncol / g.rows_per_group];
+    const float sc = g.scale ? g.scale[ncol] : 1.0f;
+    const float sf = g.shift ? g.shift[ncol] : 0.0f;
+    float v = (static_cast<float>(sum) * al) * sc + sf;
+    const int64_t off = m * g.ldy + ncol;
+    if (g.y_f32) {
+        if (g.residual) v += static_cast<const float*>(g.residual)[off];
+        if (g.relu) v = fmaxf(v, 0.0f);
+        static_cast<float*>(g.Y)[off] = v;
+    } else {
+        if (g.residual) v += bf16_to_f32(static_cast<const uint16_t*>(g.residual)[off]);
+        if (g.relu) v = fmaxf(v, 0.0f);
+        static_cast<uint16_t*>(g.Y)[off] = f32_to_bf16(v);
+    }
+}
+
+// Tile side and K ranges of the float32 path: a pure function of the shapes (the workspace query and the launch
+// agree).  Problems with at least 128 tiles of 64x64 run those, unsplit.  Smaller ones are split along K towards
+// about 1024 workgroups, every range at least two slabs long, at most 16 ranges; they keep 64x64 tiles (half the
+// LDS reads per multiply-add of 32x32 tiles) if that still gives 256 workgroups, else 32x32 tiles.
+struct Fp32Plan {
+    int ts, kslab, splits, kps;
+};
+static Fp32Plan fp32_plan(const GatherGemm& g) {
     auto blocks = [&](int ts) { return ((g.M + ts - 1) / ts) * ((g.NC + ts - 1) / ts); };
-    const int ts = blocks(64) >= 128 ? 64 : 32;
-    const int64_t nb = blocks(ts);
+    auto slabs = [&](int kslab) { return (static_cast<int64_t>(g.K) + kslab - 1) / kslab; };
+    Fp32Plan p{64, 32, 1, 0};
+    if (blocks(64) >= 128) return p;
+    const bool split = env_int("TWN_F32_SPLITK", 1) != 0;
+    auto ranges = [&](int64_t tiles, int64_t kt, int* kps) {
+        int64_t want = 1024 / tiles;
+        if (want > kt / 2) want = kt / 2;
+        if (want > 16) want = 16;
+        if (want < 2 || !split) {
+            *kps = 0;
+            return 1;
+        }
+        *kps = static_cast<int>((kt + want - 1) / want);
+        return static_cast<int>((kt + *kps - 1) / *kps);
+    };
+    int kps64 = 0;
+    const int s64 = ranges(blocks(64), slabs(32), &kps64);
+    if (split && g.M >= 48 && g.NC >= 48 && blocks(64) * s64 >= 256) {
+        p.splits = s64;
+        p.kps = kps64;
+        return p;
+    }
+    p.ts = 32;
+    p.kslab = 64;
+    p.splits = ranges(blocks(32), slabs(64), &p.kps);
+    return p;
+}
+
+int32_t gather_gemm_fp32_splits(const GatherGemm& g) { return fp32_plan(g).splits; }
+
+int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st) {
+    const Fp32Plan p = fp32_plan(g);
+    const int64_t nb = ((g.M + p.ts - 1) / p.ts) * ((g.NC + p.ts - 1) / p.ts);
     if (nb <= 0 || nb >= (1LL << 31)) return TWN_ERR_SHAPE;
-    if (ts == 64)
-        gather_gemm_fp32_kernel<64><<<static_cast<unsigned>(nb), 256, 0, st>>>(g);
+    if (g.splits > 1) {
+        if (g.splits != p.splits || !g.partial) return TWN_ERR_WORKSPACE;
+        const int64_t total = g.M * g.NC;
+        if (total >= (1LL << 31) * 256) return TWN_ERR_SHAPE;
+        const dim3 grid(static_cast<unsigned>(nb), static_cast<unsigned>(g.splits));
+        if (p.ts == 64)
+            gather_gemm_fp32_kernel<64, true><<<grid, 256, 0, st>>>(g, p.kps);
+        else
+            gather_gemm_fp32_kernel<32, true><<<grid, 256, 0, st>>>(g, p.kps);
+        fp32_splitk_finish_kernel<<<static_cast<unsigned>((total + 255) / 256), 256, 0, st>>>(g);
+        return launch_status();
+    }
+    if (p.ts == 64)
+        gather_gemm_fp32_kernel<64, false><<<static_cast<unsigned>(nb), 256, 0, st>>>(g, 0);
     else
-        gather_gemm_fp32_kernel<32><<<static_cast<unsigned>(nb), 256, 0, st>>>(g);
+        gather_gemm_fp32_kernel<32, false><<<static_cast<unsigned>(nb), 256, 0, st>>>(g, 0);
     return launch_status();
 }
 

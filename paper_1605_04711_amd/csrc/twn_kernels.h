@@ -40,7 +40,7 @@ struct GatherGemm {
     // [N][orU][orV] grid is written to pixel (n, ora + orsh*u, orb + orsw*v) of an [N][orH][orW] image.
     // orU == 0: rows are written in order.
     int32_t orU, orV, orH, orW, ora, orb, orsh, orsw;
-    float* partial;         // split-K workspace [splits][M][NC] float32 (null when splits == 1)
+    float* partial;         // split-K workspace [splits][M][NC] float32 (float64 on the float32 path; null when splits == 1)
     int32_t splits;         // K is cut into this many ranges of whole 64-wide slabs
 };
 
@@ -75,6 +75,8 @@ int32_t launch_gather_gemm_dma(const GatherGemm& g, int tile, hipStream_t st);
 int32_t gather_gemm_dma_tile(const GatherGemm& g, bool instead_of_persistent = false);
 int32_t launch_gather_gemm_dma_batch(const GatherGemm* gs, int count, int tile, hipStream_t st);
 int32_t launch_gather_gemm_fp32(const GatherGemm& g, hipStream_t st);
+// K ranges of the float32 path (1 = no split); with more than one, g.partial holds [splits][M][NC] float64 sums.
+int32_t gather_gemm_fp32_splits(const GatherGemm& g);
 // Multiplication-free comparison kernel (vector ALUs, zero codes skipped); `applicable` is a pure function of the problem.
 bool conv_addsub_applicable(const GatherGemm& g);
 int32_t launch_conv_addsub(const GatherGemm& g, hipStream_t st);

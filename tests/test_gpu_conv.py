@@ -311,6 +311,37 @@ def test_lenet_layers_fp32(batch):
     assert rel_err(to_host_f64(y), oc.gemm_fwd(x, codes.reshape(layer.O, layer.C), alpha)) <= FP32_TOL
 
 
+F32_SPLIT_CASES = [   # M, N, K: float32 problems with few tiles, so that K is cut into ranges (ragged last range and slab)
+    (64, 500, 800), (64, 10, 500), (200, 100, 1000), (33, 48, 130), (96, 130, 2000), (5, 7, 4000),
+]
+
+
+@pytest.mark.parametrize("split", [1, 0])
+@pytest.mark.parametrize("m,n,k", F32_SPLIT_CASES)
+def test_gemm_fwd_fp32_split_k(m, n, k, split, knob):
+    knob("TWN_F32_SPLITK", str(split))
+    g = np.random.default_rng(m + n + k)
+    x = g.uniform(-1.0, 1.0, (m, k)).astype(np.float32)
+    w = (g.standard_normal((n, k)) * 0.05).astype(np.float32)
+    tw = api.twn_ternarize(to_dev_f32(w), F)
+    codes, delta, alpha, nnz = ot.ternarize(w.reshape(n, k, 1, 1), F)
+    # no shift here: a float32 addition that cancels the sum would put its own rounding above the bound of this path
+    y = api.twn_gemm_fwd(to_dev_f32(x), tw, y_dtype=torch.float32, relu=True)
+    ref = oc.epilogue(oc.gemm_fwd(x, codes.reshape(n, k), alpha), relu=True)
+    assert rel_err(to_host_f64(y), ref) <= FP32_TOL
+
+
+def test_conv2d_fwd_fp32_split_k_on_large_tiles():
+    # 4096 pixels x 64 filters x K = 800: few 64x64 tiles, the reduction is cut into ranges of 32-wide slabs
+    x = wl.uniform01(0, 91, (16, 20, 20, 32))
+    g = np.random.default_rng(17)
+    w = (g.standard_normal((64, 32, 5, 5)) * 0.05).astype(np.float32)
+    tw = api.twn_ternarize(to_dev_f32(w), F)
+    codes, delta, alpha, nnz = ot.ternarize(w, F)
+    y = api.twn_conv2d_fwd(to_dev_f32(x), tw, (1, 1), (0, 0), (1, 1), y_dtype=torch.float32)
+    assert rel_err(to_host_f64(y), oc.conv2d_fwd(x, codes, alpha, (1, 1), (0, 0), (1, 1))) <= FP32_TOL
+
+
 BWD_CASES = list(range(len(CONV_CASES)))      # includes the 7x7 / stride-2 / C = 3 stem shape (index 5)
 
 
