@@ -805,6 +805,19 @@ def test_resident_weight_3x3_kernel_backward_data(ci):
     assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, (n, h, w_, c), st, pd, dl)) <= BF16_TOL
 
 
+@pytest.mark.parametrize("ci", [0, 3])
+def test_resident_weight_3x3_kernel_backward_data_per_filter_alpha(ci):
+    # one alpha per filter: alpha * dY goes through the kernel as two bf16 terms, the second adding onto the first in place
+    n, h, w_, c, pd = C64_CASES[ci]
+    st = dl = (1, 1)
+    x, w, tw, codes, alpha = make_layer(940 + ci, (n, h, w_, c), (64, c, 3, 3), groups=64, transposed=True)
+    p, q = h + 2 * pd[0] - 2, w_ + 2 * pd[1] - 2
+    dy = wl.bf16_round(np.random.default_rng(50 + ci).standard_normal((n, p, q, 64)).astype(np.float32))
+    dx, _, _ = api.twn_conv2d_bwd_ste(None, to_dev_bf16(dy), tw, st, pd, dl, need_dx=True, need_dw=False,
+                                      x_shape=(n, h, w_, c))
+    assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, (n, h, w_, c), st, pd, dl)) <= BF16_TOL
+
+
 def test_resident_weight_3x3_kernel_long_tile_walks(knob):
     knob("TWN_C64_OCC", "1")          # half the workgroups: two to three tiles each
     n, h, w_, o, pd = C64_CASES[5]
