@@ -9,8 +9,8 @@
 //     channels, and its 36 weight fragments (144 registers) are built ONCE per workgroup, straight from the packed
 //     2-bit rows in global memory.  The main loop has no code expansion and no weight traffic at all;
 //   * persistent workgroups walk 8x8 tiles of output pixels; the 10x10 input patch (tile + halo) is read ONCE from
-//     global memory (the next tile's patch is in flight in registers while the current one is multiplied) and all
-//     nine taps read their shifted windows of it from LDS.  A patch pixel takes 144 bytes and a patch row 1664
+//     global memory (the patch of tile i+2 is requested during tile i and is in flight in registers while tile i+1
+//     is multiplied) and all nine taps read their shifted windows of it from LDS.  A patch pixel takes 144 bytes and a patch row 1664
 //     bytes in LDS, which makes every 16-lane group of a fragment read (two tile rows of eight pixels) hit 16
 //     different 16-byte bank groups for every tap, and makes the tap and channel-chunk part of a fragment's
 //     address a compile-time constant: one address register, the rest sits in the read's immediate offset;
