@@ -215,7 +215,7 @@ __global__ __launch_bounds__(256, 2) void conv_c64_kernel(const C64Args a) {
             // offset is an immediate.  The reads run AHEAD steps in front of the MFMAs through a ring of RING
             // registers (inline assembly with exact lgkmcnt waits: LDS operations complete in issue order); the
             // read of step ks + AHEAD lands in the registers of step ks - 1.
-            constexpr int AHEAD = 5, RING = 6;
+            constexpr int AHEAD = 8, RING = 9;
             u32x4 af[RING];
             auto read_step = [&](auto ks_tag) __attribute__((always_inline)) {
                 constexpr int ks = decltype(ks_tag)::value;
