@@ -228,7 +228,8 @@ int32_t twn_conv2d_fwd(const twn_conv_desc* d, const void* X, const void* weight
  * residual block and its projection shortcut (the ResNet-18 of Sec. 3.1 has three
  * such block heads).  Results are those of two twn_conv2d_fwd calls (each problem
  * has its own filters, alpha, geometry, epilogue and output); when both problems
- * get the same tile shape they run in ONE launch, else one after the other.
+ * get the same tile shape and short reductions (K <= 1536) they run in ONE
+ * launch, else one after the other.
  * Product variant, bf16 in and out, C % 8 == 0 (else TWN_ERR_UNSUPPORTED); d0 and
  * d1 must agree in N, H, W, C (else TWN_ERR_SHAPE); no workspace is used. */
 int32_t twn_conv2d_fwd_pair(const twn_conv_desc* d0, const twn_conv_desc* d1, const void* X,
