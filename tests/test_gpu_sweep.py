@@ -1,6 +1,7 @@
 """Seeded random shapes through the specialised forward kernels (first layers with three channels, 3x3 layers
-over 64 channels, two convolutions over one input, the float32 path with K ranges) against the direct-loop
-oracle (Eq. 2; Alg. 1 steps 8-9): the fixed cases elsewhere pick shapes by hand, these do not."""
+over 64 channels, two convolutions over one input, the float32 path with K ranges) and random geometries through
+forward, data gradient and weight gradient, against the direct-loop oracle (Eq. 2; Alg. 1 steps 8-10): the fixed
+cases elsewhere pick shapes by hand, these do not."""
 
 import numpy as np
 import pytest
@@ -99,3 +100,29 @@ def test_random_float32_products(seed):
     codes, delta, alpha, nnz = ot.ternarize(w.reshape(n, k, 1, 1), F)
     y = api.twn_gemm_fwd(to_dev_f32(x), tw, y_dtype=torch.float32)
     assert rel_err(to_host_f64(y), oc.gemm_fwd(x, codes.reshape(n, k), alpha)) <= FP32_TOL
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_geometries_forward_and_backward(seed):
+    rng = np.random.default_rng(5000 + seed)
+    n, h, w_ = int(rng.integers(1, 5)), int(rng.integers(3, 34)), int(rng.integers(3, 34))
+    c = int(rng.choice([8, 16, 24, 32, 64, 72, 128, 192, 256]))
+    o = int(rng.choice([8, 10, 16, 40, 64, 72, 128, 136, 256, 320]))
+    r, s = int(rng.choice([1, 3, 5])), int(rng.choice([1, 3, 5]))
+    st = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+    dl = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+    pd = (int(rng.integers(0, 3)), int(rng.integers(0, 3)))
+    if h + 2 * pd[0] < dl[0] * (r - 1) + 1 or w_ + 2 * pd[1] < dl[1] * (s - 1) + 1:
+        pd = (dl[0] * (r - 1), dl[1] * (s - 1))
+    x = wl.bf16_round(rng.standard_normal((n, h, w_, c)).astype(np.float32))
+    w = (rng.standard_normal((o, c, r, s)) * np.sqrt(2.0 / (c * r * s))).astype(np.float32)
+    tw = api.twn_ternarize(to_dev_f32(w), F, transposed=True)
+    codes, delta, alpha, nnz = ot.ternarize(w, F)
+    ref0 = oc.conv2d_fwd(x, codes, alpha, st, pd, dl)
+    relu = bool(rng.integers(0, 2))
+    y = api.twn_conv2d_fwd(to_dev_bf16(x), tw, st, pd, dl, relu=relu)
+    assert rel_err(to_host_f64(y), oc.epilogue(ref0, relu=relu)) <= BF16_TOL
+    dy = wl.bf16_round(rng.standard_normal(ref0.shape).astype(np.float32))
+    dx, dw, _ = api.twn_conv2d_bwd_ste(to_dev_bf16(x), to_dev_bf16(dy), tw, st, pd, dl)
+    assert rel_err(to_host_f64(dx), oc.conv2d_bwd_data(dy, codes, alpha, x.shape, st, pd, dl)) <= BF16_TOL
+    assert rel_err(to_host_f64(dw), oc.conv2d_bwd_weight(x, dy, codes.shape, st, pd, dl)) <= 1e-3
